@@ -1,0 +1,177 @@
+/*
+ * dart.h -- C ABI of the duplication-aware token reduction step (DART,
+ * arXiv 2502.11494, Section 3.3) for AMD MI355X (gfx950).
+ *
+ * The step runs between two decoder layers of a multimodal LLM.  Per sample it
+ *   (a) picks P pivot tokens by the largest L1 norm of a criterion row
+ *       (Definition 1; Table 1 caption; the footnote of Section 3.3 that
+ *       defines the K-norm as an L1 norm),
+ *   (b) scores every token against every pivot with the cosine similarity of
+ *       Definition 2 / Eq. (7),
+ *   (c) retains the pivots plus, pivot by pivot, the tokens that duplicate that
+ *       pivot least, until the keep budget is met (Eq. (9)-(10) with the
+ *       per-pivot threshold fixed by the reduction ratio),
+ *   (d) compacts hidden-state rows and position ids to the retained tokens in
+ *       their original order, so the remaining layers run on the shorter
+ *       sequence (Appendix D, post-pruning sequence length).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Memory.  `desc` is host memory, read during the call only.  Every other
+ *   pointer is DEVICE memory owned by the caller unless stated otherwise.  The
+ *   library never allocates, frees or keeps a pointer; scratch comes from the
+ *   caller's workspace `ws` of at least dart_workspace_bytes(desc) bytes,
+ *   256-byte aligned.  Inputs are never written.  Outputs must not alias inputs.
+ * Layout.  X holds `total_N` token rows of D elements, row stride `ld`
+ *   elements, sample after sample.  Dense: sample b owns rows [b*N, (b+1)*N).
+ *   Ragged: sample b owns rows [cu_seqlens[b], cu_seqlens[b+1]).  Row starts
+ *   must be 16-byte aligned (X base, ld*elemsize and D*elemsize multiples of 16).
+ * Budget.  Sample b keeps K_b tokens: K_b = K if K > 0, otherwise
+ *   K_b = floor(N_b * keep_num / keep_den).  P <= K_b <= N_b is required.
+ *   keep/pos_out/Y are packed: sample b owns rows [cu_keep[b], cu_keep[b+1]),
+ *   cu_keep[b] = sum of K_b' over b' < b (dense with K > 0: b*K).
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   Calls only enqueue work; outputs are valid once the stream reaches that
+ *   point.  No call synchronises except dart_device_status.
+ * Errors.  Violations visible on the host return a negative dart_status and
+ *   enqueue nothing.  In ragged mode the per-sample sizes live on the device:
+ *   a sample with N_b > max_N, N_b < P, K_b < P or K_b > N_b (N_b == 0 is a
+ *   valid empty sample) is skipped -- it keeps zero tokens -- and a flag is
+ *   raised in the workspace that dart_device_status reports.
+ *   Non-finite input values give unspecified (but memory-safe) results.
+ * Determinism.  Same inputs give bit-identical outputs, call after call, and a
+ *   row's score depends only on its bytes and the pivot's bytes, not on where
+ *   the row sits in the batch.
+ * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N < 2^31 / 64.
+ */
+#ifndef DART_H_
+#define DART_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dart_status {
+  DART_OK = 0,
+  DART_ERR_NULL = -1,      /* a required pointer is NULL                          */
+  DART_ERR_SHAPE = -2,     /* B, N, D, P, ld, total_N or max_N out of range        */
+  DART_ERR_BUDGET = -3,    /* P <= K <= N violated, or bad keep_num/keep_den       */
+  DART_ERR_DTYPE = -4,     /* unknown dtype or pivot mode                          */
+  DART_ERR_WORKSPACE = -5, /* ws NULL, misaligned or smaller than required         */
+  DART_ERR_ALIGN = -6,     /* a row start would not be 16-byte aligned             */
+  DART_ERR_HIP = -7,       /* a HIP call or kernel launch failed                   */
+  DART_ERR_DEVICE = -8     /* dart_device_status: a ragged sample was rejected     */
+} dart_status;
+
+typedef enum dart_dtype {
+  DART_F32 = 0,  /* IEEE binary32 hidden states                                    */
+  DART_BF16 = 1  /* bfloat16 hidden states (upper half of a binary32)              */
+} dart_dtype;
+
+typedef enum dart_pivot_mode {
+  DART_PIVOT_MAX_L1 = 0, /* largest criterion L1 norm first (Table 1 caption)      */
+  DART_PIVOT_MIN_L1 = 1  /* smallest first (the "heart" rows of the pivot ablation) */
+} dart_pivot_mode;
+
+/* Problem descriptor (host memory, plain data). */
+typedef struct dart_desc {
+  int32_t B;        /* samples in the batch, >= 0 (0 is a valid no-op)              */
+  int32_t D;        /* hidden size: elements per token row                          */
+  int32_t P;        /* pivots per sample (Definition 1), 1..64                      */
+  int32_t N;        /* tokens per sample, dense layout; ignored when ragged         */
+  const int32_t* cu_seqlens; /* DEVICE int32[B+1] row offsets, or NULL for dense    */
+  int32_t total_N;  /* rows of X; dense: B*N (0 means "derive"); ragged: required   */
+  int32_t max_N;    /* ragged: host-known upper bound of every N_b; dense: ignored  */
+  int64_t ld;       /* row stride of X in elements, >= D                            */
+  int32_t dtype;    /* dart_dtype of X, crit and Y                                  */
+  int32_t K;        /* keep budget per sample (pivots included); 0 = use the ratio  */
+  int32_t keep_num; /* K == 0: K_b = floor(N_b * keep_num / keep_den)               */
+  int32_t keep_den;
+  int32_t pivot_mode; /* dart_pivot_mode                                            */
+  int32_t reserved;   /* must be 0                                                  */
+} dart_desc;
+
+/* Bytes of workspace every entry point below accepts for this descriptor
+ * (host arithmetic only; 0 if the descriptor is invalid). */
+size_t dart_workspace_bytes(const dart_desc* desc);
+
+/* (a) Pivot selection -- Definition 1 with the max-L1-norm criterion of the
+ * Table 1 caption.  crit: criterion rows [total_N, crit_D] with row stride
+ * crit_ld (same dtype as X, e.g. the layer's key states), or NULL to use the
+ * hidden-state rows themselves (then crit_D/crit_ld are ignored).
+ * Output piv[b*P + i] = index, local to sample b, of its i-th pivot, ordered by
+ * (L1 norm descending, index ascending) -- ascending norm for DART_PIVOT_MIN_L1.
+ * Norms are accumulated in fp32 and every token whose fp32 norm could still
+ * reach the top P within the rounding bound is re-evaluated in fp64, so the
+ * order is that of the exact norms.  l1_out (optional, float[total_N]) receives
+ * the fp32 L1 norm of every criterion row. */
+dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,
+                               int32_t crit_D, int64_t crit_ld, int32_t* piv, float* l1_out,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* (b) Duplication scores -- Eq. (7): S = <p_i, x_j> / (|p_i| |x_j|), Euclidean
+ * norms, 0 when either norm is 0.  piv as produced by dart_select_pivots.
+ * S is pivot-major per sample: sample b, pivot i, token j at
+ * S[P*row0(b) + i*N_b + j] with row0(b) the sample's first row in X.
+ * bf16 inputs: exact bf16 products, fp32 matrix-core accumulation over 256
+ * elements at a time, fp64 across; fp32 inputs: fp64 throughout.  The stored
+ * value is rounded to fp32. */
+dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
+                                    float* S, void* ws, size_t ws_bytes, void* stream);
+
+/* (c) Retained set -- Eq. (9)-(10).  R starts as the pivots; with m = K_b - P,
+ * pivot i (in pivot order) adds the floor(m/P) (+1 for the first m mod P
+ * pivots) not-yet-retained tokens of lowest S[i][.], ties to the lowest index.
+ * keep receives each sample's retained indices (local to the sample) in
+ * ascending order; cu_keep (optional, int32[B+1]) receives the packed offsets.
+ * X == NULL: S is taken as exact.  X != NULL: wherever two fp32 scores at a
+ * decision boundary are closer than the rounding bound of
+ * dart_duplication_scores, the candidates involved are re-scored in fp64 from
+ * the rows of X before deciding. */
+dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t* piv,
+                           const void* X, int32_t* keep, int32_t* cu_keep, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* (d) Compaction -- the shortened sequence of Appendix D.  For sample b and
+ * r < K_b: Y[cu_keep[b]+r][:] = X[row0(b)+keep[cu_keep[b]+r]][:] (D elements,
+ * bit copy, Y rows densely packed with stride D) and
+ * pos_out[cu_keep[b]+r] = pos[row0(b)+keep[...]].  pos/pos_out may both be NULL. */
+dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int64_t* pos,
+                                const int32_t* keep, void* Y, int64_t* pos_out, void* ws,
+                                size_t ws_bytes, void* stream);
+
+/* (a)-(d) in one call.  Optional outputs (NULL to skip): pos/pos_out, cu_keep,
+ * piv_out [B*P], S_out [P*total_N]. */
+dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
+                        int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
+                        int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* dart_reduce that also records the caller's HIP events around its kernels:
+ * events is a HOST array of 7 hipEvent_t (as void*); events[k] is recorded
+ * before kernel stage k (0 row norms, 1 pivot selection, 2 scores, 3 score
+ * ordering, 4 retained set, 5 compaction) and events[6] after the last. */
+dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const void* crit,
+                                 int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
+                                 int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                                 int32_t* piv_out, float* S_out, void* ws, size_t ws_bytes,
+                                 void* stream, void* const* events);
+
+/* Waits for `stream`, then reports DART_ERR_DEVICE if the last call that used
+ * `ws` skipped a ragged sample (see Errors), DART_OK otherwise. */
+dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream);
+
+/* The absolute bound on |fp32 score - exact score| that dart_topk_keep and
+ * dart_reduce certify decisions against, for this dtype. */
+double dart_score_tolerance(int32_t dtype);
+
+/* Static, NUL-terminated description of a status code. */
+const char* dart_strerror(dart_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DART_H_ */

@@ -1,0 +1,186 @@
+"""ctypes front end of the CPU oracle (oracle/dart_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product never does.  Nothing here
+touches the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dart_oracle.cpp")
+_LIB = os.path.join(_HERE, "libdart_oracle.so")
+_lib = None
+
+F32, BF16 = 0, 1
+MAX_L1, MIN_L1 = 0, 1
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with the host compiler (plain -O2, OpenMP on)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+               _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = C.CDLL(_LIB)
+        vp, i32, i64, dp = C.c_void_p, C.c_int, C.c_int64, C.c_void_p
+        L.oracle_set_threads.argtypes = [i32]
+        L.oracle_set_threads.restype = i32
+        L.oracle_l1_norms.argtypes = [vp, i32, i64, i64, i64, dp]
+        L.oracle_l1_norms.restype = None
+        L.oracle_select_pivots.argtypes = [dp, i64, i32, i32, vp]
+        L.oracle_select_pivots.restype = None
+        L.oracle_scores.argtypes = [vp, i32, i64, i64, i64, vp, i32, dp]
+        L.oracle_scores.restype = None
+        L.oracle_retain.argtypes = [dp, i64, vp, i32, i32, vp, vp, vp, dp]
+        L.oracle_retain.restype = i32
+        L.oracle_gather.argtypes = [vp, i32, i64, i64, vp, vp, i32, vp, vp]
+        L.oracle_gather.restype = None
+        L.oracle_reduce.argtypes = [vp, i32, i64, i64, i64, vp, i64, i64, vp, i32, i32, i32,
+                                    vp, vp, dp, dp, vp, vp, dp, vp, vp, dp]
+        L.oracle_reduce.restype = i32
+        _lib = L
+    return _lib
+
+
+def set_threads(n: int) -> int:
+    return int(lib().oracle_set_threads(int(n)))
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _check_rows(X: np.ndarray, dtype: int):
+    want = np.uint16 if dtype == BF16 else np.float32
+    assert X.dtype == want and X.ndim == 2 and X.strides[1] == X.itemsize, (X.dtype, X.shape)
+    return X.shape[0], X.shape[1], X.strides[0] // X.itemsize
+
+
+def l1_norms(Cm: np.ndarray, dtype: int) -> np.ndarray:
+    n, d, ld = _check_rows(Cm, dtype)
+    out = np.empty(n, dtype=np.float64)
+    lib().oracle_l1_norms(_p(Cm), dtype, n, d, ld, _p(out))
+    return out
+
+
+def select_pivots(c: np.ndarray, P: int, mode: int = MAX_L1) -> np.ndarray:
+    c = np.ascontiguousarray(c, dtype=np.float64)
+    piv = np.empty(P, dtype=np.int32)
+    lib().oracle_select_pivots(_p(c), c.shape[0], P, mode, _p(piv))
+    return piv
+
+
+def scores(X: np.ndarray, dtype: int, piv: np.ndarray) -> np.ndarray:
+    n, d, ld = _check_rows(X, dtype)
+    piv = np.ascontiguousarray(piv, dtype=np.int32)
+    S = np.empty((piv.shape[0], n), dtype=np.float64)
+    lib().oracle_scores(_p(X), dtype, n, d, ld, _p(piv), piv.shape[0], _p(S))
+    return S
+
+
+def retain(S: np.ndarray, piv: np.ndarray, K: int, diagnostics: bool = False):
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    P, n = S.shape
+    piv = np.ascontiguousarray(piv, dtype=np.int32)
+    keep = np.empty(K, dtype=np.int32)
+    last = np.empty(P, dtype=np.int32)
+    nxt = np.empty(P, dtype=np.int32)
+    gap = np.empty(P, dtype=np.float64)
+    rc = lib().oracle_retain(_p(S), n, _p(piv), P, K, _p(keep), _p(last), _p(nxt), _p(gap))
+    if rc != 0:
+        raise ValueError(f"oracle_retain failed rc={rc} (P={P}, K={K}, N={n})")
+    return (keep, last, nxt, gap) if diagnostics else keep
+
+
+def gather(X: np.ndarray, dtype: int, pos: Optional[np.ndarray], keep: np.ndarray):
+    n, d, ld = _check_rows(X, dtype)
+    keep = np.ascontiguousarray(keep, dtype=np.int32)
+    K = keep.shape[0]
+    Y = np.empty((K, d), dtype=X.dtype)
+    pos_out = None
+    if pos is not None:
+        pos = np.ascontiguousarray(pos, dtype=np.int64)
+        pos_out = np.empty(K, dtype=np.int64)
+    lib().oracle_gather(_p(X), dtype, d, ld, _p(pos), _p(keep), K, _p(Y), _p(pos_out))
+    return Y, pos_out
+
+
+class Reduced:
+    """Everything oracle_reduce reports for one sample."""
+    __slots__ = ("piv", "keep", "c", "S", "Y", "pos_out", "piv_gap", "stage_last",
+                 "stage_next", "stage_gap")
+
+
+def reduce(X: np.ndarray, dtype: int, P: int, K: int, pos: Optional[np.ndarray] = None,
+           crit: Optional[np.ndarray] = None, mode: int = MAX_L1, want_scores: bool = True,
+           want_rows: bool = True) -> Reduced:
+    n, d, ld = _check_rows(X, dtype)
+    cd = cld = 0
+    if crit is not None:
+        cn, cd, cld = _check_rows(crit, dtype)
+        assert cn == n
+    r = Reduced()
+    r.piv = np.empty(P, dtype=np.int32)
+    r.keep = np.empty(K, dtype=np.int32)
+    r.c = np.empty(n, dtype=np.float64)
+    r.S = np.empty((P, n), dtype=np.float64) if want_scores else None
+    r.Y = np.empty((K, d), dtype=X.dtype) if want_rows else None
+    r.pos_out = None
+    if pos is not None:
+        pos = np.ascontiguousarray(pos, dtype=np.int64)
+        if want_rows:
+            r.pos_out = np.empty(K, dtype=np.int64)
+    r.piv_gap = np.empty(P, dtype=np.float64)
+    r.stage_last = np.empty(P, dtype=np.int32)
+    r.stage_next = np.empty(P, dtype=np.int32)
+    r.stage_gap = np.empty(P, dtype=np.float64)
+    rc = lib().oracle_reduce(_p(X), dtype, n, d, ld, _p(crit), cd, cld, _p(pos), P, K, mode,
+                             _p(r.piv), _p(r.keep), _p(r.c), _p(r.S), _p(r.Y), _p(r.pos_out),
+                             _p(r.piv_gap), _p(r.stage_last), _p(r.stage_next), _p(r.stage_gap))
+    if rc != 0:
+        raise ValueError(f"oracle_reduce failed rc={rc} (P={P}, K={K}, N={n})")
+    return r
+
+
+def admissible(X: np.ndarray, r: Reduced, rel: float = 1e-9) -> bool:
+    """True if every decision the oracle took is safe from fp64 rounding: each
+    margin (between consecutive pivots' norms, and between the last token taken
+    and the first one refused at every stage) is either clearly non-zero, or an
+    exact tie between two rows that are bit-identical (then the lowest index is
+    the true answer)."""
+    P = r.piv.shape[0]
+    ranked = list(r.piv)
+    for i in range(P):
+        g = r.piv_gap[i]
+        if np.isinf(g) or g > rel * abs(r.c[ranked[i]]):
+            continue
+        if g == 0.0 and i + 1 < P and np.array_equal(X[ranked[i]], X[ranked[i + 1]]):
+            continue
+        if g == 0.0 and i + 1 == P:
+            # the rival is not a pivot: find it by its norm and compare rows
+            rivals = [j for j in np.flatnonzero(r.c == r.c[ranked[i]]) if j not in ranked]
+            if rivals and all(np.array_equal(X[ranked[i]], X[j]) for j in rivals):
+                continue
+        return False
+    for i in range(P):
+        g = r.stage_gap[i]
+        if np.isinf(g) or g > rel:
+            continue
+        if g == 0.0 and np.array_equal(X[r.stage_last[i]], X[r.stage_next[i]]):
+            continue
+        return False
+    return True

@@ -1,0 +1,205 @@
+// CPU oracle for the duplication-aware token reduction step of DART
+// (arXiv 2502.11494, Section 3.3).
+//
+// THIS IS TEST INFRASTRUCTURE, not part of the product.  It is the yardstick the
+// GPU library is compared with: plain loops, fp64 arithmetic, one sample at a
+// time, nothing blocked, fused or reordered.  Only the test-suite, the smoke
+// check and the benchmark's CPU-baseline leg may call it.  It shares no code
+// with the GPU path.
+//
+// The method is a heuristic, so the oracle is the algorithm taken step by step:
+//   1. criterion c_j = L1 norm of token j's criterion row        (Sec. 3.3 footnote)
+//   2. pivots = the P tokens of largest c_j                       (Def. 1, Table 1 caption)
+//   3. dup(p_i, x_j) = <p_i, x_j> / (|p_i| |x_j|)                 (Def. 2, Eq. 7)
+//   4. R = pivots U_i R_i, with R_i the tokens of lowest dup(p_i, .) and the
+//      per-pivot threshold set by the reduction ratio             (Eq. 9-10)
+//   5. later layers see only the retained tokens, in order        (Appendix D)
+// Readings where the paper is silent (all listed in the design notes):
+//   * the budget K is split evenly over the pivots, q = floor((K-P)/P), the first
+//     (K-P) mod P pivots take one more; pivots are processed in rank order and a
+//     token retained earlier is no longer a candidate, so |R| = K exactly;
+//   * ties are broken towards the lowest token index, everywhere;
+//   * a zero-norm row scores 0 against everything;
+//   * the retained tokens keep their original order and their position ids.
+//
+// Parity status: every step below is pinned by closed forms, invariants, a
+// library cosine for P = 1 and brute-force enumeration on tiny inputs.  The
+// pipeline as a whole is "parity unpinned" against the paper's own numbers: the
+// paper prints no pivot list, score or retained set for any input.
+//
+// Threads: the two loops over tokens carry an OpenMP pragma; every token's
+// arithmetic is still one sequential fp64 loop, so results do not depend on the
+// thread count.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+enum { kF32 = 0, kBF16 = 1 };
+enum { kMaxL1 = 0, kMinL1 = 1 };
+
+// Exact widening of one stored element to double.
+inline double elem(const void* base, int dtype, int64_t idx) {
+  if (dtype == kBF16) {
+    uint32_t bits = static_cast<uint32_t>(static_cast<const uint16_t*>(base)[idx]) << 16;
+    float f;
+    std::memcpy(&f, &bits, sizeof f);
+    return static_cast<double>(f);
+  }
+  return static_cast<double>(static_cast<const float*>(base)[idx]);
+}
+
+inline size_t elem_size(int dtype) { return dtype == kBF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+// Number of threads the token loops use (0 = leave OpenMP's default). Returns the
+// count that will be used.
+int oracle_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+  return omp_get_max_threads();
+#else
+  (void)n;
+  return 1;
+#endif
+}
+
+// Step 1: c[j] = sum_d |C[j][d]|  (L1 norm; footnote of Sec. 3.3).
+void oracle_l1_norms(const void* C, int dtype, int64_t N, int64_t D, int64_t ld, double* c) {
+#pragma omp parallel for schedule(static)
+  for (int64_t j = 0; j < N; ++j) {
+    double s = 0.0;
+    for (int64_t d = 0; d < D; ++d) s += std::fabs(elem(C, dtype, j * ld + d));
+    c[j] = s;
+  }
+}
+
+// Step 2: the P tokens of largest criterion, ordered by (c descending, index
+// ascending); smallest first for mode kMinL1 (Table 8's "heart" rows).
+void oracle_select_pivots(const double* c, int64_t N, int P, int mode, int32_t* piv) {
+  std::vector<int32_t> order(N);
+  for (int64_t j = 0; j < N; ++j) order[j] = static_cast<int32_t>(j);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+    if (c[a] != c[b]) return mode == kMinL1 ? c[a] < c[b] : c[a] > c[b];
+    return a < b;
+  });
+  for (int i = 0; i < P; ++i) piv[i] = order[i];
+}
+
+// Step 3: S[i*N + j] = <x_piv[i], x_j> / (|x_piv[i]| * |x_j|), 0 if a norm is 0 (Eq. 7).
+void oracle_scores(const void* X, int dtype, int64_t N, int64_t D, int64_t ld,
+                   const int32_t* piv, int P, double* S) {
+  std::vector<double> norm(N);
+#pragma omp parallel for schedule(static)
+  for (int64_t j = 0; j < N; ++j) {
+    double s = 0.0;
+    for (int64_t d = 0; d < D; ++d) {
+      double v = elem(X, dtype, j * ld + d);
+      s += v * v;
+    }
+    norm[j] = std::sqrt(s);
+  }
+  for (int i = 0; i < P; ++i) {
+    const int64_t p = piv[i];
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+      double dot = 0.0;
+      for (int64_t d = 0; d < D; ++d) dot += elem(X, dtype, p * ld + d) * elem(X, dtype, j * ld + d);
+      double den = norm[p] * norm[j];
+      S[i * N + j] = den > 0.0 ? dot / den : 0.0;
+    }
+  }
+}
+
+// Step 4: the retained set (Eq. 9-10).  Returns 0, or -1 if P <= K <= N fails.
+// keep[K]: retained indices ascending.
+// Optional diagnostics, each of length P (pass NULL to skip): for stage i,
+//   stage_last[i]  = token taken last (highest score taken), -1 if the stage took none
+//   stage_next[i]  = best candidate NOT taken, -1 if none was left
+//   stage_gap[i]   = S[i][stage_next] - S[i][stage_last]  (+inf if either is missing)
+int oracle_retain(const double* S, int64_t N, const int32_t* piv, int P, int K, int32_t* keep,
+                  int32_t* stage_last, int32_t* stage_next, double* stage_gap) {
+  if (P < 1 || K < P || K > N) return -1;
+  std::vector<char> in_R(N, 0);
+  for (int i = 0; i < P; ++i) in_R[piv[i]] = 1;
+  const int m = K - P, q = m / P, r = m % P;
+  for (int i = 0; i < P; ++i) {
+    const int quota = q + (i < r ? 1 : 0);
+    std::vector<int32_t> cand;
+    for (int64_t j = 0; j < N; ++j)
+      if (!in_R[j]) cand.push_back(static_cast<int32_t>(j));
+    const double* s = S + static_cast<int64_t>(i) * N;
+    std::stable_sort(cand.begin(), cand.end(), [&](int32_t a, int32_t b) {
+      if (s[a] != s[b]) return s[a] < s[b];
+      return a < b;
+    });
+    for (int t = 0; t < quota; ++t) in_R[cand[t]] = 1;
+    const int32_t last = quota > 0 ? cand[quota - 1] : -1;
+    const int32_t next = quota < static_cast<int>(cand.size()) ? cand[quota] : -1;
+    if (stage_last) stage_last[i] = last;
+    if (stage_next) stage_next[i] = next;
+    if (stage_gap) stage_gap[i] = (last >= 0 && next >= 0) ? s[next] - s[last] : INFINITY;
+  }
+  int n = 0;
+  for (int64_t j = 0; j < N; ++j)
+    if (in_R[j]) keep[n++] = static_cast<int32_t>(j);
+  return n == K ? 0 : -2;
+}
+
+// Step 5: Y[r][:] = X[keep[r]][:] (bit copy, Y rows packed with stride D),
+// pos_out[r] = pos[keep[r]] (skipped when pos is NULL).
+void oracle_gather(const void* X, int dtype, int64_t D, int64_t ld, const int64_t* pos,
+                   const int32_t* keep, int K, void* Y, int64_t* pos_out) {
+  const size_t es = elem_size(dtype);
+  for (int r = 0; r < K; ++r) {
+    std::memcpy(static_cast<char*>(Y) + static_cast<size_t>(r) * D * es,
+                static_cast<const char*>(X) + static_cast<size_t>(keep[r]) * ld * es, D * es);
+    if (pos) pos_out[r] = pos[keep[r]];
+  }
+}
+
+// Steps 1-5 for one sample.  crit == NULL means the hidden-state rows are their
+// own criterion.  Optional outputs may be NULL: c [N], S [P*N], Y, pos_out,
+// piv_gap [P] (c[piv[i]] - c[next in rank], sign-corrected for kMinL1),
+// stage_last/stage_next/stage_gap [P] as in oracle_retain.
+int oracle_reduce(const void* X, int dtype, int64_t N, int64_t D, int64_t ld, const void* crit,
+                  int64_t crit_D, int64_t crit_ld, const int64_t* pos, int P, int K, int mode,
+                  int32_t* piv, int32_t* keep, double* c_out, double* S_out, void* Y,
+                  int64_t* pos_out, double* piv_gap, int32_t* stage_last, int32_t* stage_next,
+                  double* stage_gap) {
+  if (P < 1 || K < P || K > N) return -1;
+  std::vector<double> c(N);
+  if (crit)
+    oracle_l1_norms(crit, dtype, N, crit_D, crit_ld, c.data());
+  else
+    oracle_l1_norms(X, dtype, N, D, ld, c.data());
+  if (c_out) std::memcpy(c_out, c.data(), sizeof(double) * N);
+  // Rank P+1 tokens so that the margin behind the last pivot can be reported.
+  const int P1 = static_cast<int>(std::min<int64_t>(N, P + 1));
+  std::vector<int32_t> ranked(P1);
+  oracle_select_pivots(c.data(), N, P1, mode, ranked.data());
+  for (int i = 0; i < P; ++i) piv[i] = ranked[i];
+  if (piv_gap)
+    for (int i = 0; i < P; ++i)
+      piv_gap[i] = i + 1 < P1 ? std::fabs(c[ranked[i]] - c[ranked[i + 1]]) : INFINITY;
+  std::vector<double> S(static_cast<size_t>(P) * N);
+  oracle_scores(X, dtype, N, D, ld, piv, P, S.data());
+  if (S_out) std::memcpy(S_out, S.data(), sizeof(double) * S.size());
+  int rc = oracle_retain(S.data(), N, piv, P, K, keep, stage_last, stage_next, stage_gap);
+  if (rc != 0) return rc;
+  if (Y) oracle_gather(X, dtype, D, ld, pos, keep, K, Y, pos_out);
+  return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,172 @@
+"""Seeded synthetic inputs with the shapes of the paper's workloads.
+
+The paper's inputs (LLaVA-1.5 images with 576 vision tokens, LLaVA-Next
+multi-crop images with 2880, dynamic-resolution Qwen2-VL images, multi-frame
+video; Section 4 and Tables 1-6) need model weights and datasets.  These
+generators stand in for them: hidden states are clustered Gaussians, so that
+near-duplicate tokens abound the way they do after an early decoder layer.
+
+This module holds no arithmetic of the reduction method itself.  It only draws
+numbers; both the CPU oracle's tests and the GPU path's tests consume its
+arrays.  numpy only.
+
+bf16 tensors are returned as uint16 bit patterns (round-to-nearest-even of the
+fp32 value).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional
+
+import numpy as np
+
+F32 = 0
+BF16 = 1
+
+
+@dataclasses.dataclass
+class Workload:
+    """One batch for the reduction step.
+
+    X        [total_N, D] float32, or uint16 bit patterns when dtype == BF16
+    pos      [total_N] int64 position ids (0..N_b-1 inside every sample)
+    cu       [B+1] int32 row offsets of the samples (also given for dense)
+    ragged   True if the per-sample lengths differ (packed layout)
+    K        per-sample keep budget, or 0 when the ratio keep_num/keep_den rules
+    """
+    name: str
+    X: np.ndarray
+    pos: np.ndarray
+    cu: np.ndarray
+    dtype: int
+    B: int
+    D: int
+    P: int
+    K: int
+    keep_num: int
+    keep_den: int
+    ragged: bool
+
+    @property
+    def lengths(self) -> np.ndarray:
+        return np.diff(self.cu).astype(np.int64)
+
+    def budget(self, b: int) -> int:
+        n = int(self.cu[b + 1] - self.cu[b])
+        return self.K if self.K > 0 else (n * self.keep_num) // self.keep_den
+
+    def sample(self, b: int) -> np.ndarray:
+        return self.X[self.cu[b]:self.cu[b + 1]]
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bits."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _rng(seed: int, *stream: int) -> np.random.Generator:
+    return np.random.default_rng(np.random.SeedSequence([seed, *stream]))
+
+
+def clustered_tokens(rng: np.random.Generator, n: int, d: int, n_centroids: int,
+                     sigma: float) -> np.ndarray:
+    """n rows = unit-normal centroid (drawn uniformly among n_centroids) plus
+    N(0, sigma^2) noise; float32."""
+    cent = rng.standard_normal((n_centroids, d), dtype=np.float32)
+    which = rng.integers(0, n_centroids, size=n)
+    out = cent[which]
+    chunk = max(1, (1 << 24) // d)
+    for s in range(0, n, chunk):
+        e = min(n, s + chunk)
+        out[s:e] += np.float32(sigma) * rng.standard_normal((e - s, d), dtype=np.float32)
+    return out
+
+
+def _finish(name, rows: List[np.ndarray], dtype, P, K, keep_num=0, keep_den=1,
+            ragged=False) -> Workload:
+    lens = [r.shape[0] for r in rows]
+    cu = np.zeros(len(rows) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    D = rows[0].shape[1]
+    if dtype == BF16:
+        X = np.empty((int(cu[-1]), D), dtype=np.uint16)
+        for b, r in enumerate(rows):
+            X[cu[b]:cu[b + 1]] = f32_to_bf16_bits(r)
+    else:
+        X = np.ascontiguousarray(np.concatenate(rows, axis=0), dtype=np.float32)
+    pos = np.concatenate([np.arange(n, dtype=np.int64) for n in lens])
+    return Workload(name, X, pos, cu, dtype, len(rows), D, P, K, keep_num, keep_den, ragged)
+
+
+def single_image(seed: int = 0xDA270000, N: int = 576, D: int = 4096, P: int = 8,
+                 K: int = 64, n_centroids: int = 64, sigma: float = 0.05) -> Workload:
+    """One 576-token image, fp32 (LLaVA-1.5 token count, Table 1)."""
+    rows = [clustered_tokens(_rng(seed, 0), N, D, n_centroids, sigma)]
+    return _finish("single_image", rows, F32, P, K)
+
+
+def image_batch(seed: int = 0xDA270001, B: int = 16, N: int = 576, D: int = 4096, P: int = 8,
+                K: int = 64, n_centroids: int = 128, sigma: float = 0.1) -> Workload:
+    """Batch of 576-token images, bf16; budgets 64/128/192 are those of Table 1."""
+    rows = [clustered_tokens(_rng(seed, b), N, D, n_centroids, sigma) for b in range(B)]
+    return _finish("image_batch", rows, BF16, P, K)
+
+
+def multicrop_batch(seed: int = 0xDA270002, B: int = 8, N: int = 2880, D: int = 4096,
+                    P: int = 16, K: int = 320, n_centroids: int = 256, sigma: float = 0.1,
+                    copy_frac: float = 0.10) -> Workload:
+    """High-resolution multi-crop images (2880 tokens kept down to 320, Tables 2-3),
+    bf16, with a tenth of the tokens overwritten by bit-exact copies of others."""
+    rows = []
+    for b in range(B):
+        rng = _rng(seed, b)
+        x = clustered_tokens(rng, N, D, n_centroids, sigma)
+        n_copy = int(N * copy_frac)
+        perm = rng.permutation(N)
+        dst, pool = perm[:n_copy], perm[n_copy:]
+        src = pool[rng.integers(0, pool.shape[0], size=n_copy)]
+        x[dst] = x[src]
+        rows.append(x)
+    return _finish("multicrop_batch", rows, BF16, P, K)
+
+
+def ragged_batch(seed: int = 0xDA270003, B: int = 32, n_lo: int = 1024, n_hi: int = 16384,
+                 D: int = 3584, P: int = 16, keep_num: int = 111, keep_den: int = 1000,
+                 sigma: float = 0.1, lengths: Optional[List[int]] = None) -> Workload:
+    """Dynamic-resolution images of different token counts packed back to back
+    (Table 4's model family); N_b uniform in [n_lo, n_hi], N_b/16 centroids,
+    each sample keeps floor(11.1 %) of its tokens."""
+    if lengths is None:
+        lengths = [int(v) for v in _rng(seed, 1 << 20).integers(n_lo, n_hi + 1, size=B)]
+    rows = [clustered_tokens(_rng(seed, b), n, D, max(1, n // 16), sigma)
+            for b, n in enumerate(lengths)]
+    return _finish("ragged_batch", rows, BF16, P, 0, keep_num, keep_den, ragged=True)
+
+
+def video_batch(seed: int = 0xDA270004, B: int = 4, frames: int = 64, per_frame: int = 144,
+                D: int = 3584, P: int = 32, K: int = 1024, n_centroids: int = 16,
+                sigma: float = 0.1, drift: float = 0.02) -> Workload:
+    """Video: frame f = frame f-1 + N(0, drift^2), accumulated in fp32, so tokens
+    duplicate heavily across frames (Table 6's setting); token index f*per_frame+t."""
+    rows = []
+    for b in range(B):
+        rng = _rng(seed, b)
+        x = np.empty((frames * per_frame, D), dtype=np.float32)
+        cur = clustered_tokens(rng, per_frame, D, n_centroids, sigma)
+        x[:per_frame] = cur
+        for f in range(1, frames):
+            cur = cur + np.float32(drift) * rng.standard_normal((per_frame, D), dtype=np.float32)
+            x[f * per_frame:(f + 1) * per_frame] = cur
+        rows.append(x)
+    return _finish("video_batch", rows, BF16, P, K)
+
+
+def by_index(i: int, **kw) -> Workload:
+    """The five benchmark configurations, 0..4, at their full sizes by default."""
+    return [single_image, image_batch, multicrop_batch, ragged_batch, video_batch][i](**kw)

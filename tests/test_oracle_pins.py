@@ -1,0 +1,339 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests looks at the GPU library.  Each one is chosen so that a
+plausible mistake in oracle/dart_oracle.cpp (a dropped term, a wrong sign or
+index, transposed operands, a wrong tie rule) makes it fail.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2502_11494_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rows_f32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+
+
+# ----------------------------------------------------------------- norms / scores
+
+def test_l1_norm_closed_forms():
+    X = rows_f32([[1, -2, 3, 0], [0, 0, 0, 0], [-0.5, -0.25, 0, 8]])
+    np.testing.assert_array_equal(oracle.l1_norms(X, oracle.F32), [6.0, 0.0, 8.75])
+
+
+def test_l1_norm_uses_row_stride_and_width():
+    base = rows_f32(np.arange(24).reshape(4, 6))
+    view = base[:, :4]  # D = 4, ld = 6: the last two columns must be ignored
+    np.testing.assert_array_equal(oracle.l1_norms(view, oracle.F32), [6, 30, 54, 78])
+
+
+def test_bf16_widening_is_exact():
+    # 0x3FC0 = 1.5, 0xC000 = -2.0, 0x3E80 = 0.25, 0x0000 = 0
+    X = np.array([[0x3FC0, 0xC000, 0x3E80, 0x0000]], dtype=np.uint16)
+    assert oracle.l1_norms(X, oracle.BF16)[0] == 3.75
+    S = oracle.scores(np.vstack([X, X]), oracle.BF16, np.array([0], dtype=np.int32))
+    np.testing.assert_allclose(S, [[1.0, 1.0]], rtol=0, atol=2.3e-16)
+
+
+def test_cosine_closed_forms():
+    X = rows_f32([[3, 4, 0, 0], [4, 3, 0, 0], [0, 0, 5, 0], [-3, -4, 0, 0], [0, 0, 0, 0],
+                  [6, 8, 0, 0]])
+    S = oracle.scores(X, oracle.F32, np.array([0, 2], dtype=np.int32))
+    assert S.shape == (2, 6)
+    np.testing.assert_allclose(S[0], [1.0, 24 / 25, 0.0, -1.0, 0.0, 1.0], rtol=0, atol=2.3e-16)
+    np.testing.assert_allclose(S[1], [0.0, 0.0, 1.0, 0.0, 0.0, 0.0], rtol=0, atol=2.3e-16)
+    assert S[0, 4] == 0.0 and S[1, 4] == 0.0  # zero row: score 0, never NaN
+
+
+def test_score_layout_is_pivot_major():
+    # asymmetric case: pivot 0 = token 2, pivot 1 = token 0; a transposed or
+    # mis-indexed S would not reproduce these entries.
+    X = rows_f32([[1, 0, 0], [1, 1, 0], [0, 1, 0], [0, 1, 1]])
+    S = oracle.scores(X, oracle.F32, np.array([2, 0], dtype=np.int32))
+    r2 = 1 / np.sqrt(2)
+    np.testing.assert_allclose(S, [[0, r2, 1, r2], [1, r2, 0, 0]], rtol=0, atol=3e-16)
+
+
+def test_self_similarity_and_exact_copies():
+    w = W.multicrop_batch(B=1, N=96, D=256, P=4, K=16, n_centroids=8)
+    X = w.X
+    r = oracle.reduce(X, w.dtype, w.P, w.K)
+    for i, p in enumerate(r.piv):
+        assert abs(r.S[i, p] - 1.0) <= 2.3e-16
+    # bit-identical rows must get bit-identical scores (and an exact copy of a
+    # pivot the pivot's own self-score)
+    _, inv, cnt = np.unique(X, axis=0, return_inverse=True, return_counts=True)
+    assert cnt.max() > 1
+    for g in np.flatnonzero(cnt > 1):
+        members = np.flatnonzero(inv == g)
+        for j in members[1:]:
+            np.testing.assert_array_equal(r.S[:, j], r.S[:, members[0]])
+
+
+def test_scale_invariance_power_of_two():
+    rng = np.random.default_rng(7)
+    X = rng.standard_normal((40, 64)).astype(np.float32)
+    a = oracle.reduce(X, oracle.F32, 3, 12)
+    scale = np.ones((40, 1), dtype=np.float32)
+    scale[::3] = 8.0
+    scale[1::3] = 0.25
+    b = oracle.reduce(X * 4.0, oracle.F32, 3, 12)     # uniform scale: nothing may change
+    np.testing.assert_array_equal(a.piv, b.piv)
+    np.testing.assert_array_equal(a.keep, b.keep)
+    np.testing.assert_array_equal(a.S, b.S)
+    S_rowscaled = oracle.scores(X * scale, oracle.F32, a.piv)  # per-row scale: same scores
+    np.testing.assert_array_equal(a.S, S_rowscaled)
+
+
+def test_law_of_cosines_identity():
+    # |p - x|^2 = |p|^2 + |x|^2 - 2 dup |p| |x|  (first line of Lemma 1's proof)
+    rng = np.random.default_rng(11)
+    X = rng.standard_normal((30, 128)).astype(np.float32)
+    piv = np.array([4, 17], dtype=np.int32)
+    S = oracle.scores(X, oracle.F32, piv)
+    Xd = X.astype(np.float64)
+    for i, p in enumerate(piv):
+        lhs = ((Xd[p] - Xd) ** 2).sum(axis=1)
+        np_, nx = np.linalg.norm(Xd[p]), np.linalg.norm(Xd, axis=1)
+        rhs = np_ ** 2 + nx ** 2 - 2 * S[i] * np_ * nx
+        np.testing.assert_allclose(lhs, rhs, rtol=1e-12, atol=1e-12)
+
+
+def test_single_pivot_equals_library_cosine_and_argsort():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(3)
+    N, D, K = 200, 96, 37
+    X = rng.standard_normal((N, D)).astype(np.float32)
+    r = oracle.reduce(X, oracle.F32, 1, K)
+    c = np.abs(X.astype(np.float64)).sum(axis=1)
+    p = int(np.argmax(c))
+    assert r.piv[0] == p
+    Xt = torch.from_numpy(X).double()
+    cos = torch.nn.functional.cosine_similarity(Xt[p:p + 1], Xt, dim=1).numpy()
+    np.testing.assert_allclose(r.S[0], cos, rtol=1e-12, atol=1e-14)
+    order = [j for j in np.argsort(cos, kind="stable") if j != p][:K - 1]
+    np.testing.assert_array_equal(r.keep, np.sort(np.array(order + [p])))
+
+
+# ----------------------------------------------------------------- pivot selection
+
+def test_pivot_selection_bruteforce_and_ties():
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        N, P = int(rng.integers(1, 40)), 0
+        P = int(rng.integers(1, N + 1))
+        c = rng.integers(0, 6, size=N).astype(np.float64)  # many ties
+        got = oracle.select_pivots(c, P)
+        want = sorted(range(N), key=lambda j: (-c[j], j))[:P]
+        np.testing.assert_array_equal(got, want)
+        got_min = oracle.select_pivots(c, P, oracle.MIN_L1)
+        want_min = sorted(range(N), key=lambda j: (c[j], j))[:P]
+        np.testing.assert_array_equal(got_min, want_min)
+
+
+def test_pivot_invariants_on_workload():
+    w = W.image_batch(B=2, N=144, D=512, P=8, K=32, n_centroids=16)
+    for b in range(w.B):
+        X = w.sample(b)
+        r = oracle.reduce(X, w.dtype, w.P, w.K)
+        assert len(set(r.piv.tolist())) == w.P
+        cp = r.c[r.piv]
+        assert np.all(cp[:-1] >= cp[1:])
+        rest = np.setdiff1d(np.arange(X.shape[0]), r.piv)
+        assert np.all(r.c[rest] <= cp[-1])
+        np.testing.assert_array_equal(
+            r.c, np.abs(W.bf16_bits_to_f32(X).astype(np.float64)).sum(axis=1))
+
+
+def test_separate_criterion_rows_drive_the_pivots_only():
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((50, 32)).astype(np.float32)
+    crit = rng.standard_normal((50, 8)).astype(np.float32)
+    r = oracle.reduce(X, oracle.F32, 4, 12, crit=crit)
+    c = np.abs(crit.astype(np.float64)).sum(axis=1)
+    np.testing.assert_array_equal(r.piv, sorted(range(50), key=lambda j: (-c[j], j))[:4])
+    np.testing.assert_array_equal(r.S, oracle.scores(X, oracle.F32, r.piv))
+
+
+# ----------------------------------------------------------------- retained set
+
+def _stagewise_reference(S, piv, K):
+    """Independent restatement with Python sorts: used only on small inputs."""
+    P, N = S.shape
+    R = set(int(p) for p in piv)
+    m = K - P
+    stages = []
+    for i in range(P):
+        q = m // P + (1 if i < m % P else 0)
+        cand = sorted((j for j in range(N) if j not in R), key=lambda j: (S[i, j], j))
+        stages.append((cand[:q], cand[q:]))
+        R.update(cand[:q])
+    return sorted(R), stages
+
+
+def test_paper_budgets_divide_evenly():
+    with open(os.path.join(GOLDEN, "paper_budgets.txt")) as f:
+        rows = [tuple(map(int, l.split())) for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    rng = np.random.default_rng(0)
+    for N, P, K, quota in rows:
+        assert (K - P) % P == 0 and (K - P) // P == quota
+        S = rng.standard_normal((P, N))
+        piv = rng.permutation(N)[:P].astype(np.int32)
+        keep, last, nxt, gap = oracle.retain(S, piv, K, diagnostics=True)
+        assert keep.shape[0] == K  # retained count equals the budget (Table 2, KV cache)
+        # every stage took exactly `quota` tokens: the stage's taken set is the
+        # `quota` lowest not-yet-retained scores
+        ref, stages = _stagewise_reference(S, piv, K)
+        assert all(len(t) == quota for t, _ in stages)
+        np.testing.assert_array_equal(keep, ref)
+
+
+def test_retain_invariants_and_threshold():
+    rng = np.random.default_rng(21)
+    for trial in range(30):
+        N = int(rng.integers(4, 120))
+        P = int(rng.integers(1, min(N, 9) + 1))
+        K = int(rng.integers(P, N + 1))
+        S = np.round(rng.standard_normal((P, N)), 1)  # coarse grid: plenty of ties
+        piv = rng.permutation(N)[:P].astype(np.int32)
+        keep, last, nxt, gap = oracle.retain(S, piv, K, diagnostics=True)
+        assert keep.shape[0] == K
+        assert np.all(np.diff(keep) > 0)
+        assert set(piv.tolist()) <= set(keep.tolist())
+        ref, stages = _stagewise_reference(S, piv, K)
+        np.testing.assert_array_equal(keep, ref)
+        pruned = np.setdiff1d(np.arange(N), keep)
+        for i, (taken, refused) in enumerate(stages):
+            if not taken:
+                assert last[i] == -1
+                continue
+            key_last = (S[i, taken[-1]], taken[-1])
+            assert last[i] == taken[-1]
+            # Eq. 9 read with a per-pivot threshold: whatever ends up pruned lies
+            # strictly above the stage's last taken key, for every stage
+            for j in pruned:
+                assert (S[i, j], j) > key_last
+            if refused:
+                assert nxt[i] == refused[0]
+                assert gap[i] == S[i, refused[0]] - S[i, taken[-1]]
+
+
+def test_retain_bruteforce_subsets_tiny():
+    # Each stage must pick, among all q-subsets of its candidates, the one of
+    # minimum total score (the top-k form of Eq. 4 with the order reversed),
+    # and the lexicographically smallest index set among equal minima.
+    rng = np.random.default_rng(33)
+    for trial in range(40):
+        N = int(rng.integers(3, 11))
+        P = int(rng.integers(1, 4))
+        if P > N:
+            continue
+        K = int(rng.integers(P, N + 1))
+        if trial % 2:
+            S = rng.integers(-2, 3, size=(P, N)).astype(np.float64) / 4.0  # exact sums, ties
+        else:
+            S = rng.standard_normal((P, N))
+        piv = rng.permutation(N)[:P].astype(np.int32)
+        keep = oracle.retain(S, piv, K)
+        R = set(piv.tolist())
+        m = K - P
+        for i in range(P):
+            q = m // P + (1 if i < m % P else 0)
+            cand = [j for j in range(N) if j not in R]
+            best = min(itertools.combinations(cand, q),
+                       key=lambda T: (sum(S[i, j] for j in T), T))
+            # what the oracle took at this stage = keep minus what was and will be known
+            R_after = R | set(best)
+            R = R_after
+        np.testing.assert_array_equal(keep, sorted(R))
+
+
+def test_retain_permutation_equivariance():
+    rng = np.random.default_rng(44)
+    N, P, K = 60, 4, 20
+    S = rng.standard_normal((P, N))  # all keys distinct
+    piv = np.array([5, 17, 30, 42], dtype=np.int32)
+    keep = oracle.retain(S, piv, K)
+    perm = rng.permutation(N)          # new index of old token j is where j lands
+    inv = np.empty(N, dtype=np.int64)
+    inv[perm] = np.arange(N)           # token at new position t is old perm[t]
+    S2 = S[:, perm]
+    piv2 = inv[piv].astype(np.int32)
+    keep2 = oracle.retain(S2, piv2, K)
+    np.testing.assert_array_equal(np.sort(perm[keep2]), keep)
+
+
+def test_retain_rejects_bad_budget():
+    S = np.zeros((2, 5))
+    piv = np.array([0, 1], dtype=np.int32)
+    with pytest.raises(ValueError):
+        oracle.retain(S, piv, 1)
+    with pytest.raises(ValueError):
+        oracle.retain(S, piv, 6)
+    np.testing.assert_array_equal(oracle.retain(S, piv, 2), [0, 1])       # K == P: pivots only
+    np.testing.assert_array_equal(oracle.retain(S, piv, 5), [0, 1, 2, 3, 4])  # K == N: everything
+
+
+def test_remainder_goes_to_the_first_pivots():
+    # K - P = 5 over P = 3 pivots: quotas 2, 2, 1
+    S = np.array([[9, 9, 9, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7],
+                  [9, 9, 9, 0.7, 0.6, 0.5, 0.4, 0.3, 0.2, 0.1],
+                  [9, 9, 9, 0.5, 0.5, 0.5, 0.5, 0.5, 0.5, 0.5]], dtype=np.float64)
+    piv = np.array([0, 1, 2], dtype=np.int32)
+    keep = oracle.retain(S, piv, 8)
+    # stage 0 takes 3,4; stage 1 takes 9,8; stage 2 takes the lowest index left at 0.5 -> 5
+    np.testing.assert_array_equal(keep, [0, 1, 2, 3, 4, 5, 8, 9])
+
+
+def test_duplicate_of_a_pivot_is_never_its_own_stage_pick():
+    # an exact copy of the pivot has the maximal score 1 against it
+    rng = np.random.default_rng(2)
+    X = rng.standard_normal((24, 16)).astype(np.float32)
+    c = np.abs(X).sum(axis=1)
+    p = int(np.argmax(c))
+    dup = (p + 5) % 24
+    X[dup] = X[p]
+    r = oracle.reduce(X, oracle.F32, 1, 23)
+    assert r.piv[0] == min(p, dup)
+    assert r.S[0, dup] == r.S[0, p] and abs(r.S[0, p] - 1.0) < 3e-16
+    assert np.max(r.S) == r.S[0, p]
+    missing = np.setdiff1d(np.arange(24), r.keep)
+    assert missing.tolist() == [max(p, dup)]  # the one pruned token is the duplicate
+
+
+# ----------------------------------------------------------------- gather
+
+def test_gather_is_a_byte_copy_in_original_order():
+    w = W.image_batch(B=1, N=64, D=40, P=2, K=9, n_centroids=4)
+    X = np.ascontiguousarray(np.pad(w.X, ((0, 0), (0, 8))))[:, :40]  # ld = 48 > D = 40
+    pos = (np.arange(64, dtype=np.int64) * 7 + 3)
+    keep = np.array([1, 5, 6, 20, 63], dtype=np.int32)
+    Y, pos_out = oracle.gather(X, oracle.BF16, pos, keep)
+    assert Y.tobytes() == np.ascontiguousarray(X[keep]).tobytes()
+    np.testing.assert_array_equal(pos_out, pos[keep])
+
+
+def test_reduce_outputs_are_consistent():
+    w = W.single_image(N=72, D=128, P=3, K=17, n_centroids=6)
+    r = oracle.reduce(w.X, w.dtype, w.P, w.K, pos=w.pos)
+    np.testing.assert_array_equal(r.keep, oracle.retain(r.S, r.piv, w.K))
+    assert r.Y.tobytes() == w.X[r.keep].tobytes()
+    np.testing.assert_array_equal(r.pos_out, w.pos[r.keep])
+    assert oracle.admissible(w.X, r)
+
+
+def test_thread_count_does_not_change_results():
+    w = W.image_batch(B=1, N=96, D=256, P=4, K=24, n_centroids=8)
+    oracle.set_threads(1)
+    a = oracle.reduce(w.X, w.dtype, w.P, w.K)
+    oracle.set_threads(4)
+    b = oracle.reduce(w.X, w.dtype, w.P, w.K)
+    np.testing.assert_array_equal(a.S, b.S)
+    np.testing.assert_array_equal(a.keep, b.keep)
