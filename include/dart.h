@@ -42,7 +42,7 @@
  * Determinism.  Same inputs give bit-identical outputs, call after call, and a
  *   row's score depends only on its bytes and the pivot's bytes, not on where
  *   the row sits in the batch.
- * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N < 2^31 / 64.
+ * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N <= 2^27.
  */
 #ifndef DART_H_
 #define DART_H_
@@ -52,6 +52,12 @@
 
 #ifdef __cplusplus
 extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define DART_API __attribute__((visibility("default")))
+#else
+#define DART_API
 #endif
 
 typedef enum dart_status {
@@ -96,7 +102,7 @@ typedef struct dart_desc {
 
 /* Bytes of workspace every entry point below accepts for this descriptor
  * (host arithmetic only; 0 if the descriptor is invalid). */
-size_t dart_workspace_bytes(const dart_desc* desc);
+DART_API size_t dart_workspace_bytes(const dart_desc* desc);
 
 /* (a) Pivot selection -- Definition 1 with the max-L1-norm criterion of the
  * Table 1 caption.  crit: criterion rows [total_N, crit_D] with row stride
@@ -108,7 +114,7 @@ size_t dart_workspace_bytes(const dart_desc* desc);
  * reach the top P within the rounding bound is re-evaluated in fp64, so the
  * order is that of the exact norms.  l1_out (optional, float[total_N]) receives
  * the fp32 L1 norm of every criterion row. */
-dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,
+DART_API dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,
                                int32_t crit_D, int64_t crit_ld, int32_t* piv, float* l1_out,
                                void* ws, size_t ws_bytes, void* stream);
 
@@ -119,7 +125,7 @@ dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void*
  * bf16 inputs: exact bf16 products, fp32 matrix-core accumulation over 256
  * elements at a time, fp64 across; fp32 inputs: fp64 throughout.  The stored
  * value is rounded to fp32. */
-dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
+DART_API dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
                                     float* S, void* ws, size_t ws_bytes, void* stream);
 
 /* (c) Retained set -- Eq. (9)-(10).  R starts as the pivots; with m = K_b - P,
@@ -131,7 +137,7 @@ dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const 
  * decision boundary are closer than the rounding bound of
  * dart_duplication_scores, the candidates involved are re-scored in fp64 from
  * the rows of X before deciding. */
-dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t* piv,
+DART_API dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t* piv,
                            const void* X, int32_t* keep, int32_t* cu_keep, void* ws,
                            size_t ws_bytes, void* stream);
 
@@ -139,13 +145,13 @@ dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t*
  * r < K_b: Y[cu_keep[b]+r][:] = X[row0(b)+keep[cu_keep[b]+r]][:] (D elements,
  * bit copy, Y rows densely packed with stride D) and
  * pos_out[cu_keep[b]+r] = pos[row0(b)+keep[...]].  pos/pos_out may both be NULL. */
-dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int64_t* pos,
+DART_API dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int64_t* pos,
                                 const int32_t* keep, void* Y, int64_t* pos_out, void* ws,
                                 size_t ws_bytes, void* stream);
 
 /* (a)-(d) in one call.  Optional outputs (NULL to skip): pos/pos_out, cu_keep,
  * piv_out [B*P], S_out [P*total_N]. */
-dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
+DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
                         void* ws, size_t ws_bytes, void* stream);
@@ -154,7 +160,7 @@ dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, 
  * events is a HOST array of 7 hipEvent_t (as void*); events[k] is recorded
  * before kernel stage k (0 row norms, 1 pivot selection, 2 scores, 3 score
  * ordering, 4 retained set, 5 compaction) and events[6] after the last. */
-dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const void* crit,
+DART_API dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const void* crit,
                                  int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
                                  int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
                                  int32_t* piv_out, float* S_out, void* ws, size_t ws_bytes,
@@ -162,14 +168,14 @@ dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const voi
 
 /* Waits for `stream`, then reports DART_ERR_DEVICE if the last call that used
  * `ws` skipped a ragged sample (see Errors), DART_OK otherwise. */
-dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream);
+DART_API dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream);
 
 /* The absolute bound on |fp32 score - exact score| that dart_topk_keep and
  * dart_reduce certify decisions against, for this dtype. */
-double dart_score_tolerance(int32_t dtype);
+DART_API double dart_score_tolerance(int32_t dtype);
 
 /* Static, NUL-terminated description of a status code. */
-const char* dart_strerror(dart_status status);
+DART_API const char* dart_strerror(dart_status status);
 
 #ifdef __cplusplus
 }

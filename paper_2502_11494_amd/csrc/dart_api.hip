@@ -1,0 +1,410 @@
+// Host side of the DART C ABI (include/dart.h): argument checks, workspace
+// carving and kernel launches.  No allocation, no synchronisation except in
+// dart_device_status.
+#include <hip/hip_runtime.h>
+
+#include "../../include/dart.h"
+#include "common.hpp"
+#include "k_misc.hpp"
+#include "k_norms.hpp"
+#include "k_order.hpp"
+#include "k_pivots.hpp"
+#include "k_retain.hpp"
+#include "k_scores.hpp"
+
+using namespace dart;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  Geo g;
+  int esz;
+  long keep_rows_bound;  // upper bound of the total number of retained rows
+  int tiles_bound;       // upper bound of the number of 64-row score tiles
+  // workspace offsets
+  size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_idx,
+      o_scr_f64, total;
+};
+
+dart_status make_plan(const dart_desc* d, Plan& p) {
+  if (!d) return DART_ERR_NULL;
+  if (d->dtype != DART_F32 && d->dtype != DART_BF16) return DART_ERR_DTYPE;
+  if (d->pivot_mode != DART_PIVOT_MAX_L1 && d->pivot_mode != DART_PIVOT_MIN_L1)
+    return DART_ERR_DTYPE;
+  if (d->B < 0 || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
+      d->reserved != 0)
+    return DART_ERR_SHAPE;
+  const bool ragged = d->cu_seqlens != nullptr;
+  long total;
+  int maxn;
+  if (!ragged) {
+    if (d->N < 0 || d->N > kMaxN) return DART_ERR_SHAPE;
+    total = (long)d->B * d->N;
+    if (d->total_N != 0 && d->total_N != total) return DART_ERR_SHAPE;
+    maxn = d->N;
+  } else {
+    if (d->total_N < 0 || d->max_N < 1 || d->max_N > kMaxN) return DART_ERR_SHAPE;
+    total = d->total_N;
+    maxn = d->max_N;
+  }
+  if (total > (1L << 27)) return DART_ERR_SHAPE;
+  if (d->K < 0) return DART_ERR_BUDGET;
+  if (d->K == 0 && (d->keep_den <= 0 || d->keep_num < 0 || d->keep_num > d->keep_den))
+    return DART_ERR_BUDGET;
+  int K = d->K;
+  if (!ragged) {
+    if (K == 0) K = (int)(((long)d->N * d->keep_num) / d->keep_den);
+    if (d->B > 0 && (d->P > d->N || K < d->P || K > d->N)) return DART_ERR_BUDGET;
+  } else if (K > 0 && (K < d->P || K > maxn)) {
+    return DART_ERR_BUDGET;
+  }
+  const int esz = d->dtype == DART_BF16 ? 2 : 4;
+  if (((long)d->ld * esz) % 16 != 0 || ((long)d->D * esz) % 16 != 0) return DART_ERR_ALIGN;
+
+  Geo& g = p.g;
+  g.B = d->B;
+  g.D = d->D;
+  g.P = d->P;
+  g.Ppad = (d->P + 15) / 16 * 16;
+  g.N = ragged ? 0 : d->N;
+  g.total_N = (int)total;
+  g.max_N = maxn;
+  g.K = ragged ? d->K : K;
+  g.keep_num = d->keep_num;
+  g.keep_den = d->keep_den > 0 ? d->keep_den : 1;
+  g.dtype = d->dtype;
+  g.mode = d->pivot_mode;
+  g.ld = d->ld;
+  g.cu = d->cu_seqlens;
+  g.cu_keep = nullptr;
+  g.tile_start = nullptr;
+  p.esz = esz;
+  if (!ragged) {
+    p.keep_rows_bound = (long)d->B * K;
+    p.tiles_bound = d->B * ((d->N + kTileRows - 1) / kTileRows);
+  } else {
+    p.keep_rows_bound = d->K > 0 ? (long)d->B * d->K
+                                 : (long)(((__int128)total * d->keep_num) / g.keep_den);
+    if (p.keep_rows_bound > total) p.keep_rows_bound = total;
+    p.tiles_bound = (int)(total / kTileRows) + d->B;
+  }
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
+  p.o_status = take(kAlign);
+  p.o_cu_keep = take(sizeof(int) * ((size_t)d->B + 1));
+  p.o_tile_start = take(sizeof(int) * ((size_t)d->B + 1));
+  p.o_l1 = take(sizeof(float) * (size_t)total);
+  p.o_piv = take(sizeof(int) * (size_t)d->B * d->P);
+  p.o_pl2 = take(sizeof(double) * (size_t)d->B * g.Ppad);
+  p.o_S = take(sizeof(float) * (size_t)total * d->P);
+  p.o_lists = take(sizeof(unsigned long long) * (size_t)total * d->P);
+  p.o_scr_idx = take(sizeof(int) * (size_t)total);
+  p.o_scr_f64 = take(sizeof(double) * 2 * (size_t)total);
+  p.total = o;
+  return DART_OK;
+}
+
+inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+dart_status check_ws(const Plan& p, const void* ws, size_t ws_bytes) {
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0 || ws_bytes < p.total)
+    return DART_ERR_WORKSPACE;
+  return DART_OK;
+}
+
+template <typename T>
+inline T* at(void* ws, size_t off) {
+  return reinterpret_cast<T*>(static_cast<unsigned char*>(ws) + off);
+}
+
+#define DART_LAUNCH_CHECK()                              \
+  do {                                                   \
+    if (hipGetLastError() != hipSuccess) return DART_ERR_HIP; \
+  } while (0)
+
+// Fills the ragged offsets (no-op for dense batches) and points g at them.
+dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
+  if (p.g.cu == nullptr) return DART_OK;
+  int* cu_keep = at<int>(ws, p.o_cu_keep);
+  int* tile_start = at<int>(ws, p.o_tile_start);
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1024), 0, st, p.g, cu_keep, tile_start,
+                     at<int>(ws, p.o_status));
+  DART_LAUNCH_CHECK();
+  p.g.cu_keep = cu_keep;
+  p.g.tile_start = tile_start;
+  return DART_OK;
+}
+
+dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float* l1,
+                          hipStream_t st) {
+  constexpr int ROWS = 2;
+  const int rows = p.g.total_N;
+  if (rows == 0) return DART_OK;
+  const int blocks = (rows + 4 * ROWS - 1) / (4 * ROWS);
+  if (p.g.dtype == kBF16)
+    hipLaunchKernelGGL((k_row_l1<kBF16, ROWS>), dim3(blocks), dim3(256), 0, st, C, Dc, ldc, rows,
+                       l1);
+  else
+    hipLaunchKernelGGL((k_row_l1<kF32, ROWS>), dim3(blocks), dim3(256), 0, st, C, Dc, ldc, rows,
+                       l1);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, int Dc, long ldc,
+                                 const float* l1, int* piv, void* ws, hipStream_t st) {
+  const float tau = (float)l1_rel_bound(p.g.dtype, Dc);
+  double* pl2 = at<double>(ws, p.o_pl2);
+  double* scr = at<double>(ws, p.o_scr_f64);
+  if (p.g.dtype == kBF16)
+    hipLaunchKernelGGL((k_select_pivots<kBF16>), dim3(p.g.B), dim3(kSelThreads), 0, st, p.g, X, C,
+                       Dc, ldc, l1, piv, pl2, scr, tau);
+  else
+    hipLaunchKernelGGL((k_select_pivots<kF32>), dim3(p.g.B), dim3(kSelThreads), 0, st, p.g, X, C,
+                       Dc, ldc, l1, piv, pl2, scr, tau);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
+                          hipStream_t st) {
+  if (p.tiles_bound == 0) return DART_OK;
+  const double* pl2 = at<double>(ws, p.o_pl2);
+  if (p.g.dtype == kF32) {
+    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * 4), dim3(256), 0, st, p.g, X, piv, S);
+  } else {
+    const dim3 grid(p.tiles_bound), block(256);
+    switch (p.g.Ppad / 16) {
+      case 1: hipLaunchKernelGGL((k_scores_bf16<1>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 2: hipLaunchKernelGGL((k_scores_bf16<2>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 3: hipLaunchKernelGGL((k_scores_bf16<3>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      default: hipLaunchKernelGGL((k_scores_bf16<4>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+    }
+  }
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st) {
+  hipLaunchKernelGGL(k_order_scores, dim3(p.g.B * p.g.P), dim3(kSelThreads), 0, st, p.g, S,
+                     at<unsigned long long>(ws, p.o_lists));
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+dart_status launch_retain(const Plan& p, const float* S, const int* piv, const void* X, int* keep,
+                          int* cu_keep, void* ws, hipStream_t st) {
+  const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype));
+  const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
+  int* scr_idx = at<int>(ws, p.o_scr_idx);
+  double* scr_f64 = at<double>(ws, p.o_scr_f64);
+  if (p.g.dtype == kBF16)
+    hipLaunchKernelGGL((k_retain<kBF16>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,
+                       piv, X, keep, cu_keep, scr_idx, scr_f64, two_tau);
+  else
+    hipLaunchKernelGGL((k_retain<kF32>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists, piv,
+                       X, keep, cu_keep, scr_idx, scr_f64, two_tau);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, const int* keep,
+                          void* Y, int64_t* pos_out, hipStream_t st) {
+  if (p.keep_rows_bound == 0) return DART_OK;
+  const int blocks = (int)((p.keep_rows_bound + 3) / 4);
+  hipLaunchKernelGGL(k_gather, dim3(blocks), dim3(256), 0, st, p.g, p.esz, X,
+                     reinterpret_cast<const long long*>(pos), keep, Y,
+                     reinterpret_cast<long long*>(pos_out));
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+#define DART_TRY(expr)                    \
+  do {                                    \
+    dart_status _s = (expr);              \
+    if (_s != DART_OK) return _s;         \
+  } while (0)
+
+dart_status check_crit(const Plan& p, const void* X, const void*& crit, int32_t& crit_D,
+                       int64_t& crit_ld) {
+  if (!crit) {
+    crit = X;
+    crit_D = p.g.D;
+    crit_ld = p.g.ld;
+    return DART_OK;
+  }
+  if (crit_D <= 0 || crit_D > 65536 || crit_ld < crit_D) return DART_ERR_SHAPE;
+  if (misaligned16(crit) || (crit_ld * p.esz) % 16 != 0 || ((long)crit_D * p.esz) % 16 != 0)
+    return DART_ERR_ALIGN;
+  return DART_OK;
+}
+
+dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
+                        int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
+                        int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out, void* ws,
+                        size_t ws_bytes, void* stream, void* const* events) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.g.B == 0) return DART_OK;
+  if (!X || !Y || !keep || (pos != nullptr) != (pos_out != nullptr)) return DART_ERR_NULL;
+  if (misaligned16(X) || misaligned16(Y)) return DART_ERR_ALIGN;
+  DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  auto mark = [&](int k) -> dart_status {
+    if (events && hipEventRecord(static_cast<hipEvent_t>(events[k]), st) != hipSuccess)
+      return DART_ERR_HIP;
+    return DART_OK;
+  };
+  int* piv = piv_out ? piv_out : at<int>(ws, p.o_piv);
+  float* S = S_out ? S_out : at<float>(ws, p.o_S);
+  float* l1 = at<float>(ws, p.o_l1);
+  DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(mark(0));
+  DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, st));
+  DART_TRY(mark(1));
+  DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+  DART_TRY(mark(2));
+  DART_TRY(launch_scores(p, X, piv, S, ws, st));
+  DART_TRY(mark(3));
+  DART_TRY(launch_order(p, S, ws, st));
+  DART_TRY(mark(4));
+  DART_TRY(launch_retain(p, S, piv, X, keep, cu_keep, ws, st));
+  DART_TRY(mark(5));
+  DART_TRY(launch_gather(p, X, pos, keep, Y, pos_out, st));
+  DART_TRY(mark(6));
+  return DART_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dart_workspace_bytes(const dart_desc* desc) {
+  Plan p;
+  if (make_plan(desc, p) != DART_OK) return 0;
+  return p.total;
+}
+
+dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,
+                               int32_t crit_D, int64_t crit_ld, int32_t* piv, float* l1_out,
+                               void* ws, size_t ws_bytes, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.g.B == 0) return DART_OK;
+  if (!X || !piv) return DART_ERR_NULL;
+  if (misaligned16(X)) return DART_ERR_ALIGN;
+  DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* l1 = l1_out ? l1_out : at<float>(ws, p.o_l1);
+  DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, st));
+  return launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st);
+}
+
+dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
+                                    float* S, void* ws, size_t ws_bytes, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.g.B == 0) return DART_OK;
+  if (!X || !piv || !S) return DART_ERR_NULL;
+  if (misaligned16(X)) return DART_ERR_ALIGN;
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DART_TRY(launch_prepare(p, ws, st));
+  double* pl2 = at<double>(ws, p.o_pl2);
+  if (p.g.dtype == kBF16)
+    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+  else
+    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+  DART_LAUNCH_CHECK();
+  return launch_scores(p, X, piv, S, ws, st);
+}
+
+dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t* piv,
+                           const void* X, int32_t* keep, int32_t* cu_keep, void* ws,
+                           size_t ws_bytes, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.g.B == 0) return DART_OK;
+  if (!S || !piv || !keep) return DART_ERR_NULL;
+  if (X && misaligned16(X)) return DART_ERR_ALIGN;
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_order(p, S, ws, st));
+  return launch_retain(p, S, piv, X, keep, cu_keep, ws, st);
+}
+
+dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int64_t* pos,
+                                const int32_t* keep, void* Y, int64_t* pos_out, void* ws,
+                                size_t ws_bytes, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.g.B == 0) return DART_OK;
+  if (!X || !keep || !Y || (pos != nullptr) != (pos_out != nullptr)) return DART_ERR_NULL;
+  if (misaligned16(X) || misaligned16(Y)) return DART_ERR_ALIGN;
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DART_TRY(launch_prepare(p, ws, st));
+  return launch_gather(p, X, pos, keep, Y, pos_out, st);
+}
+
+dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
+                        int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
+                        int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out, void* ws,
+                        size_t ws_bytes, void* stream) {
+  return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
+                     S_out, ws, ws_bytes, stream, nullptr);
+}
+
+dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const void* crit,
+                                 int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
+                                 int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                                 int32_t* piv_out, float* S_out, void* ws, size_t ws_bytes,
+                                 void* stream, void* const* events) {
+  if (!events) return DART_ERR_NULL;
+  for (int k = 0; k < 7; ++k)
+    if (!events[k]) return DART_ERR_NULL;
+  return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
+                     S_out, ws, ws_bytes, stream, events);
+}
+
+dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (!ws) return DART_ERR_WORKSPACE;
+  if (p.g.B == 0 || p.g.cu == nullptr) return DART_OK;
+  int flag = 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&flag, static_cast<const unsigned char*>(ws) + p.o_status, sizeof(int),
+                     hipMemcpyDeviceToHost, st) != hipSuccess)
+    return DART_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return DART_ERR_HIP;
+  return flag ? DART_ERR_DEVICE : DART_OK;
+}
+
+double dart_score_tolerance(int32_t dtype) {
+  return score_abs_bound(dtype == DART_BF16 ? kBF16 : kF32);
+}
+
+const char* dart_strerror(dart_status status) {
+  switch (status) {
+    case DART_OK: return "ok";
+    case DART_ERR_NULL: return "a required pointer is NULL";
+    case DART_ERR_SHAPE: return "a size or stride is out of range";
+    case DART_ERR_BUDGET: return "the keep budget violates P <= K <= N";
+    case DART_ERR_DTYPE: return "unknown dtype or pivot mode";
+    case DART_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DART_ERR_ALIGN: return "row starts are not 16-byte aligned";
+    case DART_ERR_HIP: return "a HIP call or kernel launch failed";
+    case DART_ERR_DEVICE: return "a ragged sample violated the size or budget limits";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

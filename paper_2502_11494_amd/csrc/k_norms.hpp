@@ -1,0 +1,82 @@
+// Row L1 norms of the criterion tensor: the pivot criterion of DART (footnote of
+// Section 3.3: the K-norm is an L1 norm; Table 1 caption: pivots have the largest
+// norm).  One streaming pass over [rows, Dc]; HBM-bound.
+#pragma once
+#include "common.hpp"
+
+namespace dart {
+
+// Sum of |x| over one 16-byte piece, as a fixed pairwise tree (3 roundings for
+// 8 bf16 values, 2 for 4 floats).  |x| of a bf16 widened to fp32 is exact.
+template <int DT>
+__device__ __forceinline__ float piece_abs_sum(const u32x4& v) {
+  if (DT == kBF16) {
+    float a0 = fabsf(bf16_lo(v.x)) + fabsf(bf16_hi(v.x));
+    float a1 = fabsf(bf16_lo(v.y)) + fabsf(bf16_hi(v.y));
+    float a2 = fabsf(bf16_lo(v.z)) + fabsf(bf16_hi(v.z));
+    float a3 = fabsf(bf16_lo(v.w)) + fabsf(bf16_hi(v.w));
+    return (a0 + a1) + (a2 + a3);
+  } else {
+    float a0 = fabsf(__uint_as_float(v.x)) + fabsf(__uint_as_float(v.y));
+    float a1 = fabsf(__uint_as_float(v.z)) + fabsf(__uint_as_float(v.w));
+    return a0 + a1;
+  }
+}
+
+// Relative bound on |fp32 norm - exact norm| for k_row_l1: piece tree, then one
+// add per piece a lane owns, then the 6-step butterfly, each rounding at most
+// 2^-24 relative on a sum of non-negative terms.
+inline double l1_rel_bound(int dtype, int Dc) {
+  int per_piece = dtype == kBF16 ? 8 : 4;
+  int pieces = Dc / per_piece;
+  int chain = (pieces + kWave - 1) / kWave;
+  int tree = dtype == kBF16 ? 3 : 2;
+  return (double)(tree + chain + 6 + 1) * 5.9604644775390625e-08;
+}
+
+// grid: ceil(rows / (4 * ROWS)) blocks of 256 threads; wave w of the grid owns
+// rows [w*ROWS, (w+1)*ROWS).  Per row, lane l reads the pieces l, l+64, ... so a
+// wave's loads are 1 KiB contiguous; 8*ROWS loads are in flight per lane.
+template <int DT, int ROWS>
+__global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int Dc, long ldc,
+                                                int rows, float* __restrict__ l1) {
+  const int lane = threadIdx.x & 63;
+  const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int esz = DT == kBF16 ? 2 : 4;
+  const int pieces = Dc * esz / 16;
+  const long rowbytes = ldc * esz;
+  const unsigned char* base = static_cast<const unsigned char*>(C);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  float acc[ROWS];
+  const unsigned char* rp[ROWS];
+  bool live[ROWS];
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    long row = wave * ROWS + r;
+    live[r] = row < rows;
+    rp[r] = base + (live[r] ? row : 0) * rowbytes;
+    acc[r] = 0.f;
+  }
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
+    u32x4 v[ROWS][8];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int t = t0 + u * kWave + lane;
+        v[r][u] = (live[r] && t < pieces) ? reinterpret_cast<const u32x4*>(rp[r])[t] : zero;
+      }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc[r] += piece_abs_sum<DT>(v[r][u]);
+  }
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    float s = wave_sum(acc[r]);
+    if (lane == 0 && live[r]) l1[wave * ROWS + r] = s;
+  }
+}
+
+}  // namespace dart

@@ -1,0 +1,37 @@
+// Score ordering: for every (sample, pivot) row of the score matrix, the lowest
+// scores in ascending (score, index) order -- as many as stage i of the retained-set
+// construction (Eq. 9-10) can possibly look at: the slots filled once stage i is
+// done, plus one entry beyond to measure the margin of the stage's last decision.
+#pragma once
+#include "common.hpp"
+#include "k_select.hpp"
+
+namespace dart {
+
+// grid: B*P blocks of kSelThreads; block (b, i).
+// S: pivot-major scores; lists: same layout, 64-bit (score image << 32 | index).
+__global__ __launch_bounds__(kSelThreads) void k_order_scores(
+    Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
+  __shared__ SelectShared sh;
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x / g.P, i = blockIdx.x % g.P;
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0) return;
+  const int n = sm.n;
+  if (quota_of(sm.k, g.P, i) == 0) return;  // the stage takes nothing
+  int want = filled_after(sm.k, g.P, i) + 1;
+  want = want < n ? want : n;
+  const long base = (long)g.P * sm.row0 + (long)i * n;
+  const float* row = S + base;
+  float v[kSelPerThread];
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e) {
+    int j = tid + e * kSelThreads;
+    v[e] = j < n ? row[j] + 0.0f : 0.f;
+  }
+  collect_sorted(v, n, want, -INFINITY, tid, sh);
+  unsigned long long* out = lists + base;
+  for (int t = tid; t < want; t += kSelThreads) out[t] = sh.buf[t];
+}
+
+}  // namespace dart

@@ -1,0 +1,94 @@
+// Pivot selection (Definition 1; Table 1 caption: the P tokens of largest
+// criterion norm), one workgroup per sample.
+//
+// The fp32 norms of k_row_l1 carry a relative error of at most `tau`.  Every
+// token whose fp32 norm is within that error of the P-th best could belong to
+// the exact top P, so all of them are re-evaluated in fp64 and ranked by
+// (fp64 norm, index).  The fp64 pass also yields the squared Euclidean norm of
+// every pivot, which the score kernel divides by.
+#pragma once
+#include "common.hpp"
+#include "k_select.hpp"
+
+namespace dart {
+
+constexpr int kPivLdsCand = 512;  // candidates whose fp64 norms fit in LDS
+
+struct PivotShared {
+  SelectShared sel;
+  double c64[kPivLdsCand];
+  double l2[kPivLdsCand];
+};
+
+// grid: B blocks of kSelThreads.
+// l1 [total_N] fp32 criterion norms; piv [B*P]; pl2 [B*Ppad] squared L2 norms of
+// the pivots' hidden-state rows (0 for padding slots); scr [2*total_N] doubles.
+template <int DT>
+__global__ __launch_bounds__(kSelThreads) void k_select_pivots(
+    Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
+    const float* __restrict__ l1, int* __restrict__ piv, double* __restrict__ pl2,
+    double* __restrict__ scr, float tau) {
+  __shared__ PivotShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int b = blockIdx.x;
+  const Sample sm = sample_of(g, b);
+  if (tid < g.Ppad) pl2[b * g.Ppad + tid] = 0.0;
+  if (sm.k == 0) return;
+  const int n = sm.n, P = g.P;
+  const float sign = g.mode == kMaxL1 ? -1.f : 1.f;  // "lowest" of -norm = largest norm
+
+  float v[kSelPerThread];
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e) {
+    int j = tid + e * kSelThreads;
+    v[e] = j < n ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
+  }
+  int c = collect_sorted(v, n, P, -INFINITY, tid, sh.sel);
+  // every token with value <= thr may belong to the exact top P
+  float vP = mono_inv((uint32_t)(sh.sel.buf[P - 1] >> 32));
+  float thr = vP + 2.5f * tau * fabsf(vP);
+  float vlast = mono_inv((uint32_t)(sh.sel.buf[c - 1] >> 32));
+  __syncthreads();
+  if (c < n && vlast <= thr) c = collect_sorted(v, n, P, thr, tid, sh.sel);
+  int flag = 0;
+  for (int t = tid; t < c; t += kSelThreads)
+    flag += mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr ? 1 : 0;
+  const int nU = block_sum(flag, tid, sh.sel.redi);  // a prefix of the sorted list
+
+  double* c64 = nU <= kPivLdsCand ? sh.c64 : scr + sm.row0;
+  double* l2s = nU <= kPivLdsCand ? sh.l2 : scr + g.total_N + sm.row0;
+  const int esz = DT == kBF16 ? 2 : 4;
+  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * g.ld * esz;
+  const unsigned char* Cb = static_cast<const unsigned char*>(C) + (long)sm.row0 * ldc * esz;
+  for (int u = w; u < nU; u += kSelThreads / kWave) {
+    int j = (int)(uint32_t)sh.sel.buf[u];
+    double a, q;
+    row_l1_l2_f64<DT>(Cb + (long)j * ldc * esz, Dc, lane, a, q);
+    if (C != X) {
+      double dummy;
+      row_l1_l2_f64<DT>(Xb + (long)j * g.ld * esz, g.D, lane, dummy, q);
+    }
+    if (lane == 0) {
+      c64[u] = g.mode == kMaxL1 ? -a : a;
+      l2s[u] = q;
+    }
+  }
+  __syncthreads();
+  // rank by (fp64 value, index); only ranks < P matter, so stop counting at P
+  for (int u = tid; u < nU; u += kSelThreads) {
+    const double cu = c64[u];
+    const int ju = (int)(uint32_t)sh.sel.buf[u];
+    int cnt = 0;
+    for (int o = 0; o < nU && cnt < P; ++o) {
+      const double co = c64[o];
+      const int jo = (int)(uint32_t)sh.sel.buf[o];
+      cnt += (co < cu || (co == cu && jo < ju)) ? 1 : 0;
+    }
+    if (cnt < P) {
+      piv[b * P + cnt] = ju;
+      pl2[b * g.Ppad + cnt] = l2s[u];
+    }
+  }
+}
+
+}  // namespace dart

@@ -1,0 +1,293 @@
+// Duplication scores of Definition 2 / Eq. (7): the cosine between every pivot
+// and every token of its sample.
+//
+// bf16 hidden states: the tokens x pivots x D contraction runs on the matrix
+// cores (v_mfma_f32_16x16x32_bf16).  A workgroup of 4 waves owns 64 token rows;
+// a wave owns 16 of them and walks D in chunks of 256 elements:
+//   HBM -> registers (two rows per load instruction, 512 B contiguous each)
+//       -> LDS (row-padded) -> MFMA A fragments (ds_read_b128, conflict-free).
+// The pivot rows of the chunk are staged once per workgroup in LDS (double
+// buffered) and serve as B fragments.  Feeding the token fragment as both
+// operands yields the tile's Gram matrix, whose diagonal is |x_j|^2, at no extra
+// memory traffic.  The eight MFMAs of a chunk chain in fp32; chunks are summed in
+// fp64.  bf16 x bf16 products are exact in fp32, so the only rounding is in the
+// matrix core's 32-term sums and the 8-long fp32 chain: see score_abs_bound().
+//
+// fp32 hidden states: plain fp64 arithmetic on the vector ALU (products of two
+// floats are exact in fp64).
+#pragma once
+#include "common.hpp"
+
+namespace dart {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kChunk = 256;                 // elements of D per chunk
+constexpr int kRowB = kChunk * 2 + 16;      // LDS row stride, bytes (pad kills bank conflicts)
+
+// Absolute bound on |stored fp32 score - exact cosine|.
+// bf16: each MFMA sums 32 exact products into the running fp32 value; allowing
+// one ulp (2^-23 relative to the magnitudes involved) per product added and per
+// chained accumulation, a chunk of 8 MFMAs errs by at most (32 + 8) * 2^-23 times
+// the sum of |p_d x_d| <= |p||x|.  The token norm comes from the same kind of sum
+// and enters through a square root (half the relative error).  One more ulp for
+// rounding the quotient to fp32; fp64 steps are negligible.
+// fp32 inputs: all fp64, only the final rounding to fp32 counts.
+inline double score_abs_bound(int dtype) {
+  const double ulp = 1.1920928955078125e-07;
+  return dtype == kBF16 ? (40.0 * 1.5 + 1.0) * ulp : 2.0 * ulp;
+}
+
+template <int NB>
+struct ScoreShared {
+  unsigned char a[4 * 16 * kRowB];        // per-wave token chunk
+  unsigned char p[2 * NB * 16 * kRowB];   // pivot chunk, double buffered
+  int pivrow[NB * 16];
+};
+
+// Tile -> (sample, tile inside the sample).  Returns false for surplus blocks.
+__device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int& tl) {
+  if (g.cu == nullptr) {
+    int tps = (g.N + kTileRows - 1) / kTileRows;
+    b = tile / tps;
+    tl = tile - b * tps;
+    return b < g.B;
+  }
+  if (tile >= g.tile_start[g.B]) return false;
+  int lo = 0, hi = g.B;  // largest b with tile_start[b] <= tile
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (g.tile_start[mid] <= tile) lo = mid; else hi = mid;
+  }
+  b = lo;
+  tl = tile - g.tile_start[lo];
+  return true;
+}
+
+// grid: number of 64-row tiles (dense: B*ceil(N/64); ragged: an upper bound).
+// NB = Ppad/16 pivot column blocks.
+template <int NB>
+__global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restrict__ X,
+                                                     const int* __restrict__ piv,
+                                                     const double* __restrict__ pl2,
+                                                     float* __restrict__ S) {
+  __shared__ __align__(16) ScoreShared<NB> sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b, tl;
+  if (!locate_tile(g, blockIdx.x, b, tl)) return;
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0) return;
+  const int n = sm.n, P = g.P;
+  if (tid < NB * 16) {
+    int p = tid < P ? piv[b * P + tid] : -1;
+    sh.pivrow[tid] = p < n ? p : n - 1;  // a caller's bad index must not leave X
+    if (tid < P && p < 0) sh.pivrow[tid] = 0;
+  }
+  __syncthreads();
+
+  const long rowbytes = g.ld * 2;
+  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes;
+  const int pieces = g.D / 8;                 // 16-byte pieces per row
+  const int nchunks = (g.D + kChunk - 1) / kChunk;
+  const int col16 = lane & 31;
+  const int j0 = tl * kTileRows + wave * 16;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  // token loads: instruction t covers rows 2t and 2t+1 of the wave's 16
+  const unsigned char* aptr[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    int r = j0 + 2 * t + (lane >> 5);
+    r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
+    aptr[t] = Xb + (long)r * rowbytes + col16 * 16;
+  }
+  // pivot loads: piece id = tid + 256*k -> pivot row id/32, piece id%32 (== col16)
+  const unsigned char* pptr[2 * NB];
+#pragma unroll
+  for (int k = 0; k < 2 * NB; ++k) {
+    int pr = sh.pivrow[(tid + 256 * k) >> 5];
+    pptr[k] = pr >= 0 ? Xb + (long)pr * rowbytes + col16 * 16 : nullptr;
+  }
+
+  u32x4 ra[8], rp[2 * NB];
+#define DART_LOAD_CHUNK(c)                                                              \
+  {                                                                                     \
+    const bool in_ = (c) * 32 + col16 < pieces;                                         \
+    const long off_ = (long)(c) * (kChunk * 2);                                         \
+    _Pragma("unroll") for (int t = 0; t < 8; ++t) ra[t] =                               \
+        in_ ? *reinterpret_cast<const u32x4*>(aptr[t] + off_) : zero;                   \
+    _Pragma("unroll") for (int k = 0; k < 2 * NB; ++k) rp[k] =                          \
+        (in_ && pptr[k]) ? *reinterpret_cast<const u32x4*>(pptr[k] + off_) : zero;      \
+  }
+#define DART_STORE_P(buf)                                                               \
+  {                                                                                     \
+    _Pragma("unroll") for (int k = 0; k < 2 * NB; ++k)                                  \
+        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                    \
+                                  ((tid + 256 * k) >> 5) * kRowB + col16 * 16) = rp[k]; \
+  }
+
+  double acc64[NB][4], gram64[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    gram64[r] = 0.0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc64[nb][r] = 0.0;
+  }
+
+  unsigned char* la = sh.a + wave * (16 * kRowB);
+  const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
+
+  DART_LOAD_CHUNK(0);
+  DART_STORE_P(0);
+  for (int c = 0; c < nchunks; ++c) {
+    // the wave's own LDS region: in-order LDS ops within a wave make this safe
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      *reinterpret_cast<u32x4*>(la + (2 * t + (lane >> 5)) * kRowB + col16 * 16) = ra[t];
+    if (c + 1 < nchunks) DART_LOAD_CHUNK(c + 1);
+    __syncthreads();  // pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read
+    const unsigned char* lp = sh.p + (c & 1) * (NB * 16 * kRowB);
+    f32x4 acc[NB], gram = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);
+      gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, gram, 0, 0, 0);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        bf16x8 pf = *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, acc[nb], 0, 0, 0);
+      }
+    }
+    if (c + 1 < nchunks) DART_STORE_P((c + 1) & 1);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      gram64[r] += (double)gram[r];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
+    }
+  }
+
+#undef DART_LOAD_CHUNK
+#undef DART_STORE_P
+
+  // Output tile: lane holds column (lane&15) and rows 4*(lane>>4)..+3 of each 16x16
+  // block.  With tokens as the A operand, rows are tokens and columns are pivots
+  // (Gram: columns are tokens too, so |x_m|^2 sits in lane (m/4)*16+m, slot m%4).
+  const int g4 = lane >> 4;
+  double xn[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) xn[r] = sqrt(__shfl(gram64[r], g4 * 16 + g4 * 4 + r, kWave));
+  float* Sb = S + (long)P * sm.row0;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int i = nb * 16 + (lane & 15);
+    if (i < P) {
+      const double pn = sqrt(pl2[b * g.Ppad + i]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = j0 + g4 * 4 + r;
+        if (j < n) {
+          const double den = pn * xn[r];
+          const double s = den > 0.0 ? acc64[nb][r] / den : 0.0;
+          Sb[(long)i * n + j] = (float)s + 0.0f;
+        }
+      }
+    }
+  }
+}
+
+// fp32 hidden states.  grid: ceil(total rows / 16) blocks of 256; a wave owns 4
+// consecutive token rows of one sample and 8 pivots at a time.
+__global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restrict__ X,
+                                                    const int* __restrict__ piv,
+                                                    float* __restrict__ S) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // rows are grouped per sample: 16 rows per block, dense tiles of the sample
+  int b, tl;
+  {
+    // reuse the 64-row tile table: block = (tile, quarter)
+    int tile = blockIdx.x >> 2;
+    if (!locate_tile(g, tile, b, tl)) return;
+    tl = tl * 4 + (blockIdx.x & 3);
+  }
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0) return;
+  const int n = sm.n, P = g.P;
+  const int j0 = tl * 16 + wave * 4;
+  if (j0 >= n) return;
+  const float* Xb = static_cast<const float*>(X) + (long)sm.row0 * g.ld;
+  const int pieces = g.D / 4;
+  const f32x4v* xr[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    int j = j0 + r < n ? j0 + r : n - 1;
+    xr[r] = reinterpret_cast<const f32x4v*>(Xb + (long)j * g.ld);
+  }
+  float* Sb = S + (long)P * sm.row0;
+  for (int i0 = 0; i0 < P; i0 += 8) {
+    const f32x4v* pr[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      int i = i0 + q < P ? i0 + q : P - 1;
+      int p = piv[b * P + i];
+      p = p < 0 ? 0 : (p < n ? p : n - 1);  // a caller's bad index must not leave X
+      pr[q] = reinterpret_cast<const f32x4v*>(Xb + (long)p * g.ld);
+    }
+    double dot[4][8], xx[4], pp[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      xx[r] = 0.0;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) dot[r][q] = 0.0;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) pp[q] = 0.0;
+    for (int t = lane; t < pieces; t += kWave) {
+      f32x4v xv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) xv[r] = xr[r][t];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        f32x4v pv = pr[q][t];
+        const double p0 = pv.x, p1 = pv.y, p2 = pv.z, p3 = pv.w;
+        pp[q] = fma(p0, p0, pp[q]);
+        pp[q] = fma(p1, p1, pp[q]);
+        pp[q] = fma(p2, p2, pp[q]);
+        pp[q] = fma(p3, p3, pp[q]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          dot[r][q] = fma(p0, (double)xv[r].x, dot[r][q]);
+          dot[r][q] = fma(p1, (double)xv[r].y, dot[r][q]);
+          dot[r][q] = fma(p2, (double)xv[r].z, dot[r][q]);
+          dot[r][q] = fma(p3, (double)xv[r].w, dot[r][q]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const double x0 = xv[r].x, x1 = xv[r].y, x2 = xv[r].z, x3 = xv[r].w;
+        xx[r] = fma(x0, x0, xx[r]);
+        xx[r] = fma(x1, x1, xx[r]);
+        xx[r] = fma(x2, x2, xx[r]);
+        xx[r] = fma(x3, x3, xx[r]);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) pp[q] = sqrt(wave_sum(pp[q]));
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const double xnorm = sqrt(wave_sum(xx[r]));
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const double d = wave_sum(dot[r][q]);
+        const double den = pp[q] * xnorm;
+        const double s = den > 0.0 ? d / den : 0.0;
+        if (lane == 0 && i0 + q < P && j0 + r < n) Sb[(long)(i0 + q) * n + j0 + r] = (float)s + 0.0f;
+      }
+    }
+  }
+}
+
+}  // namespace dart

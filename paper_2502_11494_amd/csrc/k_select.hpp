@@ -1,0 +1,122 @@
+// Block-wide selection helpers: pull the `want` lowest of n fp32 values (with
+// their indices) into LDS as sorted 64-bit (value image << 32 | index) keys.
+//
+// Method: a value-linear histogram between the block's min and max finds the
+// bucket d* that holds the want-th lowest value; everything in buckets <= d* is
+// compacted and bitonic-sorted.  Ties need no special care: the composite key is
+// unique, so the sort alone yields (value ascending, index ascending).
+#pragma once
+#include "common.hpp"
+
+namespace dart {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelPerThread = kMaxN / kSelThreads;  // 16 values per thread
+constexpr int kSelBuckets = 1024;
+
+struct SelectShared {
+  unsigned long long buf[kMaxN];  // compacted keys, then sorted
+  int hist[kSelBuckets];
+  float redf[2 * (kSelThreads / kWave)];
+  int redi[kSelThreads / kWave];
+  int count;
+  int dstar;
+};
+
+__device__ __forceinline__ int block_sum(int v, int tid, int* red) {
+  const int lane = tid & 63, w = tid >> 6;
+  v = wave_sum(v);
+  __syncthreads();  // red may still be read from a previous call
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < kSelThreads / kWave; ++i) s += red[i];
+  return s;
+}
+
+// v[e] belongs to index tid + e*kSelThreads; entries with index >= n are ignored.
+// Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
+// returns how many were compacted (>= min(want, n)); the same value on every thread.
+__device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
+                                              float incl_upto, int tid, SelectShared& sh) {
+  const int lane = tid & 63, w = tid >> 6;
+  // block min / max
+  float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e)
+    if (tid + e * kSelThreads < n) {
+      lo = fminf(lo, v[e]);
+      hi = fmaxf(hi, v[e]);
+    }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    lo = fminf(lo, __shfl_xor(lo, o, kWave));
+    hi = fmaxf(hi, __shfl_xor(hi, o, kWave));
+  }
+  __syncthreads();
+  if (lane == 0) {
+    sh.redf[2 * w] = lo;
+    sh.redf[2 * w + 1] = hi;
+  }
+  sh.hist[tid] = 0;  // kSelBuckets == kSelThreads
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelThreads / kWave; ++i) {
+    lo = fminf(lo, sh.redf[2 * i]);
+    hi = fmaxf(hi, sh.redf[2 * i + 1]);
+  }
+  const float range = hi - lo;
+  const float scale = range > 0.f ? (float)kSelBuckets / range : 0.f;
+  auto bucket = [&](float x) -> int {
+    float f = (x - lo) * scale;  // non-finite input lands in a valid bucket too
+    int d = f >= (float)(kSelBuckets - 1) ? kSelBuckets - 1 : (int)f;
+    d = d < 0 ? 0 : d;
+    return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
+  };
+  int bk[kSelPerThread];
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e)
+    if (tid + e * kSelThreads < n) {
+      bk[e] = bucket(v[e]);
+      atomicAdd(&sh.hist[bk[e]], 1);
+    }
+  __syncthreads();
+  // inclusive scan of the histogram, one bucket per thread
+  int h = sh.hist[tid];
+  int incl = wave_excl_scan(h, lane) + h;
+  if (lane == 63) sh.redi[w] = incl;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int i = 0; i < kSelThreads / kWave; ++i)
+    if (i < w) before += sh.redi[i];
+  incl += before;
+  // d* = first bucket whose inclusive count reaches `want`
+  int target = want < n ? want : n;
+  int below = block_sum(incl < target ? 1 : 0, tid, sh.redi);
+  int dlim = below;
+  if (incl_upto > -INFINITY) {
+    int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
+    dlim = d2 > dlim ? d2 : dlim;
+  }
+  if (tid == 0) sh.count = 0;
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e) {
+    int j = tid + e * kSelThreads;
+    if (j < n && bk[e] <= dlim) {
+      int slot = atomicAdd(&sh.count, 1);
+      sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+    }
+  }
+  __syncthreads();
+  const int c = sh.count;
+  const int np = next_pow2(c < 2 ? 2 : c);
+  for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
+  __syncthreads();
+  block_bitonic_sort<kSelThreads>(sh.buf, np, tid);
+  return c;
+}
+
+}  // namespace dart

@@ -1,0 +1,125 @@
+"""Helpers for the GPU parity tests: run the HIP path on a Workload and compare
+it with the CPU oracle, sample by sample."""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2502_11494_amd as D
+from paper_2502_11494_amd import workloads as W
+
+# score tolerance of the target: relative 1e-5 for fp32 inputs, 2e-2 for bf16
+# inputs with fp32 accumulation, plus an absolute floor for cosines near zero
+RTOL = {W.F32: 1e-5, W.BF16: 2e-2}
+ATOL = 1e-6
+
+
+def to_device(w: W.Workload, ld: Optional[int] = None) -> torch.Tensor:
+    """Rows on the GPU (bf16 or fp32), optionally with a padded row stride."""
+    if w.dtype == W.BF16:
+        t = torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(w.X)
+    t = t.cuda()
+    if ld is not None and ld != w.D:
+        buf = torch.zeros((t.shape[0], ld), dtype=t.dtype, device="cuda")
+        buf[:, :w.D] = t
+        return buf
+    return t
+
+
+def desc_of(w: W.Workload, cu_dev: Optional[torch.Tensor], ld: Optional[int] = None,
+            mode: int = D.DART_PIVOT_MAX_L1, K: Optional[int] = None) -> D.DartDesc:
+    lens = w.lengths
+    if w.ragged:
+        return D.make_desc(w.B, w.D, w.P, w.dtype, K=w.K if K is None else K,
+                           keep_num=w.keep_num, keep_den=w.keep_den, cu_seqlens=cu_dev,
+                           total_N=int(w.cu[-1]), max_N=int(lens.max()) if len(lens) else 1,
+                           ld=ld, pivot_mode=mode)
+    return D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]) if len(lens) else 0,
+                       K=w.K if K is None else K, keep_num=w.keep_num, keep_den=w.keep_den,
+                       ld=ld, pivot_mode=mode)
+
+
+@dataclasses.dataclass
+class GpuResult:
+    piv: np.ndarray      # [B, P]
+    keep: np.ndarray     # [sum K]
+    cu_keep: np.ndarray  # [B+1]
+    S: np.ndarray        # [P * total_N] pivot-major per sample
+    Y: np.ndarray        # [sum K, D] raw element bits
+    pos_out: np.ndarray  # [sum K]
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT_MAX_L1,
+               crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None) -> GpuResult:
+    Xd = to_device(w, ld) if Xd is None else Xd
+    cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
+    desc = desc_of(w, cu_dev, ld, mode)
+    ws = D.alloc_workspace(desc)
+    total_keep = sum(w.budget(b) for b in range(w.B))
+    total_N = int(w.cu[-1])
+    pos = torch.from_numpy(w.pos).cuda()
+    Y = torch.full((max(total_keep, 1), w.D), 7, dtype=Xd.dtype, device="cuda")
+    pos_out = torch.full((max(total_keep, 1),), -1, dtype=torch.int64, device="cuda")
+    keep = torch.full((max(total_keep, 1),), -1, dtype=torch.int32, device="cuda")
+    cu_keep = torch.full((w.B + 1,), -1, dtype=torch.int32, device="cuda")
+    piv = torch.full((max(w.B * w.P, 1),), -1, dtype=torch.int32, device="cuda")
+    S = torch.full((max(w.P * total_N, 1),), float("nan"), dtype=torch.float32, device="cuda")
+    kw = {}
+    if crit is not None:
+        kw = dict(crit=crit, crit_D=crit.shape[1], crit_ld=crit.stride(0))
+    D.dart_reduce(desc, Xd, Y, keep, ws, pos=pos, pos_out=pos_out, cu_keep=cu_keep, piv_out=piv,
+                  S_out=S, **kw)
+    torch.cuda.synchronize()
+    if w.ragged:
+        assert D.dart_device_status(desc, ws) == D.DART_OK
+    return GpuResult(piv.cpu().numpy()[:w.B * w.P].reshape(w.B, w.P), keep.cpu().numpy()[:total_keep],
+                     cu_keep.cpu().numpy(), S.cpu().numpy()[:w.P * total_N], bits(Y)[:total_keep],
+                     pos_out.cpu().numpy()[:total_keep])
+
+
+def oracle_samples(w: W.Workload, mode: int = oracle.MAX_L1,
+                   crit: Optional[np.ndarray] = None) -> List[oracle.Reduced]:
+    out = []
+    for b in range(w.B):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        c = None if crit is None else crit[lo:hi]
+        out.append(oracle.reduce(w.X[lo:hi], w.dtype, w.P, w.budget(b), pos=w.pos[lo:hi], crit=c,
+                                 mode=mode))
+    return out
+
+
+def compare(w: W.Workload, g: GpuResult, refs: List[oracle.Reduced], check_admissible=True):
+    """Bit-exact pivots, retained indices, rows and position ids; scores within
+    the target's tolerance AND within the bound the library certifies against."""
+    tau = D.score_tolerance(w.dtype)
+    k0 = 0
+    worst = 0.0
+    for b, r in enumerate(refs):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        n, kb = hi - lo, w.budget(b)
+        if check_admissible:
+            assert oracle.admissible(w.X[lo:hi], r), f"sample {b}: oracle margins too small"
+        assert g.cu_keep[b] == k0 and g.cu_keep[b + 1] == k0 + kb
+        np.testing.assert_array_equal(g.piv[b], r.piv, err_msg=f"pivots of sample {b}")
+        Sg = g.S[w.P * lo: w.P * hi].reshape(w.P, n).astype(np.float64)
+        err = np.abs(Sg - r.S)
+        assert np.all(err <= RTOL[w.dtype] * np.abs(r.S) + ATOL), f"scores of sample {b}"
+        worst = max(worst, float(err.max()))
+        assert err.max() <= tau, f"sample {b}: score error {err.max():.3e} exceeds bound {tau:.3e}"
+        np.testing.assert_array_equal(g.keep[k0:k0 + kb], r.keep, err_msg=f"keep of sample {b}")
+        assert g.Y[k0:k0 + kb].tobytes() == r.Y.tobytes(), f"rows of sample {b}"
+        np.testing.assert_array_equal(g.pos_out[k0:k0 + kb], r.pos_out)
+        k0 += kb
+    return worst / tau

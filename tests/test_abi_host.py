@@ -1,0 +1,118 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol include/dart.h declares, mirrors the descriptor layout, sizes the
+workspace and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+import paper_2502_11494_amd as D
+from paper_2502_11494_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dart.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    return re.findall(r"DART_API\s+[\w\s\*]+?\b(dart_\w+)\s*\(", text)
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS) and len(names) == len(binding.EXPORTS)
+    L = binding.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_descriptor_layout_matches_the_header():
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, reserved));return 0;}\n'
+    with tempfile.TemporaryDirectory() as td:
+        c = os.path.join(td, "t.c")
+        open(c, "w").write(src)
+        exe = os.path.join(td, "t")
+        subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), c, "-o", exe],
+                       check=True)
+        out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split()
+    T = D.DartDesc
+    assert list(map(int, out)) == [C.sizeof(T), T.cu_seqlens.offset, T.ld.offset, T.K.offset,
+                                   T.reserved.offset]
+
+
+def test_workspace_grows_with_the_problem():
+    small = D.dart_workspace_bytes(D.make_desc(1, 4096, 8, D.DART_F32, N=576, K=64))
+    big = D.dart_workspace_bytes(D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320))
+    assert 0 < small < big
+    assert small % 256 == 0 and big % 256 == 0
+    assert D.dart_workspace_bytes(D.make_desc(0, 4096, 8, D.DART_F32, N=576, K=64)) > 0
+
+
+BAD = [
+    (dict(B=1, D=4096, P=0, dtype=D.DART_BF16, N=576, K=64), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=65, dtype=D.DART_BF16, N=576, K=70), D.DART_ERR_SHAPE),
+    (dict(B=-1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64), D.DART_ERR_SHAPE),
+    (dict(B=1, D=0, P=8, dtype=D.DART_BF16, N=576, K=64), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=16385, K=64), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, ld=4000), D.DART_ERR_SHAPE),
+    (dict(B=2, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, total_N=1000), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=7, N=576, K=64), D.DART_ERR_DTYPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, pivot_mode=5), D.DART_ERR_DTYPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=7), D.DART_ERR_BUDGET),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=577), D.DART_ERR_BUDGET),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=4, K=4), D.DART_ERR_BUDGET),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=0, keep_num=1, keep_den=0),
+     D.DART_ERR_BUDGET),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=0, keep_num=3, keep_den=2),
+     D.DART_ERR_BUDGET),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=0, keep_num=1, keep_den=1000),
+     D.DART_ERR_BUDGET),  # floor(0.576) = 0 < P
+    (dict(B=1, D=4100, P=8, dtype=D.DART_BF16, N=576, K=64), D.DART_ERR_ALIGN),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_F32, N=576, K=64, ld=4098), D.DART_ERR_ALIGN),
+]
+
+
+@pytest.mark.parametrize("kw,code", BAD)
+def test_bad_descriptors_are_rejected_on_the_host(kw, code):
+    kw = dict(kw)
+    d = D.make_desc(kw.pop("B"), kw.pop("D"), kw.pop("P"), kw.pop("dtype"), **kw)
+    assert D.dart_workspace_bytes(d) == 0
+    L = binding.lib()
+    fake = C.c_void_p(4096)  # never dereferenced: the descriptor is rejected first
+    rc = L.dart_reduce(C.byref(d), fake, None, 0, 0, None, fake, None, fake, None, None, None,
+                       fake, 1 << 40, None)
+    assert rc == code, D.strerror(rc)
+
+
+def test_null_and_workspace_errors_need_no_device():
+    d = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=64)
+    L = binding.lib()
+    fake = C.c_void_p(4096)
+    need = D.dart_workspace_bytes(d)
+    call = lambda X, Y, keep, ws, nbytes: L.dart_reduce(C.byref(d), X, None, 0, 0, None, Y, None,
+                                                        keep, None, None, None, ws, nbytes, None)
+    assert call(None, fake, fake, fake, need) == D.DART_ERR_NULL
+    assert call(fake, None, fake, fake, need) == D.DART_ERR_NULL
+    assert call(fake, fake, None, fake, need) == D.DART_ERR_NULL
+    assert call(fake, fake, fake, None, need) == D.DART_ERR_WORKSPACE
+    assert call(fake, fake, fake, fake, need - 1) == D.DART_ERR_WORKSPACE
+    assert call(fake, fake, fake, C.c_void_p(4096 + 8), need) == D.DART_ERR_WORKSPACE
+    assert call(C.c_void_p(4100), fake, fake, fake, need) == D.DART_ERR_ALIGN
+    # position ids come in pairs
+    rc = L.dart_reduce(C.byref(d), fake, None, 0, 0, fake, fake, None, fake, None, None, None,
+                       fake, need, None)
+    assert rc == D.DART_ERR_NULL
+    # an empty batch is a valid no-op and needs nothing else
+    d0 = D.make_desc(0, 4096, 8, D.DART_BF16, N=576, K=64)
+    assert L.dart_reduce(C.byref(d0), None, None, 0, 0, None, None, None, None, None, None,
+                         None, None, 0, None) == D.DART_OK
+
+
+def test_status_strings():
+    texts = [D.strerror(code) for code in range(0, -9, -1)]
+    assert all(texts) and len(set(texts)) == 9
+    assert D.strerror(-99) not in texts
+    assert 0 < D.score_tolerance(D.DART_F32) < D.score_tolerance(D.DART_BF16) < 1e-4

@@ -1,0 +1,196 @@
+"""Parity of the fused HIP path (dart_reduce through the C ABI) with the CPU
+oracle: pivots, retained indices, gathered rows and position ids bit for bit,
+scores within tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_11494_amd as D
+from paper_2502_11494_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def check(w, **kw):
+    print(f"[case] {w.name} B={w.B} D={w.D} P={w.P} K={w.K} lens={w.lengths[:6].tolist()}",
+          flush=True)
+    g = G.run_reduce(w, **kw)
+    frac = G.compare(w, g, G.oracle_samples(w))
+    print(f"       worst score error = {frac:.3f} of the certified bound", flush=True)
+    return g
+
+
+# ---- sizes the oracle finishes in seconds; several tiles and a ragged tail --------
+
+SMALL = [
+    lambda: W.single_image(N=200, D=1024, P=8, K=40, n_centroids=16),          # fp32
+    lambda: W.single_image(N=577, D=1000, P=5, K=64, n_centroids=32),          # fp32, odd sizes
+    lambda: W.image_batch(B=3, N=200, D=1024, P=8, K=64, n_centroids=32),      # N % 64 != 0
+    lambda: W.image_batch(B=2, N=333, D=3584, P=8, K=129, n_centroids=32),     # remainder rule
+    lambda: W.multicrop_batch(B=2, N=700, D=2048, P=16, K=80, n_centroids=64),  # exact copies
+    lambda: W.multicrop_batch(B=1, N=1000, D=520, P=20, K=111, n_centroids=64),  # D % 256 != 0
+    lambda: W.ragged_batch(B=5, n_lo=100, n_hi=900, D=1024, P=16),
+    lambda: W.video_batch(B=2, frames=8, per_frame=60, D=1024, P=32, K=96, n_centroids=8),
+    lambda: W.video_batch(B=1, frames=6, per_frame=50, D=512, P=40, K=100, n_centroids=8),
+]
+
+
+@pytest.mark.parametrize("make", SMALL)
+def test_small_cases(make):
+    check(make())
+
+
+def test_padded_row_stride():
+    w = W.image_batch(B=2, N=150, D=1024, P=8, K=32, n_centroids=16)
+    check(w, ld=1024 + 64)
+
+
+def test_min_norm_pivots():
+    w = W.image_batch(B=2, N=150, D=1024, P=8, K=32, n_centroids=16)
+    g = G.run_reduce(w, mode=D.DART_PIVOT_MIN_L1)
+    G.compare(w, g, G.oracle_samples(w, mode=oracle.MIN_L1))
+
+
+def test_separate_criterion_tensor():
+    w = W.image_batch(B=2, N=150, D=1024, P=8, K=32, n_centroids=16)
+    rng = np.random.default_rng(5)
+    crit_f = rng.standard_normal((int(w.cu[-1]), 128)).astype(np.float32)
+    crit_bits = W.f32_to_bf16_bits(crit_f)
+    crit_dev = torch.from_numpy(crit_bits.view(np.int16)).view(torch.bfloat16).cuda()
+    g = G.run_reduce(w, crit=crit_dev)
+    G.compare(w, g, G.oracle_samples(w, crit=crit_bits))
+
+
+# ---- edge cases -----------------------------------------------------------------------
+
+def test_keep_only_the_pivots_and_keep_everything():
+    for K in (8, 150):
+        w = W.image_batch(B=2, N=150, D=512, P=8, K=K, n_centroids=16)
+        check(w)
+
+
+def test_tiny_samples():
+    check(W.single_image(N=1, D=256, P=1, K=1, n_centroids=1))
+    check(W.image_batch(B=3, N=5, D=64, P=2, K=3, n_centroids=2))
+    check(W.image_batch(B=1, N=64, D=8, P=64, K=64, n_centroids=4))
+
+
+def test_identical_rows_everywhere():
+    # every decision is an exact tie: only the index rule can decide, and the
+    # fp64 re-evaluation paths handle whole samples
+    w = W.image_batch(B=2, N=300, D=512, P=4, K=37, n_centroids=1, sigma=0.0)
+    assert len(np.unique(w.sample(0), axis=0)) == 1
+    g = check(w)
+    np.testing.assert_array_equal(g.piv[0], [0, 1, 2, 3])
+    np.testing.assert_array_equal(g.keep[:37], np.arange(37))
+
+
+def test_zero_rows_score_zero():
+    w = W.image_batch(B=1, N=130, D=512, P=4, K=30, n_centroids=8)
+    w.X[5] = 0
+    w.X[77] = 0
+    w.X[100] = 0x8000  # every element -0.0
+    g = check(w)
+    S = g.S.reshape(w.P, 130)
+    assert np.all(S[:, [5, 77, 100]] == 0.0) and not np.any(np.signbit(S[:, [5, 77, 100]]))
+
+
+def test_many_pivots_and_longest_sample():
+    w = W.ragged_batch(B=2, D=256, P=64, lengths=[16384, 4100], keep_num=1, keep_den=8)
+    check(w)
+
+
+def test_ragged_with_empty_and_rejected_samples():
+    # sample 1 is empty (valid, keeps nothing); sample 3 is shorter than P (rejected)
+    w = W.ragged_batch(B=5, D=512, P=16, lengths=[300, 1, 200, 10, 400])
+    # drop the one-row sample and rebuild the offsets so that sample 1 is truly empty
+    lens = [300, 0, 200, 10, 400]
+    cu = np.zeros(6, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    X = np.concatenate([w.sample(0), w.sample(2), w.sample(3), w.sample(4)])
+    Xd = torch.from_numpy(X.view(np.int16)).view(torch.bfloat16).cuda()
+    cu_dev = torch.from_numpy(cu).cuda()
+    desc = D.make_desc(5, 512, 16, D.DART_BF16, keep_num=111, keep_den=1000, cu_seqlens=cu_dev,
+                       total_N=int(cu[-1]), max_N=400)
+    ws = D.alloc_workspace(desc)
+    budgets = [33, 0, 22, 0, 44]
+    tot = sum(budgets)
+    Y = torch.zeros((tot, 512), dtype=torch.bfloat16, device="cuda")
+    keep = torch.full((tot,), -1, dtype=torch.int32, device="cuda")
+    cu_keep = torch.full((6,), -1, dtype=torch.int32, device="cuda")
+    D.dart_reduce(desc, Xd, Y, keep, ws, cu_keep=cu_keep)
+    assert D.dart_device_status(desc, ws) == D.DART_ERR_DEVICE
+    np.testing.assert_array_equal(cu_keep.cpu().numpy(), np.concatenate([[0], np.cumsum(budgets)]))
+    keep_h, Yh, k0 = keep.cpu().numpy(), G.bits(Y), 0
+    for b, kb in enumerate(budgets):
+        if kb == 0:
+            continue
+        xs = X[cu[b]:cu[b + 1]]
+        r = oracle.reduce(xs, oracle.BF16, 16, kb)
+        np.testing.assert_array_equal(keep_h[k0:k0 + kb], r.keep)
+        assert Yh[k0:k0 + kb].tobytes() == r.Y.tobytes()
+        k0 += kb
+    # a max_N that a sample exceeds is reported, not overrun
+    desc2 = D.make_desc(5, 512, 16, D.DART_BF16, keep_num=111, keep_den=1000, cu_seqlens=cu_dev,
+                        total_N=int(cu[-1]), max_N=256)
+    ws2 = D.alloc_workspace(desc2)
+    D.dart_reduce(desc2, Xd, Y, keep, ws2, cu_keep=cu_keep)
+    assert D.dart_device_status(desc2, ws2) == D.DART_ERR_DEVICE
+    np.testing.assert_array_equal(cu_keep.cpu().numpy(), [0, 0, 0, 22, 22, 22])
+
+
+def test_empty_batch_is_a_noop():
+    desc = D.make_desc(0, 512, 4, D.DART_BF16, N=100, K=10)
+    ws = torch.empty(max(D.dart_workspace_bytes(desc), 256), dtype=torch.uint8, device="cuda")
+    X = torch.zeros((1, 512), dtype=torch.bfloat16, device="cuda")
+    keep = torch.full((4,), -5, dtype=torch.int32, device="cuda")
+    D.dart_reduce(desc, X, X, keep, ws)
+    torch.cuda.synchronize()
+    assert keep.cpu().tolist() == [-5] * 4
+
+
+def test_runs_are_bit_identical_and_position_independent():
+    w = W.multicrop_batch(B=3, N=500, D=1024, P=16, K=96, n_centroids=32)
+    a = G.run_reduce(w)
+    b = G.run_reduce(w)
+    for f in ("piv", "keep", "S", "Y", "pos_out"):
+        np.testing.assert_array_equal(getattr(a, f), getattr(b, f))
+    # the same sample placed elsewhere in a batch gives the same bits
+    solo = W.multicrop_batch(B=3, N=500, D=1024, P=16, K=96, n_centroids=32)
+    solo.X, solo.pos, solo.cu, solo.B = w.sample(2).copy(), w.pos[:500].copy(), w.cu[:2].copy(), 1
+    c = G.run_reduce(solo)
+    np.testing.assert_array_equal(c.S, a.S[16 * 1000:])
+    np.testing.assert_array_equal(c.keep, a.keep[2 * 96:])
+    # bit-identical rows get bit-identical scores
+    X0 = w.sample(0)
+    S0 = a.S[:16 * 500].reshape(16, 500)
+    _, inv, cnt = np.unique(X0, axis=0, return_inverse=True, return_counts=True)
+    for grp in np.flatnonzero(cnt > 1)[:20]:
+        m = np.flatnonzero(inv == grp)
+        assert np.all(S0[:, m] == S0[:, m[:1]])
+
+
+# ---- the five benchmark configurations at full size --------------------------------
+
+def test_config0_single_image_fp32():
+    check(W.by_index(0))
+
+
+@pytest.mark.parametrize("K", [64, 128, 192])
+def test_config1_image_batch(K):
+    check(W.by_index(1, K=K))
+
+
+def test_config2_multicrop_batch():
+    check(W.by_index(2))
+
+
+def test_config4_video_batch():
+    check(W.by_index(4))
+
+
+def test_config3_ragged_batch():
+    check(W.by_index(3))

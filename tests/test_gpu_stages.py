@@ -1,0 +1,135 @@
+"""Parity of the four stage entry points of the C ABI with the oracle's steps."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_11494_amd as D
+from paper_2502_11494_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def setup(w, ld=None):
+    Xd = G.to_device(w, ld)
+    cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
+    desc = G.desc_of(w, cu_dev, ld)
+    return Xd, cu_dev, desc, D.alloc_workspace(desc)
+
+
+CASES = [
+    lambda: W.single_image(N=300, D=512, P=8, K=64, n_centroids=16),
+    lambda: W.multicrop_batch(B=3, N=450, D=1024, P=16, K=100, n_centroids=32),
+    lambda: W.ragged_batch(B=4, n_lo=80, n_hi=700, D=768, P=12),
+]
+
+
+@pytest.mark.parametrize("make", CASES)
+def test_select_pivots_and_norms(make):
+    w = make()
+    Xd, cu_dev, desc, ws = setup(w)
+    piv = torch.full((w.B * w.P,), -1, dtype=torch.int32, device="cuda")
+    l1 = torch.zeros(int(w.cu[-1]), dtype=torch.float32, device="cuda")
+    D.dart_select_pivots(desc, Xd, piv, ws, l1_out=l1)
+    torch.cuda.synchronize()
+    piv_h, l1_h = piv.cpu().numpy().reshape(w.B, w.P), l1.cpu().numpy().astype(np.float64)
+    for b in range(w.B):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        c = oracle.l1_norms(w.X[lo:hi], w.dtype)
+        np.testing.assert_allclose(l1_h[lo:hi], c, rtol=2e-6, atol=0)
+        np.testing.assert_array_equal(piv_h[b], oracle.select_pivots(c, w.P))
+
+
+@pytest.mark.parametrize("make", CASES)
+def test_duplication_scores(make):
+    w = make()
+    Xd, cu_dev, desc, ws = setup(w)
+    rng = np.random.default_rng(1)
+    # any pivots will do for this entry point: take random distinct tokens
+    piv_h = np.stack([rng.permutation(int(n))[:w.P] for n in w.lengths]).astype(np.int32)
+    piv = torch.from_numpy(piv_h).cuda()
+    S = torch.full((w.P * int(w.cu[-1]),), float("nan"), dtype=torch.float32, device="cuda")
+    D.dart_duplication_scores(desc, Xd, piv, S, ws)
+    torch.cuda.synchronize()
+    S_h = S.cpu().numpy().astype(np.float64)
+    tau = D.score_tolerance(w.dtype)
+    for b in range(w.B):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        ref = oracle.scores(w.X[lo:hi], w.dtype, piv_h[b])
+        got = S_h[w.P * lo:w.P * hi].reshape(w.P, hi - lo)
+        err = np.abs(got - ref)
+        assert np.all(err <= G.RTOL[w.dtype] * np.abs(ref) + G.ATOL)
+        assert err.max() <= tau
+        for i, p in enumerate(piv_h[b]):
+            assert abs(got[i, p] - 1.0) <= tau  # self-similarity
+
+
+def test_topk_keep_on_given_scores_is_exact_integer_work():
+    # X = NULL: the fp32 scores are the truth, so the oracle's retain step on the
+    # same numbers must give the same indices, ties included
+    rng = np.random.default_rng(2)
+    for N, P, K, grid in [(500, 8, 64, None), (333, 5, 47, 0.25), (64, 16, 64, 0.5),
+                          (2000, 32, 999, None), (100, 1, 100, 1.0)]:
+        B = 3
+        S_h = rng.standard_normal((B, P, N)).astype(np.float32) * 0.1
+        if grid:
+            S_h = (np.round(S_h / (grid * 0.1)) * (grid * 0.1)).astype(np.float32)  # many ties
+        S_h[0, 0, :5] = -0.0
+        S_h[0, 0, 5:9] = 0.0
+        piv_h = np.stack([rng.permutation(N)[:P] for _ in range(B)]).astype(np.int32)
+        desc = D.make_desc(B, 64, P, D.DART_BF16, N=N, K=K)
+        ws = D.alloc_workspace(desc)
+        keep = torch.full((B * K,), -1, dtype=torch.int32, device="cuda")
+        cu_keep = torch.full((B + 1,), -1, dtype=torch.int32, device="cuda")
+        D.dart_topk_keep(desc, torch.from_numpy(S_h).cuda(), torch.from_numpy(piv_h).cuda(), keep,
+                         ws, cu_keep=cu_keep)
+        torch.cuda.synchronize()
+        keep_h = keep.cpu().numpy().reshape(B, K)
+        np.testing.assert_array_equal(cu_keep.cpu().numpy(), np.arange(B + 1) * K)
+        for b in range(B):
+            np.testing.assert_array_equal(keep_h[b], oracle.retain(S_h[b], piv_h[b], K))
+
+
+def test_topk_keep_ragged_with_certification():
+    w = W.ragged_batch(B=4, n_lo=80, n_hi=700, D=768, P=12)
+    Xd, cu_dev, desc, ws = setup(w)
+    refs = G.oracle_samples(w)
+    total = int(w.cu[-1])
+    # feed the oracle's own scores, rounded to fp32: decisions that fp32 cannot
+    # separate must be recovered from the rows
+    S_h = np.concatenate([r.S.astype(np.float32).ravel() for r in refs])
+    piv_h = np.concatenate([r.piv for r in refs]).astype(np.int32)
+    tk = sum(w.budget(b) for b in range(w.B))
+    keep = torch.full((tk,), -1, dtype=torch.int32, device="cuda")
+    D.dart_topk_keep(desc, torch.from_numpy(S_h).cuda(), torch.from_numpy(piv_h).cuda(), keep, ws,
+                     X=Xd)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(keep.cpu().numpy(), np.concatenate([r.keep for r in refs]))
+    assert total == S_h.shape[0] // w.P
+
+
+@pytest.mark.parametrize("make", CASES)
+def test_gather_compact(make):
+    w = make()
+    ld = w.D + (32 if w.dtype == W.BF16 else 16)
+    Xd, cu_dev, desc, ws = setup(w, ld)
+    rng = np.random.default_rng(3)
+    keeps = [np.sort(rng.permutation(int(n))[:w.budget(b)]).astype(np.int32)
+             for b, n in enumerate(w.lengths)]
+    keep = torch.from_numpy(np.concatenate(keeps)).cuda()
+    tk = keep.numel()
+    pos_h = rng.integers(-2**40, 2**40, size=int(w.cu[-1])).astype(np.int64)
+    Y = torch.zeros((tk, w.D), dtype=Xd.dtype, device="cuda")
+    pos_out = torch.zeros(tk, dtype=torch.int64, device="cuda")
+    D.dart_gather_compact(desc, Xd, keep, Y, ws, pos=torch.from_numpy(pos_h).cuda(),
+                          pos_out=pos_out)
+    torch.cuda.synchronize()
+    Yh, k0 = G.bits(Y), 0
+    for b, kp in enumerate(keeps):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        Yr, pr = oracle.gather(w.X[lo:hi], w.dtype, pos_h[lo:hi], kp)
+        assert Yh[k0:k0 + len(kp)].tobytes() == Yr.tobytes()
+        np.testing.assert_array_equal(pos_out.cpu().numpy()[k0:k0 + len(kp)], pr)
+        k0 += len(kp)
