@@ -32,7 +32,7 @@ SMALL = [
     lambda: W.image_batch(B=2, N=333, D=3584, P=8, K=129, n_centroids=32),     # remainder rule
     lambda: W.multicrop_batch(B=2, N=700, D=2048, P=16, K=80, n_centroids=64),  # exact copies
     lambda: W.multicrop_batch(B=1, N=1000, D=520, P=20, K=111, n_centroids=64),  # D % 256 != 0
-    lambda: W.ragged_batch(B=5, n_lo=100, n_hi=900, D=1024, P=16),
+    lambda: W.ragged_batch(B=5, n_lo=200, n_hi=900, D=1024, P=16),
     lambda: W.video_batch(B=2, frames=8, per_frame=60, D=1024, P=32, K=96, n_centroids=8),
     lambda: W.video_batch(B=1, frames=6, per_frame=50, D=512, P=40, K=100, n_centroids=8),
 ]
