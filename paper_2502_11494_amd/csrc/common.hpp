@@ -122,37 +122,46 @@ __device__ __forceinline__ int wave_excl_scan(int v, int lane) {
 }
 
 // ---- fp64 re-evaluation of one row (used where an fp32 decision is too close) ----
-// Each lane walks the row in 16-byte pieces, lane-strided, one fp64 chain per
-// quantity; the butterfly makes the result a pure function of the row's bytes.
+// Each lane walks the row in 16-byte pieces, lane-strided (piece t belongs to lane
+// t % 64), eight loads in flight at a time, one fp64 chain per quantity in piece
+// order; the butterfly makes the result a pure function of the row's bytes.
+
+template <int DT>
+__device__ __forceinline__ void piece_to_f64(const u32x4& v, double (&x)[8]) {
+  if (DT == kBF16) {
+    x[0] = (double)bf16_lo(v.x); x[1] = (double)bf16_hi(v.x);
+    x[2] = (double)bf16_lo(v.y); x[3] = (double)bf16_hi(v.y);
+    x[4] = (double)bf16_lo(v.z); x[5] = (double)bf16_hi(v.z);
+    x[6] = (double)bf16_lo(v.w); x[7] = (double)bf16_hi(v.w);
+  } else {
+    x[0] = (double)__uint_as_float(v.x); x[1] = (double)__uint_as_float(v.y);
+    x[2] = (double)__uint_as_float(v.z); x[3] = (double)__uint_as_float(v.w);
+    x[4] = x[5] = x[6] = x[7] = 0.0;
+  }
+}
 
 template <int DT>
 __device__ __forceinline__ void row_l1_l2_f64(const void* row, int D, int lane, double& l1,
                                               double& l2) {
+  const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
+  const u32x4* p = reinterpret_cast<const u32x4*>(row);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
   double a = 0.0, b = 0.0;
-  if (DT == kBF16) {
-    const u32x4* p = reinterpret_cast<const u32x4*>(row);
-    for (int t = lane; t < D / 8; t += kWave) {
-      u32x4 v = p[t];
-      uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
+    u32x4 v[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        double x0 = (double)bf16_lo(w[e]), x1 = (double)bf16_hi(w[e]);
-        a += fabs(x0);
-        a += fabs(x1);
-        b = fma(x0, x0, b);
-        b = fma(x1, x1, b);
-      }
+    for (int u = 0; u < 8; ++u) {
+      int t = t0 + u * kWave + lane;
+      v[u] = t < pieces ? p[t] : zero;
     }
-  } else {
-    const f32x4v* p = reinterpret_cast<const f32x4v*>(row);
-    for (int t = lane; t < D / 4; t += kWave) {
-      f32x4v v = p[t];
-      float w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        double x = (double)w[e];
-        a += fabs(x);
-        b = fma(x, x, b);
+    for (int u = 0; u < 8; ++u) {
+      double x[8];
+      piece_to_f64<DT>(v[u], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        a += fabs(x[e]);
+        b = fma(x[e], x[e], b);
       }
     }
   }
@@ -164,37 +173,29 @@ __device__ __forceinline__ void row_l1_l2_f64(const void* row, int D, int lane, 
 template <int DT>
 __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* xrow, int D,
                                                  int lane) {
+  const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
+  const u32x4* p = reinterpret_cast<const u32x4*>(prow);
+  const u32x4* x = reinterpret_cast<const u32x4*>(xrow);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
   double dot = 0.0, pp = 0.0, xx = 0.0;
-  if (DT == kBF16) {
-    const u32x4* p = reinterpret_cast<const u32x4*>(prow);
-    const u32x4* x = reinterpret_cast<const u32x4*>(xrow);
-    for (int t = lane; t < D / 8; t += kWave) {
-      u32x4 pv = p[t], xv = x[t];
-      uint32_t pw[4] = {pv.x, pv.y, pv.z, pv.w}, xw[4] = {xv.x, xv.y, xv.z, xv.w};
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 4) {
+    u32x4 pv[4], xv[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        double p0 = (double)bf16_lo(pw[e]), p1 = (double)bf16_hi(pw[e]);
-        double x0 = (double)bf16_lo(xw[e]), x1 = (double)bf16_hi(xw[e]);
-        dot = fma(p0, x0, dot);
-        dot = fma(p1, x1, dot);
-        pp = fma(p0, p0, pp);
-        pp = fma(p1, p1, pp);
-        xx = fma(x0, x0, xx);
-        xx = fma(x1, x1, xx);
-      }
+    for (int u = 0; u < 4; ++u) {
+      int t = t0 + u * kWave + lane;
+      pv[u] = t < pieces ? p[t] : zero;
+      xv[u] = t < pieces ? x[t] : zero;
     }
-  } else {
-    const f32x4v* p = reinterpret_cast<const f32x4v*>(prow);
-    const f32x4v* x = reinterpret_cast<const f32x4v*>(xrow);
-    for (int t = lane; t < D / 4; t += kWave) {
-      f32x4v pv = p[t], xv = x[t];
-      float pw[4] = {pv.x, pv.y, pv.z, pv.w}, xw[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        double p0 = (double)pw[e], x0 = (double)xw[e];
-        dot = fma(p0, x0, dot);
-        pp = fma(p0, p0, pp);
-        xx = fma(x0, x0, xx);
+    for (int u = 0; u < 4; ++u) {
+      double pe[8], xe[8];
+      piece_to_f64<DT>(pv[u], pe);
+      piece_to_f64<DT>(xv[u], xe);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        dot = fma(pe[e], xe[e], dot);
+        pp = fma(pe[e], pe[e], pp);
+        xx = fma(xe[e], xe[e], xx);
       }
     }
   }
@@ -205,25 +206,89 @@ __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* x
   return den > 0.0 ? dot / den : 0.0;
 }
 
-// ---- block-wide bitonic sort of 64-bit keys in LDS -------------------------------
-// n must be a power of two; all threads of the block must call.
-template <int THREADS>
-__device__ __forceinline__ void block_bitonic_sort(unsigned long long* s, int n, int tid) {
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int t = tid; t < (n >> 1); t += THREADS) {
-        int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-        int l = i | j;
-        unsigned long long a = s[i], b = s[l];
-        bool up = (i & k) == 0;
-        if ((a > b) == up) {
-          s[i] = b;
-          s[l] = a;
-        }
+// ---- block-wide bitonic sort of 64-bit keys -----------------------------------------
+// Thread t keeps elements t, t+THREADS, ... (M of them) in registers.  A
+// compare-exchange at distance j is done in registers when j >= THREADS, by lane
+// shuffles when j < 64, and through LDS (two barriers) only for 64 <= j < THREADS.
+
+template <int THREADS, int M, int JM>
+__device__ __forceinline__ void reg_compare_exchange(unsigned long long (&v)[M], int k, int tid) {
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    if ((m & JM) == 0 && (m | JM) < M) {
+      const bool up = (((m * THREADS + tid) & k) == 0);
+      const unsigned long long a = v[m], b = v[m | JM];
+      if ((a > b) == up) {
+        v[m] = b;
+        v[m | JM] = a;
       }
-      __syncthreads();
     }
   }
+}
+
+// Sorts s[0..n) ascending.  n is a power of two with 64 <= n; n == M*THREADS, or
+// n < THREADS with M == 1.  n must be the same on every thread; all threads call.
+template <int THREADS, int M>
+__device__ __forceinline__ void block_bitonic_sort_m(unsigned long long* s, int n, int tid) {
+  static_assert(M <= 16, "register distances 1..8 are handled");
+  const bool live = (tid & ~(kWave - 1)) < n;  // waves past the data only keep the barriers
+  unsigned long long v[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) v[m] = (m * THREADS + tid < n) ? s[m * THREADS + tid] : ~0ull;
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      if (j >= THREADS) {
+        switch (j / THREADS) {
+          case 1: reg_compare_exchange<THREADS, M, 1>(v, k, tid); break;
+          case 2: reg_compare_exchange<THREADS, M, 2>(v, k, tid); break;
+          case 4: reg_compare_exchange<THREADS, M, 4>(v, k, tid); break;
+          default: reg_compare_exchange<THREADS, M, 8>(v, k, tid); break;
+        }
+      } else if (j < kWave) {
+        if (live) {
+#pragma unroll
+          for (int m = 0; m < M; ++m) {
+            const int e = m * THREADS + tid;
+            const unsigned long long o = __shfl_xor(v[m], j, kWave);
+            const bool keep_min = ((tid & j) == 0) == ((e & k) == 0);
+            v[m] = keep_min ? (v[m] < o ? v[m] : o) : (v[m] > o ? v[m] : o);
+          }
+        }
+      } else {
+        __syncthreads();
+        if (live) {
+#pragma unroll
+          for (int m = 0; m < M; ++m) s[m * THREADS + tid] = v[m];
+        }
+        __syncthreads();
+        if (live) {
+#pragma unroll
+          for (int m = 0; m < M; ++m) {
+            const int e = m * THREADS + tid;
+            const unsigned long long o = s[e ^ j];
+            const bool keep_min = ((tid & j) == 0) == ((e & k) == 0);
+            v[m] = keep_min ? (v[m] < o ? v[m] : o) : (v[m] > o ? v[m] : o);
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int m = 0; m < M; ++m)
+    if (m * THREADS + tid < n) s[m * THREADS + tid] = v[m];
+  __syncthreads();
+}
+
+// n: power of two, 64 <= n <= 16*THREADS, identical on every thread.
+template <int THREADS>
+__device__ __forceinline__ void block_bitonic_sort(unsigned long long* s, int n, int tid) {
+  n = __builtin_amdgcn_readfirstlane(n);
+  if (n <= THREADS) block_bitonic_sort_m<THREADS, 1>(s, n, tid);
+  else if (n == 2 * THREADS) block_bitonic_sort_m<THREADS, 2>(s, n, tid);
+  else if (n == 4 * THREADS) block_bitonic_sort_m<THREADS, 4>(s, n, tid);
+  else if (n == 8 * THREADS) block_bitonic_sort_m<THREADS, 8>(s, n, tid);
+  else block_bitonic_sort_m<THREADS, 16>(s, n, tid);
 }
 
 __device__ __forceinline__ int next_pow2(int v) {

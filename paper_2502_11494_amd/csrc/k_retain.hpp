@@ -1,14 +1,18 @@
-// Retained set of Eq. (9)-(10), one workgroup per sample.
+// Retained set of Eq. (9)-(10), one workgroup of four waves per sample.
 //
 // R starts as the pivots.  Stage i (pivot order) walks pivot i's ascending score
 // list, skips tokens already in R and takes the first quota_i others -- the
 // per-pivot threshold "determined by the reduction ratio".  The walk is pure
-// integer work on the lists k_order_scores prepared.
+// integer work on the lists k_order_scores prepared, 64 entries per step.
 //
-// The scores are fp32 with absolute error <= tau.  A stage's outcome is certain
-// when the last score taken and the first one refused differ by more than 2*tau.
-// Otherwise every candidate within 2*tau of that boundary is re-scored in fp64
-// from its hidden-state row and the stage is decided on (fp64 score, index).
+// All four waves run the same walk redundantly, each on its own copy of the R
+// bitmap, so the common path needs no barrier at all.  They only meet when a
+// decision is too close for fp32:
+// the scores carry an absolute error <= tau, so a stage is certain when the last
+// score taken and the first one refused differ by more than 2*tau.  Otherwise
+// every candidate within 2*tau of that boundary is re-scored in fp64 from its
+// hidden-state row (the waves share these rows out) and the stage is decided on
+// (fp64 score, index).
 #pragma once
 #include "common.hpp"
 
@@ -17,24 +21,17 @@ namespace dart {
 constexpr int kRetThreads = 256;
 constexpr int kRetWaves = kRetThreads / kWave;
 constexpr int kRetWords = kMaxN / 32;
+constexpr int kRetBand = 128;  // boundary-band candidates held in LDS
 
 struct RetainShared {
-  uint32_t R[kRetWords];
-  uint32_t stage[kRetWords];
+  uint32_t R[kRetWaves][kRetWords];
+  int uidx[kRetBand];
+  double us64[kRetBand];
   int wsum[kRetWaves];
-  int cnt;
-  unsigned long long a, b;
 };
 
-__device__ __forceinline__ int block_sum_ret(int v, int tid, int* red) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((tid & 63) == 0) red[tid >> 6] = v;
-  __syncthreads();
-  int s = 0;
-#pragma unroll
-  for (int i = 0; i < kRetWaves; ++i) s += red[i];
-  return s;
+__device__ __forceinline__ bool bit_of(const uint32_t* R, uint32_t j) {
+  return (R[j >> 5] >> (j & 31)) & 1u;
 }
 
 // grid: B blocks of kRetThreads.
@@ -49,6 +46,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     float two_tau) {
   __shared__ RetainShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
   const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
   if (cu_keep_out && tid == 0) {
@@ -58,16 +56,12 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P, k = sm.k;
   const int words = (n + 31) >> 5;
-  for (int t = tid; t < words; t += kRetThreads) {
-    sh.R[t] = 0u;
-    sh.stage[t] = 0u;
+  uint32_t* Rw = sh.R[wave];
+  for (int t = lane; t < words; t += kWave) Rw[t] = 0u;
+  if (lane < P) {
+    int p = piv[b * P + lane];
+    if (p >= 0 && p < n) atomicOr(&Rw[p >> 5], 1u << (p & 31));
   }
-  __syncthreads();
-  if (tid < P) {
-    int p = piv[b * P + tid];
-    if (p >= 0 && p < n) atomicOr(&sh.R[p >> 5], 1u << (p & 31));
-  }
-  __syncthreads();
 
   const int esz = DT == kBF16 ? 2 : 4;
   const long rowbytes = g.ld * esz;
@@ -81,105 +75,128 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     const unsigned long long* list = lists + base;
     int len = filled_after(k, P, i) + 1;
     len = len < n ? len : n;
-    int taken = 0;
+
+    // pass 1: find the last key taken (a) and the first key refused (b)
+    unsigned long long ka = 0ull, kb = 0ull;
     bool have_b = false;
-    for (int pos = 0; pos < len && !have_b; pos += kRetThreads) {
-      const int t = pos + tid;
+    int taken = 0;
+    for (int pos = 0; pos < len && !have_b; pos += kWave) {
+      const int t = pos + lane;
       const unsigned long long e = t < len ? list[t] : 0ull;
-      const uint32_t idx = (uint32_t)e;
-      const bool cand = t < len && !((sh.R[idx >> 5] >> (idx & 31)) & 1u);
+      const bool cand = t < len && !bit_of(Rw, (uint32_t)e);
       const unsigned long long bal = __ballot(cand);
-      if (lane == 0) sh.wsum[wave] = __popcll(bal);
-      __syncthreads();
-      int before = taken, total = 0;
-#pragma unroll
-      for (int w = 0; w < kRetWaves; ++w) {
-        before += w < wave ? sh.wsum[w] : 0;
-        total += sh.wsum[w];
+      const int rank = taken + __popcll(bal & lt_mask);
+      const unsigned long long ma = __ballot(cand && rank == quota - 1);
+      const unsigned long long mb = __ballot(cand && rank == quota);
+      if (ma) ka = __shfl(e, __ffsll((long long)ma) - 1, kWave);
+      if (mb) {
+        kb = __shfl(e, __ffsll((long long)mb) - 1, kWave);
+        have_b = true;
       }
-      const int rank = before + __popcll(bal & ((1ull << lane) - 1ull));
-      if (cand) {
-        if (rank < quota) atomicOr(&sh.stage[idx >> 5], 1u << (idx & 31));
-        if (rank == quota - 1) sh.a = e;
-        if (rank == quota) sh.b = e;
-      }
-      taken += total;
-      have_b = taken > quota;
-      __syncthreads();
+      taken += __popcll(bal);
     }
-    bool certain = true;
-    float fa = 0.f, fb = 0.f;
-    if (have_b && Xb) {
-      fa = mono_inv((uint32_t)(sh.a >> 32));
-      fb = mono_inv((uint32_t)(sh.b >> 32));
-      certain = (fb - fa) > two_tau;
-    }
+    const float fa = mono_inv((uint32_t)(ka >> 32)), fb = mono_inv((uint32_t)(kb >> 32));
+    const bool certain = !(have_b && Xb) || (fb - fa) > two_tau;
     if (certain) {
-      for (int t = tid; t < words; t += kRetThreads) {
-        sh.R[t] |= sh.stage[t];
-        sh.stage[t] = 0u;
+      // pass 2: commit the first `quota` candidates
+      taken = 0;
+      for (int pos = 0; pos < len && taken < quota; pos += kWave) {
+        const int t = pos + lane;
+        const unsigned long long e = t < len ? list[t] : 0ull;
+        const uint32_t idx = (uint32_t)e;
+        const bool cand = t < len && !bit_of(Rw, idx);
+        const unsigned long long bal = __ballot(cand);
+        const int rank = taken + __popcll(bal & lt_mask);
+        if (cand && rank < quota) atomicOr(&Rw[idx >> 5], 1u << (idx & 31));
+        taken += __popcll(bal);
       }
-      __syncthreads();
       continue;
     }
+
     // ---- too close to call in fp32: decide the boundary band in fp64 ----
-    for (int t = tid; t < words; t += kRetThreads) sh.stage[t] = 0u;
-    if (tid == 0) sh.cnt = 0;
-    __syncthreads();
     const float lo = fa - two_tau, hi = fb + two_tau;
-    const float* Srow = S + base;
-    int n_in = 0;
-    for (int j = tid; j < n; j += kRetThreads) {
-      if ((sh.R[j >> 5] >> (j & 31)) & 1u) continue;
-      const float s = Srow[j] + 0.0f;
-      if (s < lo) {  // below the band: certainly among the quota lowest
-        atomicOr(&sh.R[j >> 5], 1u << (j & 31));
-        ++n_in;
-      } else if (s <= hi) {
-        int slot = atomicAdd(&sh.cnt, 1);
-        scr_idx[sm.row0 + slot] = j;
+    int n_in = 0, nU = 0;
+    bool closed = false;  // saw a key above the band: the band lies inside the list
+    for (int pos = 0; pos < len && !closed; pos += kWave) {
+      const int t = pos + lane;
+      const unsigned long long e = t < len ? list[t] : 0ull;
+      const uint32_t idx = (uint32_t)e;
+      const float key = mono_inv((uint32_t)(e >> 32));
+      const bool cand = t < len && !bit_of(Rw, idx);
+      const bool below = cand && key < lo;              // certainly among the quota lowest
+      const bool band = cand && key >= lo && key <= hi;
+      const unsigned long long mband = __ballot(band);
+      if (below) atomicOr(&Rw[idx >> 5], 1u << (idx & 31));
+      n_in += __popcll(__ballot(below));
+      const int slot = nU + __popcll(mband & lt_mask);
+      if (band && slot < kRetBand) sh.uidx[slot] = (int)idx;  // every wave writes the same
+      nU += __popcll(mband);
+      closed = __ballot(t < len && key > hi) != 0ull;
+    }
+    int* uidx = sh.uidx;
+    double* us64 = sh.us64;
+    if ((!closed && len < n) || nU > kRetBand) {
+      // the band may reach past the stored list (or is huge): sweep the whole score row
+      uidx = scr_idx + sm.row0;
+      us64 = scr_f64 + sm.row0;
+      const float* Srow = S + base;
+      nU = 0;
+      for (int j0 = 0; j0 < n; j0 += kWave) {
+        const int j = j0 + lane;
+        const bool cand = j < n && !bit_of(Rw, (uint32_t)j);
+        const float s = cand ? Srow[j] + 0.0f : 0.f;
+        const bool below = cand && s < lo;
+        const bool band = cand && s >= lo && s <= hi;
+        const unsigned long long mband = __ballot(band);
+        if (below) atomicOr(&Rw[j >> 5], 1u << (j & 31));
+        n_in += __popcll(__ballot(below));
+        if (band) uidx[nU + __popcll(mband & lt_mask)] = j;  // every wave writes the same
+        nU += __popcll(mband);
       }
     }
-    const int need = quota - block_sum_ret(n_in, tid, sh.wsum);
-    const int nU = sh.cnt;
+    __syncthreads();  // the band list (LDS or global scratch) is complete and visible
+    const int need = quota - n_in;
     int pi = piv[b * P + i];
     pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
     const unsigned char* prow = Xb + (long)pi * rowbytes;
     for (int u = wave; u < nU; u += kRetWaves) {
-      const int j = scr_idx[sm.row0 + u];
+      const int j = uidx[u];
       const double s64 = row_cosine_f64<DT>(prow, Xb + (long)j * rowbytes, g.D, lane);
-      if (lane == 0) scr_f64[sm.row0 + u] = s64;
+      if (lane == 0) us64[u] = s64;
     }
     __syncthreads();
+    // the `need` lowest of the band by (fp64 score, index) join R, in every wave's copy
     for (int u = tid; u < nU; u += kRetThreads) {
-      const double su = scr_f64[sm.row0 + u];
-      const int ju = scr_idx[sm.row0 + u];
-      int cntb = 0;
-      for (int o = 0; o < nU && cntb < need; ++o) {
-        const double so = scr_f64[sm.row0 + o];
-        const int jo = scr_idx[sm.row0 + o];
-        cntb += (so < su || (so == su && jo < ju)) ? 1 : 0;
+      const double su = us64[u];
+      const int ju = uidx[u];
+      int beaten = 0;
+      for (int o = 0; o < nU && beaten < need; ++o) {
+        const double so = us64[o];
+        const int jo = uidx[o];
+        beaten += (so < su || (so == su && jo < ju)) ? 1 : 0;
       }
-      if (cntb < need) atomicOr(&sh.R[ju >> 5], 1u << (ju & 31));
+      if (beaten < need) {
+#pragma unroll
+        for (int w = 0; w < kRetWaves; ++w) atomicOr(&sh.R[w][ju >> 5], 1u << (ju & 31));
+      }
     }
     __syncthreads();
   }
 
-  // emit the retained indices in ascending order
+  // emit the retained indices in ascending order (each wave reads its own copy)
   const int per = (words + kRetThreads - 1) / kRetThreads;
   const int w0 = tid * per;
   int mine = 0;
-  for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(sh.R[t]);
+  for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(Rw[t]);
   int off = wave_excl_scan(mine, lane);
   const int wtotal = __shfl(off + mine, 63, kWave);
-  __syncthreads();
   if (lane == 0) sh.wsum[wave] = wtotal;
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kRetWaves; ++w) off += w < wave ? sh.wsum[w] : 0;
   int* out = keep + sm.keep0 + off;
   for (int t = w0; t < w0 + per && t < words; ++t) {
-    uint32_t m = sh.R[t];
+    uint32_t m = Rw[t];
     while (m) {
       int bit = __ffs(m) - 1;
       *out++ = t * 32 + bit;

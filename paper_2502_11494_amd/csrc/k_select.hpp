@@ -111,8 +111,8 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     }
   }
   __syncthreads();
-  const int c = sh.count;
-  const int np = next_pow2(c < 2 ? 2 : c);
+  const int c = __builtin_amdgcn_readfirstlane(sh.count);
+  const int np = next_pow2(c < kWave ? kWave : c);
   for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
   __syncthreads();
   block_bitonic_sort<kSelThreads>(sh.buf, np, tid);
