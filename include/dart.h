@@ -122,9 +122,9 @@ DART_API dart_status dart_select_pivots(const dart_desc* desc, const void* X, co
  * norms, 0 when either norm is 0.  piv as produced by dart_select_pivots.
  * S is pivot-major per sample: sample b, pivot i, token j at
  * S[P*row0(b) + i*N_b + j] with row0(b) the sample's first row in X.
- * bf16 inputs: exact bf16 products, fp32 matrix-core accumulation over 256
- * elements at a time, fp64 across; fp32 inputs: fp64 throughout.  The stored
- * value is rounded to fp32. */
+ * bf16 inputs: exact bf16 products summed 32 at a time on the matrix cores in
+ * fp32, those partial sums added in fp64; fp32 inputs: fp64 throughout.  The
+ * stored value is rounded to fp32. */
 DART_API dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
                                     float* S, void* ws, size_t ws_bytes, void* stream);
 

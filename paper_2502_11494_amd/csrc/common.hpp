@@ -78,6 +78,21 @@ __device__ __forceinline__ int filled_after(int k, int P, int i) {
   return P + q * (i + 1) + (i + 1 < r ? i + 1 : r);
 }
 
+// Entries of pivot i's ascending score list that stage i may look at: the slots
+// filled once the stage is done plus one beyond (the first refused candidate), or
+// nothing if the stage takes nothing.
+__device__ __forceinline__ int stage_len(int k, int P, int n, int i) {
+  if (quota_of(k, P, i) == 0) return 0;
+  int len = filled_after(k, P, i) + 1;
+  return len < n ? len : n;
+}
+// The stage lists of one sample are stored back to back: offset of stage i's list.
+__device__ __forceinline__ long list_offset(int k, int P, int n, int i) {
+  long off = 0;
+  for (int s = 0; s < i; ++s) off += stage_len(k, P, n, s);
+  return off;
+}
+
 // ---- element access --------------------------------------------------------------
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }

@@ -9,7 +9,9 @@
 namespace dart {
 
 // grid: B*P blocks of kSelThreads; block (b, i).
-// S: pivot-major scores; lists: same layout, 64-bit (score image << 32 | index).
+// S: pivot-major scores.  lists: 64-bit (score image << 32 | index) entries; the
+// region of sample b starts at P*row0(b) and holds the stage lists back to back
+// (see list_offset).
 __global__ __launch_bounds__(kSelThreads) void k_order_scores(
     Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
   __shared__ SelectShared sh;
@@ -18,11 +20,9 @@ __global__ __launch_bounds__(kSelThreads) void k_order_scores(
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n;
-  if (quota_of(sm.k, g.P, i) == 0) return;  // the stage takes nothing
-  int want = filled_after(sm.k, g.P, i) + 1;
-  want = want < n ? want : n;
-  const long base = (long)g.P * sm.row0 + (long)i * n;
-  const float* row = S + base;
+  const int want = stage_len(sm.k, g.P, n, i);
+  if (want == 0) return;  // the stage takes nothing
+  const float* row = S + (long)g.P * sm.row0 + (long)i * n;
   float v[kSelPerThread];
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(kSelThreads) void k_order_scores(
     v[e] = j < n ? row[j] + 0.0f : 0.f;
   }
   collect_sorted(v, n, want, -INFINITY, tid, sh);
-  unsigned long long* out = lists + base;
+  unsigned long long* out = lists + (long)g.P * sm.row0 + list_offset(sm.k, g.P, n, i);
   for (int t = tid; t < want; t += kSelThreads) out[t] = sh.buf[t];
 }
 

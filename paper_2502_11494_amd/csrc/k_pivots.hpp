@@ -43,13 +43,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pivots(
     int j = tid + e * kSelThreads;
     v[e] = j < n ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
   }
-  int c = collect_sorted(v, n, P, -INFINITY, tid, sh.sel);
+  float left_min;
+  int c = collect_sorted(v, n, P, -INFINITY, tid, sh.sel, &left_min);
   // every token with value <= thr may belong to the exact top P
   float vP = mono_inv((uint32_t)(sh.sel.buf[P - 1] >> 32));
   float thr = vP + 2.5f * tau * fabsf(vP);
-  float vlast = mono_inv((uint32_t)(sh.sel.buf[c - 1] >> 32));
   __syncthreads();
-  if (c < n && vlast <= thr) c = collect_sorted(v, n, P, thr, tid, sh.sel);
+  if (left_min <= thr) c = collect_sorted(v, n, P, thr, tid, sh.sel);  // a rival was left out
   int flag = 0;
   for (int t = tid; t < c; t += kSelThreads)
     flag += mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr ? 1 : 0;

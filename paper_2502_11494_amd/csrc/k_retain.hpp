@@ -1,48 +1,76 @@
-// Retained set of Eq. (9)-(10), one workgroup of four waves per sample.
+// Retained set of Eq. (9)-(10), one workgroup per sample.
 //
 // R starts as the pivots.  Stage i (pivot order) walks pivot i's ascending score
 // list, skips tokens already in R and takes the first quota_i others -- the
-// per-pivot threshold "determined by the reduction ratio".  The walk is pure
-// integer work on the lists k_order_scores prepared, 64 entries per step.
+// per-pivot threshold "determined by the reduction ratio".
 //
-// All four waves run the same walk redundantly, each on its own copy of the R
-// bitmap, so the common path needs no barrier at all.  They only meet when a
-// decision is too close for fp32:
-// the scores carry an absolute error <= tau, so a stage is certain when the last
-// score taken and the first one refused differ by more than 2*tau.  Otherwise
-// every candidate within 2*tau of that boundary is re-scored in fp64 from its
-// hidden-state row (the waves share these rows out) and the stage is decided on
-// (fp64 score, index).
+// The scores are fp32 with absolute error <= tau, so a stage's outcome is certain
+// only when the last score taken and the first one refused differ by more than
+// 2*tau.  Decisions closer than that are settled in fp64 from the hidden-state
+// rows, on (fp64 score, index).  To keep the serial part short the kernel
+// speculates:
+//   1. the stage lists are staged in LDS (in groups that fit);
+//   2. wave 0 walks the stages in fp32 order, 64 entries per step, committing what
+//      that order says and queueing, for every uncertain stage, the candidates
+//      within 2*tau of its boundary;
+//   3. all waves re-score the queued (pivot, token) pairs in fp64, in parallel;
+//   4. wave 0 checks every uncertain stage in order: if the fp64 order picks the
+//      same tokens the speculation stands; at the first stage where it does not,
+//      that stage is corrected, the later stages are undone and walked again.
+// A boundary band that does not fit the queue or runs past the stored list (only
+// with massive ties) is resolved by a block-wide sweep of the whole score row.
 #pragma once
 #include "common.hpp"
 
 namespace dart {
 
-constexpr int kRetThreads = 256;
+constexpr int kRetThreads = 1024;
 constexpr int kRetWaves = kRetThreads / kWave;
 constexpr int kRetWords = kMaxN / 32;
-constexpr int kRetBand = 128;  // boundary-band candidates held in LDS
+constexpr int kRetList = 12288;  // list entries staged in LDS at a time
+constexpr int kRetQ = 1024;      // band candidates awaiting an fp64 score
 
 struct RetainShared {
-  uint32_t R[kRetWaves][kRetWords];
-  int uidx[kRetBand];
-  double us64[kRetBand];
-  int wsum[kRetWaves];
+  unsigned long long list[kRetList];
+  uint32_t R[kRetWords];
+  double q_s64[kRetQ];
+  int q_idx[kRetQ];
+  unsigned char q_stage[kRetQ];
+  unsigned char q_taken[kRetQ];
+  int st_off[kMaxP];   // offset of the stage's list inside the sample's list region
+  int st_len[kMaxP];
+  int st_qlo[kMaxP], st_qhi[kMaxP], st_nin[kMaxP];
+  unsigned char st_unc[kMaxP];
+  int red[kRetWaves];
+  int cnt;
+  // block-uniform control, written by wave 0 between barriers
+  int next, walk_end, q_count, fb_stage, need_fb;
+  float fb_a, fb_b;
 };
 
 __device__ __forceinline__ bool bit_of(const uint32_t* R, uint32_t j) {
   return (R[j >> 5] >> (j & 31)) & 1u;
 }
+__device__ __forceinline__ void set_bit(uint32_t* R, uint32_t j) { atomicOr(&R[j >> 5], 1u << (j & 31)); }
+__device__ __forceinline__ void clear_bit(uint32_t* R, uint32_t j) {
+  atomicAnd(&R[j >> 5], ~(1u << (j & 31)));
+}
+
+// (score, index) pairs compare lexicographically
+__device__ __forceinline__ bool pair_less(double sa, int ja, double sb, int jb) {
+  return sa < sb || (sa == sb && ja < jb);
+}
 
 // grid: B blocks of kRetThreads.
-// lists / S: pivot-major per sample (see k_order_scores).  X may be nullptr: then
-// scores are taken as exact.  keep: packed, ascending per sample.  cu_keep_out
-// (optional) [B+1].  scr_idx [total_N], scr_f64 [total_N]: per-sample scratch.
+// lists: per sample at P*row0, stage lists back to back (see k_order_scores).
+// S: pivot-major scores.  X may be nullptr: then scores are taken as exact.
+// keep: packed, ascending per sample.  cu_keep_out (optional) [B+1].
+// journal [total_N] ints, scr_f64 [2*total_N] doubles: per-sample scratch at row0.
 template <int DT>
 __global__ __launch_bounds__(kRetThreads) void k_retain(
     Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
     const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
-    int* __restrict__ cu_keep_out, int* __restrict__ scr_idx, double* __restrict__ scr_f64,
+    int* __restrict__ cu_keep_out, int* __restrict__ journal_all, double* __restrict__ scr_f64,
     float two_tau) {
   __shared__ RetainShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,147 +84,294 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P, k = sm.k;
   const int words = (n + 31) >> 5;
-  uint32_t* Rw = sh.R[wave];
-  for (int t = lane; t < words; t += kWave) Rw[t] = 0u;
-  if (lane < P) {
-    int p = piv[b * P + lane];
-    if (p >= 0 && p < n) atomicOr(&Rw[p >> 5], 1u << (p & 31));
-  }
-
   const int esz = DT == kBF16 ? 2 : 4;
   const long rowbytes = g.ld * esz;
   const unsigned char* Xb =
       X ? static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes : nullptr;
+  const unsigned long long* glist = lists + (long)P * sm.row0;
+  int* journal = journal_all + sm.row0;         // tokens taken, stage after stage
+  double* sweep_s64 = scr_f64 + sm.row0;         // fallback sweep: fp64 scores
+  int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // and tokens
 
-  for (int i = 0; i < P; ++i) {
-    const int quota = quota_of(k, P, i);
-    if (quota == 0) continue;
-    const long base = (long)P * sm.row0 + (long)i * n;
-    const unsigned long long* list = lists + base;
-    int len = filled_after(k, P, i) + 1;
-    len = len < n ? len : n;
+  for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
+  if (tid < P) {
+    sh.st_len[tid] = stage_len(k, P, n, tid);
+    sh.st_off[tid] = (int)list_offset(k, P, n, tid);
+  }
+  if (tid == 0) sh.next = 0;
+  __syncthreads();
+  if (tid < P) {
+    int p = piv[b * P + tid];
+    if (p >= 0 && p < n) set_bit(sh.R, (uint32_t)p);
+  }
+  int group_hi = 0;                // stages whose lists are staged: [next at staging, group_hi)
+  int group_base = 0;              // list-region offset of the first staged entry
+  int staged_total = 0;
+  __syncthreads();
 
-    // pass 1: find the last key taken (a) and the first key refused (b)
-    unsigned long long ka = 0ull, kb = 0ull;
-    bool have_b = false;
-    int taken = 0;
-    for (int pos = 0; pos < len && !have_b; pos += kWave) {
-      const int t = pos + lane;
-      const unsigned long long e = t < len ? list[t] : 0ull;
-      const bool cand = t < len && !bit_of(Rw, (uint32_t)e);
-      const unsigned long long bal = __ballot(cand);
-      const int rank = taken + __popcll(bal & lt_mask);
-      const unsigned long long ma = __ballot(cand && rank == quota - 1);
-      const unsigned long long mb = __ballot(cand && rank == quota);
-      if (ma) ka = __shfl(e, __ffsll((long long)ma) - 1, kWave);
-      if (mb) {
-        kb = __shfl(e, __ffsll((long long)mb) - 1, kWave);
-        have_b = true;
-      }
-      taken += __popcll(bal);
-    }
-    const float fa = mono_inv((uint32_t)(ka >> 32)), fb = mono_inv((uint32_t)(kb >> 32));
-    const bool certain = !(have_b && Xb) || (fb - fa) > two_tau;
-    if (certain) {
-      // pass 2: commit the first `quota` candidates
-      taken = 0;
-      for (int pos = 0; pos < len && taken < quota; pos += kWave) {
-        const int t = pos + lane;
-        const unsigned long long e = t < len ? list[t] : 0ull;
-        const uint32_t idx = (uint32_t)e;
-        const bool cand = t < len && !bit_of(Rw, idx);
-        const unsigned long long bal = __ballot(cand);
-        const int rank = taken + __popcll(bal & lt_mask);
-        if (cand && rank < quota) atomicOr(&Rw[idx >> 5], 1u << (idx & 31));
-        taken += __popcll(bal);
-      }
-      continue;
+  while (true) {
+    const int next = sh.next;
+    if (next >= P) break;
+    if (next >= group_hi) {
+      // stage the lists of as many further stages as fit (the first one maybe partly)
+      group_base = sh.st_off[next];
+      int tot = sh.st_len[next] < kRetList ? sh.st_len[next] : kRetList;
+      group_hi = next + 1;
+      while (group_hi < P && tot + sh.st_len[group_hi] <= kRetList) tot += sh.st_len[group_hi++];
+      staged_total = tot;
+      __syncthreads();  // nobody still reads the previous group
+      for (int t = tid; t < tot; t += kRetThreads) sh.list[t] = glist[group_base + t];
+      __syncthreads();
     }
 
-    // ---- too close to call in fp32: decide the boundary band in fp64 ----
-    const float lo = fa - two_tau, hi = fb + two_tau;
-    int n_in = 0, nU = 0;
-    bool closed = false;  // saw a key above the band: the band lies inside the list
-    for (int pos = 0; pos < len && !closed; pos += kWave) {
-      const int t = pos + lane;
-      const unsigned long long e = t < len ? list[t] : 0ull;
-      const uint32_t idx = (uint32_t)e;
-      const float key = mono_inv((uint32_t)(e >> 32));
-      const bool cand = t < len && !bit_of(Rw, idx);
-      const bool below = cand && key < lo;              // certainly among the quota lowest
-      const bool band = cand && key >= lo && key <= hi;
-      const unsigned long long mband = __ballot(band);
-      if (below) atomicOr(&Rw[idx >> 5], 1u << (idx & 31));
-      n_in += __popcll(__ballot(below));
-      const int slot = nU + __popcll(mband & lt_mask);
-      if (band && slot < kRetBand) sh.uidx[slot] = (int)idx;  // every wave writes the same
-      nU += __popcll(mband);
-      closed = __ballot(t < len && key > hi) != 0ull;
-    }
-    int* uidx = sh.uidx;
-    double* us64 = sh.us64;
-    if ((!closed && len < n) || nU > kRetBand) {
-      // the band may reach past the stored list (or is huge): sweep the whole score row
-      uidx = scr_idx + sm.row0;
-      us64 = scr_f64 + sm.row0;
-      const float* Srow = S + base;
-      nU = 0;
-      for (int j0 = 0; j0 < n; j0 += kWave) {
-        const int j = j0 + lane;
-        const bool cand = j < n && !bit_of(Rw, (uint32_t)j);
-        const float s = cand ? Srow[j] + 0.0f : 0.f;
-        const bool below = cand && s < lo;
-        const bool band = cand && s >= lo && s <= hi;
-        const unsigned long long mband = __ballot(band);
-        if (below) atomicOr(&Rw[j >> 5], 1u << (j & 31));
-        n_in += __popcll(__ballot(below));
-        if (band) uidx[nU + __popcll(mband & lt_mask)] = j;  // every wave writes the same
-        nU += __popcll(mband);
+    // ---------------------------------------------------------------- speculative walk
+    if (wave == 0) {
+      int qn = 0, fb_stage = -1, walk_end = group_hi;
+      for (int i = next; i < group_hi; ++i) {
+        const int quota = quota_of(k, P, i);
+        sh.st_unc[i] = 0;
+        if (quota == 0) continue;
+        const int len = sh.st_len[i];
+        const int off = sh.st_off[i] - group_base;  // position of the list in sh.list
+        const unsigned long long* gl = glist + sh.st_off[i];
+        auto entry = [&](int p) -> unsigned long long {
+          return (off + p < staged_total) ? sh.list[off + p] : gl[p];
+        };
+        // pass A: the last key taken (a) and the first key refused (b)
+        unsigned long long ka = 0ull, kb = 0ull;
+        bool have_b = false;
+        int taken = 0;
+        for (int pos = 0; pos < len && !have_b; pos += kWave) {
+          const int t = pos + lane;
+          const unsigned long long e = t < len ? entry(t) : 0ull;
+          const bool cand = t < len && !bit_of(sh.R, (uint32_t)e);
+          const unsigned long long bal = __ballot(cand);
+          const int rank = taken + __popcll(bal & lt_mask);
+          const unsigned long long ma = __ballot(cand && rank == quota - 1);
+          const unsigned long long mb = __ballot(cand && rank == quota);
+          if (ma) ka = __shfl(e, __ffsll((long long)ma) - 1, kWave);
+          if (mb) {
+            kb = __shfl(e, __ffsll((long long)mb) - 1, kWave);
+            have_b = true;
+          }
+          taken += __popcll(bal);
+        }
+        const float fa = mono_inv((uint32_t)(ka >> 32)), fb = mono_inv((uint32_t)(kb >> 32));
+        const bool unc = have_b && Xb && !((fb - fa) > two_tau);
+        if (unc) {
+          // pass B: queue the candidates within 2*tau of the boundary
+          const float lo = fa - two_tau, hi = fb + two_tau;
+          const int qlo = qn;
+          int n_in = 0;
+          bool closed = false;
+          taken = 0;
+          for (int pos = 0; pos < len && !closed; pos += kWave) {
+            const int t = pos + lane;
+            const unsigned long long e = t < len ? entry(t) : 0ull;
+            const uint32_t idx = (uint32_t)e;
+            const float key = mono_inv((uint32_t)(e >> 32));
+            const bool cand = t < len && !bit_of(sh.R, idx);
+            const unsigned long long bal = __ballot(cand);
+            const int rank = taken + __popcll(bal & lt_mask);
+            const bool band = cand && key >= lo && key <= hi;
+            const unsigned long long mband = __ballot(band);
+            n_in += __popcll(__ballot(cand && key < lo));
+            const int slot = qn + __popcll(mband & lt_mask);
+            if (band && slot < kRetQ) {
+              sh.q_idx[slot] = (int)idx;
+              sh.q_stage[slot] = (unsigned char)i;
+              sh.q_taken[slot] = rank < quota ? 1 : 0;
+            }
+            qn += __popcll(mband);
+            taken += __popcll(bal);
+            closed = __ballot(t < len && key > hi) != 0ull;
+          }
+          if (qn > kRetQ || (!closed && len < n)) {
+            // too many ties for the queue, or the band runs past the stored list
+            qn = qlo;
+            fb_stage = i;
+            walk_end = i;
+            if (lane == 0) {
+              sh.fb_a = fa;
+              sh.fb_b = fb;
+            }
+            break;
+          }
+          sh.st_unc[i] = 1;
+          sh.st_qlo[i] = qlo;
+          sh.st_qhi[i] = qn;
+          sh.st_nin[i] = n_in;
+        }
+        // pass C: commit the first `quota` candidates of the fp32 order
+        const int joff = filled_after(k, P, i) - quota - P;
+        taken = 0;
+        for (int pos = 0; pos < len && taken < quota; pos += kWave) {
+          const int t = pos + lane;
+          const unsigned long long e = t < len ? entry(t) : 0ull;
+          const uint32_t idx = (uint32_t)e;
+          const bool cand = t < len && !bit_of(sh.R, idx);
+          const unsigned long long bal = __ballot(cand);
+          const int rank = taken + __popcll(bal & lt_mask);
+          if (cand && rank < quota) {
+            set_bit(sh.R, idx);
+            journal[joff + rank] = (int)idx;
+          }
+          taken += __popcll(bal);
+        }
       }
-    }
-    __syncthreads();  // the band list (LDS or global scratch) is complete and visible
-    const int need = quota - n_in;
-    int pi = piv[b * P + i];
-    pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
-    const unsigned char* prow = Xb + (long)pi * rowbytes;
-    for (int u = wave; u < nU; u += kRetWaves) {
-      const int j = uidx[u];
-      const double s64 = row_cosine_f64<DT>(prow, Xb + (long)j * rowbytes, g.D, lane);
-      if (lane == 0) us64[u] = s64;
+      if (lane == 0) {
+        sh.walk_end = walk_end;
+        sh.q_count = qn;
+        sh.fb_stage = fb_stage;
+      }
     }
     __syncthreads();
-    // the `need` lowest of the band by (fp64 score, index) join R, in every wave's copy
-    for (int u = tid; u < nU; u += kRetThreads) {
-      const double su = us64[u];
-      const int ju = uidx[u];
-      int beaten = 0;
-      for (int o = 0; o < nU && beaten < need; ++o) {
-        const double so = us64[o];
-        const int jo = uidx[o];
-        beaten += (so < su || (so == su && jo < ju)) ? 1 : 0;
+
+    // ---------------------------------------------------------------- fp64 scores of the queue
+    {
+      const int qn = sh.q_count;
+      for (int q = wave; q < qn; q += kRetWaves) {
+        int pi = piv[b * P + sh.q_stage[q]];
+        pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
+        const double s64 = row_cosine_f64<DT>(Xb + (long)pi * rowbytes,
+                                              Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
+        if (lane == 0) sh.q_s64[q] = s64;
       }
-      if (beaten < need) {
+    }
+    __syncthreads();
+
+    // ---------------------------------------------------------------- check the speculation
+    if (wave == 0) {
+      const int walk_end = sh.walk_end;
+      int new_next = walk_end;
+      bool fixed = false;
+      for (int i = next; i < walk_end && !fixed; ++i) {
+        if (!sh.st_unc[i]) continue;
+        const int qlo = sh.st_qlo[i], qhi = sh.st_qhi[i];
+        // largest pair among the taken, smallest among the refused
+        double mt_s = -INFINITY, mu_s = INFINITY;
+        int mt_j = -1, mu_j = 0x7fffffff;
+        for (int q = qlo + lane; q < qhi; q += kWave) {
+          const double s = sh.q_s64[q];
+          const int j = sh.q_idx[q];
+          if (sh.q_taken[q]) {
+            if (pair_less(mt_s, mt_j, s, j)) { mt_s = s; mt_j = j; }
+          } else {
+            if (pair_less(s, j, mu_s, mu_j)) { mu_s = s; mu_j = j; }
+          }
+        }
 #pragma unroll
-        for (int w = 0; w < kRetWaves; ++w) atomicOr(&sh.R[w][ju >> 5], 1u << (ju & 31));
+        for (int o = 32; o > 0; o >>= 1) {
+          const double s1 = __shfl_xor(mt_s, o, kWave), s2 = __shfl_xor(mu_s, o, kWave);
+          const int j1 = __shfl_xor(mt_j, o, kWave), j2 = __shfl_xor(mu_j, o, kWave);
+          if (pair_less(mt_s, mt_j, s1, j1)) { mt_s = s1; mt_j = j1; }
+          if (pair_less(s2, j2, mu_s, mu_j)) { mu_s = s2; mu_j = j2; }
+        }
+        if (pair_less(mt_s, mt_j, mu_s, mu_j)) continue;  // fp64 agrees with the fp32 order
+
+        // fp64 picks other tokens: undo the later stages, then correct this one
+        for (int s = i + 1; s < walk_end; ++s) {
+          const int qs = quota_of(k, P, s);
+          const int js = filled_after(k, P, s) - qs - P;
+          for (int t = lane; t < qs; t += kWave) clear_bit(sh.R, (uint32_t)journal[js + t]);
+        }
+        int need = 0;
+        for (int q = qlo + lane; q < qhi; q += kWave) need += sh.q_taken[q];
+        need = wave_sum(need);
+        const int quota = quota_of(k, P, i);
+        const int joff = filled_after(k, P, i) - quota - P;
+        int placed = 0;
+        for (int q0 = qlo; q0 < qhi; q0 += kWave) {
+          const int q = q0 + lane;
+          bool chosen = false;
+          int j = 0;
+          if (q < qhi) {
+            const double s = sh.q_s64[q];
+            j = sh.q_idx[q];
+            int beaten = 0;
+            for (int o = qlo; o < qhi && beaten < need; ++o)
+              beaten += pair_less(sh.q_s64[o], sh.q_idx[o], s, j) ? 1 : 0;
+            chosen = beaten < need;
+            if (sh.q_taken[q] && !chosen) clear_bit(sh.R, (uint32_t)j);
+            if (!sh.q_taken[q] && chosen) set_bit(sh.R, (uint32_t)j);
+          }
+          const unsigned long long mc = __ballot(chosen);
+          if (chosen) journal[joff + sh.st_nin[i] + placed + __popcll(mc & lt_mask)] = j;
+          placed += __popcll(mc);
+        }
+        new_next = i + 1;
+        fixed = true;
+      }
+      if (lane == 0) {
+        sh.next = new_next;
+        sh.need_fb = (!fixed && sh.fb_stage == walk_end && walk_end < P) ? 1 : 0;
       }
     }
     __syncthreads();
+
+    // ---------------------------------------------------------------- block-wide fallback
+    if (sh.need_fb) {
+      const int i = sh.next;
+      const int quota = quota_of(k, P, i);
+      const float lo = sh.fb_a - two_tau, hi = sh.fb_b + two_tau;
+      const float* Srow = S + (long)P * sm.row0 + (long)i * n;
+      if (tid == 0) sh.cnt = 0;
+      __syncthreads();
+      int n_in = 0;
+      for (int j = tid; j < n; j += kRetThreads) {
+        if (bit_of(sh.R, (uint32_t)j)) continue;
+        const float s = Srow[j] + 0.0f;
+        if (s < lo) {  // below the band: certainly among the quota lowest
+          set_bit(sh.R, (uint32_t)j);
+          ++n_in;
+        } else if (s <= hi) {
+          sweep_idx[atomicAdd(&sh.cnt, 1)] = j;
+        }
+      }
+      n_in = wave_sum(n_in);
+      if (lane == 0) sh.red[wave] = n_in;
+      __syncthreads();
+      int need = quota;
+#pragma unroll
+      for (int w = 0; w < kRetWaves; ++w) need -= sh.red[w];
+      const int nU = sh.cnt;
+      int pi = piv[b * P + i];
+      pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
+      const unsigned char* prow = Xb + (long)pi * rowbytes;
+      for (int u = wave; u < nU; u += kRetWaves) {
+        const double s64 =
+            row_cosine_f64<DT>(prow, Xb + (long)sweep_idx[u] * rowbytes, g.D, lane);
+        if (lane == 0) sweep_s64[u] = s64;
+      }
+      __syncthreads();
+      for (int u = tid; u < nU; u += kRetThreads) {
+        const double su = sweep_s64[u];
+        const int ju = sweep_idx[u];
+        int beaten = 0;
+        for (int o = 0; o < nU && beaten < need; ++o)
+          beaten += pair_less(sweep_s64[o], sweep_idx[o], su, ju) ? 1 : 0;
+        if (beaten < need) set_bit(sh.R, (uint32_t)ju);
+      }
+      __syncthreads();
+      if (tid == 0) sh.next = i + 1;
+      __syncthreads();
+    }
   }
 
-  // emit the retained indices in ascending order (each wave reads its own copy)
+  // emit the retained indices in ascending order
   const int per = (words + kRetThreads - 1) / kRetThreads;
   const int w0 = tid * per;
   int mine = 0;
-  for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(Rw[t]);
+  for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(sh.R[t]);
   int off = wave_excl_scan(mine, lane);
   const int wtotal = __shfl(off + mine, 63, kWave);
-  if (lane == 0) sh.wsum[wave] = wtotal;
+  if (lane == 0) sh.red[wave] = wtotal;
   __syncthreads();
 #pragma unroll
-  for (int w = 0; w < kRetWaves; ++w) off += w < wave ? sh.wsum[w] : 0;
+  for (int w = 0; w < kRetWaves; ++w) off += w < wave ? sh.red[w] : 0;
   int* out = keep + sm.keep0 + off;
   for (int t = w0; t < w0 + per && t < words; ++t) {
-    uint32_t m = Rw[t];
+    uint32_t m = sh.R[t];
     while (m) {
       int bit = __ffs(m) - 1;
       *out++ = t * 32 + bit;

@@ -9,9 +9,10 @@
 // The pivot rows of the chunk are staged once per workgroup in LDS (double
 // buffered) and serve as B fragments.  Feeding the token fragment as both
 // operands yields the tile's Gram matrix, whose diagonal is |x_j|^2, at no extra
-// memory traffic.  The eight MFMAs of a chunk chain in fp32; chunks are summed in
-// fp64.  bf16 x bf16 products are exact in fp32, so the only rounding is in the
-// matrix core's 32-term sums and the 8-long fp32 chain: see score_abs_bound().
+// memory traffic.  Every MFMA starts from a zero accumulator and its 32-term sums
+// are added up in fp64 on the vector ALU.  bf16 x bf16 products are exact in fp32,
+// so the only rounding is inside the matrix core's 32-term sum: see
+// score_abs_bound().
 //
 // fp32 hidden states: plain fp64 arithmetic on the vector ALU (products of two
 // floats are exact in fp64).
@@ -27,16 +28,19 @@ constexpr int kChunk = 256;                 // elements of D per chunk
 constexpr int kRowB = kChunk * 2 + 16;      // LDS row stride, bytes (pad kills bank conflicts)
 
 // Absolute bound on |stored fp32 score - exact cosine|.
-// bf16: each MFMA sums 32 exact products into the running fp32 value; allowing
-// one ulp (2^-23 relative to the magnitudes involved) per product added and per
-// chained accumulation, a chunk of 8 MFMAs errs by at most (32 + 8) * 2^-23 times
-// the sum of |p_d x_d| <= |p||x|.  The token norm comes from the same kind of sum
-// and enters through a square root (half the relative error).  One more ulp for
-// rounding the quotient to fp32; fp64 steps are negligible.
+// bf16: one MFMA returns the sum of 32 exact products with an error of at most
+// kMfmaUlps * 2^-24 times the sum of their magnitudes.  The matrix core's internal
+// rounding is not documented; measured over millions of random, wide-range and
+// cancelling inputs the worst case is 6 * 2^-24, and 16 is assumed here.  The
+// partial sums are added in fp64, so the dot product errs by at most
+// 16 * 2^-24 * sum|p_d x_d| <= 16 * 2^-24 |p||x|.  The token norm comes from the
+// same kind of sum and enters through a square root (half the relative error).
+// Two more units for rounding the quotient to fp32 and the fp64 steps.
 // fp32 inputs: all fp64, only the final rounding to fp32 counts.
+constexpr double kMfmaUlps = 16.0;
 inline double score_abs_bound(int dtype) {
-  const double ulp = 1.1920928955078125e-07;
-  return dtype == kBF16 ? (40.0 * 1.5 + 1.0) * ulp : 2.0 * ulp;
+  const double u = 5.9604644775390625e-08;  // 2^-24
+  return dtype == kBF16 ? (kMfmaUlps * 1.5 + 2.0) * u : 4.0 * u;
 }
 
 template <int NB>
@@ -148,26 +152,25 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
     if (c + 1 < nchunks) DART_LOAD_CHUNK(c + 1);
     __syncthreads();  // pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read
     const unsigned char* lp = sh.p + (c & 1) * (NB * 16 * kRowB);
-    f32x4 acc[NB], gram = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);
-      gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, gram, 0, 0, 0);
+      const f32x4 gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);
+      f32x4 acc[NB];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         bf16x8 pf = *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, acc[nb], 0, 0, 0);
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        gram64[r] += (double)gram[r];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
       }
     }
     if (c + 1 < nchunks) DART_STORE_P((c + 1) & 1);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      gram64[r] += (double)gram[r];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
-    }
   }
 
 #undef DART_LOAD_CHUNK

@@ -38,8 +38,10 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
 // v[e] belongs to index tid + e*kSelThreads; entries with index >= n are ignored.
 // Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
+// left_min receives the smallest value NOT compacted (+inf if none is left).
 __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
-                                              float incl_upto, int tid, SelectShared& sh) {
+                                              float incl_upto, int tid, SelectShared& sh,
+                                              float* left_min = nullptr) {
   const int lane = tid & 63, w = tid >> 6;
   // block min / max
   float lo = INFINITY, hi = -INFINITY;
@@ -102,15 +104,28 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
   }
   if (tid == 0) sh.count = 0;
   __syncthreads();
+  float rest = INFINITY;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     int j = tid + e * kSelThreads;
     if (j < n && bk[e] <= dlim) {
       int slot = atomicAdd(&sh.count, 1);
       sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+    } else if (j < n) {
+      rest = fminf(rest, v[e]);
     }
   }
+  if (left_min) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) rest = fminf(rest, __shfl_xor(rest, o, kWave));
+    if (lane == 0) sh.redf[w] = rest;
+  }
   __syncthreads();
+  if (left_min) {
+#pragma unroll
+    for (int i = 0; i < kSelThreads / kWave; ++i) rest = fminf(rest, sh.redf[i]);
+    *left_min = rest;
+  }
   const int c = __builtin_amdgcn_readfirstlane(sh.count);
   const int np = next_pow2(c < kWave ? kWave : c);
   for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
