@@ -67,31 +67,33 @@ __device__ __forceinline__ Sample sample_of(const Geo& g, int b) {
   return s;
 }
 
-// Stage quota of Eq. (9)-(10) under an even split of the K-P non-pivot slots.
-__device__ __forceinline__ int quota_of(int k, int P, int i) {
-  int m = k - P;
-  return m / P + (i < m % P ? 1 : 0);
-}
-// Slots filled once stages 0..i are done, pivots included.
-__device__ __forceinline__ int filled_after(int k, int P, int i) {
-  int m = k - P, q = m / P, r = m % P;
-  return P + q * (i + 1) + (i + 1 < r ? i + 1 : r);
-}
-
-// Entries of pivot i's ascending score list that stage i may look at: the slots
-// filled once the stage is done plus one beyond (the first refused candidate), or
-// nothing if the stage takes nothing.
-__device__ __forceinline__ int stage_len(int k, int P, int n, int i) {
-  if (quota_of(k, P, i) == 0) return 0;
-  int len = filled_after(k, P, i) + 1;
-  return len < n ? len : n;
-}
-// The stage lists of one sample are stored back to back: offset of stage i's list.
-__device__ __forceinline__ long list_offset(int k, int P, int n, int i) {
-  long off = 0;
-  for (int s = 0; s < i; ++s) off += stage_len(k, P, n, s);
-  return off;
-}
+// Even split of the K-P non-pivot slots over the P stages of Eq. (9)-(10): stage i
+// takes q (+1 for the first r stages).  Built once per sample (two divisions).
+struct Split {
+  int P, q, r;
+  __device__ __forceinline__ Split(int k, int P_) : P(P_), q((k - P_) / P_), r((k - P_) % P_) {}
+  __device__ __forceinline__ int quota(int i) const { return q + (i < r ? 1 : 0); }
+  // slots filled once stages 0..i are done, pivots included
+  __device__ __forceinline__ int filled_after(int i) const {
+    return P + q * (i + 1) + (i + 1 < r ? i + 1 : r);
+  }
+  // tokens taken by the stages before stage i (pivots not counted)
+  __device__ __forceinline__ int taken_before(int i) const { return q * i + (i < r ? i : r); }
+  // Entries of pivot i's ascending score list that stage i may look at: the slots
+  // filled once the stage is done plus one beyond (the first refused candidate),
+  // or nothing if the stage takes nothing.
+  __device__ __forceinline__ int stage_len(int n, int i) const {
+    if (quota(i) == 0) return 0;
+    int len = filled_after(i) + 1;
+    return len < n ? len : n;
+  }
+  // The stage lists of one sample are stored back to back: offset of stage i's list.
+  __device__ __forceinline__ long list_offset(int n, int i) const {
+    long off = 0;
+    for (int s = 0; s < i; ++s) off += stage_len(n, s);
+    return off;
+  }
+};
 
 // ---- element access --------------------------------------------------------------
 

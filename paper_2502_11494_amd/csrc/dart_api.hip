@@ -25,8 +25,8 @@ struct Plan {
   long keep_rows_bound;  // upper bound of the total number of retained rows
   int tiles_bound;       // upper bound of the number of 64-row score tiles
   // workspace offsets
-  size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_idx,
-      o_scr_f64, total;
+  size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
+      total;
 };
 
 dart_status make_plan(const dart_desc* d, Plan& p) {
@@ -101,7 +101,6 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   p.o_pl2 = take(sizeof(double) * (size_t)d->B * g.Ppad);
   p.o_S = take(sizeof(float) * (size_t)total * d->P);
   p.o_lists = take(sizeof(unsigned long long) * (size_t)total * d->P);
-  p.o_scr_idx = take(sizeof(int) * (size_t)total);
   p.o_scr_f64 = take(sizeof(double) * 2 * (size_t)total);
   p.total = o;
   return DART_OK;
@@ -199,14 +198,13 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
                           int* cu_keep, void* ws, hipStream_t st) {
   const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype));
   const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
-  int* scr_idx = at<int>(ws, p.o_scr_idx);
   double* scr_f64 = at<double>(ws, p.o_scr_f64);
   if (p.g.dtype == kBF16)
     hipLaunchKernelGGL((k_retain<kBF16>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,
-                       piv, X, keep, cu_keep, scr_idx, scr_f64, two_tau);
+                       piv, X, keep, cu_keep, scr_f64, two_tau);
   else
     hipLaunchKernelGGL((k_retain<kF32>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists, piv,
-                       X, keep, cu_keep, scr_idx, scr_f64, two_tau);
+                       X, keep, cu_keep, scr_f64, two_tau);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

@@ -20,7 +20,8 @@ __global__ __launch_bounds__(kSelThreads) void k_order_scores(
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n;
-  const int want = stage_len(sm.k, g.P, n, i);
+  const Split sp(sm.k, g.P);
+  const int want = sp.stage_len(n, i);
   if (want == 0) return;  // the stage takes nothing
   const float* row = S + (long)g.P * sm.row0 + (long)i * n;
   float v[kSelPerThread];
@@ -30,7 +31,7 @@ __global__ __launch_bounds__(kSelThreads) void k_order_scores(
     v[e] = j < n ? row[j] + 0.0f : 0.f;
   }
   collect_sorted(v, n, want, -INFINITY, tid, sh);
-  unsigned long long* out = lists + (long)g.P * sm.row0 + list_offset(sm.k, g.P, n, i);
+  unsigned long long* out = lists + (long)g.P * sm.row0 + sp.list_offset(n, i);
   for (int t = tid; t < want; t += kSelThreads) out[t] = sh.buf[t];
 }
 

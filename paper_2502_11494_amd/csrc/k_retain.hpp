@@ -30,9 +30,12 @@ constexpr int kRetWords = kMaxN / 32;
 constexpr int kRetList = 12288;  // list entries staged in LDS at a time
 constexpr int kRetQ = 1024;      // band candidates awaiting an fp64 score
 
+constexpr unsigned char kOwnNone = 0xff, kOwnPivot = 0xfe;
+
 struct RetainShared {
   unsigned long long list[kRetList];
   uint32_t R[kRetWords];
+  unsigned char owner[kMaxN];  // stage that took the token (kOwnPivot, kOwnNone)
   double q_s64[kRetQ];
   int q_idx[kRetQ];
   unsigned char q_stage[kRetQ];
@@ -65,12 +68,12 @@ __device__ __forceinline__ bool pair_less(double sa, int ja, double sb, int jb) 
 // lists: per sample at P*row0, stage lists back to back (see k_order_scores).
 // S: pivot-major scores.  X may be nullptr: then scores are taken as exact.
 // keep: packed, ascending per sample.  cu_keep_out (optional) [B+1].
-// journal [total_N] ints, scr_f64 [2*total_N] doubles: per-sample scratch at row0.
+// scr_f64 [2*total_N] doubles: per-sample scratch at row0 (fallback sweep only).
 template <int DT>
 __global__ __launch_bounds__(kRetThreads) void k_retain(
     Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
     const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
-    int* __restrict__ cu_keep_out, int* __restrict__ journal_all, double* __restrict__ scr_f64,
+    int* __restrict__ cu_keep_out, double* __restrict__ scr_f64,
     float two_tau) {
   __shared__ RetainShared sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -89,20 +92,25 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   const unsigned char* Xb =
       X ? static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes : nullptr;
   const unsigned long long* glist = lists + (long)P * sm.row0;
-  int* journal = journal_all + sm.row0;         // tokens taken, stage after stage
   double* sweep_s64 = scr_f64 + sm.row0;         // fallback sweep: fp64 scores
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // and tokens
 
+  const Split sp(k, P);
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
+  for (int t = tid; t < (n + 3) / 4; t += kRetThreads)
+    reinterpret_cast<uint32_t*>(sh.owner)[t] = 0xffffffffu;
   if (tid < P) {
-    sh.st_len[tid] = stage_len(k, P, n, tid);
-    sh.st_off[tid] = (int)list_offset(k, P, n, tid);
+    sh.st_len[tid] = sp.stage_len(n, tid);
+    sh.st_off[tid] = (int)sp.list_offset(n, tid);
   }
   if (tid == 0) sh.next = 0;
   __syncthreads();
   if (tid < P) {
     int p = piv[b * P + tid];
-    if (p >= 0 && p < n) set_bit(sh.R, (uint32_t)p);
+    if (p >= 0 && p < n) {
+      set_bit(sh.R, (uint32_t)p);
+      sh.owner[p] = kOwnPivot;
+    }
   }
   int group_hi = 0;                // stages whose lists are staged: [next at staging, group_hi)
   int group_base = 0;              // list-region offset of the first staged entry
@@ -120,7 +128,19 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       while (group_hi < P && tot + sh.st_len[group_hi] <= kRetList) tot += sh.st_len[group_hi++];
       staged_total = tot;
       __syncthreads();  // nobody still reads the previous group
-      for (int t = tid; t < tot; t += kRetThreads) sh.list[t] = glist[group_base + t];
+      for (int t0 = 0; t0 < tot; t0 += 4 * kRetThreads) {
+        unsigned long long v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int t = t0 + u * kRetThreads + tid;
+          v[u] = t < tot ? glist[group_base + t] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int t = t0 + u * kRetThreads + tid;
+          if (t < tot) sh.list[t] = v[u];
+        }
+      }
       __syncthreads();
     }
 
@@ -128,7 +148,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     if (wave == 0) {
       int qn = 0, fb_stage = -1, walk_end = group_hi;
       for (int i = next; i < group_hi; ++i) {
-        const int quota = quota_of(k, P, i);
+        const int quota = sp.quota(i);
         sh.st_unc[i] = 0;
         if (quota == 0) continue;
         const int len = sh.st_len[i];
@@ -137,57 +157,139 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         auto entry = [&](int p) -> unsigned long long {
           return (off + p < staged_total) ? sh.list[off + p] : gl[p];
         };
-        // pass A: the last key taken (a) and the first key refused (b)
+        // One pass, 256 entries per step: commit the first `quota` candidates of the
+        // fp32 order and find the last key taken (a) and the first key refused (b).
         unsigned long long ka = 0ull, kb = 0ull;
         bool have_b = false;
-        int taken = 0;
-        for (int pos = 0; pos < len && !have_b; pos += kWave) {
-          const int t = pos + lane;
-          const unsigned long long e = t < len ? entry(t) : 0ull;
-          const bool cand = t < len && !bit_of(sh.R, (uint32_t)e);
-          const unsigned long long bal = __ballot(cand);
-          const int rank = taken + __popcll(bal & lt_mask);
-          const unsigned long long ma = __ballot(cand && rank == quota - 1);
-          const unsigned long long mb = __ballot(cand && rank == quota);
-          if (ma) ka = __shfl(e, __ffsll((long long)ma) - 1, kWave);
-          if (mb) {
-            kb = __shfl(e, __ffsll((long long)mb) - 1, kWave);
-            have_b = true;
+        int taken = 0, pos = 0;
+        unsigned long long e[4];
+        bool cand[4];
+        int rank[4];
+        for (; pos < len && !have_b; pos += 4 * kWave) {
+          const bool in_lds = off + pos + 4 * kWave <= staged_total;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int t = pos + c * kWave + lane;
+            if (in_lds) e[c] = sh.list[off + t];
+            else e[c] = t < len ? entry(t) : 0ull;
           }
-          taken += __popcll(bal);
+          unsigned long long bal[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int t = pos + c * kWave + lane;
+            cand[c] = t < len && !bit_of(sh.R, (uint32_t)e[c]);
+            bal[c] = __ballot(cand[c]);
+          }
+          int before = taken;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            rank[c] = before + __popcll(bal[c] & lt_mask);
+            before += __popcll(bal[c]);
+          }
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            if (cand[c] && rank[c] < quota) {
+              set_bit(sh.R, (uint32_t)e[c]);
+              sh.owner[(uint32_t)e[c]] = (unsigned char)i;
+            }
+            const unsigned long long ma = __ballot(cand[c] && rank[c] == quota - 1);
+            const unsigned long long mb = __ballot(cand[c] && rank[c] == quota);
+            if (ma) ka = __shfl(e[c], __ffsll((long long)ma) - 1, kWave);
+            if (mb) {
+              kb = __shfl(e[c], __ffsll((long long)mb) - 1, kWave);
+              have_b = true;
+            }
+          }
+          taken = before;
         }
         const float fa = mono_inv((uint32_t)(ka >> 32)), fb = mono_inv((uint32_t)(kb >> 32));
         const bool unc = have_b && Xb && !((fb - fa) > two_tau);
         if (unc) {
-          // pass B: queue the candidates within 2*tau of the boundary
+          // queue the candidates within 2*tau of the boundary for an fp64 score
           const float lo = fa - two_tau, hi = fb + two_tau;
           const int qlo = qn;
-          int n_in = 0;
+          const int pos0 = pos - 4 * kWave;  // the step that found b; its registers are live
+          // does the band start inside this step?  (some candidate of it lies below the band)
+          bool starts_here = pos0 == 0;
           bool closed = false;
-          taken = 0;
-          for (int pos = 0; pos < len && !closed; pos += kWave) {
-            const int t = pos + lane;
-            const unsigned long long e = t < len ? entry(t) : 0ull;
-            const uint32_t idx = (uint32_t)e;
-            const float key = mono_inv((uint32_t)(e >> 32));
-            const bool cand = t < len && !bit_of(sh.R, idx);
-            const unsigned long long bal = __ballot(cand);
-            const int rank = taken + __popcll(bal & lt_mask);
-            const bool band = cand && key >= lo && key <= hi;
-            const unsigned long long mband = __ballot(band);
-            n_in += __popcll(__ballot(cand && key < lo));
-            const int slot = qn + __popcll(mband & lt_mask);
-            if (band && slot < kRetQ) {
-              sh.q_idx[slot] = (int)idx;
-              sh.q_stage[slot] = (unsigned char)i;
-              sh.q_taken[slot] = rank < quota ? 1 : 0;
+          int need = 0;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int t = pos0 + c * kWave + lane;
+            const float key = mono_inv((uint32_t)(e[c] >> 32));
+            starts_here = starts_here || __ballot(cand[c] && key < lo) != 0ull;
+            closed = closed || __ballot(t < len && key > hi) != 0ull;
+          }
+          if (starts_here) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const float key = mono_inv((uint32_t)(e[c] >> 32));
+              const bool band = cand[c] && key >= lo && key <= hi;
+              const unsigned long long mband = __ballot(band);
+              const int slot = qn + __popcll(mband & lt_mask);
+              if (band && slot < kRetQ) {
+                sh.q_idx[slot] = (int)(uint32_t)e[c];
+                sh.q_stage[slot] = (unsigned char)i;
+                sh.q_taken[slot] = rank[c] < quota ? 1 : 0;
+              }
+              need += __popcll(__ballot(band && rank[c] < quota));
+              qn += __popcll(mband);
             }
-            qn += __popcll(mband);
-            taken += __popcll(bal);
-            closed = __ballot(t < len && key > hi) != 0ull;
+            // the band may go on past this step: nothing there was committed
+            for (int p2 = pos; p2 < len && !closed; p2 += kWave) {
+              const int t = p2 + lane;
+              const unsigned long long e2 = t < len ? entry(t) : 0ull;
+              const float key = mono_inv((uint32_t)(e2 >> 32));
+              const bool band = t < len && !bit_of(sh.R, (uint32_t)e2) && key <= hi;
+              const unsigned long long mband = __ballot(band);
+              const int slot = qn + __popcll(mband & lt_mask);
+              if (band && slot < kRetQ) {
+                sh.q_idx[slot] = (int)(uint32_t)e2;
+                sh.q_stage[slot] = (unsigned char)i;
+                sh.q_taken[slot] = 0;
+              }
+              qn += __popcll(mband);
+              closed = __ballot(t < len && key > hi) != 0ull;
+            }
+          } else {
+            // rare: the band reaches back into earlier steps.  Take the stage's commits
+            // back and scan its list from the start.
+            for (int j = lane; j < n; j += kWave)
+              if (sh.owner[j] == (unsigned char)i) clear_bit(sh.R, (uint32_t)j);
+            closed = false;
+            taken = 0;
+            for (int p2 = 0; p2 < len && !closed; p2 += kWave) {
+              const int t = p2 + lane;
+              const unsigned long long e2 = t < len ? entry(t) : 0ull;
+              const uint32_t idx = (uint32_t)e2;
+              const float key = mono_inv((uint32_t)(e2 >> 32));
+              const bool cnd = t < len && !bit_of(sh.R, idx);
+              const unsigned long long bal = __ballot(cnd);
+              const int rk = taken + __popcll(bal & lt_mask);
+              const bool band = cnd && key >= lo && key <= hi;
+              const unsigned long long mband = __ballot(band);
+              const int slot = qn + __popcll(mband & lt_mask);
+              if (band && slot < kRetQ) {
+                sh.q_idx[slot] = (int)idx;
+                sh.q_stage[slot] = (unsigned char)i;
+                sh.q_taken[slot] = rk < quota ? 1 : 0;
+              }
+              need += __popcll(__ballot(band && rk < quota));
+              qn += __popcll(mband);
+              taken += __popcll(bal);
+              closed = __ballot(t < len && key > hi) != 0ull;
+            }
+            for (int j = lane; j < n; j += kWave)
+              if (sh.owner[j] == (unsigned char)i) set_bit(sh.R, (uint32_t)j);
           }
           if (qn > kRetQ || (!closed && len < n)) {
-            // too many ties for the queue, or the band runs past the stored list
+            // too many ties for the queue, or the band runs past the stored list:
+            // take the stage back and leave it to the block-wide sweep
+            for (int j = lane; j < n; j += kWave)
+              if (sh.owner[j] == (unsigned char)i) {
+                clear_bit(sh.R, (uint32_t)j);
+                sh.owner[j] = kOwnNone;
+              }
             qn = qlo;
             fb_stage = i;
             walk_end = i;
@@ -200,23 +302,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
           sh.st_unc[i] = 1;
           sh.st_qlo[i] = qlo;
           sh.st_qhi[i] = qn;
-          sh.st_nin[i] = n_in;
-        }
-        // pass C: commit the first `quota` candidates of the fp32 order
-        const int joff = filled_after(k, P, i) - quota - P;
-        taken = 0;
-        for (int pos = 0; pos < len && taken < quota; pos += kWave) {
-          const int t = pos + lane;
-          const unsigned long long e = t < len ? entry(t) : 0ull;
-          const uint32_t idx = (uint32_t)e;
-          const bool cand = t < len && !bit_of(sh.R, idx);
-          const unsigned long long bal = __ballot(cand);
-          const int rank = taken + __popcll(bal & lt_mask);
-          if (cand && rank < quota) {
-            set_bit(sh.R, idx);
-            journal[joff + rank] = (int)idx;
-          }
-          taken += __popcll(bal);
+          sh.st_nin[i] = quota - need;
         }
       }
       if (lane == 0) {
@@ -270,34 +356,31 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         if (pair_less(mt_s, mt_j, mu_s, mu_j)) continue;  // fp64 agrees with the fp32 order
 
         // fp64 picks other tokens: undo the later stages, then correct this one
-        for (int s = i + 1; s < walk_end; ++s) {
-          const int qs = quota_of(k, P, s);
-          const int js = filled_after(k, P, s) - qs - P;
-          for (int t = lane; t < qs; t += kWave) clear_bit(sh.R, (uint32_t)journal[js + t]);
+        for (int j = lane; j < n; j += kWave) {
+          const unsigned char o = sh.owner[j];
+          if (o < kOwnPivot && (int)o > i) {
+            clear_bit(sh.R, (uint32_t)j);
+            sh.owner[j] = kOwnNone;
+          }
         }
         int need = 0;
         for (int q = qlo + lane; q < qhi; q += kWave) need += sh.q_taken[q];
         need = wave_sum(need);
-        const int quota = quota_of(k, P, i);
-        const int joff = filled_after(k, P, i) - quota - P;
-        int placed = 0;
-        for (int q0 = qlo; q0 < qhi; q0 += kWave) {
-          const int q = q0 + lane;
-          bool chosen = false;
-          int j = 0;
-          if (q < qhi) {
-            const double s = sh.q_s64[q];
-            j = sh.q_idx[q];
-            int beaten = 0;
-            for (int o = qlo; o < qhi && beaten < need; ++o)
-              beaten += pair_less(sh.q_s64[o], sh.q_idx[o], s, j) ? 1 : 0;
-            chosen = beaten < need;
-            if (sh.q_taken[q] && !chosen) clear_bit(sh.R, (uint32_t)j);
-            if (!sh.q_taken[q] && chosen) set_bit(sh.R, (uint32_t)j);
+        for (int q = qlo + lane; q < qhi; q += kWave) {
+          const double s = sh.q_s64[q];
+          const int j = sh.q_idx[q];
+          int beaten = 0;
+          for (int o = qlo; o < qhi && beaten < need; ++o)
+            beaten += pair_less(sh.q_s64[o], sh.q_idx[o], s, j) ? 1 : 0;
+          const bool chosen = beaten < need;
+          if (sh.q_taken[q] && !chosen) {
+            clear_bit(sh.R, (uint32_t)j);
+            sh.owner[j] = kOwnNone;
           }
-          const unsigned long long mc = __ballot(chosen);
-          if (chosen) journal[joff + sh.st_nin[i] + placed + __popcll(mc & lt_mask)] = j;
-          placed += __popcll(mc);
+          if (!sh.q_taken[q] && chosen) {
+            set_bit(sh.R, (uint32_t)j);
+            sh.owner[j] = (unsigned char)i;
+          }
         }
         new_next = i + 1;
         fixed = true;
@@ -312,7 +395,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     // ---------------------------------------------------------------- block-wide fallback
     if (sh.need_fb) {
       const int i = sh.next;
-      const int quota = quota_of(k, P, i);
+      const int quota = sp.quota(i);
       const float lo = sh.fb_a - two_tau, hi = sh.fb_b + two_tau;
       const float* Srow = S + (long)P * sm.row0 + (long)i * n;
       if (tid == 0) sh.cnt = 0;
