@@ -195,16 +195,16 @@ __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* x
   const u32x4* x = reinterpret_cast<const u32x4*>(xrow);
   const u32x4 zero = {0u, 0u, 0u, 0u};
   double dot = 0.0, pp = 0.0, xx = 0.0;
-  for (int t0 = 0; t0 < pieces; t0 += kWave * 4) {
-    u32x4 pv[4], xv[4];
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
+    u32x4 pv[8], xv[8];  // a whole 8 KiB row pair is in flight at once
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < 8; ++u) {
       int t = t0 + u * kWave + lane;
       pv[u] = t < pieces ? p[t] : zero;
       xv[u] = t < pieces ? x[t] : zero;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < 8; ++u) {
       double pe[8], xe[8];
       piece_to_f64<DT>(pv[u], pe);
       piece_to_f64<DT>(xv[u], xe);
