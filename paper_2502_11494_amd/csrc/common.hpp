@@ -186,6 +186,45 @@ __device__ __forceinline__ void row_l1_l2_f64(const void* row, int D, int lane, 
   l2 = wave_sum(b);
 }
 
+// The same for R rows at once (all their loads in flight together).  Rows past
+// `live` are skipped; each row's result is identical to row_l1_l2_f64's.
+template <int DT, int R>
+__device__ __forceinline__ void rows_l1_l2_f64(const void* const (&row)[R], int live, int D,
+                                               int lane, double (&l1)[R], double (&l2)[R]) {
+  const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  double a[R], b[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) a[r] = b[r] = 0.0;
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
+    u32x4 v[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int t = t0 + u * kWave + lane;
+        v[r][u] = (r < live && t < pieces) ? reinterpret_cast<const u32x4*>(row[r])[t] : zero;
+      }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        double x[8];
+        piece_to_f64<DT>(v[r][u], x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          a[r] += fabs(x[e]);
+          b[r] = fma(x[e], x[e], b[r]);
+        }
+      }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    l1[r] = wave_sum(a[r]);
+    l2[r] = wave_sum(b[r]);
+  }
+}
+
 // Cosine of Eq. (7) between rows p and x in fp64; 0 if either norm is 0.
 template <int DT>
 __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* xrow, int D,
@@ -297,7 +336,27 @@ __device__ __forceinline__ void block_bitonic_sort_m(unsigned long long* s, int 
   __syncthreads();
 }
 
-// n: power of two, 64 <= n <= 16*THREADS, identical on every thread.
+// Plain LDS bitonic sort (one barrier per compare-exchange distance): used only for
+// the huge lists that massive ties or a keep-everything budget produce.
+template <int THREADS>
+__device__ __forceinline__ void block_bitonic_sort_lds(unsigned long long* s, int n, int tid) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (n >> 1); t += THREADS) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const unsigned long long a = s[i], b = s[l];
+        if ((a > b) == ((i & k) == 0)) {
+          s[i] = b;
+          s[l] = a;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// n: power of two, n >= 64, identical on every thread; s holds n keys (LDS).
 template <int THREADS>
 __device__ __forceinline__ void block_bitonic_sort(unsigned long long* s, int n, int tid) {
   n = __builtin_amdgcn_readfirstlane(n);
@@ -305,7 +364,8 @@ __device__ __forceinline__ void block_bitonic_sort(unsigned long long* s, int n,
   else if (n == 2 * THREADS) block_bitonic_sort_m<THREADS, 2>(s, n, tid);
   else if (n == 4 * THREADS) block_bitonic_sort_m<THREADS, 4>(s, n, tid);
   else if (n == 8 * THREADS) block_bitonic_sort_m<THREADS, 8>(s, n, tid);
-  else block_bitonic_sort_m<THREADS, 16>(s, n, tid);
+  else if (n == 16 * THREADS) block_bitonic_sort_m<THREADS, 16>(s, n, tid);
+  else block_bitonic_sort_lds<THREADS>(s, n, tid);
 }
 
 __device__ __forceinline__ int next_pow2(int v) {

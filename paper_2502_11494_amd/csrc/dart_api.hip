@@ -14,6 +14,13 @@
 
 using namespace dart;
 
+#ifndef DART_CH1
+#define DART_CH1 256
+#endif
+#ifndef DART_CH2
+#define DART_CH2 128
+#endif
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -139,7 +146,7 @@ dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
 
 dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float* l1,
                           hipStream_t st) {
-  constexpr int ROWS = 2;
+  constexpr int ROWS = 1;  // one row per wave measured best (more, shorter-lived waves)
   const int rows = p.g.total_N;
   if (rows == 0) return DART_OK;
   const int blocks = (rows + 4 * ROWS - 1) / (4 * ROWS);
@@ -158,12 +165,16 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
   const float tau = (float)l1_rel_bound(p.g.dtype, Dc);
   double* pl2 = at<double>(ws, p.o_pl2);
   double* scr = at<double>(ws, p.o_scr_f64);
-  if (p.g.dtype == kBF16)
-    hipLaunchKernelGGL((k_select_pivots<kBF16>), dim3(p.g.B), dim3(kSelThreads), 0, st, p.g, X, C,
-                       Dc, ldc, l1, piv, pl2, scr, tau);
-  else
-    hipLaunchKernelGGL((k_select_pivots<kF32>), dim3(p.g.B), dim3(kSelThreads), 0, st, p.g, X, C,
-                       Dc, ldc, l1, piv, pl2, scr, tau);
+  const bool small = false;  // the 256-thread variant measured slower even for short samples
+#define DART_LAUNCH_PIVOTS(DT, TH)                                                              \
+  hipLaunchKernelGGL((k_select_pivots<DT, TH>), dim3(p.g.B), dim3(TH), 0, st, p.g, X, C, Dc, ldc, \
+                     l1, piv, pl2, scr, tau)
+  if (p.g.dtype == kBF16) {
+    if (small) DART_LAUNCH_PIVOTS(kBF16, 256); else DART_LAUNCH_PIVOTS(kBF16, 1024);
+  } else {
+    if (small) DART_LAUNCH_PIVOTS(kF32, 256); else DART_LAUNCH_PIVOTS(kF32, 1024);
+  }
+#undef DART_LAUNCH_PIVOTS
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -177,10 +188,10 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   } else {
     const dim3 grid(p.tiles_bound), block(256);
     switch (p.g.Ppad / 16) {
-      case 1: hipLaunchKernelGGL((k_scores_bf16<1>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      case 2: hipLaunchKernelGGL((k_scores_bf16<2>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      case 3: hipLaunchKernelGGL((k_scores_bf16<3>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      default: hipLaunchKernelGGL((k_scores_bf16<4>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 1: hipLaunchKernelGGL((k_scores_bf16<1, DART_CH1>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 2: hipLaunchKernelGGL((k_scores_bf16<2, DART_CH2>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 3: hipLaunchKernelGGL((k_scores_bf16<3, 128>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      default: hipLaunchKernelGGL((k_scores_bf16<4, 128>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
     }
   }
   DART_LAUNCH_CHECK();
@@ -188,8 +199,12 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
 }
 
 dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st) {
-  hipLaunchKernelGGL(k_order_scores, dim3(p.g.B * p.g.P), dim3(kSelThreads), 0, st, p.g, S,
-                     at<unsigned long long>(ws, p.o_lists));
+  unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
+  if (false)  // the 256-thread variant measured slower even for short samples
+    hipLaunchKernelGGL(k_order_scores<256>, dim3(p.g.B * p.g.P), dim3(256), 0, st, p.g, S, lists);
+  else
+    hipLaunchKernelGGL(k_order_scores<1024>, dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S,
+                       lists);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

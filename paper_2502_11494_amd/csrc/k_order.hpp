@@ -8,13 +8,16 @@
 
 namespace dart {
 
-// grid: B*P blocks of kSelThreads; block (b, i).
+// grid: B*P blocks of THREADS; block (b, i).  THREADS = 256 when no sample exceeds
+// kSelSmallN tokens, 1024 otherwise.
 // S: pivot-major scores.  lists: 64-bit (score image << 32 | index) entries; the
 // region of sample b starts at P*row0(b) and holds the stage lists back to back
 // (see list_offset).
-__global__ __launch_bounds__(kSelThreads) void k_order_scores(
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_order_scores(
     Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
-  __shared__ SelectShared sh;
+  constexpr int kSelThreads = THREADS;
+  __shared__ SelectShared<THREADS> sh;
   const int tid = threadIdx.x;
   const int b = blockIdx.x / g.P, i = blockIdx.x % g.P;
   const Sample sm = sample_of(g, b);
@@ -28,7 +31,7 @@ __global__ __launch_bounds__(kSelThreads) void k_order_scores(
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     int j = tid + e * kSelThreads;
-    v[e] = j < n ? row[j] + 0.0f : 0.f;
+    v[e] = (e * kSelThreads < n && j < n) ? row[j] + 0.0f : 0.f;
   }
   collect_sorted(v, n, want, -INFINITY, tid, sh);
   unsigned long long* out = lists + (long)g.P * sm.row0 + sp.list_offset(n, i);

@@ -14,21 +14,24 @@ namespace dart {
 
 constexpr int kPivLdsCand = 512;  // candidates whose fp64 norms fit in LDS
 
+template <int THREADS>
 struct PivotShared {
-  SelectShared sel;
+  SelectShared<THREADS> sel;
   double c64[kPivLdsCand];
   double l2[kPivLdsCand];
 };
 
-// grid: B blocks of kSelThreads.
+// grid: B blocks of THREADS (256 when no sample exceeds kSelSmallN tokens, else 1024).
 // l1 [total_N] fp32 criterion norms; piv [B*P]; pl2 [B*Ppad] squared L2 norms of
 // the pivots' hidden-state rows (0 for padding slots); scr [2*total_N] doubles.
-template <int DT>
-__global__ __launch_bounds__(kSelThreads) void k_select_pivots(
+template <int DT, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_select_pivots(
     Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
     const float* __restrict__ l1, int* __restrict__ piv, double* __restrict__ pl2,
     double* __restrict__ scr, float tau) {
-  __shared__ PivotShared sh;
+  constexpr int kSelThreads = THREADS;
+  constexpr int kSelWaves = THREADS / kWave;
+  __shared__ PivotShared<THREADS> sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pivots(
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     int j = tid + e * kSelThreads;
-    v[e] = j < n ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
+    v[e] = (e * kSelThreads < n && j < n) ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
   }
   float left_min;
   int c = collect_sorted(v, n, P, -INFINITY, tid, sh.sel, &left_min);
@@ -53,24 +56,38 @@ __global__ __launch_bounds__(kSelThreads) void k_select_pivots(
   int flag = 0;
   for (int t = tid; t < c; t += kSelThreads)
     flag += mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr ? 1 : 0;
-  const int nU = block_sum(flag, tid, sh.sel.redi);  // a prefix of the sorted list
+  const int nU = block_sum<THREADS>(flag, tid, sh.sel.redi);  // a prefix of the sorted list
 
   double* c64 = nU <= kPivLdsCand ? sh.c64 : scr + sm.row0;
   double* l2s = nU <= kPivLdsCand ? sh.l2 : scr + g.total_N + sm.row0;
   const int esz = DT == kBF16 ? 2 : 4;
   const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * g.ld * esz;
   const unsigned char* Cb = static_cast<const unsigned char*>(C) + (long)sm.row0 * ldc * esz;
-  for (int u = w; u < nU; u += kSelThreads / kWave) {
-    int j = (int)(uint32_t)sh.sel.buf[u];
-    double a, q;
-    row_l1_l2_f64<DT>(Cb + (long)j * ldc * esz, Dc, lane, a, q);
+  // R candidates per wave at a time: 16 rows in flight per block with 4 or 16 waves
+  constexpr int R = 16 / kSelWaves;
+  for (int u0 = w * R; u0 < nU; u0 += kSelWaves * R) {
+    const int live = nU - u0 < R ? nU - u0 : R;
+    const void* crow[R];
+    const void* xrow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int j = (int)(uint32_t)sh.sel.buf[u0 + (r < live ? r : 0)];
+      crow[r] = Cb + (long)j * ldc * esz;
+      xrow[r] = Xb + (long)j * g.ld * esz;
+    }
+    double a[R], q[R];
+    rows_l1_l2_f64<DT, R>(crow, live, Dc, lane, a, q);
     if (C != X) {
-      double dummy;
-      row_l1_l2_f64<DT>(Xb + (long)j * g.ld * esz, g.D, lane, dummy, q);
+      double dummy[R];
+      rows_l1_l2_f64<DT, R>(xrow, live, g.D, lane, dummy, q);
     }
     if (lane == 0) {
-      c64[u] = g.mode == kMaxL1 ? -a : a;
-      l2s[u] = q;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (r < live) {
+          c64[u0 + r] = g.mode == kMaxL1 ? -a[r] : a[r];
+          l2s[u0 + r] = q[r];
+        }
     }
   }
   __syncthreads();

@@ -3,9 +3,10 @@
 //
 // bf16 hidden states: the tokens x pivots x D contraction runs on the matrix
 // cores (v_mfma_f32_16x16x32_bf16).  A workgroup of 4 waves owns 64 token rows;
-// a wave owns 16 of them and walks D in chunks of 256 elements:
-//   HBM -> registers (two rows per load instruction, 512 B contiguous each)
-//       -> LDS (row-padded) -> MFMA A fragments (ds_read_b128, conflict-free).
+// a wave owns 16 of them and walks D in chunks of 128 or 256 elements:
+//   HBM -> registers (two or four rows per load instruction, 256-512 B contiguous
+//       each, two chunks ahead) -> LDS (row-padded) -> MFMA A fragments
+//       (ds_read_b128, conflict-free).
 // The pivot rows of the chunk are staged once per workgroup in LDS (double
 // buffered) and serve as B fragments.  Feeding the token fragment as both
 // operands yields the tile's Gram matrix, whose diagonal is |x_j|^2, at no extra
@@ -24,9 +25,6 @@ namespace dart {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kChunk = 256;                 // elements of D per chunk
-constexpr int kRowB = kChunk * 2 + 16;      // LDS row stride, bytes (pad kills bank conflicts)
-
 // Absolute bound on |stored fp32 score - exact cosine|.
 // bf16: one MFMA returns the sum of 32 exact products with an error of at most
 // kMfmaUlps * 2^-24 times the sum of their magnitudes.  The matrix core's internal
@@ -43,10 +41,13 @@ inline double score_abs_bound(int dtype) {
   return dtype == kBF16 ? (kMfmaUlps * 1.5 + 2.0) * u : 4.0 * u;
 }
 
-template <int NB>
+// LDS of one workgroup: CH = elements of D per chunk; rows are padded by 16 bytes
+// so that the 16-row x 64-byte fragment reads hit distinct banks.
+template <int NB, int CH>
 struct ScoreShared {
-  unsigned char a[4 * 16 * kRowB];        // per-wave token chunk
-  unsigned char p[2 * NB * 16 * kRowB];   // pivot chunk, double buffered
+  static constexpr int kRowB = CH * 2 + 16;
+  unsigned char a[4 * 16 * kRowB];       // per-wave token chunk
+  unsigned char p[2 * NB * 16 * kRowB];  // pivot chunk, double buffered
   int pivrow[NB * 16];
 };
 
@@ -70,13 +71,21 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
 }
 
 // grid: number of 64-row tiles (dense: B*ceil(N/64); ragged: an upper bound).
-// NB = Ppad/16 pivot column blocks.
-template <int NB>
+// NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256).
+// Token chunks are prefetched two ahead in registers (the only HBM traffic);
+// the pivot chunk one ahead.
+template <int NB, int CH>
 __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv,
                                                      const double* __restrict__ pl2,
                                                      float* __restrict__ S) {
-  __shared__ __align__(16) ScoreShared<NB> sh;
+  constexpr int kRowB = CH * 2 + 16;   // LDS row stride, bytes
+  constexpr int PC = CH / 8;           // 16-byte pieces per row per chunk
+  constexpr int RPI = kWave / PC;      // rows covered by one load instruction
+  constexpr int LA = 16 / RPI;         // token loads per lane per chunk
+  constexpr int LP = NB * PC / 16;     // pivot loads per thread per chunk
+  constexpr int KS = CH / 32;          // MFMA k-steps per chunk
+  __shared__ __align__(16) ScoreShared<NB, CH> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
   if (!locate_tile(g, blockIdx.x, b, tl)) return;
@@ -92,43 +101,48 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
 
   const long rowbytes = g.ld * 2;
   const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes;
-  const int pieces = g.D / 8;                 // 16-byte pieces per row
-  const int nchunks = (g.D + kChunk - 1) / kChunk;
-  const int col16 = lane & 31;
+  const int pieces = g.D / 8;  // 16-byte pieces per row
+  const int nchunks = (g.D + CH - 1) / CH;
+  const int col16 = lane % PC, rowsub = lane / PC;
   const int j0 = tl * kTileRows + wave * 16;
   const u32x4 zero = {0u, 0u, 0u, 0u};
 
-  // token loads: instruction t covers rows 2t and 2t+1 of the wave's 16
-  const unsigned char* aptr[8];
+  // token loads: instruction t covers rows t*RPI .. t*RPI+RPI-1 of the wave's 16
+  const unsigned char* aptr[LA];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    int r = j0 + 2 * t + (lane >> 5);
+  for (int t = 0; t < LA; ++t) {
+    int r = j0 + t * RPI + rowsub;
     r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
     aptr[t] = Xb + (long)r * rowbytes + col16 * 16;
   }
-  // pivot loads: piece id = tid + 256*k -> pivot row id/32, piece id%32 (== col16)
-  const unsigned char* pptr[2 * NB];
+  // pivot loads: piece id = tid + 256*k -> pivot row id/PC, piece id%PC (== col16)
+  const unsigned char* pptr[LP];
 #pragma unroll
-  for (int k = 0; k < 2 * NB; ++k) {
-    int pr = sh.pivrow[(tid + 256 * k) >> 5];
+  for (int k = 0; k < LP; ++k) {
+    int pr = sh.pivrow[(tid + 256 * k) / PC];
     pptr[k] = pr >= 0 ? Xb + (long)pr * rowbytes + col16 * 16 : nullptr;
   }
 
-  u32x4 ra[8], rp[2 * NB];
-#define DART_LOAD_CHUNK(c)                                                              \
-  {                                                                                     \
-    const bool in_ = (c) * 32 + col16 < pieces;                                         \
-    const long off_ = (long)(c) * (kChunk * 2);                                         \
-    _Pragma("unroll") for (int t = 0; t < 8; ++t) ra[t] =                               \
-        in_ ? *reinterpret_cast<const u32x4*>(aptr[t] + off_) : zero;                   \
-    _Pragma("unroll") for (int k = 0; k < 2 * NB; ++k) rp[k] =                          \
-        (in_ && pptr[k]) ? *reinterpret_cast<const u32x4*>(pptr[k] + off_) : zero;      \
+  u32x4 ra[2][LA], rp[LP];
+#define DART_LOAD_A(c, buf)                                                         \
+  {                                                                                 \
+    const bool in_ = (c) * PC + col16 < pieces;                                     \
+    const long off_ = (long)(c) * (CH * 2);                                         \
+    _Pragma("unroll") for (int t = 0; t < LA; ++t) ra[buf][t] =                     \
+        in_ ? *reinterpret_cast<const u32x4*>(aptr[t] + off_) : zero;               \
   }
-#define DART_STORE_P(buf)                                                               \
-  {                                                                                     \
-    _Pragma("unroll") for (int k = 0; k < 2 * NB; ++k)                                  \
-        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                    \
-                                  ((tid + 256 * k) >> 5) * kRowB + col16 * 16) = rp[k]; \
+#define DART_LOAD_P(c)                                                              \
+  {                                                                                 \
+    const bool in_ = (c) * PC + col16 < pieces;                                     \
+    const long off_ = (long)(c) * (CH * 2);                                         \
+    _Pragma("unroll") for (int k = 0; k < LP; ++k) rp[k] =                          \
+        (in_ && pptr[k]) ? *reinterpret_cast<const u32x4*>(pptr[k] + off_) : zero;  \
+  }
+#define DART_STORE_P(buf)                                                           \
+  {                                                                                 \
+    _Pragma("unroll") for (int k = 0; k < LP; ++k)                                  \
+        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                \
+                                  ((tid + 256 * k) / PC) * kRowB + col16 * 16) = rp[k]; \
   }
 
   double acc64[NB][4], gram64[4];
@@ -141,39 +155,47 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
 
   unsigned char* la = sh.a + wave * (16 * kRowB);
   const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
+  const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
 
-  DART_LOAD_CHUNK(0);
-  DART_STORE_P(0);
-  for (int c = 0; c < nchunks; ++c) {
-    // the wave's own LDS region: in-order LDS ops within a wave make this safe
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-      *reinterpret_cast<u32x4*>(la + (2 * t + (lane >> 5)) * kRowB + col16 * 16) = ra[t];
-    if (c + 1 < nchunks) DART_LOAD_CHUNK(c + 1);
-    __syncthreads();  // pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read
-    const unsigned char* lp = sh.p + (c & 1) * (NB * 16 * kRowB);
-    const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);
-      const f32x4 gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);
-      f32x4 acc[NB];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        bf16x8 pf = *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        gram64[r] += (double)gram[r];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
-      }
-    }
-    if (c + 1 < nchunks) DART_STORE_P((c + 1) & 1);
+  // One chunk: the wave's rows go registers -> its own LDS region (in-order LDS ops
+  // within a wave make that safe), the freed registers take the chunk two ahead,
+  // the pivot registers the next chunk; then MFMAs on chunk c.
+#define DART_CHUNK(c, buf)                                                                     \
+  {                                                                                            \
+    _Pragma("unroll") for (int t = 0; t < LA; ++t)                                             \
+        *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) = ra[buf][t];  \
+    if ((c) + 2 < nchunks) DART_LOAD_A((c) + 2, buf);                                          \
+    if ((c) + 1 < nchunks) DART_LOAD_P((c) + 1);                                               \
+    __syncthreads(); /* pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read */      \
+    const unsigned char* lp = sh.p + ((c) & 1) * (NB * 16 * kRowB);                            \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                           \
+      bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);                    \
+      const f32x4 gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);      \
+      f32x4 acc[NB];                                                                           \
+      _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                      \
+        bf16x8 pf =                                                                            \
+            *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);      \
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);             \
+      }                                                                                        \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                          \
+        gram64[r] += (double)gram[r];                                                          \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];  \
+      }                                                                                        \
+    }                                                                                          \
+    if ((c) + 1 < nchunks) DART_STORE_P(((c) + 1) & 1);                                        \
   }
 
-#undef DART_LOAD_CHUNK
+  DART_LOAD_A(0, 0);
+  if (nchunks > 1) DART_LOAD_A(1, 1);
+  DART_LOAD_P(0);
+  DART_STORE_P(0);
+  for (int c = 0; c < nchunks; c += 2) {
+    DART_CHUNK(c, 0);
+    if (c + 1 < nchunks) DART_CHUNK(c + 1, 1);
+  }
+#undef DART_CHUNK
+#undef DART_LOAD_A
+#undef DART_LOAD_P
 #undef DART_STORE_P
 
   // Output tile: lane holds column (lane&15) and rows 4*(lane>>4)..+3 of each 16x16

@@ -5,25 +5,32 @@
 // bucket d* that holds the want-th lowest value; everything in buckets <= d* is
 // compacted and bitonic-sorted.  Ties need no special care: the composite key is
 // unique, so the sort alone yields (value ascending, index ascending).
+//
+// A thread keeps up to 16 values in registers, so a block of THREADS threads
+// handles n <= 16*THREADS values: 256 threads for samples of up to 4096 tokens
+// (fewer waves = fewer instructions issued per step, cheaper barriers), 1024 beyond.
 #pragma once
 #include "common.hpp"
 
 namespace dart {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelPerThread = kMaxN / kSelThreads;  // 16 values per thread
+constexpr int kSelPerThread = 16;  // values a thread keeps in registers
 constexpr int kSelBuckets = 1024;
+constexpr int kSelSmallN = 256 * kSelPerThread;  // largest sample the 256-thread kernels take
 
+template <int THREADS>
 struct SelectShared {
-  unsigned long long buf[kMaxN];  // compacted keys, then sorted
+  unsigned long long buf[THREADS * kSelPerThread];  // compacted keys, then sorted
   int hist[kSelBuckets];
-  float redf[2 * (kSelThreads / kWave)];
-  int redi[kSelThreads / kWave];
+  float redf[2 * (THREADS / kWave)];
+  float redg[THREADS / kWave];
+  int redi[THREADS / kWave];
   int count;
-  int dstar;
 };
 
+template <int THREADS>
 __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
+  constexpr int kSelWaves = THREADS / kWave;
   const int lane = tid & 63, w = tid >> 6;
   v = wave_sum(v);
   __syncthreads();  // red may still be read from a previous call
@@ -31,23 +38,28 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
   __syncthreads();
   int s = 0;
 #pragma unroll
-  for (int i = 0; i < kSelThreads / kWave; ++i) s += red[i];
+  for (int i = 0; i < kSelWaves; ++i) s += red[i];
   return s;
 }
 
-// v[e] belongs to index tid + e*kSelThreads; entries with index >= n are ignored.
+// v[e] belongs to index tid + e*THREADS (n <= 16*THREADS); entries with index >= n are ignored.
 // Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
 // left_min receives the smallest value NOT compacted (+inf if none is left).
+template <int THREADS>
 __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
-                                              float incl_upto, int tid, SelectShared& sh,
+                                              float incl_upto, int tid, SelectShared<THREADS>& sh,
                                               float* left_min = nullptr) {
+  constexpr int kSelThreads = THREADS;
+  constexpr int kSelWaves = THREADS / kWave;
+  constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
   const int lane = tid & 63, w = tid >> 6;
+  const int ne = __builtin_amdgcn_readfirstlane((n + kSelThreads - 1) / kSelThreads);
   // block min / max
   float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e)
-    if (tid + e * kSelThreads < n) {
+    if (e < ne && tid + e * kSelThreads < n) {
       lo = fminf(lo, v[e]);
       hi = fmaxf(hi, v[e]);
     }
@@ -61,10 +73,11 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     sh.redf[2 * w] = lo;
     sh.redf[2 * w + 1] = hi;
   }
-  sh.hist[tid] = 0;  // kSelBuckets == kSelThreads
+#pragma unroll
+  for (int q = 0; q < kSelBucketsPerThread; ++q) sh.hist[tid + q * kSelThreads] = 0;
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < kSelThreads / kWave; ++i) {
+  for (int i = 0; i < kSelWaves; ++i) {
     lo = fminf(lo, sh.redf[2 * i]);
     hi = fmaxf(hi, sh.redf[2 * i + 1]);
   }
@@ -76,27 +89,32 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     d = d < 0 ? 0 : d;
     return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
   };
-  int bk[kSelPerThread];
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e)
-    if (tid + e * kSelThreads < n) {
-      bk[e] = bucket(v[e]);
-      atomicAdd(&sh.hist[bk[e]], 1);
-    }
+    if (e < ne && tid + e * kSelThreads < n) atomicAdd(&sh.hist[bucket(v[e])], 1);
   __syncthreads();
-  // inclusive scan of the histogram, one bucket per thread
-  int h = sh.hist[tid];
-  int incl = wave_excl_scan(h, lane) + h;
-  if (lane == 63) sh.redi[w] = incl;
-  __syncthreads();
-  int before = 0;
+  // inclusive scan of the histogram: thread t owns kSelBucketsPerThread consecutive buckets
+  int h[kSelBucketsPerThread], mine = 0;
 #pragma unroll
-  for (int i = 0; i < kSelThreads / kWave; ++i)
-    if (i < w) before += sh.redi[i];
-  incl += before;
-  // d* = first bucket whose inclusive count reaches `want`
-  int target = want < n ? want : n;
-  int below = block_sum(incl < target ? 1 : 0, tid, sh.redi);
+  for (int q = 0; q < kSelBucketsPerThread; ++q) {
+    h[q] = sh.hist[tid * kSelBucketsPerThread + q];
+    mine += h[q];
+  }
+  int run = wave_excl_scan(mine, lane);
+  if (lane == 63) sh.redi[w] = run + mine;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelWaves; ++i)
+    if (i < w) run += sh.redi[i];
+  // d* = first bucket whose inclusive count reaches `want` = number of buckets below it
+  const int target = want < n ? want : n;
+  int below = 0;
+#pragma unroll
+  for (int q = 0; q < kSelBucketsPerThread; ++q) {
+    run += h[q];
+    below += run < target ? 1 : 0;
+  }
+  below = block_sum<THREADS>(below, tid, sh.redi);
   int dlim = below;
   if (incl_upto > -INFINITY) {
     int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
@@ -107,23 +125,25 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
   float rest = INFINITY;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
-    int j = tid + e * kSelThreads;
-    if (j < n && bk[e] <= dlim) {
-      int slot = atomicAdd(&sh.count, 1);
-      sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
-    } else if (j < n) {
-      rest = fminf(rest, v[e]);
+    const int j = tid + e * kSelThreads;
+    if (e < ne && j < n) {
+      if (bucket(v[e]) <= dlim) {
+        const int slot = atomicAdd(&sh.count, 1);
+        sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+      } else {
+        rest = fminf(rest, v[e]);
+      }
     }
   }
   if (left_min) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) rest = fminf(rest, __shfl_xor(rest, o, kWave));
-    if (lane == 0) sh.redf[w] = rest;
+    if (lane == 0) sh.redg[w] = rest;
   }
   __syncthreads();
   if (left_min) {
 #pragma unroll
-    for (int i = 0; i < kSelThreads / kWave; ++i) rest = fminf(rest, sh.redf[i]);
+    for (int i = 0; i < kSelWaves; ++i) rest = fminf(rest, sh.redg[i]);
     *left_min = rest;
   }
   const int c = __builtin_amdgcn_readfirstlane(sh.count);
