@@ -7,15 +7,17 @@
 // The scores are fp32 with absolute error <= tau, so a stage's outcome is certain
 // only when the last score taken and the first one refused differ by more than
 // 2*tau.  Decisions closer than that are settled in fp64 from the hidden-state
-// rows, on (fp64 score, index).  To keep the serial part short the kernel
-// speculates:
+// rows, on (fp64 score, index).  The stages depend on each other, so the walk is
+// a serial chain of LDS round trips; to keep it short the kernel speculates:
 //   1. the stage lists are staged in LDS (in groups that fit);
 //   2. the block walks the stages in fp32 order, 256 list entries per step (one per
-//      thread, ranks by ballot + a prefix over the waves), committing what that order
-//      says and queueing, for every uncertain stage, the candidates within 2*tau of
-//      its boundary;
-//   3. the waves re-score the queued (pivot, token) pairs in fp64, in parallel;
-//   4. every uncertain stage is checked: if the fp64 order picks the same tokens
+//      thread, ranks by ballot + a prefix over the waves), committing what that
+//      order says and noting each stage's last key taken and first key refused;
+//   3. the waves then look at the stages in parallel: a stage whose two keys are
+//      within 2*tau is uncertain, and its candidates within 2*tau of the boundary
+//      are queued (who was a candidate is known from the per-token owner stage);
+//   4. the waves re-score the queued (pivot, token) pairs in fp64, in parallel;
+//   5. every uncertain stage is checked: if the fp64 order picks the same tokens
 //      the speculation stands; at the first stage where it does not, that stage is
 //      corrected, the later stages are undone and walked again.
 // A boundary band that does not fit the queue or runs past the stored list (only
@@ -25,7 +27,7 @@
 
 namespace dart {
 
-constexpr int kRetThreads = 256;  // one wave per SIMD: the walk is issue-bound
+constexpr int kRetThreads = 256;  // one wave per SIMD: the walk is latency-bound
 constexpr int kRetWaves = kRetThreads / kWave;
 constexpr int kRetWords = kMaxN / 32;
 constexpr int kRetList = 12288;  // list entries staged in LDS at a time
@@ -42,11 +44,11 @@ struct RetainShared {
   unsigned char q_taken[kRetQ];
   int st_off[kMaxP];  // offset of the stage's list inside the sample's list region
   int st_len[kMaxP];
+  unsigned long long st_ka[kMaxP], st_kb[kMaxP];  // last key taken, first key refused
   int st_qlo[kMaxP], st_qhi[kMaxP];
-  unsigned char st_unc[kMaxP];
+  unsigned char st_has_b[kMaxP], st_unc[kMaxP];
   __attribute__((aligned(16))) int wcnt[2][kRetWaves];
-  unsigned long long ka, kb;
-  int qn, need, cnt, bad_first;
+  int qn, cnt, bad_first, fb_first;
 };
 
 __device__ __forceinline__ bool bit_of(const uint32_t* R, uint32_t j) {
@@ -155,159 +157,159 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         }
       }
     }
-    if (tid == 0) sh.qn = 0;
+    if (tid == 0) {
+      sh.qn = 0;
+      sh.bad_first = group_hi;
+      sh.fb_first = group_hi;
+    }
     __syncthreads();
+    const int walk_end = group_hi;
+    auto entry_of = [&](int i, int p) -> unsigned long long {
+      const int o = sh.st_off[i] - group_base + p;  // position in sh.list
+      if (o < staged_total) return sh.list[o];
+      return glist[sh.st_off[i] + p];
+    };
 
     // ------------------------------------------------------------------ speculative walk
-    int walk_end = group_hi, fb_stage = -1;
-    float fb_a = 0.f, fb_b = 0.f;
-    for (int i = next; i < group_hi; ++i) {
+    for (int i = next; i < walk_end; ++i) {
       const int quota = sp.quota(i);
-      if (tid == 0) sh.st_unc[i] = 0;
-      if (quota == 0) continue;
+      if (quota == 0) {
+        if (tid == 0) sh.st_has_b[i] = 0;
+        continue;
+      }
       const int len = sh.st_len[i];
-      const int off = sh.st_off[i] - group_base;  // position of the list in sh.list
-      const unsigned long long* gl = glist + sh.st_off[i];
-      auto entry = [&](int p) -> unsigned long long {
-        if (off + p < staged_total) return sh.list[off + p];
-        return gl[p];
-      };
-      // commit the first `quota` candidates of the fp32 order; a = last key taken,
-      // b = first key refused
-      bool have_b = false;
-      int taken = 0, pos = 0, rank = 0;
-      unsigned long long e = 0ull;
-      bool cand = false;
+      const int off = sh.st_off[i] - group_base;
       const bool staged = off + len <= staged_total;  // the usual case: plain LDS reads
-      for (; pos < len && !have_b; pos += kRetThreads) {
+      bool have_b = false;
+      int taken = 0;
+      for (int pos = 0; pos < len && !have_b; pos += kRetThreads) {
         const int t = pos + tid;
+        unsigned long long e;
         if (staged) e = t < len ? sh.list[off + t] : 0ull;
-        else e = t < len ? entry(t) : 0ull;
-        cand = t < len && !bit_of(sh.R, (uint32_t)e);
+        else e = t < len ? entry_of(i, t) : 0ull;
+        const bool cand = t < len && !bit_of(sh.R, (uint32_t)e);
         int total;
-        rank = step_rank(cand, taken, total);
+        const int rank = step_rank(cand, taken, total);
         if (cand) {
           if (rank < quota) {
             set_bit(sh.R, (uint32_t)e);
             sh.owner[(uint32_t)e] = (unsigned char)i;
           }
-          if (rank == quota - 1) sh.ka = e;
-          if (rank == quota) sh.kb = e;
+          if (rank == quota - 1) sh.st_ka[i] = e;
+          if (rank == quota) sh.st_kb[i] = e;
         }
         taken += total;
         have_b = taken > quota;
       }
-      __syncthreads();
-      const float fa = mono_inv((uint32_t)(sh.ka >> 32)), fb = mono_inv((uint32_t)(sh.kb >> 32));
-      const bool unc = have_b && Xb && !((fb - fa) > two_tau);
-      if (!unc) continue;
-
-      // queue the candidates within 2*tau of the boundary for an fp64 score
-      const float lo = fa - two_tau, hi = fb + two_tau;
-      const int qlo = sh.qn;
-      const int pos0 = pos - kRetThreads;  // the step that found b; its registers are live
-      const float key = mono_inv((uint32_t)(e >> 32));
-      const bool live = pos0 + tid < len;
-      // does the band start inside this step?  (a candidate of it lies below the band)
-      const bool starts_here = __syncthreads_or((pos0 == 0) || (cand && key < lo));
-      bool closed = __syncthreads_or(live && key > hi);
-      if (tid == 0) sh.need = 0;
-      __syncthreads();
-      if (starts_here) {
-        if (cand && key >= lo && key <= hi) {
-          const int slot = atomicAdd(&sh.qn, 1);
-          if (slot < kRetQ) {
-            sh.q_idx[slot] = (int)(uint32_t)e;
-            sh.q_stage[slot] = (unsigned char)i;
-            sh.q_taken[slot] = rank < quota ? 1 : 0;
-          }
-        }
-        // the band may go on past this step: nothing there was committed
-        for (int p2 = pos; p2 < len && !closed; p2 += kRetThreads) {
-          const int t = p2 + tid;
-          const unsigned long long e2 = t < len ? entry(t) : 0ull;
-          const float key2 = mono_inv((uint32_t)(e2 >> 32));
-          if (t < len && !bit_of(sh.R, (uint32_t)e2) && key2 <= hi) {
-            const int slot = atomicAdd(&sh.qn, 1);
-            if (slot < kRetQ) {
-              sh.q_idx[slot] = (int)(uint32_t)e2;
-              sh.q_stage[slot] = (unsigned char)i;
-              sh.q_taken[slot] = 0;
-            }
-          }
-          closed = __syncthreads_or(t < len && key2 > hi);
-        }
-      } else {
-        // rare: the band reaches back into earlier steps.  Take the stage's commits
-        // back and scan its list from the start.
-        for (int j = tid; j < n; j += kRetThreads)
-          if (sh.owner[j] == (unsigned char)i) clear_bit(sh.R, (uint32_t)j);
-        __syncthreads();
-        closed = false;
-        int tk = 0;
-        for (int p2 = 0; p2 < len && !closed; p2 += kRetThreads) {
-          const int t = p2 + tid;
-          const unsigned long long e2 = t < len ? entry(t) : 0ull;
-          const float key2 = mono_inv((uint32_t)(e2 >> 32));
-          const bool c2 = t < len && !bit_of(sh.R, (uint32_t)e2);
-          int total;
-          const int rk = step_rank(c2, tk, total);
-          if (c2 && key2 >= lo && key2 <= hi) {
-            const int slot = atomicAdd(&sh.qn, 1);
-            if (slot < kRetQ) {
-              sh.q_idx[slot] = (int)(uint32_t)e2;
-              sh.q_stage[slot] = (unsigned char)i;
-              sh.q_taken[slot] = rk < quota ? 1 : 0;
-            }
-          }
-          tk += total;
-          closed = __syncthreads_or(t < len && key2 > hi);
-        }
-        for (int j = tid; j < n; j += kRetThreads)
-          if (sh.owner[j] == (unsigned char)i) set_bit(sh.R, (uint32_t)j);
-      }
-      __syncthreads();
-      if (sh.qn > kRetQ || (!closed && len < n)) {
-        // too many ties for the queue, or the band runs past the stored list:
-        // take the stage back and leave it to the block-wide sweep
-        for (int j = tid; j < n; j += kRetThreads)
-          if (sh.owner[j] == (unsigned char)i) {
-            clear_bit(sh.R, (uint32_t)j);
-            sh.owner[j] = kOwnNone;
-          }
-        __syncthreads();
-        if (tid == 0) sh.qn = qlo;
-        fb_stage = i;
-        walk_end = i;
-        fb_a = fa;
-        fb_b = fb;
-        __syncthreads();
-        break;
-      }
-      if (tid == 0) {
-        sh.st_unc[i] = 1;
-        sh.st_qlo[i] = qlo;
-        sh.st_qhi[i] = sh.qn;
-      }
-      __syncthreads();
+      if (tid == 0) sh.st_has_b[i] = have_b ? 1 : 0;
+      __syncthreads();  // this stage's commits are visible before the next stage tests R
     }
+
+    // ------------------------------------------------------------------ uncertain stages
+    // wave w looks at stages next+w, next+w+4, ...; R and owner are only read here
+    for (int i = next + wave; i < walk_end; i += kRetWaves) {
+      bool unc = false;
+      uint32_t lo_m = 0, hi_m = 0;
+      if (Xb && sp.quota(i) > 0 && sh.st_has_b[i]) {
+        const float fa = mono_inv((uint32_t)(sh.st_ka[i] >> 32));
+        const float fb = mono_inv((uint32_t)(sh.st_kb[i] >> 32));
+        unc = !((fb - fa) > two_tau);
+        lo_m = mono_of((fa - two_tau) + 0.0f);
+        hi_m = mono_of((fb + two_tau) + 0.0f);
+      }
+      if (lane == 0) sh.st_unc[i] = unc ? 1 : 0;
+      if (!unc) continue;
+      const int len = sh.st_len[i];
+      // first list position whose key reaches the band (64-ary search on the sorted keys)
+      int lo_pos = 0, span = len;
+      while (span > kWave) {
+        const int stride = (span + kWave - 1) / kWave;
+        const int p = lo_pos + lane * stride;
+        const bool below = p < len && p < lo_pos + span &&
+                           (uint32_t)(entry_of(i, p) >> 32) < lo_m;
+        const int m = __popcll(__ballot(below));
+        if (m > 0) lo_pos += (m - 1) * stride;
+        span = stride;
+      }
+      // candidates of stage i = tokens no earlier stage owned
+      auto scan = [&](int qbase) -> int {
+        int cnt = 0;
+        bool closed = false;
+        for (int p0 = lo_pos; p0 < len && !closed; p0 += kWave) {
+          const int p = p0 + lane;
+          const unsigned long long e = p < len ? entry_of(i, p) : 0ull;
+          const uint32_t key = (uint32_t)(e >> 32), idx = (uint32_t)e;
+          const unsigned char own = p < len ? sh.owner[idx] : kOwnPivot;
+          const bool band = p < len && key >= lo_m && key <= hi_m &&
+                            (own == kOwnNone || (own < kOwnPivot && (int)own >= i));
+          const unsigned long long mb = __ballot(band);
+          if (qbase >= 0 && band) {
+            const int slot = qbase + cnt + __popcll(mb & lt_mask);
+            sh.q_idx[slot] = (int)idx;
+            sh.q_stage[slot] = (unsigned char)i;
+            sh.q_taken[slot] = own == (unsigned char)i ? 1 : 0;
+          }
+          cnt += __popcll(mb);
+          closed = __ballot(p < len && key > hi_m) != 0ull;
+        }
+        return closed ? cnt : -1 - cnt;  // negative: the band reached the end of the list
+      };
+      int cnt = scan(-1);
+      const bool open = cnt < 0 && len < n;  // the band may run past the stored list
+      cnt = cnt < 0 ? -1 - cnt : cnt;
+      // reserve cnt queue slots, only if they fit (so every reserved slot gets written)
+      int qlo = kRetQ + 1;
+      if (lane == 0 && !open) {
+        int old = sh.qn;
+        while (old + cnt <= kRetQ) {
+          const int seen = atomicCAS(&sh.qn, old, old + cnt);
+          if (seen == old) {
+            qlo = old;
+            break;
+          }
+          old = seen;
+        }
+      }
+      qlo = __shfl(qlo, 0, kWave);
+      if (qlo + cnt > kRetQ) {
+        // too many ties for the queue (or an open band): leave it to the block-wide sweep
+        if (lane == 0) atomicMin(&sh.fb_first, i);
+        continue;
+      }
+      scan(qlo);
+      if (lane == 0) {
+        sh.st_qlo[i] = qlo;
+        sh.st_qhi[i] = qlo + cnt;
+      }
+    }
+    __syncthreads();
 
     // ------------------------------------------------------------------ fp64 scores of the queue
+    const int fb_first = sh.fb_first;
     const int qn = sh.qn;
-    for (int q = wave; q < qn; q += kRetWaves) {
-      int pi = piv[b * P + sh.q_stage[q]];
-      pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
-      const double s64 = row_cosine_f64<DT>(Xb + (long)pi * rowbytes,
-                                            Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
-      if (lane == 0) sh.q_s64[q] = s64;
+    for (int q = 2 * wave; q < qn; q += 2 * kRetWaves) {  // two pairs per wave at a time
+      const bool two = q + 1 < qn;
+      const int q1 = two ? q + 1 : q;
+      const int st0 = sh.q_stage[q], st1 = sh.q_stage[q1];
+      if (st0 >= fb_first && st1 >= fb_first) continue;  // will be walked again anyway
+      int p0 = piv[b * P + st0], p1 = piv[b * P + st1];
+      p0 = p0 < 0 ? 0 : (p0 < n ? p0 : n - 1);
+      p1 = p1 < 0 ? 0 : (p1 < n ? p1 : n - 1);
+      double s0, s1;
+      row_cosine_f64_x2<DT>(Xb + (long)p0 * rowbytes, Xb + (long)sh.q_idx[q] * rowbytes,
+                            Xb + (long)p1 * rowbytes, Xb + (long)sh.q_idx[q1] * rowbytes, two,
+                            g.D, lane, s0, s1);
+      if (lane == 0) {
+        sh.q_s64[q] = s0;
+        if (two) sh.q_s64[q + 1] = s1;
+      }
     }
-    if (tid == 0) sh.bad_first = walk_end;
     __syncthreads();
 
     // ------------------------------------------------------------------ check the speculation
-    // wave w checks the uncertain stages next+w, next+w+4, ...: the fp64 order agrees
-    // with the fp32 order iff the largest pair taken is below the smallest pair refused
-    for (int i = next + wave; i < walk_end; i += kRetWaves) {
+    // the fp64 order agrees with the fp32 order iff the largest pair taken is below
+    // the smallest pair refused
+    for (int i = next + wave; i < walk_end && i < fb_first; i += kRetWaves) {
       if (!sh.st_unc[i]) continue;
       const int qlo = sh.st_qlo[i], qhi = sh.st_qhi[i];
       double mt_s = -INFINITY, mu_s = INFINITY;
@@ -332,7 +334,11 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     }
     __syncthreads();
     const int bad = sh.bad_first;
-    if (bad < walk_end) {
+    if (bad >= walk_end && fb_first >= walk_end) {
+      next = walk_end;  // everything stands
+      continue;
+    }
+    if (bad < fb_first) {
       // fp64 picks other tokens at stage `bad`: undo the later stages, correct this one
       for (int j = tid; j < n; j += kRetThreads) {
         const unsigned char o = sh.owner[j];
@@ -365,14 +371,22 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       __syncthreads();
       continue;
     }
-    next = walk_end;
-    if (fb_stage != walk_end || walk_end >= P) continue;
 
     // ------------------------------------------------------------------ block-wide fallback
     {
-      const int i = fb_stage;
+      // stage i and everything after it is taken back; stage i is decided on the
+      // whole score row, then the walk goes on from i+1
+      const int i = fb_first;
+      for (int j = tid; j < n; j += kRetThreads) {
+        const unsigned char o = sh.owner[j];
+        if (o < kOwnPivot && (int)o >= i) {
+          clear_bit(sh.R, (uint32_t)j);
+          sh.owner[j] = kOwnNone;
+        }
+      }
       const int quota = sp.quota(i);
-      const float lo = fb_a - two_tau, hi = fb_b + two_tau;
+      const float lo = mono_inv((uint32_t)(sh.st_ka[i] >> 32)) - two_tau;
+      const float hi = mono_inv((uint32_t)(sh.st_kb[i] >> 32)) + two_tau;
       const float* Srow = S + (long)P * sm.row0 + (long)i * n;
       if (tid == 0) sh.cnt = 0;
       __syncthreads();
@@ -416,6 +430,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         }
       }
       next = i + 1;
+      parity = 0;
       __syncthreads();
     }
   }
