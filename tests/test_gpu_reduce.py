@@ -86,6 +86,12 @@ def test_identical_rows_everywhere():
     g = check(w)
     np.testing.assert_array_equal(g.piv[0], [0, 1, 2, 3])
     np.testing.assert_array_equal(g.keep[:37], np.arange(37))
+    # the same with more ties than the re-scoring queue holds, plus a few distinct rows
+    w = W.image_batch(B=1, N=3000, D=256, P=4, K=100, n_centroids=1, sigma=0.0)
+    rng = np.random.default_rng(3)
+    w.X[rng.permutation(3000)[:40]] = W.f32_to_bf16_bits(
+        rng.standard_normal((40, 256)).astype(np.float32))
+    check(w)
 
 
 def test_zero_rows_score_zero():

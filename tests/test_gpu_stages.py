@@ -133,3 +133,30 @@ def test_gather_compact(make):
         assert Yh[k0:k0 + len(kp)].tobytes() == Yr.tobytes()
         np.testing.assert_array_equal(pos_out.cpu().numpy()[k0:k0 + len(kp)], pr)
         k0 += len(kp)
+
+
+@pytest.mark.parametrize("drift,frames,per_frame,K", [(1e-3, 100, 16, 48), (2e-3, 40, 24, 40)])
+def test_topk_keep_recovers_from_misleading_scores(drift, frames, per_frame, K):
+    # Near-duplicate frames: many scores sit within the certified bound of each
+    # other.  The scores handed in are the oracle's, nudged by up to half the bound,
+    # so their fp32 order is wrong at many stage boundaries; with X given, the fp64
+    # re-evaluation must still reproduce the oracle's retained sets (this drives the
+    # correction / walk-again path).
+    w = W.video_batch(B=2, frames=frames, per_frame=per_frame, D=512, P=8, K=K, n_centroids=4,
+                      drift=drift)
+    Xd, cu_dev, desc, ws = setup(w)
+    refs = G.oracle_samples(w)
+    for b, r in enumerate(refs):
+        assert oracle.admissible(w.sample(b), r)
+    tau = D.score_tolerance(w.dtype)
+    rng = np.random.default_rng(11)
+    S_h = np.concatenate([(r.S + rng.uniform(-0.5 * tau, 0.5 * tau, size=r.S.shape))
+                          .astype(np.float32).ravel() for r in refs])
+    piv_h = np.concatenate([r.piv for r in refs]).astype(np.int32)
+    close = sum(int((r.stage_gap < 2 * tau).sum()) for r in refs)
+    assert close >= 4, "the case is meant to have many boundaries inside the bound"
+    keep = torch.full((w.B * w.K,), -1, dtype=torch.int32, device="cuda")
+    D.dart_topk_keep(desc, torch.from_numpy(S_h).cuda(), torch.from_numpy(piv_h).cuda(), keep, ws,
+                     X=Xd)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(keep.cpu().numpy(), np.concatenate([r.keep for r in refs]))
