@@ -32,6 +32,32 @@ STAGE_KERNELS = ["k_row_l1", "k_select_pivots", "k_scores_bf16", "k_order_scores
                  "k_gather"]
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_multicrop_B8_N2880_D4096_bf16.txt")
+
+
+def measured_traffic(kernel_prefix):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if the
+    kernel sources changed since the counters were taken."""
+    import glob
+    import hashlib
+    try:
+        lines = open(TRAFFIC_FILE).read().splitlines()
+    except OSError:
+        return None
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2502_11494_amd", "csrc", "*"))):
+        h.update(open(path, "rb").read())
+    sha = [l.split()[1] for l in lines if l.startswith("source_sha256")]
+    if not sha or sha[0] != h.hexdigest():
+        return None
+    for l in lines:
+        f = l.split()
+        if len(f) == 4 and f[0] == "kernel" and f[1].startswith("dart::" + kernel_prefix):
+            return int((float(f[2]) + float(f[3])) * 1024)
+    return None
+
+
 class HipEvents:
     """Raw hipEvent_t handles from the HIP runtime the process already uses."""
 
@@ -145,7 +171,7 @@ def main():
     achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None,
+                "traffic": measured_traffic(STAGE_KERNELS[dom]) if args.config == 2 else None,
                 "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
 
     cpu = None
