@@ -14,12 +14,11 @@
 
 using namespace dart;
 
-#ifndef DART_CH1
-#define DART_CH1 256
-#endif
-#ifndef DART_CH2
-#define DART_CH2 128
-#endif
+// Token chunks a wave of the score kernel keeps in flight.  Measured on the
+// B=8 N=2880 D=4096 and B=4 N=9216 D=3584 shapes: 2 is fastest (3 and 4 cost
+// registers and gain nothing: the kernel runs at the speed of its load stream).
+constexpr int kScoreDepth = 2;
+
 
 namespace {
 
@@ -186,13 +185,25 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   if (p.g.dtype == kF32) {
     hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * 4), dim3(256), 0, st, p.g, X, piv, S);
   } else {
-    const dim3 grid(p.tiles_bound), block(256);
+    // 4-wave workgroups (64 rows): 1- and 2-wave workgroups re-read the pivot chunks
+    // more often and measured no faster (P=16) or much slower (P=32).
+#define DART_LAUNCH_SCORES(NB, CH)                                                               \
+  do {                                                                                           \
+    const dim3 grid(p.tiles_bound), block(256);                                                  \
+    if (p.g.D % (CH) == 0)                                                                       \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, 4, kScoreDepth>), grid, block, 0, st,     \
+                         p.g, X, piv, pl2, S);                                                   \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, 4, kScoreDepth>), grid, block, 0, st,      \
+                         p.g, X, piv, pl2, S);                                                   \
+  } while (0)
     switch (p.g.Ppad / 16) {
-      case 1: hipLaunchKernelGGL((k_scores_bf16<1, DART_CH1>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      case 2: hipLaunchKernelGGL((k_scores_bf16<2, DART_CH2>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      case 3: hipLaunchKernelGGL((k_scores_bf16<3, 128>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
-      default: hipLaunchKernelGGL((k_scores_bf16<4, 128>), grid, block, 0, st, p.g, X, piv, pl2, S); break;
+      case 1: DART_LAUNCH_SCORES(1, 256); break;
+      case 2: DART_LAUNCH_SCORES(2, 128); break;
+      case 3: DART_LAUNCH_SCORES(3, 128); break;
+      default: DART_LAUNCH_SCORES(4, 128); break;
     }
+#undef DART_LAUNCH_SCORES
   }
   DART_LAUNCH_CHECK();
   return DART_OK;

@@ -65,7 +65,9 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int t = t0 + u * kWave + lane;
-        v[r][u] = (live[r] && t < pieces) ? reinterpret_cast<const u32x4*>(rp[r])[t] : zero;
+        v[r][u] = (live[r] && t < pieces)
+                      ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rp[r]) + t)
+                      : zero;
       }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r)

@@ -43,10 +43,10 @@ inline double score_abs_bound(int dtype) {
 
 // LDS of one workgroup: CH = elements of D per chunk; rows are padded by 16 bytes
 // so that the 16-row x 64-byte fragment reads hit distinct banks.
-template <int NB, int CH>
+template <int NB, int CH, int WAVES>
 struct ScoreShared {
   static constexpr int kRowB = CH * 2 + 16;
-  unsigned char a[4 * 16 * kRowB];       // per-wave token chunk
+  unsigned char a[WAVES * 16 * kRowB];   // per-wave token chunk
   unsigned char p[2 * NB * 16 * kRowB];  // pivot chunk, double buffered
   int pivrow[NB * 16];
 };
@@ -70,12 +70,16 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
   return true;
 }
 
-// grid: number of 64-row tiles (dense: B*ceil(N/64); ragged: an upper bound).
-// NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256).
-// Token chunks are prefetched two ahead in registers (the only HBM traffic);
-// the pivot chunk one ahead.
-template <int NB, int CH>
-__global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restrict__ X,
+// grid: number of 64-row tiles (dense: B*ceil(N/64); ragged: an upper bound) times
+// 4/WAVES: a workgroup of WAVES waves owns 16*WAVES rows of a tile.
+// NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256);
+// TAIL = D is not a multiple of CH (then the last chunk's missing pieces are zeroed).
+// DEPTH token chunks per wave are in flight in registers (the token rows are the
+// only HBM traffic), the pivot chunk one ahead.  All loads are unconditional
+// straight-line code, so the compiler's wait counts let the prefetched chunks stay
+// in flight.
+template <int NB, int CH, bool TAIL, int WAVES, int DEPTH>
+__global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv,
                                                      const double* __restrict__ pl2,
                                                      float* __restrict__ S) {
@@ -83,15 +87,19 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
   constexpr int PC = CH / 8;           // 16-byte pieces per row per chunk
   constexpr int RPI = kWave / PC;      // rows covered by one load instruction
   constexpr int LA = 16 / RPI;         // token loads per lane per chunk
-  constexpr int LP = NB * PC / 16;     // pivot loads per thread per chunk
+  constexpr int THREADS = WAVES * 64;
+  constexpr int SUB = 4 / WAVES;       // workgroups per 64-row tile
+  constexpr int LP = NB * 16 * PC / THREADS;  // pivot loads per thread per chunk
   constexpr int KS = CH / 32;          // MFMA k-steps per chunk
-  __shared__ __align__(16) ScoreShared<NB, CH> sh;
+  __shared__ __align__(16) ScoreShared<NB, CH, WAVES> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
-  if (!locate_tile(g, blockIdx.x, b, tl)) return;
+  if (!locate_tile(g, blockIdx.x / SUB, b, tl)) return;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P;
+  const int block_row0 = tl * kTileRows + (blockIdx.x % SUB) * (16 * WAVES);
+  if (block_row0 >= n) return;
   if (tid < NB * 16) {
     int p = tid < P ? piv[b * P + tid] : -1;
     sh.pivrow[tid] = p < n ? p : n - 1;  // a caller's bad index must not leave X
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
   const int pieces = g.D / 8;  // 16-byte pieces per row
   const int nchunks = (g.D + CH - 1) / CH;
   const int col16 = lane % PC, rowsub = lane / PC;
-  const int j0 = tl * kTileRows + wave * 16;
+  const int j0 = block_row0 + wave * 16;
   const u32x4 zero = {0u, 0u, 0u, 0u};
 
   // token loads: instruction t covers rows t*RPI .. t*RPI+RPI-1 of the wave's 16
@@ -115,34 +123,43 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
     r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
     aptr[t] = Xb + (long)r * rowbytes + col16 * 16;
   }
-  // pivot loads: piece id = tid + 256*k -> pivot row id/PC, piece id%PC (== col16)
+  // pivot loads: piece id = tid + THREADS*k -> pivot row id/PC, piece id%PC (== col16);
+  // padding slots read pivot 0's row and are zeroed after the load
   const unsigned char* pptr[LP];
+  bool preal[LP];
 #pragma unroll
   for (int k = 0; k < LP; ++k) {
-    int pr = sh.pivrow[(tid + 256 * k) / PC];
-    pptr[k] = pr >= 0 ? Xb + (long)pr * rowbytes + col16 * 16 : nullptr;
+    const int pr = sh.pivrow[(tid + THREADS * k) / PC];
+    preal[k] = pr >= 0;
+    pptr[k] = Xb + (long)(pr >= 0 ? pr : 0) * rowbytes + col16 * 16;
   }
 
-  u32x4 ra[2][LA], rp[LP];
-#define DART_LOAD_A(c, buf)                                                         \
-  {                                                                                 \
-    const bool in_ = (c) * PC + col16 < pieces;                                     \
-    const long off_ = (long)(c) * (CH * 2);                                         \
-    _Pragma("unroll") for (int t = 0; t < LA; ++t) ra[buf][t] =                     \
-        in_ ? *reinterpret_cast<const u32x4*>(aptr[t] + off_) : zero;               \
+  u32x4 ra[DEPTH][LA], rp[LP];
+  // With TAIL, a piece past the end of the row re-reads the row's first chunk and is
+  // replaced by zeros: the load itself stays unconditional.
+#define DART_LOAD_A(c, buf)                                                                    \
+  {                                                                                            \
+    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
+    const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
+    _Pragma("unroll") for (int t = 0; t < LA; ++t) {                                           \
+      const u32x4 v_ = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off_)); \
+      ra[buf][t] = in_ ? v_ : zero;                                                            \
+    }                                                                                          \
   }
-#define DART_LOAD_P(c)                                                              \
-  {                                                                                 \
-    const bool in_ = (c) * PC + col16 < pieces;                                     \
-    const long off_ = (long)(c) * (CH * 2);                                         \
-    _Pragma("unroll") for (int k = 0; k < LP; ++k) rp[k] =                          \
-        (in_ && pptr[k]) ? *reinterpret_cast<const u32x4*>(pptr[k] + off_) : zero;  \
+#define DART_LOAD_P(c)                                                                         \
+  {                                                                                            \
+    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
+    const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
+    _Pragma("unroll") for (int k = 0; k < LP; ++k) {                                           \
+      const u32x4 v_ = *reinterpret_cast<const u32x4*>(pptr[k] + off_);                        \
+      rp[k] = (in_ && preal[k]) ? v_ : zero;                                                   \
+    }                                                                                          \
   }
-#define DART_STORE_P(buf)                                                           \
-  {                                                                                 \
-    _Pragma("unroll") for (int k = 0; k < LP; ++k)                                  \
-        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                \
-                                  ((tid + 256 * k) / PC) * kRowB + col16 * 16) = rp[k]; \
+#define DART_STORE_P(buf)                                                                      \
+  {                                                                                            \
+    _Pragma("unroll") for (int k = 0; k < LP; ++k)                                             \
+        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                           \
+                                  ((tid + THREADS * k) / PC) * kRowB + col16 * 16) = rp[k];    \
   }
 
   double acc64[NB][4], gram64[4];
@@ -158,14 +175,16 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
   const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
 
   // One chunk: the wave's rows go registers -> its own LDS region (in-order LDS ops
-  // within a wave make that safe), the freed registers take the chunk two ahead,
-  // the pivot registers the next chunk; then MFMAs on chunk c.
-#define DART_CHUNK(c, buf)                                                                     \
+  // within a wave make that safe); then, if asked, the pivot registers take the next
+  // chunk and the freed token registers the chunk DEPTH ahead (pivot chunk first:
+  // vector loads return in order, so waiting for it must not drain the token
+  // prefetch); then MFMAs on chunk c.
+#define DART_CHUNK(c, buf, DO_P, DO_A)                                                         \
   {                                                                                            \
     _Pragma("unroll") for (int t = 0; t < LA; ++t)                                             \
         *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) = ra[buf][t];  \
-    if ((c) + 2 < nchunks) DART_LOAD_A((c) + 2, buf);                                          \
-    if ((c) + 1 < nchunks) DART_LOAD_P((c) + 1);                                               \
+    if (DO_P) DART_LOAD_P((c) + 1);                                                            \
+    if (DO_A) DART_LOAD_A((c) + DEPTH, buf);                                                   \
     __syncthreads(); /* pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read */      \
     const unsigned char* lp = sh.p + ((c) & 1) * (NB * 16 * kRowB);                            \
     _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                           \
@@ -182,16 +201,23 @@ __global__ __launch_bounds__(256) void k_scores_bf16(Geo g, const void* __restri
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];  \
       }                                                                                        \
     }                                                                                          \
-    if ((c) + 1 < nchunks) DART_STORE_P(((c) + 1) & 1);                                        \
+    if (DO_P) DART_STORE_P(((c) + 1) & 1);                                                     \
   }
 
-  DART_LOAD_A(0, 0);
-  if (nchunks > 1) DART_LOAD_A(1, 1);
+  // DEPTH token chunks are in flight per wave (register ring, static indices)
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < nchunks) DART_LOAD_A(d, d);
   DART_LOAD_P(0);
   DART_STORE_P(0);
-  for (int c = 0; c < nchunks; c += 2) {
-    DART_CHUNK(c, 0);
-    if (c + 1 < nchunks) DART_CHUNK(c + 1, 1);
+  int c = 0;
+  for (; c + 2 * DEPTH - 1 < nchunks; c += DEPTH) {  // steady state: every load is issued
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) DART_CHUNK(c + d, d, true, true);
+  }
+#pragma unroll
+  for (int r = 0; r < 2 * DEPTH - 1; ++r) {  // the last chunks: loads only while chunks remain
+    if (c + r < nchunks) DART_CHUNK(c + r, r % DEPTH, c + r + 1 < nchunks, c + r + DEPTH < nchunks);
   }
 #undef DART_CHUNK
 #undef DART_LOAD_A
