@@ -111,30 +111,103 @@ __device__ __forceinline__ float mono_inv(uint32_t m) {
   return __uint_as_float(u);
 }
 
-// ---- wave reductions (butterfly: every lane ends with the result) ---------------
+// ---- lane exchange on the vector ALU ------------------------------------------------
+// lane_xor<J>(v, lane) returns v of lane (lane ^ J).  Inside a row of 16 lanes these
+// are data-parallel-primitive moves (quad permutes, row rotations); across rows the
+// gfx950 row / half swaps.  None of them goes through the LDS crossbar, so a
+// butterfly costs a few ALU cycles per step.  Every lane of the wave must be active.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kDppRor4 = 0x124;      // lane i <- lane (i-4) mod 16 of its row
+constexpr int kDppRor8 = 0x128;      // lane i <- lane i^8
+constexpr int kDppRor12 = 0x12C;     // lane i <- lane (i+4) mod 16 of its row
+constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;
 
+template <int J>
+__device__ __forceinline__ int lane_xor(int v, int lane) {
+  static_assert(J == 1 || J == 2 || J == 4 || J == 8 || J == 16 || J == 32, "one bit");
+  if (J == 1) return dpp_move<kDppXor1>(v, v);
+  if (J == 2) return dpp_move<kDppXor2>(v, v);
+  if (J == 4) {
+    const int dn = dpp_move<kDppRor4>(v, v), up = dpp_move<kDppRor12>(v, v);
+    return (lane & 4) ? dn : up;
+  }
+  if (J == 8) return dpp_move<kDppRor8>(v, v);
+  if (J == 16) {  // .x = rows 0,0,2,2   .y = rows 1,1,3,3
+    const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (lane & 16) ? (int)sw[0] : (int)sw[1];
+  }
+  // .x = lower half twice, .y = upper half twice
+  const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return (lane & 32) ? (int)sw[0] : (int)sw[1];
+}
+template <int J>
+__device__ __forceinline__ float lane_xor(float v, int lane) {
+  return __int_as_float(lane_xor<J>(__float_as_int(v), lane));
+}
+template <int J>
+__device__ __forceinline__ unsigned long long lane_xor(unsigned long long v, int lane) {
+  const uint32_t lo = (uint32_t)lane_xor<J>((int)(uint32_t)v, lane);
+  const uint32_t hi = (uint32_t)lane_xor<J>((int)(uint32_t)(v >> 32), lane);
+  return ((unsigned long long)hi << 32) | lo;
+}
+template <int J>
+__device__ __forceinline__ double lane_xor(double v, int lane) {
+  return __longlong_as_double((long long)lane_xor<J>((unsigned long long)__double_as_longlong(v), lane));
+}
+
+// ---- wave reductions (butterfly: every lane ends with the same bits) ------------------
+
+#define DART_WAVE_BUTTERFLY(v, OP)          \
+  {                                         \
+    const int l_ = threadIdx.x & 63;        \
+    v = OP(v, lane_xor<1>(v, l_));          \
+    v = OP(v, lane_xor<2>(v, l_));          \
+    v = OP(v, lane_xor<4>(v, l_));          \
+    v = OP(v, lane_xor<8>(v, l_));          \
+    v = OP(v, lane_xor<16>(v, l_));         \
+    v = OP(v, lane_xor<32>(v, l_));         \
+  }
+#define DART_OP_ADD(a, b) ((a) + (b))
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  DART_WAVE_BUTTERFLY(v, DART_OP_ADD);
   return v;
 }
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  DART_WAVE_BUTTERFLY(v, DART_OP_ADD);
   return v;
 }
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  DART_WAVE_BUTTERFLY(v, DART_OP_ADD);
   return v;
 }
+__device__ __forceinline__ float wave_min(float v) {
+  DART_WAVE_BUTTERFLY(v, fminf);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  DART_WAVE_BUTTERFLY(v, fmaxf);
+  return v;
+}
+#undef DART_OP_ADD
+#undef DART_WAVE_BUTTERFLY
+
+// Exclusive prefix sum over the lanes of a wave: a shift-and-add scan inside every row
+// of 16 lanes (lanes without a source add 0), then the totals of the rows before.
 __device__ __forceinline__ int wave_excl_scan(int v, int lane) {
   int x = v;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) {
-    int y = __shfl_up(x, o, kWave);
-    if (lane >= o) x += y;
-  }
+  x += dpp_move<kDppShr1>(0, x);
+  x += dpp_move<kDppShr2>(0, x);
+  x += dpp_move<kDppShr4>(0, x);
+  x += dpp_move<kDppShr8>(0, x);
+  const int t0 = __builtin_amdgcn_readlane(x, 15), t1 = __builtin_amdgcn_readlane(x, 31),
+            t2 = __builtin_amdgcn_readlane(x, 47);
+  const int row = lane >> 4;
+  x += (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
   return x - v;
 }
 
@@ -313,7 +386,7 @@ __device__ __forceinline__ void row_cosine_f64_x2(const void* p0, const void* x0
 // ---- block-wide bitonic sort of 64-bit keys -----------------------------------------
 // Thread t keeps elements t, t+THREADS, ... (M of them) in registers.  A
 // compare-exchange at distance j is done in registers when j >= THREADS, by lane
-// shuffles when j < 64, and through LDS (two barriers) only for 64 <= j < THREADS.
+// exchanges on the vector ALU when j < 64, and through LDS (two barriers) only for 64 <= j < THREADS.
 
 template <int THREADS, int M, int JM>
 __device__ __forceinline__ void reg_compare_exchange(unsigned long long (&v)[M], int k, int tid) {
@@ -330,6 +403,51 @@ __device__ __forceinline__ void reg_compare_exchange(unsigned long long (&v)[M],
   }
 }
 
+// Compare-exchange at lane distance J < 64 (partner in the same wave).
+template <int THREADS, int M, int J>
+__device__ __forceinline__ void lane_compare_exchange(unsigned long long (&v)[M], int k, int tid) {
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    const int e = m * THREADS + tid;
+    const unsigned long long o = lane_xor<J>(v[m], tid & 63);
+    const bool keep_min = ((tid & J) == 0) == ((e & k) == 0);
+    v[m] = keep_min ? (v[m] < o ? v[m] : o) : (v[m] > o ? v[m] : o);
+  }
+}
+
+// Merge stage k >= 64, distances 32..1: all partners are in the same wave.
+template <int THREADS, int M>
+__device__ __forceinline__ void wave_merge_tail(unsigned long long (&v)[M], int k, int tid) {
+  lane_compare_exchange<THREADS, M, 32>(v, k, tid);
+  lane_compare_exchange<THREADS, M, 16>(v, k, tid);
+  lane_compare_exchange<THREADS, M, 8>(v, k, tid);
+  lane_compare_exchange<THREADS, M, 4>(v, k, tid);
+  lane_compare_exchange<THREADS, M, 2>(v, k, tid);
+  lane_compare_exchange<THREADS, M, 1>(v, k, tid);
+}
+
+// Stages k = 2..64 (21 compare-exchanges, straight-line): every run of 64 consecutive
+// elements ends up sorted, ascending or descending as stage 128 needs it.
+template <int THREADS, int M>
+__device__ __forceinline__ void wave_sort_runs(unsigned long long (&v)[M], int tid) {
+  lane_compare_exchange<THREADS, M, 1>(v, 2, tid);
+  lane_compare_exchange<THREADS, M, 2>(v, 4, tid);
+  lane_compare_exchange<THREADS, M, 1>(v, 4, tid);
+  lane_compare_exchange<THREADS, M, 4>(v, 8, tid);
+  lane_compare_exchange<THREADS, M, 2>(v, 8, tid);
+  lane_compare_exchange<THREADS, M, 1>(v, 8, tid);
+  lane_compare_exchange<THREADS, M, 8>(v, 16, tid);
+  lane_compare_exchange<THREADS, M, 4>(v, 16, tid);
+  lane_compare_exchange<THREADS, M, 2>(v, 16, tid);
+  lane_compare_exchange<THREADS, M, 1>(v, 16, tid);
+  lane_compare_exchange<THREADS, M, 16>(v, 32, tid);
+  lane_compare_exchange<THREADS, M, 8>(v, 32, tid);
+  lane_compare_exchange<THREADS, M, 4>(v, 32, tid);
+  lane_compare_exchange<THREADS, M, 2>(v, 32, tid);
+  lane_compare_exchange<THREADS, M, 1>(v, 32, tid);
+  wave_merge_tail<THREADS, M>(v, 64, tid);
+}
+
 // Sorts s[0..n) ascending.  n is a power of two with 64 <= n; n == M*THREADS, or
 // n < THREADS with M == 1.  n must be the same on every thread; all threads call.
 template <int THREADS, int M>
@@ -339,24 +457,15 @@ __device__ __forceinline__ void block_bitonic_sort_m(unsigned long long* s, int 
   unsigned long long v[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) v[m] = (m * THREADS + tid < n) ? s[m * THREADS + tid] : ~0ull;
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
+  if (live) wave_sort_runs<THREADS, M>(v, tid);
+  for (int k = 128; k <= n; k <<= 1) {
+    for (int j = k >> 1; j >= kWave; j >>= 1) {
       if (j >= THREADS) {
         switch (j / THREADS) {
           case 1: reg_compare_exchange<THREADS, M, 1>(v, k, tid); break;
           case 2: reg_compare_exchange<THREADS, M, 2>(v, k, tid); break;
           case 4: reg_compare_exchange<THREADS, M, 4>(v, k, tid); break;
           default: reg_compare_exchange<THREADS, M, 8>(v, k, tid); break;
-        }
-      } else if (j < kWave) {
-        if (live) {
-#pragma unroll
-          for (int m = 0; m < M; ++m) {
-            const int e = m * THREADS + tid;
-            const unsigned long long o = __shfl_xor(v[m], j, kWave);
-            const bool keep_min = ((tid & j) == 0) == ((e & k) == 0);
-            v[m] = keep_min ? (v[m] < o ? v[m] : o) : (v[m] > o ? v[m] : o);
-          }
         }
       } else {
         __syncthreads();
@@ -376,6 +485,7 @@ __device__ __forceinline__ void block_bitonic_sort_m(unsigned long long* s, int 
         }
       }
     }
+    if (live) wave_merge_tail<THREADS, M>(v, k, tid);
   }
   __syncthreads();
 #pragma unroll

@@ -19,6 +19,7 @@ struct PivotShared {
   SelectShared<THREADS> sel;
   double c64[kPivLdsCand];
   double l2[kPivLdsCand];
+  int nU;
 };
 
 // grid: B blocks of THREADS (256 when no sample exceeds kSelSmallN tokens, else 1024).
@@ -51,12 +52,17 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
   // every token with value <= thr may belong to the exact top P
   float vP = mono_inv((uint32_t)(sh.sel.buf[P - 1] >> 32));
   float thr = vP + 2.5f * tau * fabsf(vP);
+  if (tid == 0) sh.nU = 0;
   __syncthreads();
   if (left_min <= thr) c = collect_sorted(v, n, P, thr, tid, sh.sel);  // a rival was left out
-  int flag = 0;
-  for (int t = tid; t < c; t += kSelThreads)
-    flag += mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr ? 1 : 0;
-  const int nU = block_sum<THREADS>(flag, tid, sh.sel.redi);  // a prefix of the sorted list
+  // the candidates are a prefix of the sorted list: its end is seen by exactly one thread
+  for (int t = tid; t < c; t += kSelThreads) {
+    const bool in = mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr;
+    const bool next_in = t + 1 < c && mono_inv((uint32_t)(sh.sel.buf[t + 1] >> 32)) <= thr;
+    if (in && !next_in) sh.nU = t + 1;
+  }
+  __syncthreads();
+  const int nU = sh.nU;  // 0 only if the norms are not numbers: then no pivot is written
 
   double* c64 = nU <= kPivLdsCand ? sh.c64 : scr + sm.row0;
   double* l2s = nU <= kPivLdsCand ? sh.l2 : scr + g.total_N + sm.row0;
@@ -91,7 +97,23 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
     }
   }
   __syncthreads();
-  // rank by (fp64 value, index); only ranks < P matter, so stop counting at P
+  // rank by (fp64 value, index); only ranks < P matter
+  if (nU <= kWave) {
+    // a wave per candidate: lane o compares candidate o with it, the ballot counts
+    const bool on = lane < nU;
+    const double co = on ? c64[lane] : 0.0;
+    const int jo = on ? (int)(uint32_t)sh.sel.buf[lane] : 0;
+    for (int u = w; u < nU; u += kSelWaves) {
+      const double cu = c64[u];
+      const int ju = (int)(uint32_t)sh.sel.buf[u];
+      const int cnt = __popcll(__ballot(on && (co < cu || (co == cu && jo < ju))));
+      if (lane == 0 && cnt < P) {
+        piv[b * P + cnt] = ju;
+        pl2[b * g.Ppad + cnt] = l2s[u];
+      }
+    }
+    return;
+  }
   for (int u = tid; u < nU; u += kSelThreads) {
     const double cu = c64[u];
     const int ju = (int)(uint32_t)sh.sel.buf[u];

@@ -270,7 +270,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
           old = seen;
         }
       }
-      qlo = __shfl(qlo, 0, kWave);
+      qlo = __builtin_amdgcn_readfirstlane(qlo);
       if (qlo + cnt > kRetQ) {
         // too many ties for the queue (or an open band): leave it to the block-wide sweep
         if (lane == 0) atomicMin(&sh.fb_first, i);
@@ -323,13 +323,16 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
           if (pair_less(s, j, mu_s, mu_j)) { mu_s = s; mu_j = j; }
         }
       }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const double s1 = __shfl_xor(mt_s, o, kWave), s2 = __shfl_xor(mu_s, o, kWave);
-        const int j1 = __shfl_xor(mt_j, o, kWave), j2 = __shfl_xor(mu_j, o, kWave);
-        if (pair_less(mt_s, mt_j, s1, j1)) { mt_s = s1; mt_j = j1; }
-        if (pair_less(s2, j2, mu_s, mu_j)) { mu_s = s2; mu_j = j2; }
-      }
+#define DART_PAIR_STEP(J)                                                                      \
+  {                                                                                            \
+    const double s1 = lane_xor<J>(mt_s, lane), s2 = lane_xor<J>(mu_s, lane);                   \
+    const int j1 = lane_xor<J>(mt_j, lane), j2 = lane_xor<J>(mu_j, lane);                      \
+    if (pair_less(mt_s, mt_j, s1, j1)) { mt_s = s1; mt_j = j1; }                               \
+    if (pair_less(s2, j2, mu_s, mu_j)) { mu_s = s2; mu_j = j2; }                               \
+  }
+      DART_PAIR_STEP(32) DART_PAIR_STEP(16) DART_PAIR_STEP(8) DART_PAIR_STEP(4) DART_PAIR_STEP(2)
+      DART_PAIR_STEP(1)
+#undef DART_PAIR_STEP
       if (!pair_less(mt_s, mt_j, mu_s, mu_j) && lane == 0) atomicMin(&sh.bad_first, i);
     }
     __syncthreads();
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   int mine = 0;
   for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(sh.R[t]);
   int off = wave_excl_scan(mine, lane);
-  const int wtotal = __shfl(off + mine, 63, kWave);
+  const int wtotal = __builtin_amdgcn_readlane(off + mine, 63);
   if (lane == 0) sh.wcnt[0][wave] = wtotal;
   __syncthreads();
 #pragma unroll

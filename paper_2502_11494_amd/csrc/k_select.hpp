@@ -26,6 +26,7 @@ struct SelectShared {
   float redg[THREADS / kWave];
   int redi[THREADS / kWave];
   int count;
+  int dstar;
 };
 
 template <int THREADS>
@@ -63,11 +64,8 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
       lo = fminf(lo, v[e]);
       hi = fmaxf(hi, v[e]);
     }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    lo = fminf(lo, __shfl_xor(lo, o, kWave));
-    hi = fmaxf(hi, __shfl_xor(hi, o, kWave));
-  }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
   __syncthreads();
   if (lane == 0) {
     sh.redf[2 * w] = lo;
@@ -106,22 +104,22 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
 #pragma unroll
   for (int i = 0; i < kSelWaves; ++i)
     if (i < w) run += sh.redi[i];
-  // d* = first bucket whose inclusive count reaches `want` = number of buckets below it
+  // d* = first bucket whose inclusive count reaches `want`: exactly one thread sees the
+  // running count cross the target inside its own buckets
   const int target = want < n ? want : n;
-  int below = 0;
 #pragma unroll
   for (int q = 0; q < kSelBucketsPerThread; ++q) {
+    const int before = run;
     run += h[q];
-    below += run < target ? 1 : 0;
+    if (before < target && run >= target) sh.dstar = tid * kSelBucketsPerThread + q;
   }
-  below = block_sum<THREADS>(below, tid, sh.redi);
-  int dlim = below;
+  if (tid == 0) sh.count = 0;
+  __syncthreads();
+  int dlim = sh.dstar;
   if (incl_upto > -INFINITY) {
     int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
     dlim = d2 > dlim ? d2 : dlim;
   }
-  if (tid == 0) sh.count = 0;
-  __syncthreads();
   float rest = INFINITY;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
@@ -136,8 +134,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     }
   }
   if (left_min) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) rest = fminf(rest, __shfl_xor(rest, o, kWave));
+    rest = wave_min(rest);
     if (lane == 0) sh.redg[w] = rest;
   }
   __syncthreads();
