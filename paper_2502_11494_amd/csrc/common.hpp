@@ -335,54 +335,6 @@ __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* x
   return den > 0.0 ? dot / den : 0.0;
 }
 
-// Two cosines at once (all four rows in flight together); each result is identical
-// to row_cosine_f64's.  The second pair is skipped when `two` is false.
-template <int DT>
-__device__ __forceinline__ void row_cosine_f64_x2(const void* p0, const void* x0, const void* p1,
-                                                  const void* x1, bool two, int D, int lane,
-                                                  double& c0, double& c1) {
-  const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
-  const u32x4* pp[2] = {reinterpret_cast<const u32x4*>(p0), reinterpret_cast<const u32x4*>(p1)};
-  const u32x4* xp[2] = {reinterpret_cast<const u32x4*>(x0), reinterpret_cast<const u32x4*>(x1)};
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-  double dot[2] = {0.0, 0.0}, pn[2] = {0.0, 0.0}, xn[2] = {0.0, 0.0};
-  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
-    u32x4 pv[2][8], xv[2][8];
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int t = t0 + u * kWave + lane;
-        const bool on = t < pieces && (r == 0 || two);
-        pv[r][u] = on ? pp[r][t] : zero;
-        xv[r][u] = on ? xp[r][t] : zero;
-      }
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        double pe[8], xe[8];
-        piece_to_f64<DT>(pv[r][u], pe);
-        piece_to_f64<DT>(xv[r][u], xe);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          dot[r] = fma(pe[e], xe[e], dot[r]);
-          pn[r] = fma(pe[e], pe[e], pn[r]);
-          xn[r] = fma(xe[e], xe[e], xn[r]);
-        }
-      }
-  }
-  double res[2];
-#pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const double d = wave_sum(dot[r]), a = wave_sum(pn[r]), b = wave_sum(xn[r]);
-    const double den = sqrt(a) * sqrt(b);
-    res[r] = den > 0.0 ? d / den : 0.0;
-  }
-  c0 = res[0];
-  c1 = res[1];
-}
-
 // ---- block-wide bitonic sort of 64-bit keys -----------------------------------------
 // Thread t keeps elements t, t+THREADS, ... (M of them) in registers.  A
 // compare-exchange at distance j is done in registers when j >= THREADS, by lane

@@ -1,4 +1,4 @@
-// Retained set of Eq. (9)-(10), one workgroup of 4 waves per sample.
+// Retained set of Eq. (9)-(10), one workgroup of 16 waves per sample.
 //
 // R starts as the pivots.  Stage i (pivot order) walks pivot i's ascending score
 // list, skips tokens already in R and takes the first quota_i others -- the
@@ -10,9 +10,9 @@
 // rows, on (fp64 score, index).  The stages depend on each other, so the walk is
 // a serial chain of LDS round trips; to keep it short the kernel speculates:
 //   1. the stage lists are staged in LDS (in groups that fit);
-//   2. the block walks the stages in fp32 order, 256 list entries per step (one per
-//      thread, ranks by ballot + a prefix over the waves), committing what that
-//      order says and noting each stage's last key taken and first key refused;
+//   2. the block walks the stages in fp32 order, 1024 list entries per step (one per
+//      thread; ranks by ballot + a prefix over the 16 wave counts), committing what
+//      that order says and noting each stage's last key taken and first key refused;
 //   3. the waves then look at the stages in parallel: a stage whose two keys are
 //      within 2*tau is uncertain, and its candidates within 2*tau of the boundary
 //      are queued (who was a candidate is known from the per-token owner stage);
@@ -27,7 +27,7 @@
 
 namespace dart {
 
-constexpr int kRetThreads = 256;  // one wave per SIMD: the walk is latency-bound
+constexpr int kRetThreads = 1024;  // 16 waves for staging, the band phase and the fp64 re-scoring
 constexpr int kRetWaves = kRetThreads / kWave;
 constexpr int kRetWords = kMaxN / 32;
 constexpr int kRetList = 12288;  // list entries staged in LDS at a time
@@ -47,8 +47,8 @@ struct RetainShared {
   unsigned long long st_ka[kMaxP], st_kb[kMaxP];  // last key taken, first key refused
   int st_qlo[kMaxP], st_qhi[kMaxP];
   unsigned char st_has_b[kMaxP], st_unc[kMaxP];
-  __attribute__((aligned(16))) int wcnt[2][kRetWaves];
-  int qn, cnt, bad_first, fb_first;
+  int wcnt[kRetWaves];
+  int qn, cnt, bad_first, fb_first, walk_taken;
 };
 
 __device__ __forceinline__ bool bit_of(const uint32_t* R, uint32_t j) {
@@ -97,6 +97,41 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // fallback sweep
 
   const Split sp(k, P);
+  // Lists of the stages [first, group_hi) that fit in LDS together (the first one maybe
+  // only in part); block-uniform arithmetic, no memory access.
+  int group_hi = 0, group_base = 0, staged_total = 0;
+  auto plan_group = [&](int first) {
+    group_base = (int)sp.list_offset(n, first);
+    const int l0 = sp.stage_len(n, first);
+    int tot = l0 < kRetList ? l0 : kRetList;
+    group_hi = first + 1;
+    while (group_hi < P && tot + sp.stage_len(n, group_hi) <= kRetList)
+      tot += sp.stage_len(n, group_hi++);
+    staged_total = tot;
+  };
+  constexpr int kStageLoads = kRetList / kRetThreads;  // one step moves a whole group
+  unsigned long long staged[kStageLoads];
+  auto load_group = [&]() {
+#pragma unroll
+    for (int u = 0; u < kStageLoads; ++u) {
+      const int t = u * kRetThreads + tid;
+      staged[u] = t < staged_total ? glist[group_base + t] : 0ull;
+    }
+  };
+  auto store_group = [&]() {
+#pragma unroll
+    for (int u = 0; u < kStageLoads; ++u) {
+      const int t = u * kRetThreads + tid;
+      if (t < staged_total) sh.list[t] = staged[u];
+    }
+  };
+
+  // the first group's lists and the pivots are requested before LDS is cleared, so
+  // the kernel waits for global memory once
+  plan_group(0);
+  load_group();
+  int my_pivot = -1;
+  if (tid < P) my_pivot = piv[b * P + tid];
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
   for (int t = tid; t < (n + 3) / 4; t += kRetThreads)
     reinterpret_cast<uint32_t*>(sh.owner)[t] = 0xffffffffu;
@@ -104,58 +139,29 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     sh.st_len[tid] = sp.stage_len(n, tid);
     sh.st_off[tid] = (int)sp.list_offset(n, tid);
   }
+  store_group();
   __syncthreads();
-  if (tid < P) {
-    int p = piv[b * P + tid];
-    if (p >= 0 && p < n) {
-      set_bit(sh.R, (uint32_t)p);
-      sh.owner[p] = kOwnPivot;
-    }
+  if (my_pivot >= 0 && my_pivot < n) {
+    set_bit(sh.R, (uint32_t)my_pivot);
+    sh.owner[my_pivot] = kOwnPivot;
   }
-  __syncthreads();
 
-  // Rank, within one step of the walk, of this thread's candidate among all the
-  // block's candidates, offset by `taken`; `total` = candidates of the step.
-  // One barrier (the per-wave counts alternate between two buffers, so a slow wave
-  // still reading one step's counts is never overrun); every thread must call.
-  static_assert(kRetWaves == 4, "the wave prefix below reads four counts at once");
-  int parity = 0;
-  auto step_rank = [&](bool cand, int taken, int& total) -> int {
-    const unsigned long long bal = __ballot(cand);
-    if (lane == 0) sh.wcnt[parity][wave] = __popcll(bal);
-    __syncthreads();
-    const int c0 = sh.wcnt[parity][0], c1 = sh.wcnt[parity][1], c2 = sh.wcnt[parity][2],
-              c3 = sh.wcnt[parity][3];
-    parity ^= 1;
-    total = c0 + c1 + c2 + c3;
-    const int before = (wave > 0 ? c0 : 0) + (wave > 1 ? c1 : 0) + (wave > 2 ? c2 : 0);
-    return taken + before + __popcll(bal & lt_mask);
-  };
+  // stage constants in the lanes of every wave: lane i holds stage i's quota, list
+  // length and list offset (the offsets are the prefix sums of the lengths)
+  int quota_v = 0, len_v = 0;
+  if (lane < P) {
+    quota_v = sp.quota(lane);
+    len_v = sp.stage_len(n, lane);
+  }
+  const int off_v = wave_excl_scan(len_v, lane);
 
-  int next = 0;      // first stage not yet final (block-uniform)
-  int group_hi = 0;  // stages whose lists are staged: [stage at staging time, group_hi)
-  int group_base = 0, staged_total = 0;
+  int next = 0;  // first stage not yet final (block-uniform)
   while (next < P) {
     if (next >= group_hi) {
-      // stage the lists of as many further stages as fit (the first one maybe partly)
-      group_base = sh.st_off[next];
-      int tot = sh.st_len[next] < kRetList ? sh.st_len[next] : kRetList;
-      group_hi = next + 1;
-      while (group_hi < P && tot + sh.st_len[group_hi] <= kRetList) tot += sh.st_len[group_hi++];
-      staged_total = tot;
-      for (int t0 = 0; t0 < tot; t0 += 12 * kRetThreads) {
-        unsigned long long v[12];  // 24 KiB of loads in flight per step
-#pragma unroll
-        for (int u = 0; u < 12; ++u) {
-          const int t = t0 + u * kRetThreads + tid;
-          v[u] = t < tot ? glist[group_base + t] : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < 12; ++u) {
-          const int t = t0 + u * kRetThreads + tid;
-          if (t < tot) sh.list[t] = v[u];
-        }
-      }
+      plan_group(next);
+      load_group();
+      __syncthreads();  // nobody reads the old group any more
+      store_group();
     }
     if (tid == 0) {
       sh.qn = 0;
@@ -171,42 +177,84 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     };
 
     // ------------------------------------------------------------------ speculative walk
-    for (int i = next; i < walk_end; ++i) {
-      const int quota = sp.quota(i);
-      if (quota == 0) {
-        if (tid == 0) sh.st_has_b[i] = 0;
-        continue;
-      }
-      const int len = sh.st_len[i];
-      const int off = sh.st_off[i] - group_base;
-      const bool staged = off + len <= staged_total;  // the usual case: plain LDS reads
-      bool have_b = false;
-      int taken = 0;
-      for (int pos = 0; pos < len && !have_b; pos += kRetThreads) {
-        const int t = pos + tid;
-        unsigned long long e;
-        if (staged) e = t < len ? sh.list[off + t] : 0ull;
-        else e = t < len ? entry_of(i, t) : 0ull;
-        const bool cand = t < len && !bit_of(sh.R, (uint32_t)e);
-        int total;
-        const int rank = step_rank(cand, taken, total);
-        if (cand) {
-          if (rank < quota) {
-            set_bit(sh.R, (uint32_t)e);
-            sh.owner[(uint32_t)e] = (unsigned char)i;
-          }
-          if (rank == quota - 1) sh.st_ka[i] = e;
-          if (rank == quota) sh.st_kb[i] = e;
+    // All 16 waves walk together, 1024 list entries per step (one per thread): usually one
+    // step per stage.  On the critical path of a step: read R, ballot, exchange the 16 wave
+    // counts (barrier), commit, barrier.  The entries of the next stage are read ahead.
+    {
+      // entries [0, 1024) of a stage's list (threads past its end read the group's entry 0)
+      auto first_entries = [&](int st) -> unsigned long long {
+        const int len = __builtin_amdgcn_readlane(len_v, st);
+        const int off = __builtin_amdgcn_readlane(off_v, st) - group_base;
+        int idx = tid < len ? off + tid : 0;
+        idx = idx < kRetList ? idx : 0;
+        return sh.list[idx];
+      };
+      const int wv = __builtin_amdgcn_readfirstlane(wave);
+      unsigned long long e_pre = first_entries(next);
+      for (int i = next; i < walk_end; ++i) {
+        const int quota = __builtin_amdgcn_readlane(quota_v, i);
+        const int len = __builtin_amdgcn_readlane(len_v, i);
+        const int off = __builtin_amdgcn_readlane(off_v, i) - group_base;
+        const unsigned long long e0 = e_pre;
+        e_pre = first_entries(i + 1 < walk_end ? i + 1 : i);  // independent of this stage's commits
+        if (quota == 0) {
+          if (tid == 0) sh.st_has_b[i] = 0;
+          continue;
         }
-        taken += total;
-        have_b = taken > quota;
+        const bool staged_all = off + len <= staged_total;  // the usual case: plain LDS reads
+        bool have_b = false;
+        int taken = 0;
+        for (int pos = 0; pos < len && !have_b; pos += kRetThreads) {
+          if (pos + wv * kWave >= len) {
+            // this wave's 64 entries are past the list's end: it only keeps the barriers
+            // (an idle wave still costs its SIMD issue slots for whatever it executes)
+            if (lane == 0) sh.wcnt[wv] = 0;
+            __syncthreads();
+            __syncthreads();
+            taken = sh.walk_taken;
+            have_b = taken > quota;
+            continue;
+          }
+          const int t = pos + tid;
+          const bool in = t < len;
+          unsigned long long e;
+          if (staged_all) e = pos == 0 ? e0 : sh.list[in ? off + t : 0];
+          else e = in ? entry_of(i, t) : sh.list[0];  // a list longer than the LDS region
+          const uint32_t j = (uint32_t)e;
+          const uint32_t rw = sh.R[j >> 5];
+          const bool cand = in && ((rw >> (j & 31)) & 1u) == 0u;
+          const unsigned long long bal = __ballot(cand);
+          if (lane == 0) sh.wcnt[wv] = __popcll(bal);
+          __syncthreads();
+          // inclusive prefix of the 16 wave counts in lanes 0..15 of every wave
+          int x = lane < kRetWaves ? sh.wcnt[lane] : 0;
+          x += dpp_move<kDppShr1>(0, x);
+          x += dpp_move<kDppShr2>(0, x);
+          x += dpp_move<kDppShr4>(0, x);
+          x += dpp_move<kDppShr8>(0, x);
+          const int total = __builtin_amdgcn_readlane(x, kRetWaves - 1);
+          const int before = wv > 0 ? __builtin_amdgcn_readlane(x, wv > 0 ? wv - 1 : 0) : 0;
+          const int rank = taken + before + __popcll(bal & lt_mask);
+          if (cand) {
+            if (rank < quota) {
+              set_bit(sh.R, j);
+              sh.owner[j] = (unsigned char)i;
+            }
+            if (rank == quota - 1) sh.st_ka[i] = e;
+            if (rank == quota) sh.st_kb[i] = e;
+          }
+          taken += total;
+          have_b = taken > quota;
+          if (tid == 0) sh.walk_taken = taken;  // for the waves that sat this step out
+          __syncthreads();  // the commits are visible before anyone tests R again
+        }
+        if (tid == 0) sh.st_has_b[i] = have_b ? 1 : 0;
       }
-      if (tid == 0) sh.st_has_b[i] = have_b ? 1 : 0;
-      __syncthreads();  // this stage's commits are visible before the next stage tests R
     }
+    __syncthreads();
 
     // ------------------------------------------------------------------ uncertain stages
-    // wave w looks at stages next+w, next+w+4, ...; R and owner are only read here
+    // wave w looks at stages next+w, next+w+16, ...; R and owner are only read here
     for (int i = next + wave; i < walk_end; i += kRetWaves) {
       bool unc = false;
       uint32_t lo_m = 0, hi_m = 0;
@@ -287,22 +335,14 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     // ------------------------------------------------------------------ fp64 scores of the queue
     const int fb_first = sh.fb_first;
     const int qn = sh.qn;
-    for (int q = 2 * wave; q < qn; q += 2 * kRetWaves) {  // two pairs per wave at a time
-      const bool two = q + 1 < qn;
-      const int q1 = two ? q + 1 : q;
-      const int st0 = sh.q_stage[q], st1 = sh.q_stage[q1];
-      if (st0 >= fb_first && st1 >= fb_first) continue;  // will be walked again anyway
-      int p0 = piv[b * P + st0], p1 = piv[b * P + st1];
+    for (int q = wave; q < qn; q += kRetWaves) {  // a pair per wave: 16 row pairs in flight
+      const int st = sh.q_stage[q];
+      if (st >= fb_first) continue;  // will be walked again anyway
+      int p0 = piv[b * P + st];
       p0 = p0 < 0 ? 0 : (p0 < n ? p0 : n - 1);
-      p1 = p1 < 0 ? 0 : (p1 < n ? p1 : n - 1);
-      double s0, s1;
-      row_cosine_f64_x2<DT>(Xb + (long)p0 * rowbytes, Xb + (long)sh.q_idx[q] * rowbytes,
-                            Xb + (long)p1 * rowbytes, Xb + (long)sh.q_idx[q1] * rowbytes, two,
-                            g.D, lane, s0, s1);
-      if (lane == 0) {
-        sh.q_s64[q] = s0;
-        if (two) sh.q_s64[q + 1] = s1;
-      }
+      const double s0 = row_cosine_f64<DT>(Xb + (long)p0 * rowbytes,
+                                           Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
+      if (lane == 0) sh.q_s64[q] = s0;
     }
     __syncthreads();
 
@@ -406,11 +446,11 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         }
       }
       n_in = wave_sum(n_in);
-      if (lane == 0) sh.wcnt[0][wave] = n_in;
+      if (lane == 0) sh.wcnt[wave] = n_in;
       __syncthreads();
       int need = quota;
 #pragma unroll
-      for (int w = 0; w < kRetWaves; ++w) need -= sh.wcnt[0][w];
+      for (int w = 0; w < kRetWaves; ++w) need -= sh.wcnt[w];
       const int nU = sh.cnt;
       int pi = piv[b * P + i];
       pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
@@ -433,7 +473,6 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         }
       }
       next = i + 1;
-      parity = 0;
       __syncthreads();
     }
   }
@@ -446,10 +485,10 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(sh.R[t]);
   int off = wave_excl_scan(mine, lane);
   const int wtotal = __builtin_amdgcn_readlane(off + mine, 63);
-  if (lane == 0) sh.wcnt[0][wave] = wtotal;
+  if (lane == 0) sh.wcnt[wave] = wtotal;
   __syncthreads();
 #pragma unroll
-  for (int w = 0; w < kRetWaves; ++w) off += w < wave ? sh.wcnt[0][w] : 0;
+  for (int w = 0; w < kRetWaves; ++w) off += w < wave ? sh.wcnt[w] : 0;
   int* out = keep + sm.keep0 + off;
   for (int t = w0; t < w0 + per && t < words; ++t) {
     uint32_t m = sh.R[t];
