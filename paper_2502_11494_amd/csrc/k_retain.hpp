@@ -109,19 +109,20 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       tot += sp.stage_len(n, group_hi++);
     staged_total = tot;
   };
-  constexpr int kStageLoads = kRetList / kRetThreads;  // one step moves a whole group
+  // a group moves in two halves of kStageLoads loads per thread (48 KiB in flight each)
+  constexpr int kStageLoads = kRetList / kRetThreads / 2;
   unsigned long long staged[kStageLoads];
-  auto load_group = [&]() {
+  auto load_half = [&](int h) {
 #pragma unroll
     for (int u = 0; u < kStageLoads; ++u) {
-      const int t = u * kRetThreads + tid;
+      const int t = (h * kStageLoads + u) * kRetThreads + tid;
       staged[u] = t < staged_total ? glist[group_base + t] : 0ull;
     }
   };
-  auto store_group = [&]() {
+  auto store_half = [&](int h) {
 #pragma unroll
     for (int u = 0; u < kStageLoads; ++u) {
-      const int t = u * kRetThreads + tid;
+      const int t = (h * kStageLoads + u) * kRetThreads + tid;
       if (t < staged_total) sh.list[t] = staged[u];
     }
   };
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   // the first group's lists and the pivots are requested before LDS is cleared, so
   // the kernel waits for global memory once
   plan_group(0);
-  load_group();
+  load_half(0);
   int my_pivot = -1;
   if (tid < P) my_pivot = piv[b * P + tid];
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
@@ -139,7 +140,11 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     sh.st_len[tid] = sp.stage_len(n, tid);
     sh.st_off[tid] = (int)sp.list_offset(n, tid);
   }
-  store_group();
+  store_half(0);
+  if (staged_total > kStageLoads * kRetThreads) {
+    load_half(1);
+    store_half(1);
+  }
   __syncthreads();
   if (my_pivot >= 0 && my_pivot < n) {
     set_bit(sh.R, (uint32_t)my_pivot);
@@ -159,9 +164,13 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   while (next < P) {
     if (next >= group_hi) {
       plan_group(next);
-      load_group();
+      load_half(0);
       __syncthreads();  // nobody reads the old group any more
-      store_group();
+      store_half(0);
+      if (staged_total > kStageLoads * kRetThreads) {
+        load_half(1);
+        store_half(1);
+      }
     }
     if (tid == 0) {
       sh.qn = 0;
