@@ -14,10 +14,11 @@
 
 using namespace dart;
 
-// Token chunks a wave of the score kernel keeps in flight.  Measured on the
-// B=8 N=2880 D=4096 and B=4 N=9216 D=3584 shapes: 2 is fastest (3 and 4 cost
-// registers and gain nothing: the kernel runs at the speed of its load stream).
-constexpr int kScoreDepth = 2;
+// Chunks a wave of the score kernel requests ahead of the one it is computing on.
+// Measured on the B=8 N=2880 D=4096 and B=4 N=9216 D=3584 shapes: 1 is fastest (2, 3 and
+// 4 are 10-30% slower: the kernel runs at the speed of its load stream, which degrades
+// when every wave keeps more of its 16 rows' pieces outstanding).
+constexpr int kScoreDepth = 1;
 
 
 namespace {

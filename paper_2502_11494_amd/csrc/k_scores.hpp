@@ -74,10 +74,10 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
 // 4/WAVES: a workgroup of WAVES waves owns 16*WAVES rows of a tile.
 // NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256);
 // TAIL = D is not a multiple of CH (then the last chunk's missing pieces are zeroed).
-// DEPTH token chunks per wave are in flight in registers (the token rows are the
-// only HBM traffic), the pivot chunk one ahead.  All loads are unconditional
-// straight-line code, so the compiler's wait counts let the prefetched chunks stay
-// in flight.
+// DEPTH chunks per wave are in flight in registers: the token pieces (the only HBM
+// traffic) and, requested just before them, the chunk's pivot pieces.  All loads are
+// unconditional straight-line code, so the compiler's wait counts let the prefetched
+// chunks stay in flight.
 template <int NB, int CH, bool TAIL, int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv,
@@ -134,32 +134,38 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
     pptr[k] = Xb + (long)(pr >= 0 ? pr : 0) * rowbytes + col16 * 16;
   }
 
-  u32x4 ra[DEPTH][LA], rp[LP];
-  // With TAIL, a piece past the end of the row re-reads the row's first chunk and is
-  // replaced by zeros: the load itself stays unconditional.
+  u32x4 ra[DEPTH][LA], rp[DEPTH][LP];
+  // With TAIL, a piece past the end of the row re-reads the row's first chunk; it is
+  // replaced by zeros (as are the padding pivot slots) only when the registers go to LDS:
+  // the load stays unconditional and nothing touches its result while it is in flight.
 #define DART_LOAD_A(c, buf)                                                                    \
   {                                                                                            \
     const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
     const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
-    _Pragma("unroll") for (int t = 0; t < LA; ++t) {                                           \
-      const u32x4 v_ = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off_)); \
-      ra[buf][t] = in_ ? v_ : zero;                                                            \
-    }                                                                                          \
+    _Pragma("unroll") for (int t = 0; t < LA; ++t) ra[buf][t] =                                \
+        __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off_));            \
   }
-#define DART_LOAD_P(c)                                                                         \
+#define DART_STORE_A(c, buf)                                                                   \
+  {                                                                                            \
+    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
+    _Pragma("unroll") for (int t = 0; t < LA; ++t)                                             \
+        *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) =              \
+            in_ ? ra[buf][t] : zero;                                                           \
+  }
+#define DART_LOAD_P(c, rbuf)                                                                   \
   {                                                                                            \
     const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
     const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
-    _Pragma("unroll") for (int k = 0; k < LP; ++k) {                                           \
-      const u32x4 v_ = *reinterpret_cast<const u32x4*>(pptr[k] + off_);                        \
-      rp[k] = (in_ && preal[k]) ? v_ : zero;                                                   \
-    }                                                                                          \
+    _Pragma("unroll") for (int k = 0; k < LP; ++k) rp[rbuf][k] =                               \
+        *reinterpret_cast<const u32x4*>(pptr[k] + off_);                                       \
   }
-#define DART_STORE_P(buf)                                                                      \
+#define DART_STORE_P(c, rbuf, buf)                                                             \
   {                                                                                            \
+    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
     _Pragma("unroll") for (int k = 0; k < LP; ++k)                                             \
         *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                           \
-                                  ((tid + THREADS * k) / PC) * kRowB + col16 * 16) = rp[k];    \
+                                  ((tid + THREADS * k) / PC) * kRowB + col16 * 16) =           \
+            (in_ && preal[k]) ? rp[rbuf][k] : zero;                                            \
   }
 
   double acc64[NB][4], gram64[4];
@@ -174,17 +180,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
   const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
 
-  // One chunk: the wave's rows go registers -> its own LDS region (in-order LDS ops
-  // within a wave make that safe); then, if asked, the pivot registers take the next
-  // chunk and the freed token registers the chunk DEPTH ahead (pivot chunk first:
-  // vector loads return in order, so waiting for it must not drain the token
-  // prefetch); then MFMAs on chunk c.
-#define DART_CHUNK(c, buf, DO_P, DO_A)                                                         \
+  // One chunk c (register slot buf = c % DEPTH): the wave's rows go registers -> its own
+  // LDS region (in-order LDS ops within a wave make that safe); the freed slot takes the
+  // pivot and token pieces of chunk c + DEPTH (vector loads return in order: each chunk's
+  // pivot pieces are requested just before its token pieces, so waiting for the pivots of
+  // chunk c + 1 leaves the younger chunks in flight); MFMAs on chunk c; then the pivot
+  // registers of chunk c + 1 go to the other LDS pivot buffer.
+#define DART_CHUNK(c, buf, nbuf, DO_P, DO_A)                                                   \
   {                                                                                            \
-    _Pragma("unroll") for (int t = 0; t < LA; ++t)                                             \
-        *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) = ra[buf][t];  \
-    if (DO_P) DART_LOAD_P((c) + 1);                                                            \
-    if (DO_A) DART_LOAD_A((c) + DEPTH, buf);                                                   \
+    DART_STORE_A(c, buf);                                                                      \
+    if (DO_A) {                                                                                \
+      DART_LOAD_P((c) + DEPTH, buf);                                                           \
+      DART_LOAD_A((c) + DEPTH, buf);                                                           \
+    }                                                                                          \
     __syncthreads(); /* pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read */      \
     const unsigned char* lp = sh.p + ((c) & 1) * (NB * 16 * kRowB);                            \
     _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                           \
@@ -201,26 +209,34 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];  \
       }                                                                                        \
     }                                                                                          \
-    if (DO_P) DART_STORE_P(((c) + 1) & 1);                                                     \
+    if (DO_P) DART_STORE_P((c) + 1, nbuf, ((c) + 1) & 1);                                               \
   }
 
-  // DEPTH token chunks are in flight per wave (register ring, static indices)
+  // DEPTH chunks (pivot and token pieces) are in flight per wave (register ring, static
+  // indices)
+  // (a row shorter than DEPTH chunks re-reads chunk 0 into the unused slots: the loads
+  // stay unconditional, so every path into the loop has the same loads outstanding and
+  // the compiler's wait counts at the loop head stay exact)
 #pragma unroll
-  for (int d = 0; d < DEPTH; ++d)
-    if (d < nchunks) DART_LOAD_A(d, d);
-  DART_LOAD_P(0);
-  DART_STORE_P(0);
+  for (int d = 0; d < DEPTH; ++d) {
+    const int cc = d < nchunks ? d : 0;
+    DART_LOAD_P(cc, d);
+    DART_LOAD_A(cc, d);
+  }
+  DART_STORE_P(0, 0, 0);
   int c = 0;
   for (; c + 2 * DEPTH - 1 < nchunks; c += DEPTH) {  // steady state: every load is issued
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) DART_CHUNK(c + d, d, true, true);
+    for (int d = 0; d < DEPTH; ++d) DART_CHUNK(c + d, d, (d + 1) % DEPTH, true, true);
   }
 #pragma unroll
   for (int r = 0; r < 2 * DEPTH - 1; ++r) {  // the last chunks: loads only while chunks remain
-    if (c + r < nchunks) DART_CHUNK(c + r, r % DEPTH, c + r + 1 < nchunks, c + r + DEPTH < nchunks);
+    if (c + r < nchunks)
+      DART_CHUNK(c + r, r % DEPTH, (r + 1) % DEPTH, c + r + 1 < nchunks, c + r + DEPTH < nchunks);
   }
 #undef DART_CHUNK
 #undef DART_LOAD_A
+#undef DART_STORE_A
 #undef DART_LOAD_P
 #undef DART_STORE_P
 
