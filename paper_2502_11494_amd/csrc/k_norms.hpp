@@ -37,7 +37,10 @@ inline double l1_rel_bound(int dtype, int Dc) {
 // grid: ceil(rows / (4 * ROWS)) blocks of 256 threads; wave w of the grid owns
 // rows [w*ROWS, (w+1)*ROWS).  Per row, lane l reads the pieces l, l+64, ... so a
 // wave's loads are 1 KiB contiguous; 8*ROWS loads are in flight per lane.
-template <int DT, int ROWS>
+// KEEP: ordinary loads, which leave the rows in the memory-side cache for the score
+// kernel's second pass (worth it only if the whole matrix fits there); otherwise
+// streaming (non-temporal) loads, which read faster.
+template <int DT, int ROWS, bool KEEP>
 __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int Dc, long ldc,
                                                 int rows, float* __restrict__ l1) {
   const int lane = threadIdx.x & 63;
@@ -65,9 +68,9 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         int t = t0 + u * kWave + lane;
-        v[r][u] = (live[r] && t < pieces)
-                      ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rp[r]) + t)
-                      : zero;
+        const u32x4* src = reinterpret_cast<const u32x4*>(rp[r]) + t;
+        if (live[r] && t < pieces) v[r][u] = KEEP ? *src : __builtin_nontemporal_load(src);
+        else v[r][u] = zero;
       }
 #pragma unroll
     for (int r = 0; r < ROWS; ++r)
