@@ -33,6 +33,7 @@ constexpr int kRetWords = kMaxN / 32;
 constexpr int kRetList = 12288;  // list entries staged in LDS at a time
 constexpr int kRetQ = 1024;      // band candidates awaiting an fp64 score
 constexpr unsigned char kOwnNone = 0xff, kOwnPivot = 0xfe;
+constexpr unsigned long long kNoKey = ~0ull;  // no list entry looks like this (index < 2^14)
 
 struct RetainShared {
   unsigned long long list[kRetList];
@@ -44,9 +45,10 @@ struct RetainShared {
   unsigned char q_taken[kRetQ];
   int st_off[kMaxP];  // offset of the stage's list inside the sample's list region
   int st_len[kMaxP];
-  unsigned long long st_ka[kMaxP], st_kb[kMaxP];  // last key taken, first key refused
+  // per stage: [0] last key taken, [1] first key refused (kNoKey: the walk met none)
+  unsigned long long st_kab[kMaxP][2];
   int st_qlo[kMaxP], st_qhi[kMaxP];
-  unsigned char st_has_b[kMaxP], st_unc[kMaxP];
+  unsigned char st_unc[kMaxP];
   int wcnt[kRetWaves];
   int qn, cnt, bad_first, fb_first, walk_taken;
 };
@@ -177,6 +179,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       sh.bad_first = group_hi;
       sh.fb_first = group_hi;
     }
+    if (tid >= next && tid < group_hi) sh.st_kab[tid][1] = kNoKey;
     __syncthreads();
     const int walk_end = group_hi;
     auto entry_of = [&](int i, int p) -> unsigned long long {
@@ -186,9 +189,11 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     };
 
     // ------------------------------------------------------------------ speculative walk
-    // All 16 waves walk together, 1024 list entries per step (one per thread): usually one
-    // step per stage.  On the critical path of a step: read R, ballot, exchange the 16 wave
-    // counts (barrier), commit, barrier.  The entries of the next stage are read ahead.
+    // All 16 waves walk together, 1024 list entries per step (one per thread): one step per
+    // stage unless a list is longer.  On the critical path of a step: read R, ballot,
+    // exchange the 16 wave counts (barrier), commit, barrier.  The step is bound by the
+    // number of instructions a wave issues, so the one-step case is kept free of loops and
+    // of everything the general case needs; the next stage's entries are read ahead.
     {
       // entries [0, 1024) of a stage's list (threads past its end read the group's entry 0)
       auto first_entries = [&](int st) -> unsigned long long {
@@ -205,18 +210,56 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         const int len = __builtin_amdgcn_readlane(len_v, i);
         const int off = __builtin_amdgcn_readlane(off_v, i) - group_base;
         const unsigned long long e0 = e_pre;
-        e_pre = first_entries(i + 1 < walk_end ? i + 1 : i);  // independent of this stage's commits
+        const int inext = i + 1 < walk_end ? i + 1 : i;
         if (quota == 0) {
-          if (tid == 0) sh.st_has_b[i] = 0;
+          e_pre = first_entries(inext);
           continue;
         }
         const bool staged_all = off + len <= staged_total;  // the usual case: plain LDS reads
+        if (staged_all && len <= kRetThreads) {
+          // The whole list in one step, straight-line: the prefetched entries are the
+          // list.  Waves past the list's end only write a zero count and keep the barriers.
+          const uint32_t j = (uint32_t)e0;
+          const bool busy = wv * kWave < len;  // wave-uniform
+          unsigned long long bal = 0ull;
+          bool cand = false;
+          if (busy) {
+            const uint32_t rw = sh.R[j >> 5];
+            cand = tid < len && ((rw >> (j & 31)) & 1u) == 0u;
+            bal = __ballot(cand);
+          }
+          if (lane == 0) sh.wcnt[wv] = __popcll(bal);
+          __syncthreads();
+          // the next stage's entries (they do not depend on this stage's commits) travel
+          // together with the wave counts
+          if (wv * kWave < __builtin_amdgcn_readlane(len_v, inext)) e_pre = first_entries(inext);
+          if (busy) {
+            // inclusive prefix of the 16 wave counts in lanes 0..15
+            int x = lane < kRetWaves ? sh.wcnt[lane] : 0;
+            x += dpp_move<kDppShr1>(0, x);
+            x += dpp_move<kDppShr2>(0, x);
+            x += dpp_move<kDppShr4>(0, x);
+            x += dpp_move<kDppShr8>(0, x);
+            const int before = wv > 0 ? __builtin_amdgcn_readlane(x, wv > 0 ? wv - 1 : 0) : 0;
+            const int rank = before + __popcll(bal & lt_mask);
+            if (cand) {
+              if (rank < quota) {
+                set_bit(sh.R, j);
+                sh.owner[j] = (unsigned char)i;
+              }
+              const uint32_t rel = (uint32_t)(rank - (quota - 1));  // 0: last taken, 1: first refused
+              if (rel < 2u) sh.st_kab[i][rel] = e0;
+            }
+          }
+          __syncthreads();  // the commits are visible before anyone tests R again
+          continue;
+        }
+        e_pre = first_entries(inext);
         bool have_b = false;
         int taken = 0;
         for (int pos = 0; pos < len && !have_b; pos += kRetThreads) {
           if (pos + wv * kWave >= len) {
             // this wave's 64 entries are past the list's end: it only keeps the barriers
-            // (an idle wave still costs its SIMD issue slots for whatever it executes)
             if (lane == 0) sh.wcnt[wv] = 0;
             __syncthreads();
             __syncthreads();
@@ -227,7 +270,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
           const int t = pos + tid;
           const bool in = t < len;
           unsigned long long e;
-          if (staged_all) e = pos == 0 ? e0 : sh.list[in ? off + t : 0];
+          if (staged_all) e = sh.list[in ? off + t : 0];
           else e = in ? entry_of(i, t) : sh.list[0];  // a list longer than the LDS region
           const uint32_t j = (uint32_t)e;
           const uint32_t rw = sh.R[j >> 5];
@@ -235,7 +278,6 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
           const unsigned long long bal = __ballot(cand);
           if (lane == 0) sh.wcnt[wv] = __popcll(bal);
           __syncthreads();
-          // inclusive prefix of the 16 wave counts in lanes 0..15 of every wave
           int x = lane < kRetWaves ? sh.wcnt[lane] : 0;
           x += dpp_move<kDppShr1>(0, x);
           x += dpp_move<kDppShr2>(0, x);
@@ -249,15 +291,14 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
               set_bit(sh.R, j);
               sh.owner[j] = (unsigned char)i;
             }
-            if (rank == quota - 1) sh.st_ka[i] = e;
-            if (rank == quota) sh.st_kb[i] = e;
+            const uint32_t rel = (uint32_t)(rank - (quota - 1));
+            if (rel < 2u) sh.st_kab[i][rel] = e;
           }
           taken += total;
           have_b = taken > quota;
           if (tid == 0) sh.walk_taken = taken;  // for the waves that sat this step out
           __syncthreads();  // the commits are visible before anyone tests R again
         }
-        if (tid == 0) sh.st_has_b[i] = have_b ? 1 : 0;
       }
     }
     __syncthreads();
@@ -267,9 +308,9 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     for (int i = next + wave; i < walk_end; i += kRetWaves) {
       bool unc = false;
       uint32_t lo_m = 0, hi_m = 0;
-      if (Xb && sp.quota(i) > 0 && sh.st_has_b[i]) {
-        const float fa = mono_inv((uint32_t)(sh.st_ka[i] >> 32));
-        const float fb = mono_inv((uint32_t)(sh.st_kb[i] >> 32));
+      if (Xb && sp.quota(i) > 0 && sh.st_kab[i][1] != kNoKey) {
+        const float fa = mono_inv((uint32_t)(sh.st_kab[i][0] >> 32));
+        const float fb = mono_inv((uint32_t)(sh.st_kab[i][1] >> 32));
         unc = !((fb - fa) > two_tau);
         lo_m = mono_of((fa - two_tau) + 0.0f);
         hi_m = mono_of((fb + two_tau) + 0.0f);
@@ -437,8 +478,8 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
         }
       }
       const int quota = sp.quota(i);
-      const float lo = mono_inv((uint32_t)(sh.st_ka[i] >> 32)) - two_tau;
-      const float hi = mono_inv((uint32_t)(sh.st_kb[i] >> 32)) + two_tau;
+      const float lo = mono_inv((uint32_t)(sh.st_kab[i][0] >> 32)) - two_tau;
+      const float hi = mono_inv((uint32_t)(sh.st_kab[i][1] >> 32)) + two_tau;
       const float* Srow = S + (long)P * sm.row0 + (long)i * n;
       if (tid == 0) sh.cnt = 0;
       __syncthreads();
