@@ -35,6 +35,12 @@ SMALL = [
     lambda: W.ragged_batch(B=5, n_lo=200, n_hi=900, D=1024, P=16),
     lambda: W.video_batch(B=2, frames=8, per_frame=60, D=1024, P=32, K=96, n_centroids=8),
     lambda: W.video_batch(B=1, frames=6, per_frame=50, D=512, P=40, K=100, n_centroids=8),
+    # fewer free slots than pivots: most stages take nothing
+    lambda: W.image_batch(B=2, N=300, D=512, P=16, K=20, n_centroids=16),
+    # stage lists longer than one 1024-entry step of the walk, long scans (near-duplicate frames)
+    lambda: W.video_batch(B=1, frames=40, per_frame=64, D=256, P=8, K=1500, n_centroids=8),
+    # lists that need several LDS staging groups (32 lists of up to 2049 entries)
+    lambda: W.video_batch(B=2, frames=32, per_frame=128, D=128, P=32, K=2048, n_centroids=8),
 ]
 
 
