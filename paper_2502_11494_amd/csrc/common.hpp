@@ -12,7 +12,6 @@ typedef float f32x4v __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kMaxP = 64;        // pivots per sample
 constexpr int kMaxN = 16384;     // tokens per sample
-constexpr int kTileRows = 64;    // token rows per score tile (4 waves x 16)
 
 enum { kF32 = 0, kBF16 = 1 };
 enum { kMaxL1 = 0, kMinL1 = 1 };
@@ -26,6 +25,7 @@ struct Geo {
   int K;            // dense / uniform budget, 0 = ratio
   int keep_num, keep_den;
   int dtype, mode;
+  int tile_rows;    // token rows per score tile: 16 per wave of the score kernel's workgroup
   long ld;          // X row stride, elements
   const int* cu;    // device cu_seqlens, nullptr = dense
   // ragged only, filled by k_prepare: packed offsets of keep and of score tiles

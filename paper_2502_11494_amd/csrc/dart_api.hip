@@ -30,7 +30,7 @@ struct Plan {
   Geo g;
   int esz;
   long keep_rows_bound;  // upper bound of the total number of retained rows
-  int tiles_bound;       // upper bound of the number of 64-row score tiles
+  int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
       total;
@@ -88,15 +88,23 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.cu = d->cu_seqlens;
   g.cu_keep = nullptr;
   g.tile_start = nullptr;
+  // 8-wave score workgroups (128 rows share a pivot chunk; 84 KB of LDS, one workgroup per
+  // compute unit) measured 10% faster than 4-wave ones when the pivots fill one 16-column
+  // block and all tiles fit the 256 compute units at once; with more tiles the smaller
+  // workgroups (three per compute unit) win, with more pivots too.
+  {
+    const long tiles128 = ragged ? total / 128 + d->B : (long)d->B * ((d->N + 127) / 128);
+    g.tile_rows = (d->dtype == DART_BF16 && g.Ppad == 16 && tiles128 <= 256) ? 128 : 64;
+  }
   p.esz = esz;
   if (!ragged) {
     p.keep_rows_bound = (long)d->B * K;
-    p.tiles_bound = d->B * ((d->N + kTileRows - 1) / kTileRows);
+    p.tiles_bound = d->B * ((d->N + g.tile_rows - 1) / g.tile_rows);
   } else {
     p.keep_rows_bound = d->K > 0 ? (long)d->B * d->K
                                  : (long)(((__int128)total * d->keep_num) / g.keep_den);
     if (p.keep_rows_bound > total) p.keep_rows_bound = total;
-    p.tiles_bound = (int)(total / kTileRows) + d->B;
+    p.tiles_bound = (int)(total / g.tile_rows) + d->B;
   }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
@@ -194,25 +202,29 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   if (p.tiles_bound == 0) return DART_OK;
   const double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kF32) {
-    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * 4), dim3(256), 0, st, p.g, X, piv, S);
+    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / 16)), dim3(256), 0, st,
+                       p.g, X, piv, S);
   } else {
-    // 4-wave workgroups (64 rows): 1- and 2-wave workgroups re-read the pivot chunks
-    // more often and measured no faster (P=16) or much slower (P=32).
-#define DART_LAUNCH_SCORES(NB, CH)                                                               \
+    // A workgroup of W waves owns a tile of 16*W rows and stages each pivot chunk once:
+    // 1- and 2-wave workgroups re-read the pivot chunks too often (no faster at P=16, much
+    // slower at P=32); 8 waves halve that traffic again and win at P<=16.
+#define DART_LAUNCH_SCORES(NB, CH, W)                                                            \
   do {                                                                                           \
-    const dim3 grid(p.tiles_bound), block(256);                                                  \
+    const dim3 grid(p.tiles_bound), block(64 * (W));                                             \
     if (p.g.D % (CH) == 0)                                                                       \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, 4, kScoreDepth>), grid, block, 0, st,     \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth>), grid, block, 0, st,     \
                          p.g, X, piv, pl2, S);                                                   \
     else                                                                                         \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, 4, kScoreDepth>), grid, block, 0, st,      \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth>), grid, block, 0, st,      \
                          p.g, X, piv, pl2, S);                                                   \
   } while (0)
     switch (p.g.Ppad / 16) {
-      case 1: DART_LAUNCH_SCORES(1, 256); break;
-      case 2: DART_LAUNCH_SCORES(2, 128); break;
-      case 3: DART_LAUNCH_SCORES(3, 128); break;
-      default: DART_LAUNCH_SCORES(4, 128); break;
+      case 1:
+        if (p.g.tile_rows == 128) DART_LAUNCH_SCORES(1, 256, 8); else DART_LAUNCH_SCORES(1, 256, 4);
+        break;
+      case 2: DART_LAUNCH_SCORES(2, 128, 4); break;
+      case 3: DART_LAUNCH_SCORES(3, 128, 4); break;
+      default: DART_LAUNCH_SCORES(4, 128, 4); break;
     }
 #undef DART_LAUNCH_SCORES
   }

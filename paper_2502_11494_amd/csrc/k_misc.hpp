@@ -8,7 +8,7 @@ namespace dart {
 
 // Ragged batches only.  One block of 1024 threads: validates the offsets and every
 // sample and writes the packed offsets cu_keep[B+1] (retained rows; a skipped
-// sample keeps 0) and tile_start[B+1] (64-row score tiles).  status[0] becomes
+// sample keeps 0) and tile_start[B+1] (score tiles of g.tile_rows rows).  status[0] becomes
 // 1 if a non-empty sample was rejected, 2 if cu_seqlens itself is not a
 // non-decreasing sequence from 0 to total_N (then every sample is skipped).
 __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_keep,
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
       int kb = budget_of(g, n);
       if (sample_ok(g, n, kb)) {
         k = kb;
-        tiles = (n + kTileRows - 1) / kTileRows;
+        tiles = (n + g.tile_rows - 1) / g.tile_rows;
       } else if (n != 0) {
         bad = 1;
       }

@@ -2,8 +2,8 @@
 // and every token of its sample.
 //
 // bf16 hidden states: the tokens x pivots x D contraction runs on the matrix
-// cores (v_mfma_f32_16x16x32_bf16).  A workgroup of 4 waves owns 64 token rows;
-// a wave owns 16 of them and walks D in chunks of 128 or 256 elements:
+// cores (v_mfma_f32_16x16x32_bf16).  A workgroup of 4 or 8 waves owns 64 or 128 token
+// rows; a wave owns 16 of them and walks D in chunks of 128 or 256 elements:
 //   HBM -> registers (two or four rows per load instruction, 256-512 B contiguous
 //       each, two chunks ahead) -> LDS (row-padded) -> MFMA A fragments
 //       (ds_read_b128, conflict-free).
@@ -54,7 +54,7 @@ struct ScoreShared {
 // Tile -> (sample, tile inside the sample).  Returns false for surplus blocks.
 __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int& tl) {
   if (g.cu == nullptr) {
-    int tps = (g.N + kTileRows - 1) / kTileRows;
+    int tps = (g.N + g.tile_rows - 1) / g.tile_rows;
     b = tile / tps;
     tl = tile - b * tps;
     return b < g.B;
@@ -70,8 +70,8 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
   return true;
 }
 
-// grid: number of 64-row tiles (dense: B*ceil(N/64); ragged: an upper bound) times
-// 4/WAVES: a workgroup of WAVES waves owns 16*WAVES rows of a tile.
+// grid: number of tiles of g.tile_rows = 16*WAVES rows (dense: B*ceil(N/tile_rows);
+// ragged: an upper bound): a workgroup of WAVES waves owns one tile, a wave 16 rows.
 // NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256);
 // TAIL = D is not a multiple of CH (then the last chunk's missing pieces are zeroed).
 // DEPTH chunks per wave are in flight in registers: the token pieces (the only HBM
@@ -88,17 +88,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   constexpr int RPI = kWave / PC;      // rows covered by one load instruction
   constexpr int LA = 16 / RPI;         // token loads per lane per chunk
   constexpr int THREADS = WAVES * 64;
-  constexpr int SUB = 4 / WAVES;       // workgroups per 64-row tile
   constexpr int LP = NB * 16 * PC / THREADS;  // pivot loads per thread per chunk
   constexpr int KS = CH / 32;          // MFMA k-steps per chunk
   __shared__ __align__(16) ScoreShared<NB, CH, WAVES> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
-  if (!locate_tile(g, blockIdx.x / SUB, b, tl)) return;
+  if (!locate_tile(g, blockIdx.x, b, tl)) return;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P;
-  const int block_row0 = tl * kTileRows + (blockIdx.x % SUB) * (16 * WAVES);
+  const int block_row0 = tl * (16 * WAVES);
   if (block_row0 >= n) return;
   if (tid < NB * 16) {
     int p = tid < P ? piv[b * P + tid] : -1;
@@ -266,7 +265,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   }
 }
 
-// fp32 hidden states.  grid: ceil(total rows / 16) blocks of 256; a wave owns 4
+// fp32 hidden states.  grid: tiles * (tile_rows / 16) blocks of 256; a wave owns 4
 // consecutive token rows of one sample and 8 pivots at a time.
 __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restrict__ X,
                                                     const int* __restrict__ piv,
@@ -275,10 +274,11 @@ __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restric
   // rows are grouped per sample: 16 rows per block, dense tiles of the sample
   int b, tl;
   {
-    // reuse the 64-row tile table: block = (tile, quarter)
-    int tile = blockIdx.x >> 2;
+    // reuse the tile table: block = (tile, 16-row part of the tile)
+    const int parts = g.tile_rows / 16;
+    const int tile = blockIdx.x / parts;
     if (!locate_tile(g, tile, b, tl)) return;
-    tl = tl * 4 + (blockIdx.x & 3);
+    tl = tl * parts + (blockIdx.x - tile * parts);
   }
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
