@@ -183,15 +183,11 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
   const float tau = (float)l1_rel_bound(p.g.dtype, Dc);
   double* pl2 = at<double>(ws, p.o_pl2);
   double* scr = at<double>(ws, p.o_scr_f64);
-  const bool small = false;  // the 256-thread variant measured slower even for short samples
-#define DART_LAUNCH_PIVOTS(DT, TH)                                                              \
-  hipLaunchKernelGGL((k_select_pivots<DT, TH>), dim3(p.g.B), dim3(TH), 0, st, p.g, X, C, Dc, ldc, \
-                     l1, piv, pl2, scr, tau)
-  if (p.g.dtype == kBF16) {
-    if (small) DART_LAUNCH_PIVOTS(kBF16, 256); else DART_LAUNCH_PIVOTS(kBF16, 1024);
-  } else {
-    if (small) DART_LAUNCH_PIVOTS(kF32, 256); else DART_LAUNCH_PIVOTS(kF32, 1024);
-  }
+  // 1024 threads: a 256-thread variant measured slower even for short samples
+#define DART_LAUNCH_PIVOTS(DT)                                                                   \
+  hipLaunchKernelGGL((k_select_pivots<DT, 1024>), dim3(p.g.B), dim3(1024), 0, st, p.g, X, C, Dc,   \
+                     ldc, l1, piv, pl2, scr, tau)
+  if (p.g.dtype == kBF16) DART_LAUNCH_PIVOTS(kBF16); else DART_LAUNCH_PIVOTS(kF32);
 #undef DART_LAUNCH_PIVOTS
   DART_LAUNCH_CHECK();
   return DART_OK;
@@ -234,11 +230,8 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
 
 dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st) {
   unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
-  if (false)  // the 256-thread variant measured slower even for short samples
-    hipLaunchKernelGGL(k_order_scores<256>, dim3(p.g.B * p.g.P), dim3(256), 0, st, p.g, S, lists);
-  else
-    hipLaunchKernelGGL(k_order_scores<1024>, dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S,
-                       lists);
+  // 1024 threads: a 256-thread variant measured slower even for short samples
+  hipLaunchKernelGGL(k_order_scores<1024>, dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, lists);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

@@ -8,8 +8,7 @@
 
 namespace dart {
 
-// grid: B*P blocks of THREADS; block (b, i).  THREADS = 256 when no sample exceeds
-// kSelSmallN tokens, 1024 otherwise.
+// grid: B*P blocks of THREADS (1024); block (b, i).
 // S: pivot-major scores.  lists: 64-bit (score image << 32 | index) entries; the
 // region of sample b starts at P*row0(b) and holds the stage lists back to back
 // (see list_offset).

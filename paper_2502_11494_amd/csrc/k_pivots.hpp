@@ -22,7 +22,7 @@ struct PivotShared {
   int nU;
 };
 
-// grid: B blocks of THREADS (256 when no sample exceeds kSelSmallN tokens, else 1024).
+// grid: B blocks of THREADS (1024).
 // l1 [total_N] fp32 criterion norms; piv [B*P]; pl2 [B*Ppad] squared L2 norms of
 // the pivots' hidden-state rows (0 for padding slots); scr [2*total_N] doubles.
 template <int DT, int THREADS>

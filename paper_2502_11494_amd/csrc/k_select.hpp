@@ -7,8 +7,7 @@
 // unique, so the sort alone yields (value ascending, index ascending).
 //
 // A thread keeps up to 16 values in registers, so a block of THREADS threads
-// handles n <= 16*THREADS values: 256 threads for samples of up to 4096 tokens
-// (fewer waves = fewer instructions issued per step, cheaper barriers), 1024 beyond.
+// handles n <= 16*THREADS values (1024 threads for the 16384-token limit).
 #pragma once
 #include "common.hpp"
 
@@ -16,7 +15,6 @@ namespace dart {
 
 constexpr int kSelPerThread = 16;  // values a thread keeps in registers
 constexpr int kSelBuckets = 1024;
-constexpr int kSelSmallN = 256 * kSelPerThread;  // largest sample the 256-thread kernels take
 
 template <int THREADS>
 struct SelectShared {
