@@ -32,9 +32,11 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
     int j = tid + e * kSelThreads;
     v[e] = (e * kSelThreads < n && j < n) ? row[j] + 0.0f : 0.f;
   }
-  collect_sorted(v, n, want, -INFINITY, tid, sh);
+  int first = 0;  // keys of the first sorted run (all of them unless the sort was split)
+  collect_sorted(v, n, want, -INFINITY, tid, sh, nullptr, &first);
   unsigned long long* out = lists + (long)g.P * sm.row0 + sp.list_offset(n, i);
-  for (int t = tid; t < want; t += kSelThreads) out[t] = sh.buf[t];
+  for (int t = tid; t < want; t += kSelThreads)
+    out[t] = t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)];
 }
 
 }  // namespace dart

@@ -25,6 +25,7 @@ struct SelectShared {
   int redi[THREADS / kWave];
   int count;
   int dstar;
+  int count2, dmid, cmid, cstar;  // two-part sort: see collect_sorted
 };
 
 template <int THREADS>
@@ -45,10 +46,15 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
 // Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
 // left_min receives the smallest value NOT compacted (+inf if none is left).
+// part2 (optional, only with incl_upto == -inf): when more than THREADS keys are compacted
+// and a bucket boundary cuts them into two runs of at most THREADS keys each, the runs are
+// sorted separately (two short sorts instead of one of twice the size; the histogram
+// already orders them by value): the first *part2 keys are at buf[0..), the others at
+// buf[THREADS..).  Otherwise *part2 is the returned count (one run at buf[0..)).
 template <int THREADS>
 __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
                                               float incl_upto, int tid, SelectShared<THREADS>& sh,
-                                              float* left_min = nullptr) {
+                                              float* left_min = nullptr, int* part2 = nullptr) {
   constexpr int kSelThreads = THREADS;
   constexpr int kSelWaves = THREADS / kWave;
   constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
@@ -105,18 +111,68 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
   // d* = first bucket whose inclusive count reaches `want`: exactly one thread sees the
   // running count cross the target inside its own buckets
   const int target = want < n ? want : n;
+  if (tid == 0) {
+    sh.count = 0;
+    sh.count2 = 0;
+    sh.dmid = -1;
+  }
 #pragma unroll
   for (int q = 0; q < kSelBucketsPerThread; ++q) {
     const int before = run;
     run += h[q];
-    if (before < target && run >= target) sh.dstar = tid * kSelBucketsPerThread + q;
+    if (before < target && run >= target) {
+      sh.dstar = tid * kSelBucketsPerThread + q;
+      sh.cstar = run;
+    }
   }
-  if (tid == 0) sh.count = 0;
   __syncthreads();
+  // last bucket whose inclusive count still fits one run (none if bucket 0 alone does not)
+  if (part2) {
+    int run2 = run;
+#pragma unroll
+    for (int q = kSelBucketsPerThread - 1; q >= 0; --q) {
+      const int incl = run2;
+      run2 -= h[q];
+      // incl = count through this bucket, run2 = count before it
+      if (run2 <= kSelThreads && incl > kSelThreads && tid * kSelBucketsPerThread + q > 0) {
+        sh.dmid = tid * kSelBucketsPerThread + q - 1;
+        sh.cmid = run2;
+      }
+    }
+    __syncthreads();
+  }
   int dlim = sh.dstar;
   if (incl_upto > -INFINITY) {
     int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
     dlim = d2 > dlim ? d2 : dlim;
+  }
+  if (part2) {
+    const int dmid = sh.dmid, cmid = sh.cmid, cstar = sh.cstar;
+    if (cstar > kSelThreads && dmid >= 0 && dmid < dlim && cmid > 0 && cstar - cmid <= kSelThreads) {
+      // two runs: buckets <= dmid (cmid keys) and (dmid, dlim] (cstar - cmid keys)
+#pragma unroll
+      for (int e = 0; e < kSelPerThread; ++e) {
+        const int j = tid + e * kSelThreads;
+        if (e < ne && j < n) {
+          const int d = bucket(v[e]);
+          if (d <= dlim) {
+            const unsigned long long key = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+            if (d <= dmid) sh.buf[atomicAdd(&sh.count, 1)] = key;
+            else sh.buf[kSelThreads + atomicAdd(&sh.count2, 1)] = key;
+          }
+        }
+      }
+      __syncthreads();
+      const int c1 = cmid, c2 = cstar - cmid;
+      const int np1 = next_pow2(c1 < kWave ? kWave : c1), np2 = next_pow2(c2 < kWave ? kWave : c2);
+      for (int t = c1 + tid; t < np1; t += kSelThreads) sh.buf[t] = ~0ull;
+      for (int t = c2 + tid; t < np2; t += kSelThreads) sh.buf[kSelThreads + t] = ~0ull;
+      __syncthreads();
+      block_bitonic_sort<kSelThreads>(sh.buf, np1, tid);
+      block_bitonic_sort<kSelThreads>(sh.buf + kSelThreads, np2, tid);
+      *part2 = c1;
+      return cstar;
+    }
   }
   float rest = INFINITY;
 #pragma unroll
@@ -146,6 +202,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
   for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
   __syncthreads();
   block_bitonic_sort<kSelThreads>(sh.buf, np, tid);
+  if (part2) *part2 = c;
   return c;
 }
 
