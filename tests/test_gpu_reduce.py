@@ -185,6 +185,40 @@ def test_runs_are_bit_identical_and_position_independent():
         assert np.all(S0[:, m] == S0[:, m[:1]])
 
 
+def test_random_shapes_sweep():
+    """Forty seeded random shapes (token counts, hidden sizes, pivots, budgets, recipes,
+    dtypes) against the oracle: whatever path a shape takes must agree bit for bit."""
+    rng = np.random.default_rng(0xDA27)
+    done = 0
+    while done < 40:
+        kind = int(rng.integers(0, 4))
+        P = int(rng.choice([1, 2, 3, 7, 8, 16, 17, 24, 32, 48, 64]))
+        N = int(rng.integers(max(P, 8), 1400))
+        K = int(rng.integers(P, N + 1)) if rng.random() < 0.3 else int(
+            rng.integers(P, max(P + 1, N // 3)))
+        D_ = int(rng.choice([8, 64, 200, 256, 520, 1024, 1536]))
+        B = int(rng.integers(1, 4))
+        seed = int(rng.integers(1, 1 << 30))
+        if kind == 0:
+            w = W.single_image(seed=seed, N=N, D=(D_ + 3) // 4 * 4, P=P, K=K, n_centroids=16)
+        elif kind == 1:
+            w = W.image_batch(seed=seed, B=B, N=N, D=D_, P=P, K=K, n_centroids=24)
+        elif kind == 2:
+            w = W.multicrop_batch(seed=seed, B=B, N=N, D=D_, P=P, K=K, n_centroids=32)
+        else:
+            frames = int(rng.integers(2, 12))
+            per = max(N // frames, P // frames + 1)
+            if frames * per < max(P, K):
+                continue
+            w = W.video_batch(seed=seed, B=B, frames=frames, per_frame=per, D=D_, P=P,
+                              K=min(K, frames * per), n_centroids=8)
+        refs = G.oracle_samples(w)
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            continue  # a margin below the oracle's own resolution: not a parity case
+        check(w)
+        done += 1
+
+
 # ---- the five benchmark configurations at full size --------------------------------
 
 def test_config0_single_image_fp32():
