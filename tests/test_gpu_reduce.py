@@ -219,6 +219,24 @@ def test_random_shapes_sweep():
         done += 1
 
 
+def test_random_ragged_sweep():
+    """Twelve seeded random packed batches (lengths, ratios, pivots) against the oracle."""
+    rng = np.random.default_rng(0xDA28)
+    for _ in range(12):
+        P = int(rng.choice([1, 4, 8, 16, 32, 64]))
+        num, den = int(rng.integers(60, 600)), 1000
+        n_min = -(-P * den // num) + 1  # the shortest sample still keeps >= P tokens
+        B = int(rng.integers(1, 7))
+        lengths = [int(rng.integers(n_min, n_min + 1500)) for _ in range(B)]
+        D_ = int(rng.choice([64, 256, 520, 1024]))
+        w = W.ragged_batch(seed=int(rng.integers(1, 1 << 30)), B=B, D=D_, P=P, keep_num=num,
+                           keep_den=den, lengths=lengths)
+        refs = G.oracle_samples(w)
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            continue
+        check(w)
+
+
 # ---- the five benchmark configurations at full size --------------------------------
 
 def test_config0_single_image_fp32():
