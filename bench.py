@@ -38,7 +38,8 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_multicrop_B8_N2880_D4
 def measured_traffic(kernel_prefix):
     """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if the
-    kernel sources changed since the counters were taken."""
+    kernel sources changed since the counters were taken.  An empty prefix sums all
+    the kernels of one step."""
     import glob
     import hashlib
     try:
@@ -51,11 +52,15 @@ def measured_traffic(kernel_prefix):
     sha = [l.split()[1] for l in lines if l.startswith("source_sha256")]
     if not sha or sha[0] != h.hexdigest():
         return None
+    total, found = 0, False
     for l in lines:
         f = l.split()
         if len(f) == 4 and f[0] == "kernel" and f[1].startswith("dart::" + kernel_prefix):
-            return int((float(f[2]) + float(f[3])) * 1024)
-    return None
+            if kernel_prefix:
+                return int((float(f[2]) + float(f[3])) * 1024)
+            total += int((float(f[2]) + float(f[3])) * 1024)
+            found = True
+    return total if found else None
 
 
 class HipEvents:
@@ -93,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload 0..4 (2 is the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hot", action="store_true",
+                    help="context run: the same input buffer every step (cache-hot), not the "
+                         "headline measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the reduction step is per-sample work with no "
@@ -120,6 +128,8 @@ def main():
         X0 = torch.from_numpy(w.X).cuda()
     copies = max(2, -(-(1 << 30) // x_bytes) + 1)
     copies = min(copies, max(2, int(64e9 // x_bytes)))
+    if args.hot:
+        copies = 1
     Xs = [X0] + [X0.clone() for _ in range(copies - 1)]
     pos = torch.from_numpy(w.pos).cuda()
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
@@ -191,6 +201,13 @@ def main():
         cpu = {"value": round(total_N * reps / cpu_wall, 1), "unit": "tokens/s", "cores": threads,
                "kind": "oracle",
                "sample": f"the whole {w.name} batch ({total_N} tokens), {reps} passes"}
+        # the same oracle on one thread, one sample (context for the threaded figure)
+        oracle.set_threads(1)
+        lo, hi = int(w.cu[0]), int(w.cu[1])
+        t0 = time.perf_counter()
+        oracle.reduce(w.X[lo:hi], w.dtype, w.P, w.budget(0), pos=w.pos[lo:hi])
+        cpu["single_thread_value"] = round((hi - lo) / (time.perf_counter() - t0), 1)
+        oracle.set_threads(0)
 
     out = {
         "metric": "vision tokens reduced/sec (input tokens per dart_reduce call), "
@@ -207,6 +224,9 @@ def main():
         "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),
         "whole_path_algorithmic_GBps": round(
             (x_bytes + total_K * w.D * esz + 16 * total_K) / (ms_per_step * 1e-3) / 1e9, 1),
+        "whole_path_counter_GBps": (None if args.config != 2 or measured_traffic("") is None else
+                                    round(measured_traffic("") / (ms_per_step * 1e-3) / 1e9, 1)),
+        "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
