@@ -69,7 +69,8 @@ typedef enum dart_status {
   DART_ERR_WORKSPACE = -5, /* ws NULL, misaligned or smaller than required         */
   DART_ERR_ALIGN = -6,     /* a row start would not be 16-byte aligned             */
   DART_ERR_HIP = -7,       /* a HIP call or kernel launch failed                   */
-  DART_ERR_DEVICE = -8     /* dart_device_status: a ragged sample was rejected     */
+  DART_ERR_DEVICE = -8     /* dart_device_status: a ragged sample or a given pivot
+                              list was rejected on the device                      */
 } dart_status;
 
 typedef enum dart_dtype {
@@ -79,7 +80,9 @@ typedef enum dart_dtype {
 
 typedef enum dart_pivot_mode {
   DART_PIVOT_MAX_L1 = 0, /* largest criterion L1 norm first (Table 1 caption)      */
-  DART_PIVOT_MIN_L1 = 1  /* smallest first (the "heart" rows of the pivot ablation) */
+  DART_PIVOT_MIN_L1 = 1, /* smallest first (the "heart" rows of the pivot ablation) */
+  DART_PIVOT_GIVEN = 2   /* dart_reduce only: the caller supplies the pivots (e.g. drawn at
+                            random, the random rows of the pivot ablation); see dart_reduce */
 } dart_pivot_mode;
 
 /* Problem descriptor (host memory, plain data). */
@@ -150,7 +153,12 @@ DART_API dart_status dart_gather_compact(const dart_desc* desc, const void* X, c
                                 size_t ws_bytes, void* stream);
 
 /* (a)-(d) in one call.  Optional outputs (NULL to skip): pos/pos_out, cu_keep,
- * piv_out [B*P], S_out [P*total_N]. */
+ * piv_out [B*P], S_out [P*total_N].
+ * DART_PIVOT_GIVEN: step (a) is skipped and piv_out (required) is READ: piv_out[b*P + i]
+ * is the index, local to sample b, of the pivot of stage i; crit is ignored.  The P
+ * indices of a sample must be distinct and inside the sample: a list that is not makes
+ * dart_device_status report DART_ERR_DEVICE and leaves that call's outputs unspecified
+ * (nothing is read or written out of bounds). */
 DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
@@ -167,7 +175,8 @@ DART_API dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, 
                                  void* stream, void* const* events);
 
 /* Waits for `stream`, then reports DART_ERR_DEVICE if the last call that used
- * `ws` skipped a ragged sample (see Errors), DART_OK otherwise. */
+ * `ws` (with this descriptor) skipped a ragged sample or met an invalid given pivot
+ * list, DART_OK otherwise. */
 DART_API dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream);
 
 /* The absolute bound on |fp32 score - exact score| that dart_topk_keep and

@@ -156,6 +156,20 @@ def reduce(X: np.ndarray, dtype: int, P: int, K: int, pos: Optional[np.ndarray] 
     return r
 
 
+def reduce_given(X: np.ndarray, dtype: int, piv: np.ndarray, K: int,
+                 pos: Optional[np.ndarray] = None) -> Reduced:
+    """Steps 3-5 with caller-supplied pivots (the random rows of the pivot ablation):
+    scores against the given pivots in the given stage order, retained set, gather."""
+    r = Reduced()
+    r.piv = np.ascontiguousarray(piv, dtype=np.int32)
+    r.c = l1_norms(X, dtype)
+    r.S = scores(X, dtype, r.piv)
+    r.keep, r.stage_last, r.stage_next, r.stage_gap = retain(r.S, r.piv, K, diagnostics=True)
+    r.Y, r.pos_out = gather(X, dtype, pos, r.keep)
+    r.piv_gap = np.full(r.piv.shape[0], np.inf)  # no ranking decision was taken
+    return r
+
+
 def admissible(X: np.ndarray, r: Reduced, rel: float = 1e-9) -> bool:
     """True if every decision the oracle took is safe from fp64 rounding: each
     margin (between consecutive pivots' norms, and between the last token taken

@@ -19,7 +19,7 @@ DART_OK = 0
 DART_ERR_NULL, DART_ERR_SHAPE, DART_ERR_BUDGET, DART_ERR_DTYPE = -1, -2, -3, -4
 DART_ERR_WORKSPACE, DART_ERR_ALIGN, DART_ERR_HIP, DART_ERR_DEVICE = -5, -6, -7, -8
 DART_F32, DART_BF16 = 0, 1
-DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1 = 0, 1
+DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
            "dart_topk_keep", "dart_gather_compact", "dart_reduce", "dart_reduce_profiled",

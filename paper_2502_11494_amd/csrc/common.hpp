@@ -14,7 +14,7 @@ constexpr int kMaxP = 64;        // pivots per sample
 constexpr int kMaxN = 16384;     // tokens per sample
 
 enum { kF32 = 0, kBF16 = 1 };
-enum { kMaxL1 = 0, kMinL1 = 1 };
+enum { kMaxL1 = 0, kMinL1 = 1, kGiven = 2 };
 
 // Shape of one call, passed to every kernel by value.
 struct Geo {

@@ -39,7 +39,8 @@ struct Plan {
 dart_status make_plan(const dart_desc* d, Plan& p) {
   if (!d) return DART_ERR_NULL;
   if (d->dtype != DART_F32 && d->dtype != DART_BF16) return DART_ERR_DTYPE;
-  if (d->pivot_mode != DART_PIVOT_MAX_L1 && d->pivot_mode != DART_PIVOT_MIN_L1)
+  if (d->pivot_mode != DART_PIVOT_MAX_L1 && d->pivot_mode != DART_PIVOT_MIN_L1 &&
+      d->pivot_mode != DART_PIVOT_GIVEN)
     return DART_ERR_DTYPE;
   if (d->B < 0 || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
       d->reserved != 0)
@@ -193,6 +194,17 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
   return DART_OK;
 }
 
+dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, void* ws,
+                               hipStream_t st) {
+  double* pl2 = at<double>(ws, p.o_pl2);
+  if (p.g.dtype == kBF16)
+    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+  else
+    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
 dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
@@ -290,7 +302,9 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   DART_TRY(make_plan(desc, p));
   if (p.g.B == 0) return DART_OK;
   if (!X || !Y || !keep || (pos != nullptr) != (pos_out != nullptr)) return DART_ERR_NULL;
+  if (p.g.mode == kGiven && !piv_out) return DART_ERR_NULL;
   if (misaligned16(X) || misaligned16(Y)) return DART_ERR_ALIGN;
+  if (p.g.mode == kGiven) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -304,10 +318,20 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   float* l1 = at<float>(ws, p.o_l1);
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(mark(0));
-  DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st));
-  DART_TRY(mark(1));
-  DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
-  DART_TRY(mark(2));
+  if (p.g.mode == kGiven) {
+    // the caller's pivots: check them, compute their norms; no pass over the criterion
+    hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
+                       at<int>(ws, p.o_status));
+    DART_LAUNCH_CHECK();
+    DART_TRY(mark(1));
+    DART_TRY(launch_pivot_norms(p, X, piv, ws, st));
+    DART_TRY(mark(2));
+  } else {
+    DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st));
+    DART_TRY(mark(1));
+    DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+    DART_TRY(mark(2));
+  }
   DART_TRY(launch_scores(p, X, piv, S, ws, st));
   DART_TRY(mark(3));
   DART_TRY(launch_order(p, S, ws, st));
@@ -334,6 +358,7 @@ dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void*
                                void* ws, size_t ws_bytes, void* stream) {
   Plan p;
   DART_TRY(make_plan(desc, p));
+  if (p.g.mode == kGiven) return DART_ERR_DTYPE;  // nothing to select
   if (p.g.B == 0) return DART_OK;
   if (!X || !piv) return DART_ERR_NULL;
   if (misaligned16(X)) return DART_ERR_ALIGN;
@@ -356,12 +381,7 @@ dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const 
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
-  double* pl2 = at<double>(ws, p.o_pl2);
-  if (p.g.dtype == kBF16)
-    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
-  else
-    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
-  DART_LAUNCH_CHECK();
+  DART_TRY(launch_pivot_norms(p, X, piv, ws, st));
   return launch_scores(p, X, piv, S, ws, st);
 }
 
@@ -418,14 +438,16 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   Plan p;
   DART_TRY(make_plan(desc, p));
   if (!ws) return DART_ERR_WORKSPACE;
-  if (p.g.B == 0 || p.g.cu == nullptr) return DART_OK;
-  int flag = 0;
+  if (p.g.B == 0 || (p.g.cu == nullptr && p.g.mode != kGiven)) return DART_OK;
+  int flag[2] = {0, 0};  // [0] ragged offsets / budgets, [1] given pivots
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (hipMemcpyAsync(&flag, static_cast<const unsigned char*>(ws) + p.o_status, sizeof(int),
+  if (hipMemcpyAsync(flag, static_cast<const unsigned char*>(ws) + p.o_status, sizeof(flag),
                      hipMemcpyDeviceToHost, st) != hipSuccess)
     return DART_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return DART_ERR_HIP;
-  return flag ? DART_ERR_DEVICE : DART_OK;
+  if (p.g.cu == nullptr) flag[0] = 0;
+  if (p.g.mode != kGiven) flag[1] = 0;
+  return (flag[0] | flag[1]) ? DART_ERR_DEVICE : DART_OK;
 }
 
 double dart_score_tolerance(int32_t dtype) {
@@ -442,7 +464,8 @@ const char* dart_strerror(dart_status status) {
     case DART_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case DART_ERR_ALIGN: return "row starts are not 16-byte aligned";
     case DART_ERR_HIP: return "a HIP call or kernel launch failed";
-    case DART_ERR_DEVICE: return "a ragged sample violated the size or budget limits";
+    case DART_ERR_DEVICE:
+      return "a ragged sample violated the size or budget limits, or a given pivot list is invalid";
   }
   return "unknown status";
 }

@@ -72,6 +72,23 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
   }
 }
 
+// Caller-supplied pivots: status[1] = 1 if any processed sample's P indices are not
+// distinct indices inside the sample, else 0.  grid: 1 block of 1024.
+__global__ __launch_bounds__(1024) void k_check_pivots(Geo g, const int* __restrict__ piv,
+                                                       int* __restrict__ status) {
+  int bad = 0;
+  for (int idx = threadIdx.x; idx < g.B * g.P; idx += 1024) {
+    const int b = idx / g.P, i = idx - b * g.P;
+    const Sample sm = sample_of(g, b);
+    if (sm.k == 0) continue;
+    const int p = piv[idx];
+    bad |= (p < 0 || p >= sm.n) ? 1 : 0;
+    for (int o = 0; o < i; ++o) bad |= piv[b * g.P + o] == p ? 1 : 0;
+  }
+  bad = __syncthreads_or(bad);
+  if (threadIdx.x == 0) status[1] = bad ? 1 : 0;
+}
+
 // Squared Euclidean norms of the pivots' rows in fp64.  grid: B blocks of 256.
 template <int DT>
 __global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restrict__ X,

@@ -62,7 +62,9 @@ def bits(t: torch.Tensor) -> np.ndarray:
 
 
 def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT_MAX_L1,
-               crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None) -> GpuResult:
+               crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None,
+               given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK) -> GpuResult:
+    """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots."""
     Xd = to_device(w, ld) if Xd is None else Xd
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
     desc = desc_of(w, cu_dev, ld, mode)
@@ -75,6 +77,8 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
     keep = torch.full((max(total_keep, 1),), -1, dtype=torch.int32, device="cuda")
     cu_keep = torch.full((w.B + 1,), -1, dtype=torch.int32, device="cuda")
     piv = torch.full((max(w.B * w.P, 1),), -1, dtype=torch.int32, device="cuda")
+    if given_piv is not None:
+        piv = torch.from_numpy(np.ascontiguousarray(given_piv, dtype=np.int32).reshape(-1)).cuda()
     S = torch.full((max(w.P * total_N, 1),), float("nan"), dtype=torch.float32, device="cuda")
     kw = {}
     if crit is not None:
@@ -82,8 +86,8 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
     D.dart_reduce(desc, Xd, Y, keep, ws, pos=pos, pos_out=pos_out, cu_keep=cu_keep, piv_out=piv,
                   S_out=S, **kw)
     torch.cuda.synchronize()
-    if w.ragged:
-        assert D.dart_device_status(desc, ws) == D.DART_OK
+    if w.ragged or given_piv is not None:
+        assert D.dart_device_status(desc, ws) == expect_status
     return GpuResult(piv.cpu().numpy()[:w.B * w.P].reshape(w.B, w.P), keep.cpu().numpy()[:total_keep],
                      cu_keep.cpu().numpy(), S.cpu().numpy()[:w.P * total_N], bits(Y)[:total_keep],
                      pos_out.cpu().numpy()[:total_keep])

@@ -105,6 +105,14 @@ def test_null_and_workspace_errors_need_no_device():
     rc = L.dart_reduce(C.byref(d), fake, None, 0, 0, fake, fake, None, fake, None, None, None,
                        fake, need, None)
     assert rc == D.DART_ERR_NULL
+    # caller-supplied pivots: the pivot list is required, and there is nothing to select
+    dg = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=64, pivot_mode=D.DART_PIVOT_GIVEN)
+    assert D.dart_workspace_bytes(dg) == need
+    rc = L.dart_reduce(C.byref(dg), fake, None, 0, 0, None, fake, None, fake, None, None, None,
+                       fake, need, None)
+    assert rc == D.DART_ERR_NULL
+    rc = L.dart_select_pivots(C.byref(dg), fake, None, 0, 0, fake, None, fake, need, None)
+    assert rc == D.DART_ERR_DTYPE
     # an empty batch is a valid no-op and needs nothing else
     d0 = D.make_desc(0, 4096, 8, D.DART_BF16, N=576, K=64)
     assert L.dart_reduce(C.byref(d0), None, None, 0, 0, None, None, None, None, None, None,

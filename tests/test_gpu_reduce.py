@@ -219,6 +219,36 @@ def test_random_shapes_sweep():
         done += 1
 
 
+def test_caller_supplied_pivots():
+    """DART_PIVOT_GIVEN: random distinct pivots per sample (the random rows of the pivot
+    ablation), dense and ragged; scores, retained sets and rows match the oracle run with
+    the same pivots.  An invalid list is reported and nothing is overrun."""
+    rng = np.random.default_rng(0xDA29)
+    for w in (W.multicrop_batch(B=3, N=700, D=1024, P=16, K=120, n_centroids=64),
+              W.image_batch(B=2, N=333, D=520, P=5, K=64, n_centroids=32),
+              W.single_image(N=300, D=256, P=8, K=50, n_centroids=16),
+              W.ragged_batch(B=4, n_lo=300, n_hi=1200, D=512, P=16)):
+        piv = np.stack([rng.permutation(int(w.lengths[b]))[:w.P] for b in range(w.B)]).astype(np.int32)
+        refs = [oracle.reduce_given(w.sample(b), w.dtype, piv[b], w.budget(b),
+                                    pos=w.pos[int(w.cu[b]):int(w.cu[b + 1])]) for b in range(w.B)]
+        assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+        g = G.run_reduce(w, mode=D.DART_PIVOT_GIVEN, given_piv=piv)
+        G.compare(w, g, refs)
+    # the oracle's own pivots give back the default result
+    w = W.multicrop_batch(B=2, N=500, D=1024, P=16, K=96, n_centroids=32)
+    base = G.run_reduce(w)
+    again = G.run_reduce(w, mode=D.DART_PIVOT_GIVEN, given_piv=base.piv)
+    for f in ("keep", "S", "Y", "pos_out"):
+        np.testing.assert_array_equal(getattr(again, f), getattr(base, f))
+    # a duplicated and an out-of-range pivot are reported
+    bad = base.piv.copy()
+    bad[1, 3] = bad[1, 2]
+    G.run_reduce(w, mode=D.DART_PIVOT_GIVEN, given_piv=bad, expect_status=D.DART_ERR_DEVICE)
+    bad = base.piv.copy()
+    bad[0, 0] = 500
+    G.run_reduce(w, mode=D.DART_PIVOT_GIVEN, given_piv=bad, expect_status=D.DART_ERR_DEVICE)
+
+
 def test_random_ragged_sweep():
     """Twelve seeded random packed batches (lengths, ratios, pivots) against the oracle."""
     rng = np.random.default_rng(0xDA28)

@@ -337,3 +337,28 @@ def test_thread_count_does_not_change_results():
     b = oracle.reduce(w.X, w.dtype, w.P, w.K)
     np.testing.assert_array_equal(a.S, b.S)
     np.testing.assert_array_equal(a.keep, b.keep)
+
+
+def test_given_pivots_reproduce_and_reorder():
+    """Caller-supplied pivots: the oracle's own pivots give back oracle.reduce; another
+    stage order still keeps exactly K tokens, the pivots among them, and obeys the
+    threshold invariant of Eq. (9) stage by stage."""
+    w = W.image_batch(B=1, N=180, D=64, P=6, K=40, n_centroids=8)
+    X = w.sample(0)
+    full = oracle.reduce(X, w.dtype, 6, 40, pos=w.pos[:180])
+    same = oracle.reduce_given(X, w.dtype, full.piv, 40, pos=w.pos[:180])
+    np.testing.assert_array_equal(same.keep, full.keep)
+    np.testing.assert_array_equal(same.S, full.S)
+    assert same.Y.tobytes() == full.Y.tobytes()
+    rng = np.random.default_rng(11)
+    piv = rng.permutation(180)[:6].astype(np.int32)
+    r = oracle.reduce_given(X, w.dtype, piv, 40, pos=w.pos[:180])
+    assert len(r.keep) == 40 and np.all(np.diff(r.keep) > 0) and set(piv) <= set(r.keep)
+    kept = set(int(j) for j in r.keep)
+    for i in range(6):
+        last = int(r.stage_last[i])
+        if last < 0:
+            continue
+        for j in range(180):
+            if j not in kept:
+                assert (r.S[i, j], j) > (r.S[i, last], last)
