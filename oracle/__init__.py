@@ -47,6 +47,8 @@ def lib():
         L.oracle_scores.restype = None
         L.oracle_retain.argtypes = [dp, i64, vp, i32, i32, vp, vp, vp, dp]
         L.oracle_retain.restype = i32
+        L.oracle_retain_single.argtypes = [dp, i64, vp, i32, i32, i32, vp, vp, vp, dp]
+        L.oracle_retain_single.restype = i32
         L.oracle_gather.argtypes = [vp, i32, i64, i64, vp, vp, i32, vp, vp]
         L.oracle_gather.restype = None
         L.oracle_reduce.argtypes = [vp, i32, i64, i64, i64, vp, i64, i64, vp, i32, i32, i32,
@@ -103,6 +105,26 @@ def retain(S: np.ndarray, piv: np.ndarray, K: int, diagnostics: bool = False):
     rc = lib().oracle_retain(_p(S), n, _p(piv), P, K, _p(keep), _p(last), _p(nxt), _p(gap))
     if rc != 0:
         raise ValueError(f"oracle_retain failed rc={rc} (P={P}, K={K}, N={n})")
+    return (keep, last, nxt, gap) if diagnostics else keep
+
+
+AGG_MIN, AGG_MAX = 1, 2
+
+
+def retain_single(S: np.ndarray, piv: np.ndarray, K: int, agg: int, diagnostics: bool = False):
+    """Retained set under one threshold common to all pivots (aggregate = min or max of a
+    token's scores over the pivots)."""
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    P, n = S.shape
+    piv = np.ascontiguousarray(piv, dtype=np.int32)
+    keep = np.empty(K, dtype=np.int32)
+    last = np.empty(1, dtype=np.int32)
+    nxt = np.empty(1, dtype=np.int32)
+    gap = np.empty(1, dtype=np.float64)
+    rc = lib().oracle_retain_single(_p(S), n, _p(piv), P, K, agg, _p(keep), _p(last), _p(nxt),
+                                    _p(gap))
+    if rc != 0:
+        raise ValueError(f"oracle_retain_single failed rc={rc} (P={P}, K={K}, N={n})")
     return (keep, last, nxt, gap) if diagnostics else keep
 
 
@@ -170,6 +192,19 @@ def reduce_given(X: np.ndarray, dtype: int, piv: np.ndarray, K: int,
     return r
 
 
+def reduce_single(X: np.ndarray, dtype: int, P: int, K: int, agg: int,
+                  pos: Optional[np.ndarray] = None, mode: int = MAX_L1) -> Reduced:
+    """The whole step with the single-threshold retained set: pivots and scores as in
+    reduce(), then retain_single."""
+    base = reduce(X, dtype, P, P, mode=mode, want_rows=False)  # pivots, norms, scores
+    r = Reduced()
+    r.piv, r.c, r.S, r.piv_gap = base.piv, base.c, base.S, base.piv_gap
+    r.keep, r.stage_last, r.stage_next, r.stage_gap = retain_single(r.S, r.piv, K, agg,
+                                                                    diagnostics=True)
+    r.Y, r.pos_out = gather(X, dtype, pos, r.keep)
+    return r
+
+
 def admissible(X: np.ndarray, r: Reduced, rel: float = 1e-9) -> bool:
     """True if every decision the oracle took is safe from fp64 rounding: each
     margin (between consecutive pivots' norms, and between the last token taken
@@ -190,7 +225,7 @@ def admissible(X: np.ndarray, r: Reduced, rel: float = 1e-9) -> bool:
             if rivals and all(np.array_equal(X[ranked[i]], X[j]) for j in rivals):
                 continue
         return False
-    for i in range(P):
+    for i in range(len(r.stage_gap)):
         g = r.stage_gap[i]
         if np.isinf(g) or g > rel:
             continue

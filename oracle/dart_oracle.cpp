@@ -157,6 +157,48 @@ int oracle_retain(const double* S, int64_t N, const int32_t* piv, int P, int K, 
   return n == K ? 0 : -2;
 }
 
+// Step 4 under ONE threshold common to all pivots (a second reading of Eq. 9-10; the
+// introduction speaks of the tokens "with the lowest similarity to the pivots").  With
+// the same epsilon for every pivot, Eq. (9)-(10) retain token j iff min_i dup(p_i, x_j)
+// <= epsilon (agg = 1); agg = 2 aggregates with max_i instead (a token counts as a
+// duplicate as soon as it duplicates any pivot).  The budget sets the threshold: R =
+// pivots + the K-P non-pivot tokens of lowest aggregate, ties to the lowest index.
+// Optional diagnostics (one decision): last = token taken last, next = best token not
+// taken (-1 if none), gap = aggregate(next) - aggregate(last) (+inf if either is missing).
+int oracle_retain_single(const double* S, int64_t N, const int32_t* piv, int P, int K, int agg,
+                         int32_t* keep, int32_t* last, int32_t* next, double* gap) {
+  if (P < 1 || K < P || K > N || (agg != 1 && agg != 2)) return -1;
+  std::vector<char> in_R(N, 0);
+  for (int i = 0; i < P; ++i) in_R[piv[i]] = 1;
+  std::vector<double> a(N);
+  for (int64_t j = 0; j < N; ++j) {
+    double v = S[j];
+    for (int i = 1; i < P; ++i) {
+      const double s = S[static_cast<int64_t>(i) * N + j];
+      v = agg == 1 ? std::min(v, s) : std::max(v, s);
+    }
+    a[j] = v;
+  }
+  std::vector<int32_t> cand;
+  for (int64_t j = 0; j < N; ++j)
+    if (!in_R[j]) cand.push_back(static_cast<int32_t>(j));
+  std::stable_sort(cand.begin(), cand.end(), [&](int32_t x, int32_t y) {
+    if (a[x] != a[y]) return a[x] < a[y];
+    return x < y;
+  });
+  const int m = K - P;
+  for (int t = 0; t < m; ++t) in_R[cand[t]] = 1;
+  const int32_t l = m > 0 ? cand[m - 1] : -1;
+  const int32_t nx = m < static_cast<int>(cand.size()) ? cand[m] : -1;
+  if (last) *last = l;
+  if (next) *next = nx;
+  if (gap) *gap = (l >= 0 && nx >= 0) ? a[nx] - a[l] : INFINITY;
+  int n = 0;
+  for (int64_t j = 0; j < N; ++j)
+    if (in_R[j]) keep[n++] = static_cast<int32_t>(j);
+  return n == K ? 0 : -2;
+}
+
 // Step 5: Y[r][:] = X[keep[r]][:] (bit copy, Y rows packed with stride D),
 // pos_out[r] = pos[keep[r]] (skipped when pos is NULL).
 void oracle_gather(const void* X, int dtype, int64_t D, int64_t ld, const int64_t* pos,

@@ -362,3 +362,35 @@ def test_given_pivots_reproduce_and_reorder():
         for j in range(180):
             if j not in kept:
                 assert (r.S[i, j], j) > (r.S[i, last], last)
+
+
+@pytest.mark.parametrize("agg", [oracle.AGG_MIN, oracle.AGG_MAX])
+def test_single_threshold_retain(agg):
+    """One threshold common to all pivots: brute force on a tiny input, the budget and
+    order invariants, the threshold invariant on the aggregate, and P = 1 (where the
+    aggregate is the only score) equal to the per-pivot rule."""
+    rng = np.random.default_rng(21 + agg)
+    S = rng.standard_normal((3, 11))
+    S[:, 4] = S[:, 7]                      # an exact tie between two tokens
+    piv = np.array([9, 2, 5], dtype=np.int32)
+    a = S.min(axis=0) if agg == oracle.AGG_MIN else S.max(axis=0)
+    for K in (3, 5, 8, 11):
+        keep, last, nxt, gap = oracle.retain_single(S, piv, K, agg, diagnostics=True)
+        others = sorted((j for j in range(11) if j not in piv), key=lambda j: (a[j], j))
+        np.testing.assert_array_equal(keep, sorted(list(piv) + others[:K - 3]))
+        if 3 < K < 11:
+            assert last[0] == others[K - 4] and nxt[0] == others[K - 3]
+            assert gap[0] == a[nxt[0]] - a[last[0]]
+    w = W.image_batch(B=1, N=150, D=64, P=4, K=30, n_centroids=8)
+    X = w.sample(0)
+    r = oracle.reduce_single(X, w.dtype, 4, 30, agg, pos=w.pos[:150])
+    full = oracle.reduce(X, w.dtype, 4, 30)
+    np.testing.assert_array_equal(r.piv, full.piv)
+    assert len(r.keep) == 30 and np.all(np.diff(r.keep) > 0) and set(r.piv) <= set(r.keep)
+    ag = r.S.min(axis=0) if agg == oracle.AGG_MIN else r.S.max(axis=0)
+    kept = [j for j in r.keep if j not in r.piv]
+    worst = max((ag[j], j) for j in kept)
+    assert all((ag[j], j) > worst for j in range(150) if j not in r.keep)
+    assert r.Y.tobytes() == X[r.keep].tobytes()
+    one = oracle.reduce_single(X, w.dtype, 1, 30, agg)
+    np.testing.assert_array_equal(one.keep, oracle.reduce(X, w.dtype, 1, 30).keep)
