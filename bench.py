@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload 0..4 (2 is the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--score-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0 = a threshold per pivot (the headline), 1/2 = one threshold on the "
+                         "min/max aggregate (variant, context only)")
     ap.add_argument("--hot", action="store_true",
                     help="context run: the same input buffer every step (cache-hot), not the "
                          "headline measurement")
@@ -136,9 +139,11 @@ def main():
     lens = w.lengths
     if w.ragged:
         desc = D.make_desc(w.B, w.D, w.P, w.dtype, keep_num=w.keep_num, keep_den=w.keep_den,
-                           cu_seqlens=cu_dev, total_N=total_N, max_N=int(lens.max()))
+                           cu_seqlens=cu_dev, total_N=total_N, max_N=int(lens.max()),
+                           score_mode=args.score_mode)
     else:
-        desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K)
+        desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K,
+                           score_mode=args.score_mode)
     ws = D.alloc_workspace(desc)
     Y = torch.empty((total_K, w.D), dtype=X0.dtype, device="cuda")
     keep = torch.empty(total_K, dtype=torch.int32, device="cuda")
@@ -219,6 +224,8 @@ def main():
         "config": {"workload": f"configs[{args.config}] {w.name}: B={w.B} "
                                f"N={'ragged' if w.ragged else int(lens[0])} D={w.D} P={w.P} "
                                f"K={w.K if w.K else 'floor(0.111 N)'}",
+                   "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
+                                  "one threshold on the maximum"][args.score_mode],
                    "total_tokens": total_N, "retained_tokens": total_K,
                    "input_copies_rotated": copies},
         "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),

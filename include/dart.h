@@ -85,6 +85,12 @@ typedef enum dart_pivot_mode {
                             random, the random rows of the pivot ablation); see dart_reduce */
 } dart_pivot_mode;
 
+typedef enum dart_score_mode {
+  DART_SCORE_PER_PIVOT = 0, /* Eq. (9)-(10) with a threshold per pivot: the staged rule  */
+  DART_SCORE_MIN = 1,       /* one threshold for all pivots on min_i S[i][j]             */
+  DART_SCORE_MAX = 2        /* one threshold for all pivots on max_i S[i][j]             */
+} dart_score_mode;
+
 /* Problem descriptor (host memory, plain data). */
 typedef struct dart_desc {
   int32_t B;        /* samples in the batch, >= 0 (0 is a valid no-op)              */
@@ -100,7 +106,7 @@ typedef struct dart_desc {
   int32_t keep_num; /* K == 0: K_b = floor(N_b * keep_num / keep_den)               */
   int32_t keep_den;
   int32_t pivot_mode; /* dart_pivot_mode                                            */
-  int32_t reserved;   /* must be 0                                                  */
+  int32_t score_mode; /* dart_score_mode (0 = the default staged rule)              */
 } dart_desc;
 
 /* Bytes of workspace every entry point below accepts for this descriptor
@@ -139,7 +145,10 @@ DART_API dart_status dart_duplication_scores(const dart_desc* desc, const void* 
  * X == NULL: S is taken as exact.  X != NULL: wherever two fp32 scores at a
  * decision boundary are closer than the rounding bound of
  * dart_duplication_scores, the candidates involved are re-scored in fp64 from
- * the rows of X before deciding. */
+ * the rows of X before deciding.
+ * DART_SCORE_MIN / DART_SCORE_MAX: a second reading of Eq. (9)-(10), one threshold
+ * common to all pivots: R = the pivots plus the K_b - P other tokens whose aggregate
+ * score over the pivots (minimum or maximum) is lowest, ties to the lowest index. */
 DART_API dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t* piv,
                            const void* X, int32_t* keep, int32_t* cu_keep, void* ws,
                            size_t ws_bytes, void* stream);

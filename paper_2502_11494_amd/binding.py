@@ -20,6 +20,7 @@ DART_ERR_NULL, DART_ERR_SHAPE, DART_ERR_BUDGET, DART_ERR_DTYPE = -1, -2, -3, -4
 DART_ERR_WORKSPACE, DART_ERR_ALIGN, DART_ERR_HIP, DART_ERR_DEVICE = -5, -6, -7, -8
 DART_F32, DART_BF16 = 0, 1
 DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN = 0, 1, 2
+DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
            "dart_topk_keep", "dart_gather_compact", "dart_reduce", "dart_reduce_profiled",
@@ -32,7 +33,7 @@ class DartDesc(C.Structure):
                 ("cu_seqlens", C.c_void_p), ("total_N", C.c_int32), ("max_N", C.c_int32),
                 ("ld", C.c_int64), ("dtype", C.c_int32), ("K", C.c_int32),
                 ("keep_num", C.c_int32), ("keep_den", C.c_int32), ("pivot_mode", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("score_mode", C.c_int32)]
 
 
 class DartError(RuntimeError):
@@ -95,14 +96,15 @@ def _stream(stream) -> C.c_void_p:
 def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, keep_num: int = 0,
               keep_den: int = 1, cu_seqlens: Optional[torch.Tensor] = None, total_N: int = 0,
               max_N: int = 0, ld: Optional[int] = None,
-              pivot_mode: int = DART_PIVOT_MAX_L1) -> DartDesc:
+              pivot_mode: int = DART_PIVOT_MAX_L1,
+              score_mode: int = DART_SCORE_PER_PIVOT) -> DartDesc:
     d = DartDesc()
     d.B, d.D, d.P, d.N = B, D, P, N
     d.cu_seqlens = None if cu_seqlens is None else cu_seqlens.data_ptr()
     d.total_N, d.max_N = total_N, max_N
     d.ld = D if ld is None else ld
     d.dtype, d.K, d.keep_num, d.keep_den = dtype, K, keep_num, keep_den
-    d.pivot_mode, d.reserved = pivot_mode, 0
+    d.pivot_mode, d.score_mode = pivot_mode, score_mode
     return d
 
 

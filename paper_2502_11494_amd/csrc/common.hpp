@@ -25,6 +25,7 @@ struct Geo {
   int K;            // dense / uniform budget, 0 = ratio
   int keep_num, keep_den;
   int dtype, mode;
+  int score_mode;   // 0: a threshold per pivot (staged rule); 1/2: one threshold on the min/max
   int tile_rows;    // token rows per score tile: 16 per wave of the score kernel's workgroup
   long ld;          // X row stride, elements
   const int* cu;    // device cu_seqlens, nullptr = dense

@@ -11,6 +11,7 @@
 #include "k_pivots.hpp"
 #include "k_retain.hpp"
 #include "k_scores.hpp"
+#include "k_single.hpp"
 
 using namespace dart;
 
@@ -43,7 +44,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
       d->pivot_mode != DART_PIVOT_GIVEN)
     return DART_ERR_DTYPE;
   if (d->B < 0 || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
-      d->reserved != 0)
+      d->score_mode < 0 || d->score_mode > 2)
     return DART_ERR_SHAPE;
   const bool ragged = d->cu_seqlens != nullptr;
   long total;
@@ -85,6 +86,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.keep_den = d->keep_den > 0 ? d->keep_den : 1;
   g.dtype = d->dtype;
   g.mode = d->pivot_mode;
+  g.score_mode = d->score_mode;
   g.ld = d->ld;
   g.cu = d->cu_seqlens;
   g.cu_keep = nullptr;
@@ -241,6 +243,7 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
 }
 
 dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st) {
+  if (p.g.score_mode != 0) return DART_OK;  // the single-threshold rule orders nothing per pivot
   unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   // 1024 threads: a 256-thread variant measured slower even for short samples
   hipLaunchKernelGGL(k_order_scores<1024>, dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, lists);
@@ -253,6 +256,16 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
   const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype));
   const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   double* scr_f64 = at<double>(ws, p.o_scr_f64);
+  if (p.g.score_mode != 0) {  // one threshold for all pivots: no stage lists
+    if (p.g.dtype == kBF16)
+      hipLaunchKernelGGL((k_keep_single<kBF16>), dim3(p.g.B), dim3(1024), 0, st, p.g, S, piv, X,
+                         keep, cu_keep, scr_f64, two_tau, p.g.score_mode);
+    else
+      hipLaunchKernelGGL((k_keep_single<kF32>), dim3(p.g.B), dim3(1024), 0, st, p.g, S, piv, X,
+                         keep, cu_keep, scr_f64, two_tau, p.g.score_mode);
+    DART_LAUNCH_CHECK();
+    return DART_OK;
+  }
   if (p.g.dtype == kBF16)
     hipLaunchKernelGGL((k_retain<kBF16>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,
                        piv, X, keep, cu_keep, scr_f64, two_tau);

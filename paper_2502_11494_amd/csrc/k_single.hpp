@@ -1,0 +1,181 @@
+// Retained set under ONE threshold common to all pivots: Eq. (9)-(10) with the same
+// epsilon for every pivot keep token j iff its aggregate score over the pivots (the
+// minimum, or the maximum: a token duplicates the context as soon as it duplicates any
+// pivot) is below epsilon, and the budget sets epsilon: R = pivots + the K-P non-pivot
+// tokens of lowest aggregate, ties to the lowest index.  One workgroup per sample.
+//
+// The aggregate of fp32 scores that each err by at most tau errs by at most tau (min
+// and max are 1-Lipschitz), so the scheme of the staged kernel applies to the single
+// decision: if the last aggregate taken and the first refused differ by more than
+// 2*tau the fp32 order stands; otherwise every token within 2*tau of the boundary gets
+// its P cosines recomputed in fp64 from the rows and the band is ranked on (fp64
+// aggregate, index).
+#pragma once
+#include "common.hpp"
+#include "k_select.hpp"
+
+namespace dart {
+
+enum { kAggMin = 1, kAggMax = 2 };
+
+struct SingleShared {
+  SelectShared<1024> sel;
+  uint32_t R[kMaxN / 32];
+  int piv[kMaxP];
+  int wcnt[16];
+  int below, nband;
+  double pair[1024];  // fp64 cosines of (band token, pivot) pairs
+};
+
+// grid: B blocks of 1024.  S: pivot-major scores.  X may be nullptr (scores exact).
+// scr_f64 [2*total_N]: per sample, fp64 aggregates of the band at row0 and their
+// indices (as ints) at total_N + row0.
+template <int DT>
+__global__ __launch_bounds__(1024) void k_keep_single(
+    Geo g, const float* __restrict__ S, const int* __restrict__ piv, const void* __restrict__ X,
+    int* __restrict__ keep, int* __restrict__ cu_keep_out, double* __restrict__ scr_f64,
+    float two_tau, int agg) {
+  __shared__ SingleShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x;
+  const Sample sm = sample_of(g, b);
+  if (cu_keep_out && tid == 0) {
+    cu_keep_out[b] = sm.keep0;
+    if (b == g.B - 1) cu_keep_out[g.B] = sm.keep0 + sm.k;
+  }
+  if (sm.k == 0) return;
+  const int n = sm.n, P = g.P, m = sm.k - P;
+  const int words = (n + 31) >> 5;
+  const int esz = DT == kBF16 ? 2 : 4;
+  const long rowbytes = g.ld * esz;
+  const unsigned char* Xb =
+      X ? static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes : nullptr;
+  double* band_v = scr_f64 + sm.row0;
+  int* band_j = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);
+
+  for (int t = tid; t < words; t += 1024) sh.R[t] = 0u;
+  if (tid < P) {
+    int p = piv[b * P + tid];
+    sh.piv[tid] = p < 0 ? 0 : (p < n ? p : n - 1);  // a caller's bad index must not leave X
+  }
+  __syncthreads();
+  if (tid < P) atomicOr(&sh.R[sh.piv[tid] >> 5], 1u << (sh.piv[tid] & 31));
+  __syncthreads();
+
+  if (m > 0) {
+    // aggregate of every token; pivots get 2 (above any cosine), so they sort last
+    const float* Sb = S + (long)P * sm.row0;
+    float v[kSelPerThread];
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) {
+      const int j = tid + e * 1024;
+      float a = 2.0f;
+      if (e * 1024 < n && j < n && !((sh.R[j >> 5] >> (j & 31)) & 1u)) {
+        a = Sb[j] + 0.0f;
+        for (int i = 1; i < P; ++i) {
+          const float s = Sb[(long)i * n + j] + 0.0f;
+          a = agg == kAggMin ? fminf(a, s) : fmaxf(a, s);
+        }
+      }
+      v[e] = a;
+    }
+    const int want = m + 1 < n ? m + 1 : n;
+    int c = collect_sorted(v, n, want, -INFINITY, tid, sh.sel);
+    const float fa = mono_inv((uint32_t)(sh.sel.buf[m - 1] >> 32));
+    float fb = m < c ? mono_inv((uint32_t)(sh.sel.buf[m] >> 32)) : INFINITY;
+    if (fb >= 2.0f) fb = INFINITY;  // only pivots are left
+    const bool certain = Xb == nullptr || fb - fa > two_tau;
+    __syncthreads();
+    if (certain) {
+      for (int t = tid; t < m; t += 1024) {
+        const uint32_t j = (uint32_t)sh.sel.buf[t];
+        atomicOr(&sh.R[j >> 5], 1u << (j & 31));
+      }
+    } else {
+      // every token whose aggregate can still be on either side of the boundary
+      const float lo = fa - two_tau, hi = fb + two_tau;
+      c = collect_sorted(v, n, want, hi, tid, sh.sel);
+      if (tid == 0) {
+        sh.below = 0;
+        sh.nband = 0;
+      }
+      __syncthreads();
+      for (int t = tid; t < c; t += 1024) {
+        const float a = mono_inv((uint32_t)(sh.sel.buf[t] >> 32));
+        const uint32_t j = (uint32_t)sh.sel.buf[t];
+        if (a < lo) {  // certainly among the m lowest
+          atomicOr(&sh.R[j >> 5], 1u << (j & 31));
+          atomicAdd(&sh.below, 1);
+        } else if (a <= hi) {
+          band_j[atomicAdd(&sh.nband, 1)] = (int)j;
+        }
+      }
+      __syncthreads();
+      const int nband = sh.nband, need = m - sh.below;
+      // fp64 aggregate of every band token from its P cosines, recomputed from the rows
+      if (nband * P <= 1024) {
+        // a (token, pivot) pair per wave at a time, then the aggregate per token
+        for (int t = wave; t < nband * P; t += 16) {
+          const int u = t / P, i = t - u * P;
+          const double s = row_cosine_f64<DT>(Xb + (long)sh.piv[i] * rowbytes,
+                                              Xb + (long)band_j[u] * rowbytes, g.D, lane);
+          if (lane == 0) sh.pair[t] = s;
+        }
+        __syncthreads();
+        for (int u = tid; u < nband; u += 1024) {
+          double a = sh.pair[u * P];
+          for (int i = 1; i < P; ++i)
+            a = agg == kAggMin ? fmin(a, sh.pair[u * P + i]) : fmax(a, sh.pair[u * P + i]);
+          band_v[u] = a;
+        }
+      } else {
+        for (int u = wave; u < nband; u += 16) {  // a large band: one token per wave
+          const unsigned char* xrow = Xb + (long)band_j[u] * rowbytes;
+          double a = row_cosine_f64<DT>(Xb + (long)sh.piv[0] * rowbytes, xrow, g.D, lane);
+          for (int i = 1; i < P; ++i) {
+            const double s =
+                row_cosine_f64<DT>(Xb + (long)sh.piv[i] * rowbytes, xrow, g.D, lane);
+            a = agg == kAggMin ? fmin(a, s) : fmax(a, s);
+          }
+          if (lane == 0) band_v[u] = a;
+        }
+      }
+      __syncthreads();
+      for (int u = tid; u < nband; u += 1024) {
+        const double au = band_v[u];
+        const int ju = band_j[u];
+        int beaten = 0;
+        for (int o = 0; o < nband && beaten < need; ++o) {
+          const double ao = band_v[o];
+          const int jo = band_j[o];
+          beaten += (ao < au || (ao == au && jo < ju)) ? 1 : 0;
+        }
+        if (beaten < need) atomicOr(&sh.R[ju >> 5], 1u << (ju & 31));
+      }
+    }
+  }
+  __syncthreads();
+
+  // emit the retained indices in ascending order
+  const int per = (words + 1023) / 1024;
+  const int w0 = tid * per;
+  int mine = 0;
+  for (int t = w0; t < w0 + per && t < words; ++t) mine += __popc(sh.R[t]);
+  int off = wave_excl_scan(mine, lane);
+  const int wtotal = __builtin_amdgcn_readlane(off + mine, 63);
+  if (lane == 0) sh.wcnt[wave] = wtotal;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < 16; ++w) off += w < wave ? sh.wcnt[w] : 0;
+  int* out = keep + sm.keep0 + off;
+  for (int t = w0; t < w0 + per && t < words; ++t) {
+    uint32_t mk = sh.R[t];
+    while (mk) {
+      const int bit = __ffs(mk) - 1;
+      *out++ = t * 32 + bit;
+      mk &= mk - 1;
+    }
+  }
+}
+
+}  // namespace dart

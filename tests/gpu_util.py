@@ -33,16 +33,17 @@ def to_device(w: W.Workload, ld: Optional[int] = None) -> torch.Tensor:
 
 
 def desc_of(w: W.Workload, cu_dev: Optional[torch.Tensor], ld: Optional[int] = None,
-            mode: int = D.DART_PIVOT_MAX_L1, K: Optional[int] = None) -> D.DartDesc:
+            mode: int = D.DART_PIVOT_MAX_L1, K: Optional[int] = None,
+            score_mode: int = D.DART_SCORE_PER_PIVOT) -> D.DartDesc:
     lens = w.lengths
     if w.ragged:
         return D.make_desc(w.B, w.D, w.P, w.dtype, K=w.K if K is None else K,
                            keep_num=w.keep_num, keep_den=w.keep_den, cu_seqlens=cu_dev,
                            total_N=int(w.cu[-1]), max_N=int(lens.max()) if len(lens) else 1,
-                           ld=ld, pivot_mode=mode)
+                           ld=ld, pivot_mode=mode, score_mode=score_mode)
     return D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]) if len(lens) else 0,
                        K=w.K if K is None else K, keep_num=w.keep_num, keep_den=w.keep_den,
-                       ld=ld, pivot_mode=mode)
+                       ld=ld, pivot_mode=mode, score_mode=score_mode)
 
 
 @dataclasses.dataclass
@@ -63,11 +64,12 @@ def bits(t: torch.Tensor) -> np.ndarray:
 
 def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT_MAX_L1,
                crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None,
-               given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK) -> GpuResult:
+               given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK,
+               score_mode: int = D.DART_SCORE_PER_PIVOT) -> GpuResult:
     """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots."""
     Xd = to_device(w, ld) if Xd is None else Xd
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
-    desc = desc_of(w, cu_dev, ld, mode)
+    desc = desc_of(w, cu_dev, ld, mode, score_mode=score_mode)
     ws = D.alloc_workspace(desc)
     total_keep = sum(w.budget(b) for b in range(w.B))
     total_N = int(w.cu[-1])

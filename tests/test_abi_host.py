@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_descriptor_layout_matches_the_header():
-    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, reserved));return 0;}\n'
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode));return 0;}\n'
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "t.c")
         open(c, "w").write(src)
@@ -40,7 +40,7 @@ def test_descriptor_layout_matches_the_header():
         out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split()
     T = D.DartDesc
     assert list(map(int, out)) == [C.sizeof(T), T.cu_seqlens.offset, T.ld.offset, T.K.offset,
-                                   T.reserved.offset]
+                                   T.score_mode.offset]
 
 
 def test_workspace_grows_with_the_problem():

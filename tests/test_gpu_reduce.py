@@ -249,6 +249,29 @@ def test_caller_supplied_pivots():
     G.run_reduce(w, mode=D.DART_PIVOT_GIVEN, given_piv=bad, expect_status=D.DART_ERR_DEVICE)
 
 
+@pytest.mark.parametrize("agg", [oracle.AGG_MIN, oracle.AGG_MAX])
+def test_single_threshold_rule(agg):
+    """DART_SCORE_MIN / DART_SCORE_MAX: one threshold for all pivots.  Exact copies put the
+    boundary on ties (the fp64 band path), near-duplicate frames on near-ties."""
+    mode = D.DART_SCORE_MIN if agg == oracle.AGG_MIN else D.DART_SCORE_MAX
+    cases = [W.multicrop_batch(B=3, N=700, D=1024, P=16, K=120, n_centroids=64),
+             W.image_batch(B=2, N=333, D=520, P=5, K=64, n_centroids=32),
+             W.single_image(N=300, D=256, P=8, K=50, n_centroids=16),
+             W.video_batch(B=2, frames=8, per_frame=60, D=512, P=8, K=96, n_centroids=8),
+             W.image_batch(B=2, N=150, D=256, P=8, K=8, n_centroids=16),     # pivots only
+             W.image_batch(B=2, N=150, D=256, P=8, K=150, n_centroids=16),   # keep everything
+             W.image_batch(B=1, N=300, D=256, P=4, K=37, n_centroids=1, sigma=0.0),  # all ties
+             W.ragged_batch(B=4, n_lo=300, n_hi=2500, D=512, P=16)]
+    for w in cases:
+        refs = [oracle.reduce_single(w.sample(b), w.dtype, w.P, w.budget(b), agg,
+                                     pos=w.pos[int(w.cu[b]):int(w.cu[b + 1])]) for b in range(w.B)]
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            continue
+        print(f"[case] {w.name} agg={agg} B={w.B} P={w.P}", flush=True)
+        g = G.run_reduce(w, score_mode=mode)
+        G.compare(w, g, refs)
+
+
 def test_random_ragged_sweep():
     """Twelve seeded random packed batches (lengths, ratios, pivots) against the oracle."""
     rng = np.random.default_rng(0xDA28)
@@ -280,6 +303,16 @@ def test_config1_image_batch(K):
 
 def test_config2_multicrop_batch():
     check(W.by_index(2))
+
+
+@pytest.mark.parametrize("agg", [oracle.AGG_MIN, oracle.AGG_MAX])
+def test_config2_single_threshold(agg):
+    w = W.by_index(2)
+    refs = [oracle.reduce_single(w.sample(b), w.dtype, w.P, w.budget(b), agg,
+                                 pos=w.pos[int(w.cu[b]):int(w.cu[b + 1])]) for b in range(w.B)]
+    assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+    g = G.run_reduce(w, score_mode=D.DART_SCORE_MIN if agg == oracle.AGG_MIN else D.DART_SCORE_MAX)
+    G.compare(w, g, refs)
 
 
 def test_config4_video_batch():
