@@ -45,6 +45,8 @@ def lib():
         L.oracle_select_pivots.restype = None
         L.oracle_scores.argtypes = [vp, i32, i64, i64, i64, vp, i32, dp]
         L.oracle_scores.restype = None
+        L.oracle_scores_rows.argtypes = [vp, i32, i64, i64, i64, vp, i32, i64, dp]
+        L.oracle_scores_rows.restype = None
         L.oracle_retain.argtypes = [dp, i64, vp, i32, i32, vp, vp, vp, dp]
         L.oracle_retain.restype = i32
         L.oracle_retain_single.argtypes = [dp, i64, vp, i32, i32, i32, vp, vp, vp, dp]
@@ -91,6 +93,16 @@ def scores(X: np.ndarray, dtype: int, piv: np.ndarray) -> np.ndarray:
     piv = np.ascontiguousarray(piv, dtype=np.int32)
     S = np.empty((piv.shape[0], n), dtype=np.float64)
     lib().oracle_scores(_p(X), dtype, n, d, ld, _p(piv), piv.shape[0], _p(S))
+    return S
+
+
+def scores_rows(X: np.ndarray, dtype: int, E: np.ndarray) -> np.ndarray:
+    """Scores of every token of X against rows E that are not tokens of X."""
+    n, d, ld = _check_rows(X, dtype)
+    pe, de, lde = _check_rows(E, dtype)
+    assert de == d
+    S = np.empty((pe, n), dtype=np.float64)
+    lib().oracle_scores_rows(_p(X), dtype, n, d, ld, _p(E), pe, lde, _p(S))
     return S
 
 
@@ -192,6 +204,45 @@ def reduce_given(X: np.ndarray, dtype: int, piv: np.ndarray, K: int,
     return r
 
 
+def reduce_mixed(X: np.ndarray, dtype: int, E: np.ndarray, P_in: int, K: int,
+                 pos: Optional[np.ndarray] = None, mode: int = MAX_L1, agg: int = 0,
+                 given: Optional[np.ndarray] = None) -> Reduced:
+    """The step with pivots of two sources (the 4 visual + 4 text pivots of the pivot
+    ablation): P_in pivots chosen among the tokens of X (by norm, or `given`), then the
+    rows of E, which are scored against but are no tokens of X.  piv marks them -1-e.
+    agg = 0: the staged rule; AGG_MIN / AGG_MAX: the single-threshold rule."""
+    n = X.shape[0]
+    r = Reduced()
+    r.c = l1_norms(X, dtype)
+    if given is not None:
+        inside = np.ascontiguousarray(given, dtype=np.int32)
+        assert inside.shape[0] == P_in
+        r.piv_gap = np.full(P_in, np.inf)
+    elif P_in > 0:
+        ranked = select_pivots(r.c, min(n, P_in + 1), mode)
+        inside = ranked[:P_in]
+        r.piv_gap = np.array([abs(r.c[ranked[i]] - r.c[ranked[i + 1]]) if i + 1 < len(ranked)
+                              else np.inf for i in range(P_in)])
+    else:
+        inside = np.empty(0, dtype=np.int32)
+        r.piv_gap = np.empty(0)
+    pe = E.shape[0]
+    r.piv = np.concatenate([inside, -1 - np.arange(pe, dtype=np.int32)]).astype(np.int32)
+    parts = []
+    if P_in > 0:
+        parts.append(scores(X, dtype, inside))
+    if pe > 0:
+        parts.append(scores_rows(X, dtype, E))
+    r.S = np.concatenate(parts, axis=0)
+    if agg == 0:
+        r.keep, r.stage_last, r.stage_next, r.stage_gap = retain(r.S, r.piv, K, diagnostics=True)
+    else:
+        r.keep, r.stage_last, r.stage_next, r.stage_gap = retain_single(r.S, r.piv, K, agg,
+                                                                        diagnostics=True)
+    r.Y, r.pos_out = gather(X, dtype, pos, r.keep)
+    return r
+
+
 def reduce_single(X: np.ndarray, dtype: int, P: int, K: int, agg: int,
                   pos: Optional[np.ndarray] = None, mode: int = MAX_L1) -> Reduced:
     """The whole step with the single-threshold retained set: pivots and scores as in
@@ -211,8 +262,8 @@ def admissible(X: np.ndarray, r: Reduced, rel: float = 1e-9) -> bool:
     and the first one refused at every stage) is either clearly non-zero, or an
     exact tie between two rows that are bit-identical (then the lowest index is
     the true answer)."""
-    P = r.piv.shape[0]
-    ranked = list(r.piv)
+    ranked = [p for p in r.piv if p >= 0]  # pivots from outside the sample took no decision
+    P = len(ranked)
     for i in range(P):
         g = r.piv_gap[i]
         if np.isinf(g) or g > rel * abs(r.c[ranked[i]]):

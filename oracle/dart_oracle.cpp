@@ -20,7 +20,10 @@
 //     token retained earlier is no longer a candidate, so |R| = K exactly;
 //   * ties are broken towards the lowest token index, everywhere;
 //   * a zero-norm row scores 0 against everything;
-//   * the retained tokens keep their original order and their position ids.
+//   * the retained tokens keep their original order and their position ids;
+//   * pivots may also come from outside the scored tokens (text-token pivots): they are
+//     scored against and have their stage, after the pivots chosen among the tokens, but
+//     take no slot of the budget.
 //
 // Parity status: every step below is pinned by closed forms, invariants, a
 // library cosine for P = 1 and brute-force enumeration on tiny inputs.  The
@@ -122,18 +125,54 @@ void oracle_scores(const void* X, int dtype, int64_t N, int64_t D, int64_t ld,
   }
 }
 
+// Step 3 for pivots that are not tokens of the scored set (Table 8 mixes 4 visual with 4
+// text pivots; the section on the modalities of pivot tokens draws them from text alone):
+// S[e*N + j] = <E[e], x_j> / (|E[e]| * |x_j|), 0 if a norm is 0 (Eq. 7).  E holds Pe rows
+// of D elements, row stride lde.
+void oracle_scores_rows(const void* X, int dtype, int64_t N, int64_t D, int64_t ld, const void* E,
+                        int Pe, int64_t lde, double* S) {
+  for (int e = 0; e < Pe; ++e) {
+    double pp = 0.0;
+    for (int64_t d = 0; d < D; ++d) {
+      double v = elem(E, dtype, e * lde + d);
+      pp += v * v;
+    }
+    const double pnorm = std::sqrt(pp);
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < N; ++j) {
+      double dot = 0.0, xx = 0.0;
+      for (int64_t d = 0; d < D; ++d) {
+        double x = elem(X, dtype, j * ld + d);
+        dot += elem(E, dtype, e * lde + d) * x;
+        xx += x * x;
+      }
+      double den = pnorm * std::sqrt(xx);
+      S[e * N + j] = den > 0.0 ? dot / den : 0.0;
+    }
+  }
+}
+
 // Step 4: the retained set (Eq. 9-10).  Returns 0, or -1 if P <= K <= N fails.
 // keep[K]: retained indices ascending.
 // Optional diagnostics, each of length P (pass NULL to skip): for stage i,
 //   stage_last[i]  = token taken last (highest score taken), -1 if the stage took none
 //   stage_next[i]  = best candidate NOT taken, -1 if none was left
 //   stage_gap[i]   = S[i][stage_next] - S[i][stage_last]  (+inf if either is missing)
+//
+// piv[i] < 0 marks a pivot that is not one of the N tokens (a text-token pivot, Table 8):
+// tokens are scored against it and it has its stage like any pivot, but it holds no slot
+// of R, so R starts as the Pin <= P pivots inside the sample, Pin <= K <= N is required
+// and the stages share K - Pin slots.
 int oracle_retain(const double* S, int64_t N, const int32_t* piv, int P, int K, int32_t* keep,
                   int32_t* stage_last, int32_t* stage_next, double* stage_gap) {
-  if (P < 1 || K < P || K > N) return -1;
+  if (P < 1) return -1;
+  int Pin = 0;
+  for (int i = 0; i < P; ++i) Pin += piv[i] >= 0 ? 1 : 0;
+  if (K < Pin || K > N) return -1;
   std::vector<char> in_R(N, 0);
-  for (int i = 0; i < P; ++i) in_R[piv[i]] = 1;
-  const int m = K - P, q = m / P, r = m % P;
+  for (int i = 0; i < P; ++i)
+    if (piv[i] >= 0) in_R[piv[i]] = 1;
+  const int m = K - Pin, q = m / P, r = m % P;
   for (int i = 0; i < P; ++i) {
     const int quota = q + (i < r ? 1 : 0);
     std::vector<int32_t> cand;
@@ -167,9 +206,13 @@ int oracle_retain(const double* S, int64_t N, const int32_t* piv, int P, int K, 
 // taken (-1 if none), gap = aggregate(next) - aggregate(last) (+inf if either is missing).
 int oracle_retain_single(const double* S, int64_t N, const int32_t* piv, int P, int K, int agg,
                          int32_t* keep, int32_t* last, int32_t* next, double* gap) {
-  if (P < 1 || K < P || K > N || (agg != 1 && agg != 2)) return -1;
+  if (P < 1 || (agg != 1 && agg != 2)) return -1;
+  int Pin = 0;  // pivots inside the sample (piv[i] < 0: a pivot from outside, see oracle_retain)
+  for (int i = 0; i < P; ++i) Pin += piv[i] >= 0 ? 1 : 0;
+  if (K < Pin || K > N) return -1;
   std::vector<char> in_R(N, 0);
-  for (int i = 0; i < P; ++i) in_R[piv[i]] = 1;
+  for (int i = 0; i < P; ++i)
+    if (piv[i] >= 0) in_R[piv[i]] = 1;
   std::vector<double> a(N);
   for (int64_t j = 0; j < N; ++j) {
     double v = S[j];
@@ -186,7 +229,7 @@ int oracle_retain_single(const double* S, int64_t N, const int32_t* piv, int P, 
     if (a[x] != a[y]) return a[x] < a[y];
     return x < y;
   });
-  const int m = K - P;
+  const int m = K - Pin;
   for (int t = 0; t < m; ++t) in_R[cand[t]] = 1;
   const int32_t l = m > 0 ? cand[m - 1] : -1;
   const int32_t nx = m < static_cast<int>(cand.size()) ? cand[m] : -1;

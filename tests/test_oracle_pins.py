@@ -394,3 +394,114 @@ def test_single_threshold_retain(agg):
     assert r.Y.tobytes() == X[r.keep].tobytes()
     one = oracle.reduce_single(X, w.dtype, 1, 30, agg)
     np.testing.assert_array_equal(one.keep, oracle.reduce(X, w.dtype, 1, 30).keep)
+
+
+# ----------------------------------------------------------------- pivots from outside the sample
+
+def test_outside_rows_score_like_inside_rows():
+    """Scores against rows that are no tokens of X: closed forms, and equal to the ordinary
+    scores when the outside row is a copy of a token (Eq. 7 does not care where the pivot
+    row is stored)."""
+    X = rows_f32([[3, 4, 0], [0, 0, 2], [1, 0, 0], [0, 0, 0]])
+    E = rows_f32([[6, 8, 0], [0, -1, 0], [0, 0, 0]])
+    S = oracle.scores_rows(X, oracle.F32, E)
+    np.testing.assert_allclose(S, [[1.0, 0.0, 0.6, 0.0], [-0.8, 0.0, 0.0, 0.0],
+                                   [0.0, 0.0, 0.0, 0.0]], rtol=0, atol=1e-15)
+    w = W.image_batch(B=1, N=90, D=64, P=4, K=20, n_centroids=6)
+    X = w.sample(0)
+    piv = np.array([17, 3, 88], dtype=np.int32)
+    big = np.zeros((3, 100), dtype=X.dtype)     # a wider row stride for the outside rows
+    big[:, :64] = X[piv]
+    np.testing.assert_array_equal(oracle.scores_rows(X, w.dtype, big[:, :64]),
+                                  oracle.scores(X, w.dtype, piv))
+
+
+def _mixed_reference(S, piv, K):
+    """Python restatement for pivots of which some (piv < 0) are outside the sample."""
+    P, N = S.shape
+    R = set(int(p) for p in piv if p >= 0)
+    m = K - len(R)
+    for i in range(P):
+        q = m // P + (1 if i < m % P else 0)
+        cand = sorted((j for j in range(N) if j not in R), key=lambda j: (S[i, j], j))
+        R.update(cand[:q])
+    return sorted(R)
+
+
+def test_retain_with_outside_pivots_bruteforce_and_invariants():
+    rng = np.random.default_rng(77)
+    for trial in range(40):
+        N = int(rng.integers(3, 40))
+        P = int(rng.integers(1, 7))
+        Pin = int(rng.integers(0, min(P, N) + 1))
+        K = int(rng.integers(Pin, N + 1))
+        S = np.round(rng.standard_normal((P, N)), 1)
+        piv = np.concatenate([rng.permutation(N)[:Pin], -1 - np.arange(P - Pin)]).astype(np.int32)
+        keep, last, nxt, gap = oracle.retain(S, piv, K, diagnostics=True)
+        assert keep.shape[0] == K and np.all(np.diff(keep) > 0)
+        assert set(piv[:Pin].tolist()) <= set(keep.tolist())
+        np.testing.assert_array_equal(keep, _mixed_reference(S, piv, K))
+        # the budget left after the inside pivots is split over ALL P stages
+        m = K - Pin
+        taken = [0 if last[i] < 0 else 1 for i in range(P)]
+        assert sum(taken) == min(P, m)
+    # each stage picks the minimum-sum subset (tiny inputs, every subset enumerated)
+    for trial in range(20):
+        N, P = int(rng.integers(3, 9)), int(rng.integers(1, 4))
+        Pin = int(rng.integers(0, min(P, N) + 1))
+        K = int(rng.integers(Pin, N + 1))
+        S = rng.integers(-2, 3, size=(P, N)).astype(np.float64) / 4.0
+        piv = np.concatenate([rng.permutation(N)[:Pin], -1 - np.arange(P - Pin)]).astype(np.int32)
+        R = set(piv[:Pin].tolist())
+        m = K - Pin
+        for i in range(P):
+            q = m // P + (1 if i < m % P else 0)
+            cand = [j for j in range(N) if j not in R]
+            best = min(itertools.combinations(cand, q), key=lambda T: (sum(S[i, j] for j in T), T))
+            R |= set(best)
+        np.testing.assert_array_equal(oracle.retain(S, piv, K), sorted(R))
+
+
+@pytest.mark.parametrize("agg", [0, oracle.AGG_MIN, oracle.AGG_MAX])
+def test_mixed_pivots_equal_the_step_on_the_joined_sequence(agg):
+    """Appending the outside pivot rows to the sample as extra tokens, naming them as
+    caller-supplied pivots and raising the budget by their number is the ordinary step on
+    the joined sequence; dropping the appended tokens from its retained set must give the
+    mixed-pivot result (the pivot ablation's 4 visual + 4 text pivots, Table 8)."""
+    w = W.image_batch(B=1, N=200, D=64, P=4, K=40, n_centroids=8)
+    X = w.sample(0)
+    rng = np.random.default_rng(5)
+    if w.dtype == oracle.BF16:
+        E = (rng.standard_normal((4, 64)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    else:
+        E = rng.standard_normal((4, 64)).astype(np.float32)
+    E[2] = X[11]                                  # a text pivot that equals a vision token
+    for P_in, K in ((4, 40), (4, 4), (0, 30), (3, 200), (1, 17)):
+        r = oracle.reduce_mixed(X, w.dtype, E, P_in, K, pos=w.pos[:200], agg=agg)
+        assert len(r.keep) == K and np.all(np.diff(r.keep) > 0)
+        assert list(r.piv[P_in:]) == [-1, -2, -3, -4]
+        joined = np.concatenate([X, E], axis=0)
+        pj = np.concatenate([r.piv[:P_in], 200 + np.arange(4)]).astype(np.int32)
+        Sj = oracle.scores(joined, w.dtype, pj)
+        if agg == 0:
+            kj = oracle.retain(Sj, pj, K + 4)
+        else:
+            kj = oracle.retain_single(Sj, pj, K + 4, agg)
+        np.testing.assert_array_equal(kj[-4:], 200 + np.arange(4))
+        np.testing.assert_array_equal(r.keep, kj[:-4])
+        np.testing.assert_array_equal(r.S, Sj[:, :200])
+        assert r.Y.tobytes() == X[r.keep].tobytes()
+        if P_in == 4:  # the inside pivots are those of the ordinary step
+            np.testing.assert_array_equal(r.piv[:4], oracle.reduce(X, w.dtype, 4, 40).piv)
+
+
+def test_no_outside_pivots_is_the_ordinary_step():
+    w = W.image_batch(B=1, N=120, D=64, P=5, K=33, n_centroids=8)
+    X = w.sample(0)
+    E = np.empty((0, 64), dtype=X.dtype)
+    r = oracle.reduce_mixed(X, w.dtype, E, 5, 33, pos=w.pos[:120])
+    full = oracle.reduce(X, w.dtype, 5, 33, pos=w.pos[:120])
+    np.testing.assert_array_equal(r.piv, full.piv)
+    np.testing.assert_array_equal(r.keep, full.keep)
+    np.testing.assert_array_equal(r.piv_gap, full.piv_gap)
+    np.testing.assert_array_equal(r.stage_gap, full.stage_gap)
