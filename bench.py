@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--score-mode", type=int, default=0, choices=[0, 1, 2],
                     help="0 = a threshold per pivot (the headline), 1/2 = one threshold on the "
                          "min/max aggregate (variant, context only)")
+    ap.add_argument("--p-ext", type=int, default=0,
+                    help="variant, context only: the last P_EXT of the workload's pivots are "
+                         "synthetic text-token rows from outside the samples")
     ap.add_argument("--hot", action="store_true",
                     help="context run: the same input buffer every step (cache-hot), not the "
                          "headline measurement")
@@ -137,13 +140,17 @@ def main():
     pos = torch.from_numpy(w.pos).cuda()
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
     lens = w.lengths
+    ext = None
+    if args.p_ext > 0:
+        E = W.text_pivot_rows(w, args.p_ext).reshape(-1, w.D)
+        ext = (torch.from_numpy(E.view(np.int16)).view(torch.bfloat16) if w.dtype == W.BF16
+               else torch.from_numpy(E)).cuda()
+    more = dict(score_mode=args.score_mode, ext_pivots=ext, P_ext=args.p_ext)
     if w.ragged:
         desc = D.make_desc(w.B, w.D, w.P, w.dtype, keep_num=w.keep_num, keep_den=w.keep_den,
-                           cu_seqlens=cu_dev, total_N=total_N, max_N=int(lens.max()),
-                           score_mode=args.score_mode)
+                           cu_seqlens=cu_dev, total_N=total_N, max_N=int(lens.max()), **more)
     else:
-        desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K,
-                           score_mode=args.score_mode)
+        desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K, **more)
     ws = D.alloc_workspace(desc)
     Y = torch.empty((total_K, w.D), dtype=X0.dtype, device="cuda")
     keep = torch.empty(total_K, dtype=torch.int32, device="cuda")
@@ -226,6 +233,7 @@ def main():
                                f"K={w.K if w.K else 'floor(0.111 N)'}",
                    "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
                                   "one threshold on the maximum"][args.score_mode],
+                   "pivots_from_outside": args.p_ext,
                    "total_tokens": total_N, "retained_tokens": total_K,
                    "input_copies_rotated": copies},
         "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),

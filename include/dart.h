@@ -43,6 +43,15 @@
  *   row's score depends only on its bytes and the pivot's bytes, not on where
  *   the row sits in the batch.
  * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N <= 2^27.
+ * Pivots from outside (desc.P_ext > 0).  Tokens are scored against such a pivot and it
+ *   has its stage in step (c) like any pivot -- after the pivots that are tokens, in the
+ *   order of its rows -- but it is no token: it is never retained and holds no slot of
+ *   the budget.  With P_in = P - P_ext, R starts as the P_in pivots inside the sample, the
+ *   P stages share K_b - P_in slots (floor((K_b - P_in)/P) each, +1 for the first
+ *   (K_b - P_in) mod P stages) and P_in <= K_b <= N_b is required instead of
+ *   P <= K_b <= N_b.  In every piv array entry i >= P_in of a sample is not read; where
+ *   the library writes piv it sets that entry to -1 - (i - P_in).  Step (a) chooses P_in
+ *   pivots (none if P_ext == P).
  */
 #ifndef DART_H_
 #define DART_H_
@@ -107,6 +116,14 @@ typedef struct dart_desc {
   int32_t keep_den;
   int32_t pivot_mode; /* dart_pivot_mode                                            */
   int32_t score_mode; /* dart_score_mode (0 = the default staged rule)              */
+  /* Pivots from outside the scored tokens (the text-token pivots of the pivot ablation,
+   * Table 8, and of the study of the pivots' modality): of the P pivots of every sample
+   * the LAST P_ext are rows of ext_pivots, the first P - P_ext are tokens of the sample.
+   * 0 = all pivots are tokens of the sample (then the two fields below are ignored).    */
+  int32_t P_ext;
+  int64_t ext_ld;         /* row stride of ext_pivots in elements, >= D                  */
+  const void* ext_pivots; /* DEVICE rows [B*P_ext, D] of X's dtype, 16-byte aligned row
+                             starts: sample b's outside pivot e is row b*P_ext + e        */
 } dart_desc;
 
 /* Bytes of workspace every entry point below accepts for this descriptor

@@ -33,7 +33,8 @@ class DartDesc(C.Structure):
                 ("cu_seqlens", C.c_void_p), ("total_N", C.c_int32), ("max_N", C.c_int32),
                 ("ld", C.c_int64), ("dtype", C.c_int32), ("K", C.c_int32),
                 ("keep_num", C.c_int32), ("keep_den", C.c_int32), ("pivot_mode", C.c_int32),
-                ("score_mode", C.c_int32)]
+                ("score_mode", C.c_int32), ("P_ext", C.c_int32), ("ext_ld", C.c_int64),
+                ("ext_pivots", C.c_void_p)]
 
 
 class DartError(RuntimeError):
@@ -97,7 +98,9 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
               keep_den: int = 1, cu_seqlens: Optional[torch.Tensor] = None, total_N: int = 0,
               max_N: int = 0, ld: Optional[int] = None,
               pivot_mode: int = DART_PIVOT_MAX_L1,
-              score_mode: int = DART_SCORE_PER_PIVOT) -> DartDesc:
+              score_mode: int = DART_SCORE_PER_PIVOT,
+              ext_pivots: Optional[torch.Tensor] = None, P_ext: int = 0,
+              ext_ld: Optional[int] = None) -> DartDesc:
     d = DartDesc()
     d.B, d.D, d.P, d.N = B, D, P, N
     d.cu_seqlens = None if cu_seqlens is None else cu_seqlens.data_ptr()
@@ -105,6 +108,10 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
     d.ld = D if ld is None else ld
     d.dtype, d.K, d.keep_num, d.keep_den = dtype, K, keep_num, keep_den
     d.pivot_mode, d.score_mode = pivot_mode, score_mode
+    d.P_ext = P_ext
+    if ext_pivots is not None:  # a tensor, or a raw device address
+        d.ext_pivots = ext_pivots.data_ptr() if hasattr(ext_pivots, "data_ptr") else int(ext_pivots)
+    d.ext_ld = (D if ext_ld is None else ext_ld) if P_ext > 0 else 0
     return d
 
 

@@ -32,6 +32,12 @@ struct Geo {
   // ragged only, filled by k_prepare: packed offsets of keep and of score tiles
   const int* cu_keep;
   const int* tile_start;
+  // Pivots from outside the scored tokens (text-token pivots): the last Pe of the P pivots
+  // of every sample are rows of E (sample b, outside pivot e at row b*Pe + e, stride lde
+  // elements); the first Pin = P - Pe are tokens of the sample.
+  int Pe, Pin;
+  long lde;
+  const void* E;
 };
 
 struct Sample {
@@ -47,7 +53,7 @@ __device__ __forceinline__ int budget_of(const Geo& g, int n) {
 
 // A ragged sample is processed only if its sizes respect the limits and the budget.
 __device__ __forceinline__ bool sample_ok(const Geo& g, int n, int k) {
-  return n > 0 && n <= g.max_N && g.P <= n && k >= g.P && k <= n;
+  return n > 0 && n <= g.max_N && g.Pin <= n && k >= g.Pin && k <= n;
 }
 
 // Dense: arithmetic.  Ragged: k_prepare has validated the offsets and stored the
@@ -68,15 +74,29 @@ __device__ __forceinline__ Sample sample_of(const Geo& g, int b) {
   return s;
 }
 
-// Even split of the K-P non-pivot slots over the P stages of Eq. (9)-(10): stage i
-// takes q (+1 for the first r stages).  Built once per sample (two divisions).
+// Row of pivot i of sample b: a token of the sample (index piv[b*P + i], clamped so that a
+// caller's bad index cannot leave X) or, for the last Pe pivots, a row of E.
+__device__ __forceinline__ const unsigned char* pivot_row(const Geo& g, const void* X, int esz,
+                                                          const Sample& sm, int b, int i,
+                                                          const int* __restrict__ piv) {
+  if (i >= g.Pin)
+    return static_cast<const unsigned char*>(g.E) + ((long)b * g.Pe + (i - g.Pin)) * g.lde * esz;
+  int p = piv[b * g.P + i];
+  p = p < 0 ? 0 : (p < sm.n ? p : sm.n - 1);
+  return static_cast<const unsigned char*>(X) + ((long)sm.row0 + p) * g.ld * esz;
+}
+
+// Even split of the K-Pin non-pivot slots over the P stages of Eq. (9)-(10): stage i
+// takes q (+1 for the first r stages).  Pin <= P pivots are tokens of the sample and hold
+// a slot each; the others come from outside.  Built once per sample (two divisions).
 struct Split {
-  int P, q, r;
-  __device__ __forceinline__ Split(int k, int P_) : P(P_), q((k - P_) / P_), r((k - P_) % P_) {}
+  int pin, q, r;  // pin: slots held by pivots; q, r: quotient and remainder over the stages
+  __device__ __forceinline__ Split(int k, int stages, int Pin)
+      : pin(Pin), q((k - Pin) / stages), r((k - Pin) % stages) {}
   __device__ __forceinline__ int quota(int i) const { return q + (i < r ? 1 : 0); }
   // slots filled once stages 0..i are done, pivots included
   __device__ __forceinline__ int filled_after(int i) const {
-    return P + q * (i + 1) + (i + 1 < r ? i + 1 : r);
+    return pin + q * (i + 1) + (i + 1 < r ? i + 1 : r);
   }
   // tokens taken by the stages before stage i (pivots not counted)
   __device__ __forceinline__ int taken_before(int i) const { return q * i + (i < r ? i : r); }

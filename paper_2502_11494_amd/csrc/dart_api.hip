@@ -44,8 +44,9 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
       d->pivot_mode != DART_PIVOT_GIVEN)
     return DART_ERR_DTYPE;
   if (d->B < 0 || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
-      d->score_mode < 0 || d->score_mode > 2)
+      d->score_mode < 0 || d->score_mode > 2 || d->P_ext < 0 || d->P_ext > d->P)
     return DART_ERR_SHAPE;
+  const int Pin = d->P - d->P_ext;  // pivots that are tokens of the sample
   const bool ragged = d->cu_seqlens != nullptr;
   long total;
   int maxn;
@@ -66,12 +67,18 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   int K = d->K;
   if (!ragged) {
     if (K == 0) K = (int)(((long)d->N * d->keep_num) / d->keep_den);
-    if (d->B > 0 && (d->P > d->N || K < d->P || K > d->N)) return DART_ERR_BUDGET;
-  } else if (K > 0 && (K < d->P || K > maxn)) {
+    if (d->B > 0 && (Pin > d->N || K < Pin || K > d->N)) return DART_ERR_BUDGET;
+  } else if (K > 0 && (K < Pin || K > maxn)) {
     return DART_ERR_BUDGET;
   }
   const int esz = d->dtype == DART_BF16 ? 2 : 4;
   if (((long)d->ld * esz) % 16 != 0 || ((long)d->D * esz) % 16 != 0) return DART_ERR_ALIGN;
+  if (d->P_ext > 0) {
+    if (!d->ext_pivots) return DART_ERR_NULL;
+    if (d->ext_ld < d->D) return DART_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(d->ext_pivots) & 15u) != 0 || ((long)d->ext_ld * esz) % 16 != 0)
+      return DART_ERR_ALIGN;
+  }
 
   Geo& g = p.g;
   g.B = d->B;
@@ -91,6 +98,10 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.cu = d->cu_seqlens;
   g.cu_keep = nullptr;
   g.tile_start = nullptr;
+  g.Pe = d->P_ext;
+  g.Pin = Pin;
+  g.lde = d->P_ext > 0 ? d->ext_ld : 0;
+  g.E = d->P_ext > 0 ? d->ext_pivots : nullptr;
   // 8-wave score workgroups (128 rows share a pivot chunk; 84 KB of LDS, one workgroup per
   // compute unit) measured 10% faster than 4-wave ones when the pivots fill one 16-column
   // block and all tiles fit the 256 compute units at once; with more tiles the smaller
@@ -196,13 +207,17 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
   return DART_OK;
 }
 
-dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, void* ws,
-                               hipStream_t st) {
+// Norms of the pivots first..P-1; piv_mark (optional) receives the marks of the pivots from
+// outside the samples.
+dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int first,
+                               int* piv_mark, void* ws, hipStream_t st) {
   double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kBF16)
-    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
+                       pl2, piv_mark);
   else
-    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, pl2);
+    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
+                       pl2, piv_mark);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -337,12 +352,15 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
                        at<int>(ws, p.o_status));
     DART_LAUNCH_CHECK();
     DART_TRY(mark(1));
-    DART_TRY(launch_pivot_norms(p, X, piv, ws, st));
+    DART_TRY(launch_pivot_norms(p, X, piv, 0, piv, ws, st));
     DART_TRY(mark(2));
   } else {
-    DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st));
+    // pivots chosen among the tokens (none if all of them come from outside) ...
+    if (p.g.Pin > 0) DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st));
     DART_TRY(mark(1));
-    DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+    if (p.g.Pin > 0) DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+    // ... then the norms and marks of those from outside
+    if (p.g.Pe > 0) DART_TRY(launch_pivot_norms(p, X, piv, p.g.Pin, piv, ws, st));
     DART_TRY(mark(2));
   }
   DART_TRY(launch_scores(p, X, piv, S, ws, st));
@@ -380,8 +398,12 @@ dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void*
   hipStream_t st = static_cast<hipStream_t>(stream);
   float* l1 = l1_out ? l1_out : at<float>(ws, p.o_l1);
   DART_TRY(launch_prepare(p, ws, st));
-  DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, false, st));
-  return launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st);
+  if (p.g.Pin > 0) {
+    DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, false, st));
+    DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+  }
+  if (p.g.Pe > 0) DART_TRY(launch_pivot_norms(p, X, piv, p.g.Pin, piv, ws, st));
+  return DART_OK;
 }
 
 dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const int32_t* piv,
@@ -394,7 +416,7 @@ dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const 
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
-  DART_TRY(launch_pivot_norms(p, X, piv, ws, st));
+  DART_TRY(launch_pivot_norms(p, X, piv, 0, nullptr, ws, st));
   return launch_scores(p, X, piv, S, ws, st);
 }
 

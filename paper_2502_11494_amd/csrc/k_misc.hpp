@@ -72,13 +72,14 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
   }
 }
 
-// Caller-supplied pivots: status[1] = 1 if any processed sample's P indices are not
+// Caller-supplied pivots: status[1] = 1 if any processed sample's Pin indices are not
 // distinct indices inside the sample, else 0.  grid: 1 block of 1024.
 __global__ __launch_bounds__(1024) void k_check_pivots(Geo g, const int* __restrict__ piv,
                                                        int* __restrict__ status) {
   int bad = 0;
   for (int idx = threadIdx.x; idx < g.B * g.P; idx += 1024) {
     const int b = idx / g.P, i = idx - b * g.P;
+    if (i >= g.Pin) continue;  // a pivot from outside the sample: nothing to check
     const Sample sm = sample_of(g, b);
     if (sm.k == 0) continue;
     const int p = piv[idx];
@@ -89,24 +90,22 @@ __global__ __launch_bounds__(1024) void k_check_pivots(Geo g, const int* __restr
   if (threadIdx.x == 0) status[1] = bad ? 1 : 0;
 }
 
-// Squared Euclidean norms of the pivots' rows in fp64.  grid: B blocks of 256.
+// Squared Euclidean norms of the rows of pivots first..Ppad-1 in fp64 (0 for padding
+// slots).  piv_mark (optional): entry i of a pivot from outside the sample is set to
+// -1 - (its row in the sample's share of E).  grid: B blocks of 256.
 template <int DT>
 __global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restrict__ X,
-                                                     const int* __restrict__ piv,
-                                                     double* __restrict__ pl2) {
+                                                     const int* __restrict__ piv, int first,
+                                                     double* __restrict__ pl2,
+                                                     int* __restrict__ piv_mark) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
   const int esz = DT == kBF16 ? 2 : 4;
-  for (int i = wave; i < g.Ppad; i += 4) {
+  if (piv_mark && tid >= g.Pin && tid < g.P) piv_mark[b * g.P + tid] = -1 - (tid - g.Pin);
+  for (int i = first + wave; i < g.Ppad; i += 4) {
     double l1 = 0.0, l2 = 0.0;
-    if (sm.k != 0 && i < g.P) {
-      int p = piv[b * g.P + i];
-      p = p < 0 ? 0 : (p < sm.n ? p : sm.n - 1);  // a caller's bad index must not leave X
-      const unsigned char* row =
-          static_cast<const unsigned char*>(X) + ((long)sm.row0 + p) * g.ld * esz;
-      row_l1_l2_f64<DT>(row, g.D, lane, l1, l2);
-    }
+    if (sm.k != 0 && i < g.P) row_l1_l2_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv), g.D, lane, l1, l2);
     if (lane == 0) pl2[b * g.Ppad + i] = l2;
   }
 }

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n;
-  const Split sp(sm.k, g.P);
+  const Split sp(sm.k, g.P, g.Pin);
   const int want = sp.stage_len(n, i);
   if (want == 0) return;  // the stage takes nothing
   const float* row = S + (long)g.P * sm.row0 + (long)i * n;

@@ -23,8 +23,9 @@ struct PivotShared {
 };
 
 // grid: B blocks of THREADS (1024).
-// l1 [total_N] fp32 criterion norms; piv [B*P]; pl2 [B*Ppad] squared L2 norms of
-// the pivots' hidden-state rows (0 for padding slots); scr [2*total_N] doubles.
+// l1 [total_N] fp32 criterion norms; piv [B*P] (the first Pin entries of a sample are
+// written); pl2 [B*Ppad] squared L2 norms of the pivots' hidden-state rows (0 for the
+// other slots); scr [2*total_N] doubles.
 template <int DT, int THREADS>
 __global__ __launch_bounds__(THREADS) void k_select_pivots(
     Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
   const Sample sm = sample_of(g, b);
   if (tid < g.Ppad) pl2[b * g.Ppad + tid] = 0.0;
   if (sm.k == 0) return;
-  const int n = sm.n, P = g.P;
+  const int n = sm.n, P = g.Pin;  // pivots chosen among the tokens; stride of piv is g.P
   const float sign = g.mode == kMaxL1 ? -1.f : 1.f;  // "lowest" of -norm = largest norm
 
   float v[kSelPerThread];
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
       const int ju = (int)(uint32_t)sh.sel.buf[u];
       const int cnt = __popcll(__ballot(on && (co < cu || (co == cu && jo < ju))));
       if (lane == 0 && cnt < P) {
-        piv[b * P + cnt] = ju;
+        piv[b * g.P + cnt] = ju;
         pl2[b * g.Ppad + cnt] = l2s[u];
       }
     }
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
       cnt += (co < cu || (co == cu && jo < ju)) ? 1 : 0;
     }
     if (cnt < P) {
-      piv[b * P + cnt] = ju;
+      piv[b * g.P + cnt] = ju;
       pl2[b * g.Ppad + cnt] = l2s[u];
     }
   }

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   double* sweep_s64 = scr_f64 + sm.row0;                                   // fallback sweep
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // fallback sweep
 
-  const Split sp(k, P);
+  const Split sp(k, P, g.Pin);
   // Lists of the stages [first, group_hi) that fit in LDS together (the first one maybe
   // only in part); block-uniform arithmetic, no memory access.
   int group_hi = 0, group_base = 0, staged_total = 0;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   plan_group(0);
   load_half(0);
   int my_pivot = -1;
-  if (tid < P) my_pivot = piv[b * P + tid];
+  if (tid < g.Pin) my_pivot = piv[b * P + tid];  // pivots from outside hold no slot
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
   for (int t = tid; t < (n + 3) / 4; t += kRetThreads)
     reinterpret_cast<uint32_t*>(sh.owner)[t] = 0xffffffffu;
@@ -388,9 +388,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     for (int q = wave; q < qn; q += kRetWaves) {  // a pair per wave: 16 row pairs in flight
       const int st = sh.q_stage[q];
       if (st >= fb_first) continue;  // will be walked again anyway
-      int p0 = piv[b * P + st];
-      p0 = p0 < 0 ? 0 : (p0 < n ? p0 : n - 1);
-      const double s0 = row_cosine_f64<DT>(Xb + (long)p0 * rowbytes,
+      const double s0 = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, st, piv),
                                            Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
       if (lane == 0) sh.q_s64[q] = s0;
     }
@@ -502,9 +500,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
 #pragma unroll
       for (int w = 0; w < kRetWaves; ++w) need -= sh.wcnt[w];
       const int nU = sh.cnt;
-      int pi = piv[b * P + i];
-      pi = pi < 0 ? 0 : (pi < n ? pi : n - 1);
-      const unsigned char* prow = Xb + (long)pi * rowbytes;
+      const unsigned char* prow = pivot_row(g, X, esz, sm, b, i, piv);
       for (int u = wave; u < nU; u += kRetWaves) {
         const double s64 =
             row_cosine_f64<DT>(prow, Xb + (long)sweep_idx[u] * rowbytes, g.D, lane);

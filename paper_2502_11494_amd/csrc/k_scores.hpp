@@ -48,7 +48,7 @@ struct ScoreShared {
   static constexpr int kRowB = CH * 2 + 16;
   unsigned char a[WAVES * 16 * kRowB];   // per-wave token chunk
   unsigned char p[2 * NB * 16 * kRowB];  // pivot chunk, double buffered
-  int pivrow[NB * 16];
+  const unsigned char* pivptr[NB * 16];  // pivot rows (nullptr: padding slot)
 };
 
 // Tile -> (sample, tile inside the sample).  Returns false for surplus blocks.
@@ -99,11 +99,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   const int n = sm.n, P = g.P;
   const int block_row0 = tl * (16 * WAVES);
   if (block_row0 >= n) return;
-  if (tid < NB * 16) {
-    int p = tid < P ? piv[b * P + tid] : -1;
-    sh.pivrow[tid] = p < n ? p : n - 1;  // a caller's bad index must not leave X
-    if (tid < P && p < 0) sh.pivrow[tid] = 0;
-  }
+  if (tid < NB * 16) sh.pivptr[tid] = tid < P ? pivot_row(g, X, 2, sm, b, tid, piv) : nullptr;
   __syncthreads();
 
   const long rowbytes = g.ld * 2;
@@ -123,14 +119,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
     aptr[t] = Xb + (long)r * rowbytes + col16 * 16;
   }
   // pivot loads: piece id = tid + THREADS*k -> pivot row id/PC, piece id%PC (== col16);
-  // padding slots read pivot 0's row and are zeroed after the load
+  // padding slots read the sample's first row and are zeroed after the load
   const unsigned char* pptr[LP];
   bool preal[LP];
 #pragma unroll
   for (int k = 0; k < LP; ++k) {
-    const int pr = sh.pivrow[(tid + THREADS * k) / PC];
-    preal[k] = pr >= 0;
-    pptr[k] = Xb + (long)(pr >= 0 ? pr : 0) * rowbytes + col16 * 16;
+    const unsigned char* pr = sh.pivptr[(tid + THREADS * k) / PC];
+    preal[k] = pr != nullptr;
+    pptr[k] = (pr != nullptr ? pr : Xb) + col16 * 16;
   }
 
   u32x4 ra[DEPTH][LA], rp[DEPTH][LP];
@@ -299,9 +295,7 @@ __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restric
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       int i = i0 + q < P ? i0 + q : P - 1;
-      int p = piv[b * P + i];
-      p = p < 0 ? 0 : (p < n ? p : n - 1);  // a caller's bad index must not leave X
-      pr[q] = reinterpret_cast<const f32x4v*>(Xb + (long)p * g.ld);
+      pr[q] = reinterpret_cast<const f32x4v*>(pivot_row(g, X, 4, sm, b, i, piv));
     }
     double dot[4][8], xx[4], pp[8];
 #pragma unroll

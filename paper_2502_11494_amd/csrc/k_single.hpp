@@ -44,7 +44,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     if (b == g.B - 1) cu_keep_out[g.B] = sm.keep0 + sm.k;
   }
   if (sm.k == 0) return;
-  const int n = sm.n, P = g.P, m = sm.k - P;
+  const int n = sm.n, P = g.P, m = sm.k - g.Pin;  // pivots from outside hold no slot
   const int words = (n + 31) >> 5;
   const int esz = DT == kBF16 ? 2 : 4;
   const long rowbytes = g.ld * esz;
@@ -54,12 +54,12 @@ __global__ __launch_bounds__(1024) void k_keep_single(
   int* band_j = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);
 
   for (int t = tid; t < words; t += 1024) sh.R[t] = 0u;
-  if (tid < P) {
+  if (tid < g.Pin) {
     int p = piv[b * P + tid];
     sh.piv[tid] = p < 0 ? 0 : (p < n ? p : n - 1);  // a caller's bad index must not leave X
   }
   __syncthreads();
-  if (tid < P) atomicOr(&sh.R[sh.piv[tid] >> 5], 1u << (sh.piv[tid] & 31));
+  if (tid < g.Pin) atomicOr(&sh.R[sh.piv[tid] >> 5], 1u << (sh.piv[tid] & 31));
   __syncthreads();
 
   if (m > 0) {
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
         // a (token, pivot) pair per wave at a time, then the aggregate per token
         for (int t = wave; t < nband * P; t += 16) {
           const int u = t / P, i = t - u * P;
-          const double s = row_cosine_f64<DT>(Xb + (long)sh.piv[i] * rowbytes,
+          const double s = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv),
                                               Xb + (long)band_j[u] * rowbytes, g.D, lane);
           if (lane == 0) sh.pair[t] = s;
         }
@@ -131,10 +131,10 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       } else {
         for (int u = wave; u < nband; u += 16) {  // a large band: one token per wave
           const unsigned char* xrow = Xb + (long)band_j[u] * rowbytes;
-          double a = row_cosine_f64<DT>(Xb + (long)sh.piv[0] * rowbytes, xrow, g.D, lane);
+          double a = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, 0, piv), xrow, g.D, lane);
           for (int i = 1; i < P; ++i) {
             const double s =
-                row_cosine_f64<DT>(Xb + (long)sh.piv[i] * rowbytes, xrow, g.D, lane);
+                row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv), xrow, g.D, lane);
             a = agg == kAggMin ? fmin(a, s) : fmax(a, s);
           }
           if (lane == 0) band_v[u] = a;

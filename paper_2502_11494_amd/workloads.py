@@ -170,3 +170,23 @@ def video_batch(seed: int = 0xDA270004, B: int = 4, frames: int = 64, per_frame:
 def by_index(i: int, **kw) -> Workload:
     """The five benchmark configurations, 0..4, at their full sizes by default."""
     return [single_image, image_batch, multicrop_batch, ragged_batch, video_batch][i](**kw)
+
+
+def text_pivot_rows(w: Workload, P_ext: int, seed: int = 1, mix: float = 0.5) -> np.ndarray:
+    """[B, P_ext, D] rows standing in for the hidden states of text tokens used as pivots
+    (the pivot ablation mixes 4 visual with 4 text pivots): a different distribution from
+    the vision tokens -- unit-normal rows -- each blended with one vision token of its
+    sample (weight `mix`) so that the vision tokens' scores against it are spread out
+    rather than all near zero.  Same element type as w.X."""
+    out = np.empty((w.B, P_ext, w.D), dtype=np.float32)
+    for b in range(w.B):
+        rng = _rng(seed, 77, b)
+        rows = rng.standard_normal((P_ext, w.D)).astype(np.float32)
+        n = int(w.cu[b + 1] - w.cu[b])
+        if n > 0:
+            pick = rng.integers(0, n, size=P_ext)
+            xs = w.sample(b)[pick]
+            xs = bf16_bits_to_f32(xs) if w.dtype == BF16 else xs
+            rows = (1.0 - mix) * rows + mix * xs
+        out[b] = rows
+    return f32_to_bf16_bits(out) if w.dtype == BF16 else out

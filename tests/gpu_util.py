@@ -34,16 +34,20 @@ def to_device(w: W.Workload, ld: Optional[int] = None) -> torch.Tensor:
 
 def desc_of(w: W.Workload, cu_dev: Optional[torch.Tensor], ld: Optional[int] = None,
             mode: int = D.DART_PIVOT_MAX_L1, K: Optional[int] = None,
-            score_mode: int = D.DART_SCORE_PER_PIVOT) -> D.DartDesc:
+            score_mode: int = D.DART_SCORE_PER_PIVOT, ext: Optional[torch.Tensor] = None,
+            P_ext: int = 0) -> D.DartDesc:
+    """ext [B*P_ext, D] device rows: the last P_ext of the w.P pivots come from outside."""
     lens = w.lengths
+    more = dict(ld=ld, pivot_mode=mode, score_mode=score_mode, ext_pivots=ext, P_ext=P_ext,
+                ext_ld=None if ext is None else ext.stride(0))
     if w.ragged:
         return D.make_desc(w.B, w.D, w.P, w.dtype, K=w.K if K is None else K,
                            keep_num=w.keep_num, keep_den=w.keep_den, cu_seqlens=cu_dev,
                            total_N=int(w.cu[-1]), max_N=int(lens.max()) if len(lens) else 1,
-                           ld=ld, pivot_mode=mode, score_mode=score_mode)
+                           **more)
     return D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]) if len(lens) else 0,
                        K=w.K if K is None else K, keep_num=w.keep_num, keep_den=w.keep_den,
-                       ld=ld, pivot_mode=mode, score_mode=score_mode)
+                       **more)
 
 
 @dataclasses.dataclass
@@ -65,11 +69,23 @@ def bits(t: torch.Tensor) -> np.ndarray:
 def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT_MAX_L1,
                crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None,
                given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK,
-               score_mode: int = D.DART_SCORE_PER_PIVOT) -> GpuResult:
-    """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots."""
+               score_mode: int = D.DART_SCORE_PER_PIVOT,
+               ext: Optional[np.ndarray] = None, ext_ld: Optional[int] = None) -> GpuResult:
+    """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots.
+    ext [B, P_ext, D] element bits: pivot rows from outside the samples (the last P_ext
+    of the w.P pivots)."""
     Xd = to_device(w, ld) if Xd is None else Xd
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
-    desc = desc_of(w, cu_dev, ld, mode, score_mode=score_mode)
+    ext_dev, P_ext = None, 0
+    if ext is not None:
+        P_ext = ext.shape[1]
+        flat = np.ascontiguousarray(ext.reshape(-1, w.D))
+        t = (torch.from_numpy(flat.view(np.int16)).view(torch.bfloat16) if w.dtype == W.BF16
+             else torch.from_numpy(flat))
+        ext_dev = torch.zeros((max(flat.shape[0], 1), ext_ld or w.D), dtype=t.dtype, device="cuda")
+        ext_dev[:flat.shape[0], :w.D] = t.cuda()
+        ext_dev = ext_dev[:, :w.D]  # rows keep the padded stride
+    desc = desc_of(w, cu_dev, ld, mode, score_mode=score_mode, ext=ext_dev, P_ext=P_ext)
     ws = D.alloc_workspace(desc)
     total_keep = sum(w.budget(b) for b in range(w.B))
     total_N = int(w.cu[-1])

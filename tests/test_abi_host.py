@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_descriptor_layout_matches_the_header():
-    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode));return 0;}\n'
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode), offsetof(dart_desc, P_ext), offsetof(dart_desc, ext_ld), offsetof(dart_desc, ext_pivots));return 0;}\n'
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "t.c")
         open(c, "w").write(src)
@@ -40,7 +40,8 @@ def test_descriptor_layout_matches_the_header():
         out = subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split()
     T = D.DartDesc
     assert list(map(int, out)) == [C.sizeof(T), T.cu_seqlens.offset, T.ld.offset, T.K.offset,
-                                   T.score_mode.offset]
+                                   T.score_mode.offset, T.P_ext.offset, T.ext_ld.offset,
+                                   T.ext_pivots.offset]
 
 
 def test_workspace_grows_with_the_problem():
@@ -70,6 +71,19 @@ BAD = [
      D.DART_ERR_BUDGET),
     (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=0, keep_num=1, keep_den=1000),
      D.DART_ERR_BUDGET),  # floor(0.576) = 0 < P
+    # pivots from outside the samples
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, P_ext=9, ext_pivots=4096),
+     D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, P_ext=-1), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, P_ext=4), D.DART_ERR_NULL),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, P_ext=4, ext_pivots=4096,
+          ext_ld=4000), D.DART_ERR_SHAPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, P_ext=4, ext_pivots=4100),
+     D.DART_ERR_ALIGN),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_F32, N=576, K=64, P_ext=4, ext_pivots=4096,
+          ext_ld=4098), D.DART_ERR_ALIGN),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=3, P_ext=4, ext_pivots=4096),
+     D.DART_ERR_BUDGET),  # K < P - P_ext
     (dict(B=1, D=4100, P=8, dtype=D.DART_BF16, N=576, K=64), D.DART_ERR_ALIGN),
     (dict(B=1, D=4096, P=8, dtype=D.DART_F32, N=576, K=64, ld=4098), D.DART_ERR_ALIGN),
 ]
@@ -117,6 +131,16 @@ def test_null_and_workspace_errors_need_no_device():
     d0 = D.make_desc(0, 4096, 8, D.DART_BF16, N=576, K=64)
     assert L.dart_reduce(C.byref(d0), None, None, 0, 0, None, None, None, None, None, None,
                          None, None, 0, None) == D.DART_OK
+
+
+def test_outside_pivots_relax_the_budget_check():
+    """With P_ext pivots from outside, P - P_ext <= K suffices (they hold no slot), and the
+    workspace does not depend on where the pivots come from."""
+    base = D.dart_workspace_bytes(D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=64))
+    d = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=5, P_ext=4, ext_pivots=4096)
+    assert D.dart_workspace_bytes(d) == base
+    d = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=1, P_ext=8, ext_pivots=4096)
+    assert D.dart_workspace_bytes(d) == base
 
 
 def test_status_strings():

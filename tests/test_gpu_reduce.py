@@ -272,6 +272,57 @@ def test_single_threshold_rule(agg):
         G.compare(w, g, refs)
 
 
+def _mixed_refs(w, E, P_ext, agg=0, given=None):
+    return [oracle.reduce_mixed(w.sample(b), w.dtype, E[b], w.P - P_ext, w.budget(b),
+                                pos=w.pos[int(w.cu[b]):int(w.cu[b + 1])], agg=agg,
+                                given=None if given is None else given[b][:w.P - P_ext])
+            for b in range(w.B)]
+
+
+def test_pivots_from_outside_the_samples():
+    """The last P_ext pivots are rows that are no tokens of the sample (text-token pivots of
+    the pivot ablation): scored against, staged after the inside pivots, never retained, no
+    slot of the budget.  Mixed 4 + 4, all pivots from outside, budgets between P_in and P,
+    ragged batches, fp32, a padded stride of the outside rows."""
+    cases = [(W.multicrop_batch(B=3, N=700, D=1024, P=8, K=128, n_centroids=64), 4),
+             (W.image_batch(B=2, N=333, D=520, P=8, K=64, n_centroids=32), 4),
+             (W.image_batch(B=2, N=333, D=520, P=6, K=61, n_centroids=32), 6),   # none inside
+             (W.single_image(N=300, D=256, P=8, K=50, n_centroids=16), 3),       # fp32
+             (W.image_batch(B=2, N=200, D=256, P=16, K=16, n_centroids=16), 12),  # K < P
+             (W.image_batch(B=2, N=200, D=256, P=16, K=200, n_centroids=16), 5),  # keep all
+             (W.video_batch(B=2, frames=8, per_frame=60, D=512, P=40, K=120, n_centroids=8), 8),
+             (W.ragged_batch(B=4, n_lo=300, n_hi=1500, D=512, P=16), 8)]
+    for ci, (w, P_ext) in enumerate(cases):
+        if w.K == 16 and P_ext == 12:
+            w.K = 7  # P_in = 4 <= K < P
+        E = W.text_pivot_rows(w, P_ext, seed=ci + 1)
+        refs = _mixed_refs(w, E, P_ext)
+        assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)), ci
+        print(f"[case] {w.name} B={w.B} P={w.P} P_ext={P_ext} K={w.K}", flush=True)
+        g = G.run_reduce(w, ext=E, ext_ld=w.D + 8 * (ci % 2))
+        G.compare(w, g, refs)
+
+
+@pytest.mark.parametrize("agg", [oracle.AGG_MIN, oracle.AGG_MAX])
+def test_pivots_from_outside_single_threshold_and_given(agg):
+    """Outside pivots with the single-threshold rule, and with caller-supplied inside pivots."""
+    mode = D.DART_SCORE_MIN if agg == oracle.AGG_MIN else D.DART_SCORE_MAX
+    rng = np.random.default_rng(0xDA30 + agg)
+    for ci, (w, P_ext) in enumerate(
+            [(W.multicrop_batch(B=2, N=700, D=1024, P=8, K=128, n_centroids=64), 4),
+             (W.image_batch(B=2, N=333, D=520, P=6, K=61, n_centroids=32), 6),
+             (W.ragged_batch(B=3, n_lo=300, n_hi=1500, D=512, P=16), 8)]):
+        E = W.text_pivot_rows(w, P_ext, seed=10 + ci)
+        refs = _mixed_refs(w, E, P_ext, agg=agg)
+        if all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            G.compare(w, G.run_reduce(w, ext=E, score_mode=mode), refs)
+        piv = np.stack([np.concatenate([rng.permutation(int(w.lengths[b]))[:w.P - P_ext],
+                                        np.full(P_ext, 12345)]) for b in range(w.B)]).astype(np.int32)
+        refs = _mixed_refs(w, E, P_ext, given=piv)
+        assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+        G.compare(w, G.run_reduce(w, ext=E, mode=D.DART_PIVOT_GIVEN, given_piv=piv), refs)
+
+
 def test_random_ragged_sweep():
     """Twelve seeded random packed batches (lengths, ratios, pivots) against the oracle."""
     rng = np.random.default_rng(0xDA28)
@@ -299,6 +350,17 @@ def test_config0_single_image_fp32():
 @pytest.mark.parametrize("K", [64, 128, 192])
 def test_config1_image_batch(K):
     check(W.by_index(1, K=K))
+
+
+def test_config1_pivot_ablation_four_visual_four_text():
+    """The pivot ablation's setting at full size: B=16 images of 576 tokens, 4 visual + 4 text
+    pivots, 128 retained tokens (Table 8 caption)."""
+    w = W.by_index(1, K=128)
+    assert w.P == 8
+    E = W.text_pivot_rows(w, 4, seed=8)
+    refs = _mixed_refs(w, E, 4)
+    assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+    G.compare(w, G.run_reduce(w, ext=E), refs)
 
 
 def test_config2_multicrop_batch():

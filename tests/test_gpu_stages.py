@@ -160,3 +160,46 @@ def test_topk_keep_recovers_from_misleading_scores(drift, frames, per_frame, K):
                      X=Xd)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(keep.cpu().numpy(), np.concatenate([r.keep for r in refs]))
+
+
+def test_stage_entry_points_with_pivots_from_outside():
+    """The stage entry points chained by hand with P_ext pivot rows that are no tokens of the
+    samples: selection picks P - P_ext pivots and marks the others, scores cover all P,
+    the retained set spends K - (P - P_ext) slots over the P stages."""
+    for w, P_ext in ((W.multicrop_batch(B=2, N=450, D=1024, P=8, K=100, n_centroids=32), 4),
+                     (W.ragged_batch(B=3, n_lo=200, n_hi=700, D=768, P=12), 12),
+                     (W.single_image(N=300, D=512, P=8, K=64, n_centroids=16), 2)):
+        E = W.text_pivot_rows(w, P_ext, seed=3)
+        flat = np.ascontiguousarray(E.reshape(-1, w.D))
+        Ed = (torch.from_numpy(flat.view(np.int16)).view(torch.bfloat16) if w.dtype == W.BF16
+              else torch.from_numpy(flat)).cuda()
+        Xd = G.to_device(w)
+        cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
+        desc = G.desc_of(w, cu_dev, ext=Ed, P_ext=P_ext)
+        ws = D.alloc_workspace(desc)
+        total, total_keep = int(w.cu[-1]), sum(w.budget(b) for b in range(w.B))
+        piv = torch.full((w.B * w.P,), 777, dtype=torch.int32, device="cuda")
+        S = torch.full((w.P * total,), float("nan"), dtype=torch.float32, device="cuda")
+        keep = torch.full((total_keep,), -1, dtype=torch.int32, device="cuda")
+        cu_keep = torch.full((w.B + 1,), -1, dtype=torch.int32, device="cuda")
+        Y = torch.zeros((total_keep, w.D), dtype=Xd.dtype, device="cuda")
+        D.dart_select_pivots(desc, Xd, piv, ws)
+        D.dart_duplication_scores(desc, Xd, piv, S, ws)
+        D.dart_topk_keep(desc, S, piv, keep, ws, X=Xd, cu_keep=cu_keep)
+        D.dart_gather_compact(desc, Xd, keep, Y, ws)
+        torch.cuda.synchronize()
+        assert D.dart_device_status(desc, ws) == D.DART_OK
+        piv_h, keep_h = piv.cpu().numpy().reshape(w.B, w.P), keep.cpu().numpy()
+        S_h, Y_h = S.cpu().numpy().astype(np.float64), G.bits(Y)
+        tau = D.score_tolerance(w.dtype)
+        k0 = 0
+        for b in range(w.B):
+            lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+            r = oracle.reduce_mixed(w.sample(b), w.dtype, E[b], w.P - P_ext, w.budget(b))
+            assert oracle.admissible(w.sample(b), r)
+            np.testing.assert_array_equal(piv_h[b], r.piv)
+            got = S_h[w.P * lo:w.P * hi].reshape(w.P, hi - lo)
+            assert np.abs(got - r.S).max() <= tau
+            np.testing.assert_array_equal(keep_h[k0:k0 + w.budget(b)], r.keep)
+            assert Y_h[k0:k0 + w.budget(b)].tobytes() == r.Y.tobytes()
+            k0 += w.budget(b)

@@ -52,3 +52,12 @@ def test_video_frames_drift_slowly():
 def test_full_size_shapes_of_the_headline_configuration():
     w = W.by_index(2, B=1)
     assert (w.X.shape, w.P, w.K, w.dtype) == ((2880, 4096), 16, 320, W.BF16)
+
+
+def test_text_pivot_rows_are_seeded_and_typed():
+    w = W.image_batch(B=2, N=100, D=64, P=8, K=20, n_centroids=8)
+    a, b = W.text_pivot_rows(w, 4, seed=3), W.text_pivot_rows(w, 4, seed=3)
+    assert a.shape == (2, 4, 64) and a.dtype == w.X.dtype
+    np.testing.assert_array_equal(a, b)
+    assert not np.array_equal(a, W.text_pivot_rows(w, 4, seed=4))
+    assert not np.array_equal(a[0], a[1])
