@@ -53,6 +53,10 @@ def lib():
         L.oracle_retain_single.restype = i32
         L.oracle_gather.argtypes = [vp, i32, i64, i64, vp, vp, i32, vp, vp]
         L.oracle_gather.restype = None
+        L.oracle_sequence_map.argtypes = [i64, i64, i64, vp, i32, vp]
+        L.oracle_sequence_map.restype = i64
+        L.oracle_gather_rows.argtypes = [vp, i64, i64, vp, i64, vp, i64]
+        L.oracle_gather_rows.restype = None
         L.oracle_reduce.argtypes = [vp, i32, i64, i64, i64, vp, i64, i64, vp, i32, i32, i32,
                                     vp, vp, dp, dp, vp, vp, dp, vp, vp, dp]
         L.oracle_reduce.restype = i32
@@ -151,6 +155,41 @@ def gather(X: np.ndarray, dtype: int, pos: Optional[np.ndarray], keep: np.ndarra
         pos_out = np.empty(K, dtype=np.int64)
     lib().oracle_gather(_p(X), dtype, d, ld, _p(pos), _p(keep), K, _p(Y), _p(pos_out))
     return Y, pos_out
+
+
+def sequence_map(T: int, vs: int, N: int, keep: np.ndarray) -> np.ndarray:
+    """Rows of the original sequence (T rows, vision span [vs, vs+N)) that make up the
+    shortened one: text before, retained vision tokens, text after."""
+    keep = np.ascontiguousarray(keep, dtype=np.int32)
+    out = np.empty(T - N + keep.shape[0], dtype=np.int32)
+    n = lib().oracle_sequence_map(T, vs, N, _p(keep), keep.shape[0], _p(out))
+    if n != out.shape[0]:
+        raise ValueError(f"oracle_sequence_map failed (T={T}, vs={vs}, N={N}, K={keep.shape[0]})")
+    return out
+
+
+def gather_rows(src: np.ndarray, row_map: np.ndarray) -> np.ndarray:
+    """dst[r] = src[row_map[r]] as a byte copy; src is 2-D with contiguous rows (any stride)."""
+    assert src.ndim == 2 and src.strides[1] == src.itemsize
+    row_map = np.ascontiguousarray(row_map, dtype=np.int32)
+    dst = np.empty((row_map.shape[0], src.shape[1]), dtype=src.dtype)
+    lib().oracle_gather_rows(_p(src), src.shape[1] * src.itemsize, src.strides[0], _p(row_map),
+                             row_map.shape[0], _p(dst), dst.strides[0] if dst.size else 0)
+    return dst
+
+
+def compact_sequences(seq_cu: np.ndarray, span_start: np.ndarray, lengths: np.ndarray, keeps):
+    """A packed batch: sequence b is rows [seq_cu[b], seq_cu[b+1]) and its vision span starts
+    at row span_start[b] (a row of the packed tensor) with lengths[b] tokens; keeps[b] are
+    its retained tokens.  Returns (row_map over the packed tensor, new seq_cu)."""
+    maps, cu = [], [0]
+    for b in range(len(lengths)):
+        lo, hi = int(seq_cu[b]), int(seq_cu[b + 1])
+        m = sequence_map(hi - lo, int(span_start[b]) - lo, int(lengths[b]), keeps[b]) + lo
+        maps.append(m.astype(np.int32))
+        cu.append(cu[-1] + m.shape[0])
+    row_map = np.concatenate(maps) if maps else np.empty(0, dtype=np.int32)
+    return row_map, np.asarray(cu, dtype=np.int32)
 
 
 class Reduced:

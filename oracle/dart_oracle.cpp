@@ -254,6 +254,33 @@ void oracle_gather(const void* X, int dtype, int64_t D, int64_t ld, const int64_
   }
 }
 
+// Step 5 for a whole sequence (Appendix D: the layers after the step see the text tokens
+// and the retained vision tokens; Table 2's KV-cache column shrinks the same way).  The
+// sequence has T rows; its vision tokens are rows [vs, vs + N); keep[K] are the retained
+// vision tokens (ascending, local to the span).  row_map[T - N + K] receives, for every row
+// of the shortened sequence, the row of the original sequence it comes from: the text
+// before the span, the retained vision tokens, the text after the span, all in order.
+// Returns the new length, or -1 if the span does not fit the sequence.
+int64_t oracle_sequence_map(int64_t T, int64_t vs, int64_t N, const int32_t* keep, int K,
+                            int32_t* row_map) {
+  if (vs < 0 || N < 0 || vs + N > T || K < 0 || K > N) return -1;
+  int64_t r = 0;
+  for (int64_t t = 0; t < vs; ++t) row_map[r++] = static_cast<int32_t>(t);
+  for (int k = 0; k < K; ++k) row_map[r++] = static_cast<int32_t>(vs + keep[k]);
+  for (int64_t t = vs + N; t < T; ++t) row_map[r++] = static_cast<int32_t>(t);
+  return r;
+}
+
+// dst row r = src row row_map[r], bit copy of row_bytes bytes (hidden states, the key and
+// value rows of the layers before the step, any per-token tensor).
+void oracle_gather_rows(const void* src, int64_t row_bytes, int64_t src_ld_bytes,
+                        const int32_t* row_map, int64_t n, void* dst, int64_t dst_ld_bytes) {
+  for (int64_t r = 0; r < n; ++r)
+    std::memcpy(static_cast<char*>(dst) + r * dst_ld_bytes,
+                static_cast<const char*>(src) + static_cast<int64_t>(row_map[r]) * src_ld_bytes,
+                static_cast<size_t>(row_bytes));
+}
+
 // Steps 1-5 for one sample.  crit == NULL means the hidden-state rows are their
 // own criterion.  Optional outputs may be NULL: c [N], S [P*N], Y, pos_out,
 // piv_gap [P] (c[piv[i]] - c[next in rank], sign-corrected for kMinL1),

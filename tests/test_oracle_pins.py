@@ -505,3 +505,57 @@ def test_no_outside_pivots_is_the_ordinary_step():
     np.testing.assert_array_equal(r.keep, full.keep)
     np.testing.assert_array_equal(r.piv_gap, full.piv_gap)
     np.testing.assert_array_equal(r.stage_gap, full.stage_gap)
+
+
+# ----------------------------------------------------------------- whole-sequence compaction
+
+def test_sequence_map_equals_a_boolean_mask():
+    """The shortened sequence is the original one with the pruned vision tokens masked out:
+    numpy's mask selection gives the same rows (Appendix D)."""
+    rng = np.random.default_rng(9)
+    for trial in range(50):
+        T = int(rng.integers(1, 80))
+        N = int(rng.integers(0, T + 1))
+        vs = int(rng.integers(0, T - N + 1))
+        K = int(rng.integers(0, N + 1))
+        keep = np.sort(rng.permutation(N)[:K]).astype(np.int32)
+        m = oracle.sequence_map(T, vs, N, keep)
+        mask = np.ones(T, dtype=bool)
+        mask[vs:vs + N] = False
+        mask[vs + keep] = True
+        np.testing.assert_array_equal(m, np.flatnonzero(mask))
+        assert m.shape[0] == T - N + K
+    # keeping every vision token changes nothing; a span that sticks out is refused
+    np.testing.assert_array_equal(oracle.sequence_map(9, 2, 5, np.arange(5)), np.arange(9))
+    with pytest.raises(ValueError):
+        oracle.sequence_map(9, 6, 5, np.arange(2))
+    # worked example: T=10, span rows 3..7, keep local 1 and 4 -> 0 1 2 | 4 7 | 8 9
+    np.testing.assert_array_equal(oracle.sequence_map(10, 3, 5, np.array([1, 4])),
+                                  [0, 1, 2, 4, 7, 8, 9])
+
+
+def test_gather_rows_and_packed_batches():
+    rng = np.random.default_rng(10)
+    src = rng.integers(0, 1 << 16, size=(40, 24)).astype(np.uint16)
+    wide = np.zeros((40, 32), dtype=np.uint16)
+    wide[:, :24] = src
+    m = np.array([5, 5, 0, 39, 17], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.gather_rows(src, m), src[m])
+    np.testing.assert_array_equal(oracle.gather_rows(wide[:, :24], m), src[m])  # padded stride
+    # three packed sequences of 12, 7 and 21 rows with spans inside
+    seq_cu = np.array([0, 12, 19, 40], dtype=np.int32)
+    span = np.array([2, 12, 25], dtype=np.int32)
+    lens = np.array([6, 7, 10])
+    keeps = [np.array([0, 5], dtype=np.int32), np.array([3], dtype=np.int32),
+             np.arange(10, dtype=np.int32)]
+    row_map, cu = oracle.compact_sequences(seq_cu, span, lens, keeps)
+    np.testing.assert_array_equal(cu, [0, 8, 9, 30])
+    mask = np.ones(40, dtype=bool)
+    for b in range(3):
+        mask[span[b]:span[b] + lens[b]] = False
+        mask[span[b] + keeps[b]] = True
+    np.testing.assert_array_equal(row_map, np.flatnonzero(mask))
+    # position ids with several planes: every plane is gathered with the same map
+    pos = rng.integers(0, 1000, size=(3, 40)).astype(np.int64)
+    got = np.stack([oracle.gather_rows(pos[p].reshape(-1, 1), row_map)[:, 0] for p in range(3)])
+    np.testing.assert_array_equal(got, pos[:, mask])
