@@ -17,7 +17,9 @@
  *
  * Conventions shared by every entry point
  * ---------------------------------------
- * Memory.  `desc` is host memory, read during the call only.  Every other
+ * Memory.  `desc` is host memory, read during the call only; the device arrays it
+ *   names (cu_seqlens, ext_pivots, span_start) are read by the enqueued kernels and must
+ *   stay valid and unchanged until that work has finished.  Every other
  *   pointer is DEVICE memory owned by the caller unless stated otherwise.  The
  *   library never allocates, frees or keeps a pointer; scratch comes from the
  *   caller's workspace `ws` of at least dart_workspace_bytes(desc) bytes,
@@ -36,8 +38,9 @@
  * Errors.  Violations visible on the host return a negative dart_status and
  *   enqueue nothing.  In ragged mode the per-sample sizes live on the device:
  *   a sample with N_b > max_N, N_b < P, K_b < P or K_b > N_b (N_b == 0 is a
- *   valid empty sample) is skipped -- it keeps zero tokens -- and a flag is
- *   raised in the workspace that dart_device_status reports.
+ *   valid empty sample), or whose span (desc.span_start) leaves X, is skipped -- it
+ *   keeps zero tokens -- and a flag is raised in the workspace that
+ *   dart_device_status reports.
  *   Non-finite input values give unspecified (but memory-safe) results.
  * Determinism.  Same inputs give bit-identical outputs, call after call, and a
  *   row's score depends only on its bytes and the pivot's bytes, not on where
@@ -124,6 +127,14 @@ typedef struct dart_desc {
   int64_t ext_ld;         /* row stride of ext_pivots in elements, >= D                  */
   const void* ext_pivots; /* DEVICE rows [B*P_ext, D] of X's dtype, 16-byte aligned row
                              starts: sample b's outside pivot e is row b*P_ext + e        */
+  /* Samples that are spans of a larger tensor (the vision tokens inside whole sequences of
+   * text and vision tokens): with span_start != NULL (ragged layout required) sample b's
+   * N_b = cu_seqlens[b+1] - cu_seqlens[b] tokens are rows span_start[b] .. span_start[b] +
+   * N_b - 1 of X -- and of crit and pos, which are indexed like X -- and X has X_rows rows.
+   * S, l1_out and keep stay packed by cu_seqlens.  A span that leaves [0, X_rows) makes its
+   * sample a skipped one (see Errors).  NULL: the samples are packed back to back.        */
+  const int32_t* span_start; /* DEVICE int32[B], or NULL                                   */
+  int32_t X_rows;            /* rows of X when span_start != NULL (>= total_N)             */
 } dart_desc;
 
 /* Bytes of workspace every entry point below accepts for this descriptor
@@ -179,7 +190,8 @@ DART_API dart_status dart_gather_compact(const dart_desc* desc, const void* X, c
                                 size_t ws_bytes, void* stream);
 
 /* (a)-(d) in one call.  Optional outputs (NULL to skip): pos/pos_out, cu_keep,
- * piv_out [B*P], S_out [P*total_N].
+ * piv_out [B*P], S_out [P*total_N].  Y == NULL skips step (d) (pos/pos_out are then
+ * ignored): for callers that compact whole sequences with dart_compact_sequences.
  * DART_PIVOT_GIVEN: step (a) is skipped and piv_out (required) is READ: piv_out[b*P + i]
  * is the index, local to sample b, of the pivot of stage i; crit is ignored.  The P
  * indices of a sample must be distinct and inside the sample: a list that is not makes
@@ -189,6 +201,43 @@ DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const voi
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* One per-token tensor for dart_compact_sequences: rows of row_bytes bytes (a multiple of
+ * 16), row r of src at src + r*src_ld_bytes, likewise dst; bases and strides multiples of
+ * 16.  src has desc.X_rows rows; dst needs room for the shortened batch. */
+typedef struct dart_row_tensor {
+  const void* src;      /* DEVICE */
+  void* dst;            /* DEVICE, must not overlap src */
+  int64_t row_bytes;
+  int64_t src_ld_bytes;
+  int64_t dst_ld_bytes;
+} dart_row_tensor;
+
+/* (d) for whole sequences -- Appendix D: the layers after the step see the text tokens and
+ * the retained vision tokens; the key/value rows cached by the layers before it shrink the
+ * same way (Table 2, KV-cache column).  Needs desc.span_start.  Sequence b is rows
+ * [seq_cu[b], seq_cu[b+1]) of every per-token tensor (seq_cu: DEVICE int32[B+1], from 0 to
+ * desc.X_rows, non-decreasing) and must contain its span; keep as produced by dart_reduce /
+ * dart_topk_keep for the same descriptor.  Outputs:
+ *   seq_cu_out [B+1]  offsets of the shortened sequences (the cu_seqlens a variable-length
+ *                     attention kernel takes): sequence b keeps its rows before the span,
+ *                     then rows span_start[b] + keep[.] in ascending order, then its rows
+ *                     after the span;
+ *   row_map [X_rows - total_N + sum of K_b at most]  row_map[r] = the row of the original
+ *                     tensors that row r of the shortened batch is a copy of;
+ *   tensors[i].dst    the n_tensors (HOST array, may be 0) tensors gathered by row_map, bit
+ *                     copies (hidden states, per-layer key and value rows, ...);
+ *   pos_out           pos_planes planes of position ids (plane p at pos + p*pos_plane_stride,
+ *                     X_rows entries; e.g. 3 planes for multimodal rotary embeddings),
+ *                     gathered into pos_out + p*pos_out_plane_stride; pos_planes may be 0.
+ * A seq_cu that is not as described, or a span outside its sequence, sets every entry of
+ * seq_cu_out to 0, copies nothing and makes dart_device_status report DART_ERR_DEVICE. */
+DART_API dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
+                                   const int32_t* keep, int32_t n_tensors,
+                                   const dart_row_tensor* tensors, const int64_t* pos,
+                                   int32_t pos_planes, int64_t pos_plane_stride, int64_t* pos_out,
+                                   int64_t pos_out_plane_stride, int32_t* seq_cu_out,
+                                   int32_t* row_map, void* ws, size_t ws_bytes, void* stream);
 
 /* dart_reduce that also records the caller's HIP events around its kernels:
  * events is a HOST array of 7 hipEvent_t (as void*); events[k] is recorded

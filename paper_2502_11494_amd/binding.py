@@ -23,7 +23,8 @@ DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN = 0, 1, 2
 DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
-           "dart_topk_keep", "dart_gather_compact", "dart_reduce", "dart_reduce_profiled",
+           "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
+           "dart_reduce_profiled",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -34,7 +35,13 @@ class DartDesc(C.Structure):
                 ("ld", C.c_int64), ("dtype", C.c_int32), ("K", C.c_int32),
                 ("keep_num", C.c_int32), ("keep_den", C.c_int32), ("pivot_mode", C.c_int32),
                 ("score_mode", C.c_int32), ("P_ext", C.c_int32), ("ext_ld", C.c_int64),
-                ("ext_pivots", C.c_void_p)]
+                ("ext_pivots", C.c_void_p), ("span_start", C.c_void_p), ("X_rows", C.c_int32)]
+
+
+class DartRowTensor(C.Structure):
+    """Mirror of `struct dart_row_tensor`."""
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("row_bytes", C.c_int64),
+                ("src_ld_bytes", C.c_int64), ("dst_ld_bytes", C.c_int64)]
 
 
 class DartError(RuntimeError):
@@ -61,12 +68,14 @@ def lib():
         L.dart_duplication_scores.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.dart_topk_keep.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dart_gather_compact.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.dart_compact_sequences.argtypes = [dp, vp, vp, i32, C.POINTER(DartRowTensor), vp, i32,
+                                             i64, vp, i64, vp, vp, vp, sz, vp]
         L.dart_reduce.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dart_reduce_profiled.argtypes = L.dart_reduce.argtypes + [C.POINTER(vp)]
         L.dart_device_status.argtypes = [dp, vp, vp]
         for name in ("dart_select_pivots", "dart_duplication_scores", "dart_topk_keep",
-                     "dart_gather_compact", "dart_reduce", "dart_reduce_profiled",
-                     "dart_device_status"):
+                     "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
+                     "dart_reduce_profiled", "dart_device_status"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -100,7 +109,8 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
               pivot_mode: int = DART_PIVOT_MAX_L1,
               score_mode: int = DART_SCORE_PER_PIVOT,
               ext_pivots: Optional[torch.Tensor] = None, P_ext: int = 0,
-              ext_ld: Optional[int] = None) -> DartDesc:
+              ext_ld: Optional[int] = None, span_start: Optional[torch.Tensor] = None,
+              X_rows: int = 0) -> DartDesc:
     d = DartDesc()
     d.B, d.D, d.P, d.N = B, D, P, N
     d.cu_seqlens = None if cu_seqlens is None else cu_seqlens.data_ptr()
@@ -112,6 +122,12 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
     if ext_pivots is not None:  # a tensor, or a raw device address
         d.ext_pivots = ext_pivots.data_ptr() if hasattr(ext_pivots, "data_ptr") else int(ext_pivots)
     d.ext_ld = (D if ext_ld is None else ext_ld) if P_ext > 0 else 0
+    if span_start is not None:  # a tensor, or a raw device address
+        d.span_start = (span_start.data_ptr() if hasattr(span_start, "data_ptr")
+                        else int(span_start))
+    d.X_rows = X_rows
+    # the descriptor holds raw device addresses: keep their tensors alive with it
+    d._keepalive = (cu_seqlens, ext_pivots, span_start)
     return d
 
 
@@ -153,6 +169,23 @@ def dart_gather_compact(desc, X, keep, Y, ws, *, pos=None, pos_out=None, stream=
     _check(lib().dart_gather_compact(C.byref(desc), _ptr(X), _ptr(pos), _ptr(keep), _ptr(Y),
                                      _ptr(pos_out), _ptr(ws), ws.numel(), _stream(stream)),
            "dart_gather_compact")
+
+
+def dart_compact_sequences(desc, seq_cu, keep, tensors, seq_cu_out, row_map, ws, *, pos=None,
+                           pos_out=None, stream=None):
+    """tensors: list of (src, dst) 2-D tensors with contiguous rows (any row stride).
+    pos / pos_out: [planes, rows] int64 tensors (plane-major), or None."""
+    arr = (DartRowTensor * max(len(tensors), 1))()
+    for i, (src, dst) in enumerate(tensors):
+        esz = src.element_size()
+        arr[i] = DartRowTensor(src.data_ptr(), dst.data_ptr(), src.shape[1] * esz,
+                               src.stride(0) * esz, dst.stride(0) * esz)
+    planes = 0 if pos is None else pos.shape[0]
+    _check(lib().dart_compact_sequences(
+        C.byref(desc), _ptr(seq_cu), _ptr(keep), len(tensors), arr, _ptr(pos), planes,
+        0 if pos is None else pos.stride(0), _ptr(pos_out),
+        0 if pos_out is None else pos_out.stride(0), _ptr(seq_cu_out), _ptr(row_map), _ptr(ws),
+        ws.numel(), _stream(stream)), "dart_compact_sequences")
 
 
 def dart_reduce(desc, X, Y, keep, ws, *, crit=None, crit_D=0, crit_ld=0, pos=None, pos_out=None,

@@ -38,10 +38,16 @@ struct Geo {
   int Pe, Pin;
   long lde;
   const void* E;
+  // Ragged only, optional: sample b's tokens are rows span[b] .. span[b]+N_b-1 of X (of
+  // the criterion tensor, of the position ids), X having x_rows rows; nullptr: the samples
+  // are packed back to back (row cu[b]).  Workspace arrays are always indexed by cu[b].
+  const int* span;
+  int x_rows;
 };
 
 struct Sample {
-  int row0;  // first row of the sample in X
+  int row0;  // first row of the sample in the packed per-token arrays (scores, norms, ...)
+  int xrow;  // first row of the sample in X
   int n;     // tokens
   int k;     // tokens to keep (0: skip the sample)
   int keep0; // first row of the sample in keep / Y / pos_out
@@ -62,11 +68,13 @@ __device__ __forceinline__ Sample sample_of(const Geo& g, int b) {
   Sample s;
   if (g.cu == nullptr) {
     s.row0 = b * g.N;
+    s.xrow = s.row0;
     s.n = g.N;
     s.k = g.K;
     s.keep0 = b * g.K;
   } else {
     s.row0 = g.cu[b];
+    s.xrow = g.span ? g.span[b] : s.row0;
     s.n = g.cu[b + 1] - s.row0;
     s.keep0 = g.cu_keep[b];
     s.k = g.cu_keep[b + 1] - s.keep0;
@@ -83,7 +91,7 @@ __device__ __forceinline__ const unsigned char* pivot_row(const Geo& g, const vo
     return static_cast<const unsigned char*>(g.E) + ((long)b * g.Pe + (i - g.Pin)) * g.lde * esz;
   int p = piv[b * g.P + i];
   p = p < 0 ? 0 : (p < sm.n ? p : sm.n - 1);
-  return static_cast<const unsigned char*>(X) + ((long)sm.row0 + p) * g.ld * esz;
+  return static_cast<const unsigned char*>(X) + ((long)sm.xrow + p) * g.ld * esz;
 }
 
 // Even split of the K-Pin non-pivot slots over the P stages of Eq. (9)-(10): stage i

@@ -61,6 +61,10 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
     maxn = d->max_N;
   }
   if (total > (1L << 27)) return DART_ERR_SHAPE;
+  if (d->span_start) {  // spans of a larger tensor: packed lengths required, X_rows bounds them
+    if (!ragged) return DART_ERR_NULL;
+    if (d->X_rows < total || d->X_rows > (1 << 30)) return DART_ERR_SHAPE;
+  }
   if (d->K < 0) return DART_ERR_BUDGET;
   if (d->K == 0 && (d->keep_den <= 0 || d->keep_num < 0 || d->keep_num > d->keep_den))
     return DART_ERR_BUDGET;
@@ -102,6 +106,8 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.Pin = Pin;
   g.lde = d->P_ext > 0 ? d->ext_ld : 0;
   g.E = d->P_ext > 0 ? d->ext_pivots : nullptr;
+  g.span = d->span_start;
+  g.x_rows = d->span_start ? d->X_rows : (int)total;
   // 8-wave score workgroups (128 rows share a pivot chunk; 84 KB of LDS, one workgroup per
   // compute unit) measured 10% faster than 4-wave ones when the pivots fill one 16-column
   // block and all tiles fit the 256 compute units at once; with more tiles the smaller
@@ -179,12 +185,15 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   const bool keep = keep_cached && (double)rows * ldc * p.esz <= 224e6;
 #define DART_LAUNCH_L1(DT)                                                                       \
   do {                                                                                           \
-    if (keep)                                                                                    \
-      hipLaunchKernelGGL((k_row_l1<DT, ROWS, true>), dim3(blocks), dim3(256), 0, st, C, Dc, ldc, \
-                         rows, l1);                                                              \
+    if (p.g.span)                                                                                \
+      hipLaunchKernelGGL((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,   \
+                         Dc, ldc, rows, l1, p.g);                                                \
+    else if (keep)                                                                               \
+      hipLaunchKernelGGL((k_row_l1<DT, ROWS, true, false>), dim3(blocks), dim3(256), 0, st, C,   \
+                         Dc, ldc, rows, l1, p.g);                                                \
     else                                                                                         \
-      hipLaunchKernelGGL((k_row_l1<DT, ROWS, false>), dim3(blocks), dim3(256), 0, st, C, Dc,     \
-                         ldc, rows, l1);                                                         \
+      hipLaunchKernelGGL((k_row_l1<DT, ROWS, false, false>), dim3(blocks), dim3(256), 0, st, C,  \
+                         Dc, ldc, rows, l1, p.g);                                                \
   } while (0)
   if (p.g.dtype == kBF16) DART_LAUNCH_L1(kBF16); else DART_LAUNCH_L1(kF32);
 #undef DART_LAUNCH_L1
@@ -329,9 +338,9 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   Plan p;
   DART_TRY(make_plan(desc, p));
   if (p.g.B == 0) return DART_OK;
-  if (!X || !Y || !keep || (pos != nullptr) != (pos_out != nullptr)) return DART_ERR_NULL;
+  if (!X || !keep || (Y && (pos != nullptr) != (pos_out != nullptr))) return DART_ERR_NULL;
   if (p.g.mode == kGiven && !piv_out) return DART_ERR_NULL;
-  if (misaligned16(X) || misaligned16(Y)) return DART_ERR_ALIGN;
+  if (misaligned16(X) || (Y && misaligned16(Y))) return DART_ERR_ALIGN;
   if (p.g.mode == kGiven) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
@@ -369,7 +378,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   DART_TRY(mark(4));
   DART_TRY(launch_retain(p, S, piv, X, keep, cu_keep, ws, st));
   DART_TRY(mark(5));
-  DART_TRY(launch_gather(p, X, pos, keep, Y, pos_out, st));
+  if (Y) DART_TRY(launch_gather(p, X, pos, keep, Y, pos_out, st));  // NULL: the caller compacts
   DART_TRY(mark(6));
   return DART_OK;
 }
@@ -449,6 +458,68 @@ dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int6
   return launch_gather(p, X, pos, keep, Y, pos_out, st);
 }
 
+dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
+                                   const int32_t* keep, int32_t n_tensors,
+                                   const dart_row_tensor* tensors, const int64_t* pos,
+                                   int32_t pos_planes, int64_t pos_plane_stride, int64_t* pos_out,
+                                   int64_t pos_out_plane_stride, int32_t* seq_cu_out,
+                                   int32_t* row_map, void* ws, size_t ws_bytes, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (!desc->span_start) return DART_ERR_NULL;  // sequences exist only around spans
+  if (n_tensors < 0 || pos_planes < 0) return DART_ERR_SHAPE;
+  if (!seq_cu || !keep || !seq_cu_out || !row_map || (n_tensors > 0 && !tensors) ||
+      (pos_planes > 0 && (!pos || !pos_out)))
+    return DART_ERR_NULL;
+  for (int i = 0; i < n_tensors; ++i) {
+    const dart_row_tensor& t = tensors[i];
+    if (!t.src || !t.dst) return DART_ERR_NULL;
+    if (t.row_bytes <= 0 || t.src_ld_bytes < t.row_bytes || t.dst_ld_bytes < t.row_bytes)
+      return DART_ERR_SHAPE;
+    if (misaligned16(t.src) || misaligned16(t.dst) || t.row_bytes % 16 || t.src_ld_bytes % 16 ||
+        t.dst_ld_bytes % 16)
+      return DART_ERR_ALIGN;
+  }
+  if (pos_planes > 0 && (pos_plane_stride < p.g.x_rows || pos_out_plane_stride < 0))
+    return DART_ERR_SHAPE;
+  DART_TRY(check_ws(p, ws, ws_bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DART_TRY(launch_prepare(p, ws, st));
+  // every sequence loses its pruned vision tokens; at most this many rows remain
+  const long rows_bound = (long)p.g.x_rows - p.g.total_N + p.keep_rows_bound;
+  hipLaunchKernelGGL(k_seq_offsets, dim3(1), dim3(1024), 0, st, p.g, seq_cu, seq_cu_out,
+                     at<int>(ws, p.o_status));
+  DART_LAUNCH_CHECK();
+  if (p.g.B == 0 || rows_bound <= 0) return DART_OK;
+  hipLaunchKernelGGL(k_seq_row_map, dim3((unsigned)((rows_bound + 255) / 256)), dim3(256), 0, st,
+                     p.g, seq_cu, seq_cu_out, keep, row_map);
+  DART_LAUNCH_CHECK();
+  const int* n_rows = seq_cu_out + p.g.B;
+  for (int i0 = 0; i0 < n_tensors; i0 += kSeqOps) {
+    SeqOps ops;
+    const int cnt = n_tensors - i0 < kSeqOps ? n_tensors - i0 : kSeqOps;
+    for (int i = 0; i < kSeqOps; ++i) {
+      const dart_row_tensor& t = tensors[i0 + (i < cnt ? i : 0)];
+      ops.src[i] = static_cast<const unsigned char*>(t.src);
+      ops.dst[i] = static_cast<unsigned char*>(t.dst);
+      ops.row_bytes[i] = t.row_bytes;
+      ops.src_ld[i] = t.src_ld_bytes;
+      ops.dst_ld[i] = t.dst_ld_bytes;
+    }
+    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)((rows_bound + 3) / 4), cnt), dim3(256), 0,
+                       st, ops, n_rows, row_map);
+    DART_LAUNCH_CHECK();
+  }
+  if (pos_planes > 0) {
+    hipLaunchKernelGGL(k_gather_pos, dim3((unsigned)((rows_bound + 255) / 256), pos_planes),
+                       dim3(256), 0, st, n_rows, row_map,
+                       reinterpret_cast<const long long*>(pos), (long)pos_plane_stride,
+                       reinterpret_cast<long long*>(pos_out), (long)pos_out_plane_stride);
+    DART_LAUNCH_CHECK();
+  }
+  return DART_OK;
+}
+
 dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out, void* ws,
@@ -474,7 +545,8 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   DART_TRY(make_plan(desc, p));
   if (!ws) return DART_ERR_WORKSPACE;
   if (p.g.B == 0 || (p.g.cu == nullptr && p.g.mode != kGiven)) return DART_OK;
-  int flag[2] = {0, 0};  // [0] ragged offsets / budgets, [1] given pivots
+  // [0] ragged offsets / budgets / spans, [1] given pivots, [2] sequences around the spans
+  int flag[3] = {0, 0, 0};
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hipMemcpyAsync(flag, static_cast<const unsigned char*>(ws) + p.o_status, sizeof(flag),
                      hipMemcpyDeviceToHost, st) != hipSuccess)
@@ -482,7 +554,8 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   if (hipStreamSynchronize(st) != hipSuccess) return DART_ERR_HIP;
   if (p.g.cu == nullptr) flag[0] = 0;
   if (p.g.mode != kGiven) flag[1] = 0;
-  return (flag[0] | flag[1]) ? DART_ERR_DEVICE : DART_OK;
+  if (p.g.span == nullptr) flag[2] = 0;
+  return (flag[0] | flag[1] | flag[2]) ? DART_ERR_DEVICE : DART_OK;
 }
 
 double dart_score_tolerance(int32_t dtype) {
@@ -500,7 +573,8 @@ const char* dart_strerror(dart_status status) {
     case DART_ERR_ALIGN: return "row starts are not 16-byte aligned";
     case DART_ERR_HIP: return "a HIP call or kernel launch failed";
     case DART_ERR_DEVICE:
-      return "a ragged sample violated the size or budget limits, or a given pivot list is invalid";
+      return "a ragged sample violated the size or budget limits, a span or sequence is invalid, "
+             "or a given pivot list is invalid";
   }
   return "unknown status";
 }

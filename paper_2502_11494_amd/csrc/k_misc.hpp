@@ -9,8 +9,9 @@ namespace dart {
 // Ragged batches only.  One block of 1024 threads: validates the offsets and every
 // sample and writes the packed offsets cu_keep[B+1] (retained rows; a skipped
 // sample keeps 0) and tile_start[B+1] (score tiles of g.tile_rows rows).  status[0] becomes
-// 1 if a non-empty sample was rejected, 2 if cu_seqlens itself is not a
-// non-decreasing sequence from 0 to total_N (then every sample is skipped).
+// 1 if a non-empty sample was rejected (its sizes or budget, or a span that leaves X), 2 if
+// cu_seqlens itself is not a non-decreasing sequence from 0 to total_N (then every sample
+// is skipped).
 __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_keep,
                                                   int* __restrict__ tile_start,
                                                   int* __restrict__ status) {
@@ -32,7 +33,10 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
     if (b < g.B && !broken) {
       int n = g.cu[b + 1] - g.cu[b];
       int kb = budget_of(g, n);
-      if (sample_ok(g, n, kb)) {
+      // a span must lie inside X (long arithmetic: the caller's start may be anything)
+      const bool inside = g.span == nullptr ||
+                          (g.span[b] >= 0 && (long)g.span[b] + n <= (long)g.x_rows);
+      if (inside && sample_ok(g, n, kb)) {
         k = kb;
         tiles = (n + g.tile_rows - 1) / g.tile_rows;
       } else if (n != 0) {
@@ -69,6 +73,7 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
     cu_keep[g.B] = carry[0];
     tile_start[g.B] = carry[1];
     status[0] = broken ? 2 : bad;
+    status[2] = 0;  // set by k_seq_offsets if it runs after this
   }
 }
 
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(256) void k_gather(Geo g, int esz, const void* __re
   const int n = g.cu ? g.cu[b + 1] - row0 : g.N;
   int kr = keep[r];
   kr = kr < 0 ? 0 : (kr < n ? kr : n - 1);  // a caller's bad index must not leave X
-  const long src = (long)row0 + kr;
+  const long src = (long)(g.span ? g.span[b] : row0) + kr;
   const u32x4* in = reinterpret_cast<const u32x4*>(static_cast<const unsigned char*>(X) +
                                                    src * g.ld * esz);
   u32x4* out = reinterpret_cast<u32x4*>(static_cast<unsigned char*>(Y) + r * (long)g.D * esz);
@@ -155,6 +160,136 @@ __global__ __launch_bounds__(256) void k_gather(Geo g, int esz, const void* __re
     }
   }
   if (pos && lane == 0) pos_out[r] = pos[src];
+}
+
+// ---- whole-sequence compaction (Appendix D: text before the vision span, the retained
+// vision tokens, text after it) ------------------------------------------------------
+
+// One block of 1024.  Sequence b is rows [seq_cu[b], seq_cu[b+1]) of the caller's per-token
+// tensors and must contain its span [span[b], span[b] + N_b).  Writes the new offsets
+// seq_cu_out[B+1]: sequence b shrinks by N_b - K_b rows (K_b = 0 for a skipped sample, whose
+// vision tokens are all dropped).  status[2] = 1 and all-zero offsets if seq_cu is not a
+// non-decreasing sequence from 0 to x_rows or a span is not inside its sequence.
+__global__ __launch_bounds__(1024) void k_seq_offsets(Geo g, const int* __restrict__ seq_cu,
+                                                      int* __restrict__ seq_cu_out,
+                                                      int* __restrict__ status) {
+  __shared__ int red[16];
+  __shared__ int carry;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  int bad = 0;
+  for (int b = tid; b < g.B; b += 1024) {
+    const int lo = seq_cu[b], hi = seq_cu[b + 1];
+    const int n = g.cu[b + 1] - g.cu[b];
+    bad |= (hi < lo || g.span[b] < lo || (long)g.span[b] + n > (long)hi) ? 1 : 0;
+  }
+  if (tid == 0) {
+    carry = 0;
+    // status[0] == 2: k_prepare found cu_seqlens itself broken (lengths are meaningless)
+    bad |= (status[0] == 2 || seq_cu[0] != 0 || seq_cu[g.B] != g.x_rows) ? 1 : 0;
+  }
+  bad = __syncthreads_or(bad);
+  for (int b0 = 0; b0 < g.B; b0 += 1024) {
+    const int b = b0 + tid;
+    int len = 0;
+    if (b < g.B && !bad) {
+      const int n = g.cu[b + 1] - g.cu[b];
+      len = (seq_cu[b + 1] - seq_cu[b]) - n + (g.cu_keep[b + 1] - g.cu_keep[b]);
+    }
+    const int sc = wave_excl_scan(len, lane);
+    if (lane == 63) red[w] = sc + len;
+    __syncthreads();
+    int base = carry, tot = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      base += i < w ? red[i] : 0;
+      tot += red[i];
+    }
+    if (b < g.B) seq_cu_out[b] = base + sc;
+    __syncthreads();
+    if (tid == 0) carry += tot;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    seq_cu_out[g.B] = carry;
+    status[2] = bad;
+  }
+}
+
+// row_map[r] = row of the original tensors that row r of the shortened ones comes from.
+// grid: ceil(rows_bound / 256) blocks of 256; rows beyond seq_cu_out[B] are left alone.
+__global__ __launch_bounds__(256) void k_seq_row_map(Geo g, const int* __restrict__ seq_cu,
+                                                     const int* __restrict__ seq_cu_out,
+                                                     const int* __restrict__ keep,
+                                                     int* __restrict__ row_map) {
+  const long r = (long)blockIdx.x * 256 + threadIdx.x;
+  if (r >= seq_cu_out[g.B]) return;
+  int lo = 0, hi = g.B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (seq_cu_out[mid] <= r) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  const int t = (int)(r - seq_cu_out[b]);
+  const int n = g.cu[b + 1] - g.cu[b];
+  const int k = g.cu_keep[b + 1] - g.cu_keep[b];
+  const int before = g.span[b] - seq_cu[b];  // text rows ahead of the span
+  int src;
+  if (t < before) {
+    src = seq_cu[b] + t;
+  } else if (t < before + k) {
+    int kr = keep[g.cu_keep[b] + (t - before)];
+    kr = kr < 0 ? 0 : (kr < n ? kr : n - 1);  // a caller's bad index must not leave the span
+    src = g.span[b] + kr;
+  } else {
+    src = g.span[b] + n + (t - before - k);
+  }
+  row_map[r] = src;
+}
+
+constexpr int kSeqOps = 8;  // tensors one gather launch moves
+struct SeqOps {
+  const unsigned char* src[kSeqOps];
+  unsigned char* dst[kSeqOps];
+  long row_bytes[kSeqOps], src_ld[kSeqOps], dst_ld[kSeqOps];  // bytes, multiples of 16
+};
+
+// dst row r = src row row_map[r] for every tensor of ops.  One wave per (row, tensor):
+// grid (ceil(rows_bound / 4), tensors) blocks of 256; 16 bytes per lane, 1 KiB per access.
+__global__ __launch_bounds__(256) void k_gather_rows(SeqOps ops, const int* __restrict__ n_rows,
+                                                     const int* __restrict__ row_map) {
+  const int lane = threadIdx.x & 63, o = blockIdx.y;
+  const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= *n_rows) return;
+  const long src = row_map[r];
+  const u32x4* in = reinterpret_cast<const u32x4*>(ops.src[o] + src * ops.src_ld[o]);
+  u32x4* out = reinterpret_cast<u32x4*>(ops.dst[o] + r * ops.dst_ld[o]);
+  const int pieces = (int)(ops.row_bytes[o] / 16);
+  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = t0 + u * kWave + lane;
+      v[u] = t < pieces ? __builtin_nontemporal_load(in + t) : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = t0 + u * kWave + lane;
+      if (t < pieces) out[t] = v[u];
+    }
+  }
+}
+
+// Position ids, plane-major: pos_out[p*out_stride + r] = pos[p*in_stride + row_map[r]].
+// grid: (ceil(rows_bound / 256), planes) blocks of 256.
+__global__ __launch_bounds__(256) void k_gather_pos(const int* __restrict__ n_rows,
+                                                    const int* __restrict__ row_map,
+                                                    const long long* __restrict__ pos,
+                                                    long in_stride, long long* __restrict__ pos_out,
+                                                    long out_stride) {
+  const long r = (long)blockIdx.x * 256 + threadIdx.x;
+  if (r >= *n_rows) return;
+  const long p = blockIdx.y;
+  pos_out[p * out_stride + r] = pos[p * in_stride + row_map[r]];
 }
 
 }  // namespace dart

@@ -40,9 +40,12 @@ inline double l1_rel_bound(int dtype, int Dc) {
 // KEEP: ordinary loads, which leave the rows in the memory-side cache for the score
 // kernel's second pass (worth it only if the whole matrix fits there); otherwise
 // streaming (non-temporal) loads, which read faster.
-template <int DT, int ROWS, bool KEEP>
+// SPAN: the samples' rows are spans of C (Geo::span); packed row r belongs to the sample b
+// with cu[b] <= r < cu[b+1] and lives at row span[b] + (r - cu[b]) of C.  Rows of a sample
+// that keeps nothing (skipped: its span may be invalid) are not read.
+template <int DT, int ROWS, bool KEEP, bool SPAN>
 __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int Dc, long ldc,
-                                                int rows, float* __restrict__ l1) {
+                                                int rows, float* __restrict__ l1, Geo g) {
   const int lane = threadIdx.x & 63;
   const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int esz = DT == kBF16 ? 2 : 4;
@@ -58,7 +61,17 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
   for (int r = 0; r < ROWS; ++r) {
     long row = wave * ROWS + r;
     live[r] = row < rows;
-    rp[r] = base + (live[r] ? row : 0) * rowbytes;
+    long crow = live[r] ? row : 0;
+    if (SPAN && live[r]) {
+      int lo = 0, hi = g.B;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (g.cu[mid] <= row) lo = mid; else hi = mid;
+      }
+      live[r] = g.cu_keep[lo + 1] != g.cu_keep[lo];
+      crow = live[r] ? (long)g.span[lo] + (row - g.cu[lo]) : 0;
+    }
+    rp[r] = base + crow * rowbytes;
     acc[r] = 0.f;
   }
   for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {

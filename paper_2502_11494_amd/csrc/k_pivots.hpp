@@ -68,8 +68,8 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
   double* c64 = nU <= kPivLdsCand ? sh.c64 : scr + sm.row0;
   double* l2s = nU <= kPivLdsCand ? sh.l2 : scr + g.total_N + sm.row0;
   const int esz = DT == kBF16 ? 2 : 4;
-  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * g.ld * esz;
-  const unsigned char* Cb = static_cast<const unsigned char*>(C) + (long)sm.row0 * ldc * esz;
+  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.xrow * g.ld * esz;
+  const unsigned char* Cb = static_cast<const unsigned char*>(C) + (long)sm.xrow * ldc * esz;
   // R candidates per wave at a time: 16 rows in flight per block with 4 or 16 waves
   constexpr int R = 16 / kSelWaves;
   for (int u0 = w * R; u0 < nU; u0 += kSelWaves * R) {

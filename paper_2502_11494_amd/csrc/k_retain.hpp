@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   const int esz = DT == kBF16 ? 2 : 4;
   const long rowbytes = g.ld * esz;
   const unsigned char* Xb =
-      X ? static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes : nullptr;
+      X ? static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes : nullptr;
   const unsigned long long* glist = lists + (long)P * sm.row0;
   double* sweep_s64 = scr_f64 + sm.row0;                                   // fallback sweep
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // fallback sweep

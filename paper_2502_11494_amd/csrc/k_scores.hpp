@@ -103,7 +103,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   __syncthreads();
 
   const long rowbytes = g.ld * 2;
-  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes;
+  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes;
   const int pieces = g.D / 8;  // 16-byte pieces per row
   const int nchunks = (g.D + CH - 1) / CH;
   const int col16 = lane % PC, rowsub = lane / PC;
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restric
   const int n = sm.n, P = g.P;
   const int j0 = tl * 16 + wave * 4;
   if (j0 >= n) return;
-  const float* Xb = static_cast<const float*>(X) + (long)sm.row0 * g.ld;
+  const float* Xb = static_cast<const float*>(X) + (long)sm.xrow * g.ld;
   const int pieces = g.D / 4;
   const f32x4v* xr[4];
 #pragma unroll

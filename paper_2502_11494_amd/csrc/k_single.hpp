@@ -49,7 +49,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
   const int esz = DT == kBF16 ? 2 : 4;
   const long rowbytes = g.ld * esz;
   const unsigned char* Xb =
-      X ? static_cast<const unsigned char*>(X) + (long)sm.row0 * rowbytes : nullptr;
+      X ? static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes : nullptr;
   double* band_v = scr_f64 + sm.row0;
   int* band_j = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);
 

@@ -190,3 +190,56 @@ def text_pivot_rows(w: Workload, P_ext: int, seed: int = 1, mix: float = 0.5) ->
             rows = (1.0 - mix) * rows + mix * xs
         out[b] = rows
     return f32_to_bf16_bits(out) if w.dtype == BF16 else out
+
+
+@dataclasses.dataclass
+class SequenceBatch:
+    """Whole sequences around the vision tokens of a Workload, packed row after row.
+
+    H           [rows, D] hidden states: per sequence text rows, the sample's vision rows
+                (bit-identical to the Workload's), text rows
+    seq_cu      [B+1] int32 offsets of the sequences in H
+    span_start  [B] int32 row of H where sequence b's vision tokens start
+    pos         [3, rows] int64 position ids in three planes (temporal, height, width: text
+                rows carry their index in all three, vision rows a grid), the layout
+                multimodal rotary embeddings use
+    kv          list of [rows, W] per-token tensors standing in for the cached key and value
+                rows of the layers before the step (same element type as H)
+    """
+    H: np.ndarray
+    seq_cu: np.ndarray
+    span_start: np.ndarray
+    pos: np.ndarray
+    kv: List[np.ndarray]
+
+
+def sequences_around(w: Workload, seed: int = 1, before=(3, 40), after=(0, 60), n_kv: int = 2,
+                     kv_width: int = 256) -> SequenceBatch:
+    """Wraps every sample of `w` in text rows: U{before} rows ahead of the vision span and
+    U{after} rows behind it (unit-normal rows; a system prompt and a question)."""
+    rng = _rng(seed, 88)
+    pre = rng.integers(before[0], before[1] + 1, size=w.B)
+    post = rng.integers(after[0], after[1] + 1, size=w.B)
+    lens = w.lengths
+    seq_cu = np.zeros(w.B + 1, dtype=np.int32)
+    seq_cu[1:] = np.cumsum(pre + lens + post)
+    rows = int(seq_cu[-1])
+    text = rng.standard_normal((rows, w.D)).astype(np.float32)
+    H = f32_to_bf16_bits(text) if w.dtype == BF16 else text
+    span = (seq_cu[:-1] + pre).astype(np.int32)
+    pos = np.zeros((3, rows), dtype=np.int64)
+    for b in range(w.B):
+        lo, n = int(seq_cu[b]), int(lens[b])
+        H[span[b]:span[b] + n] = w.sample(b)
+        T = int(seq_cu[b + 1]) - lo
+        pos[:, lo:lo + T] = np.arange(T)
+        side = max(1, int(np.sqrt(max(n, 1))))
+        j = np.arange(n)
+        pos[0, span[b]:span[b] + n] = pre[b]
+        pos[1, span[b]:span[b] + n] = pre[b] + j // side
+        pos[2, span[b]:span[b] + n] = pre[b] + j % side
+    kv = []
+    for i in range(n_kv):
+        t = rng.standard_normal((rows, kv_width)).astype(np.float32)
+        kv.append(f32_to_bf16_bits(t) if w.dtype == BF16 else t)
+    return SequenceBatch(H, seq_cu, span, pos, kv)

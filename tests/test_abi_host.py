@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_descriptor_layout_matches_the_header():
-    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode), offsetof(dart_desc, P_ext), offsetof(dart_desc, ext_ld), offsetof(dart_desc, ext_pivots));return 0;}\n'
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode), offsetof(dart_desc, P_ext), offsetof(dart_desc, ext_ld), offsetof(dart_desc, ext_pivots), offsetof(dart_desc, span_start), offsetof(dart_desc, X_rows), sizeof(dart_row_tensor));return 0;}\n'
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "t.c")
         open(c, "w").write(src)
@@ -41,7 +41,8 @@ def test_descriptor_layout_matches_the_header():
     T = D.DartDesc
     assert list(map(int, out)) == [C.sizeof(T), T.cu_seqlens.offset, T.ld.offset, T.K.offset,
                                    T.score_mode.offset, T.P_ext.offset, T.ext_ld.offset,
-                                   T.ext_pivots.offset]
+                                   T.ext_pivots.offset, T.span_start.offset, T.X_rows.offset,
+                                   C.sizeof(binding.DartRowTensor)]
 
 
 def test_workspace_grows_with_the_problem():
@@ -109,7 +110,8 @@ def test_null_and_workspace_errors_need_no_device():
     call = lambda X, Y, keep, ws, nbytes: L.dart_reduce(C.byref(d), X, None, 0, 0, None, Y, None,
                                                         keep, None, None, None, ws, nbytes, None)
     assert call(None, fake, fake, fake, need) == D.DART_ERR_NULL
-    assert call(fake, None, fake, fake, need) == D.DART_ERR_NULL
+    # Y == NULL is allowed (the compaction step is skipped): the next check is reached
+    assert call(fake, None, fake, None, need) == D.DART_ERR_WORKSPACE
     assert call(fake, fake, None, fake, need) == D.DART_ERR_NULL
     assert call(fake, fake, fake, None, need) == D.DART_ERR_WORKSPACE
     assert call(fake, fake, fake, fake, need - 1) == D.DART_ERR_WORKSPACE
@@ -141,6 +143,36 @@ def test_outside_pivots_relax_the_budget_check():
     assert D.dart_workspace_bytes(d) == base
     d = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=1, P_ext=8, ext_pivots=4096)
     assert D.dart_workspace_bytes(d) == base
+
+
+def test_spans_need_the_packed_lengths_and_the_row_count():
+    fake = 4096
+    ok = D.make_desc(2, 4096, 8, D.DART_BF16, keep_num=1, keep_den=9, cu_seqlens=None,
+                     total_N=1000, max_N=600, span_start=fake, X_rows=1200)
+    assert D.dart_workspace_bytes(ok) == 0          # dense layout: spans are refused
+    ok.cu_seqlens = fake
+    assert D.dart_workspace_bytes(ok) > 0
+    ok.X_rows = 999                                  # fewer rows than scored tokens
+    assert D.dart_workspace_bytes(ok) == 0
+    # sequences exist only around spans
+    L = binding.lib()
+    d = D.make_desc(2, 4096, 8, D.DART_BF16, keep_num=1, keep_den=9, total_N=1000, max_N=600)
+    d.cu_seqlens = fake
+    p = C.c_void_p(fake)
+    rc = L.dart_compact_sequences(C.byref(d), p, p, 0, None, None, 0, 0, None, 0, p, p, p,
+                                  1 << 40, None)
+    assert rc == D.DART_ERR_NULL
+    d.span_start, d.X_rows = fake, 1200
+    need = D.dart_workspace_bytes(d)
+    t = (binding.DartRowTensor * 1)(binding.DartRowTensor(fake, fake, 100, 128, 128))
+    rc = L.dart_compact_sequences(C.byref(d), p, p, 1, t, None, 0, 0, None, 0, p, p, p, need, None)
+    assert rc == D.DART_ERR_ALIGN                    # rows must be multiples of 16 bytes
+    t[0].row_bytes, t[0].src_ld_bytes = 128, 64
+    rc = L.dart_compact_sequences(C.byref(d), p, p, 1, t, None, 0, 0, None, 0, p, p, p, need, None)
+    assert rc == D.DART_ERR_SHAPE
+    rc = L.dart_compact_sequences(C.byref(d), p, p, 0, None, None, 0, 0, None, 0, p, None, p,
+                                  need, None)
+    assert rc == D.DART_ERR_NULL                     # the row map is required
 
 
 def test_status_strings():
