@@ -182,6 +182,8 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   // The 256 MB memory-side cache serves part of the score kernel's second pass if this
   // pass leaves the rows there: measured -12% on that kernel for +8% on this one at 189
   // MB (a net gain), no net gain at 264 MB, a loss for matrices that cannot fit.
+  // With spans the caller moves whole sequences afterwards, which sweeps that cache anyway:
+  // measured slower with ordinary loads there.
   const bool keep = keep_cached && (double)rows * ldc * p.esz <= 224e6;
 #define DART_LAUNCH_L1(DT)                                                                       \
   do {                                                                                           \
