@@ -183,6 +183,13 @@ def main():
     ap.add_argument("--p-ext", type=int, default=0,
                     help="variant, context only: the last P_EXT of the workload's pivots are "
                          "synthetic text-token rows from outside the samples")
+    ap.add_argument("--workload", default="", choices=["", "audio", "action", "wide13b", "wide72b"],
+                    help="context only: a shape beyond the five configurations (audio tokens, "
+                         "a vision-language-action model, 13B / 72B hidden sizes)")
+    ap.add_argument("--crit-d", type=int, default=0,
+                    help="variant, context only: pivots by the L1 norm of separate key-state "
+                         "rows of this width (grouped-query shapes, e.g. 1024) instead of the "
+                         "hidden states")
     ap.add_argument("--sequences", action="store_true",
                     help="context run: spans inside whole sequences and whole-sequence "
                          "compaction (prints its own line)")
@@ -206,11 +213,14 @@ def main():
     if args.sequences:
         return bench_sequences(args)
     torch.cuda.set_device(0)
-    w = W.by_index(args.config)
+    w = W.by_name(args.workload) if args.workload else W.by_index(args.config)
     total_N = int(w.cu[-1])
     total_K = sum(w.budget(b) for b in range(w.B))
     esz = 2 if w.dtype == W.BF16 else 4
     x_bytes = total_N * w.D * esz
+    # the counter figures under profiles/ were taken on the headline run only
+    headline = (args.config == 2 and not args.workload and args.p_ext == 0 and args.crit_d == 0
+                and args.score_mode == 0 and not args.hot)
 
     if w.dtype == W.BF16:
         X0 = torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).cuda()
@@ -241,8 +251,16 @@ def main():
     pos_out = torch.empty(total_K, dtype=torch.int64, device="cuda")
     stream = torch.cuda.current_stream()
 
+    ckw = {}
+    if args.crit_d > 0:
+        cb = W.key_states(w, args.crit_d)
+        crit = (torch.from_numpy(cb.view(np.int16)).view(torch.bfloat16) if w.dtype == W.BF16
+                else torch.from_numpy(cb)).cuda()
+        ckw = dict(crit=crit, crit_D=args.crit_d, crit_ld=args.crit_d)
+
     def step(i):
-        D.dart_reduce(desc, Xs[i % copies], Y, keep, ws, pos=pos, pos_out=pos_out, stream=stream)
+        D.dart_reduce(desc, Xs[i % copies], Y, keep, ws, pos=pos, pos_out=pos_out, stream=stream,
+                      **ckw)
 
     for i in range(args.warmup):
         step(i)
@@ -260,7 +278,7 @@ def main():
     for i in range(args.steps):
         D.dart_reduce_profiled(desc, Xs[(args.warmup + i) % copies], Y, keep, ws,
                                evs.handles(7 * i, 7 * i + 7), pos=pos, pos_out=pos_out,
-                               stream=stream)
+                               stream=stream, **ckw)
     torch.cuda.synchronize()
     stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
                 for s in range(6)]
@@ -268,7 +286,7 @@ def main():
     dom = max(range(6), key=lambda s: stage_ms[s])
     # algorithmic bytes of one launch of each streaming kernel
     alg_bytes = {
-        0: x_bytes + 4 * total_N,                                   # read X, write norms
+        0: (total_N * args.crit_d * esz if args.crit_d > 0 else x_bytes) + 4 * total_N,  # norms
         2: x_bytes + 4 * w.P * total_N + w.B * w.P * w.D * esz,     # read X + pivots, write S
         5: 2 * total_K * w.D * esz + 16 * total_K + 4 * total_K,    # rows + position ids
     }
@@ -277,7 +295,7 @@ def main():
     achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(STAGE_KERNELS[dom]) if args.config == 2 else None,
+                "traffic": measured_traffic(STAGE_KERNELS[dom]) if headline else None,
                 "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
 
     cpu = None
@@ -312,18 +330,21 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == W.BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {w.name}: B={w.B} "
+        "config": {"workload": f"{'extra' if args.workload else f'configs[{args.config}]'} "
+                               f"{w.name}: B={w.B} "
                                f"N={'ragged' if w.ragged else int(lens[0])} D={w.D} P={w.P} "
-                               f"K={w.K if w.K else 'floor(0.111 N)'}",
+                               f"K={w.K if w.K else f'floor({w.keep_num}/{w.keep_den} N)'}",
                    "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
                                   "one threshold on the maximum"][args.score_mode],
                    "pivots_from_outside": args.p_ext,
+                   "criterion": (f"separate key-state rows of width {args.crit_d}"
+                                 if args.crit_d > 0 else "the hidden states themselves"),
                    "total_tokens": total_N, "retained_tokens": total_K,
                    "input_copies_rotated": copies},
         "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),
         "whole_path_algorithmic_GBps": round(
             (x_bytes + total_K * w.D * esz + 16 * total_K) / (ms_per_step * 1e-3) / 1e9, 1),
-        "whole_path_counter_GBps": (None if args.config != 2 or measured_traffic("") is None else
+        "whole_path_counter_GBps": (None if not headline or measured_traffic("") is None else
                                     round(measured_traffic("") / (ms_per_step * 1e-3) / 1e9, 1)),
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "roofline": roofline,

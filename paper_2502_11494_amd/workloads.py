@@ -243,3 +243,68 @@ def sequences_around(w: Workload, seed: int = 1, before=(3, 40), after=(0, 60), 
         t = rng.standard_normal((rows, kv_width)).astype(np.float32)
         kv.append(f32_to_bf16_bits(t) if w.dtype == BF16 else t)
     return SequenceBatch(H, seq_cu, span, pos, kv)
+
+
+def key_states(w: Workload, Dc: int, seed: int = 1, heavy: float = 0.02) -> np.ndarray:
+    """[total_N, Dc] rows standing in for a layer's key states, the pivot criterion the paper
+    uses (K-norm): with grouped-query attention Dc = kv_heads * head_dim is much smaller than
+    the hidden size.  Unit-normal rows; a fraction `heavy` of the tokens is scaled up (the
+    massive-norm tokens early decoder layers are known for), so the top of the norm ranking
+    is not a near-tie.  Same element type as w.X."""
+    rng = _rng(seed, 99)
+    total = int(w.cu[-1])
+    c = rng.standard_normal((total, Dc)).astype(np.float32)
+    big = rng.random(total) < heavy
+    c[big] *= rng.uniform(1.5, 4.0, size=(int(big.sum()), 1)).astype(np.float32)
+    return f32_to_bf16_bits(c) if w.dtype == BF16 else c
+
+
+def audio_batch(seed: int = 0xDA270005, B: int = 16, n_lo: int = 300, n_hi: int = 1500,
+                D: int = 3072, P: int = 8, keep_num: int = 700, keep_den: int = 1000,
+                n_centroids: int = 64, sigma: float = 0.1,
+                lengths: Optional[List[int]] = None) -> Workload:
+    """Audio tokens of utterances of different lengths, packed (the speech-recognition study
+    prunes 20-50 % of the audio tokens with 8 pivots): runs of 3-12 consecutive frames share
+    a centroid (a held sound), so neighbouring tokens duplicate each other; bf16."""
+    if lengths is None:
+        lengths = [int(v) for v in _rng(seed, 1 << 20).integers(n_lo, n_hi + 1, size=B)]
+    rows = []
+    for b, n in enumerate(lengths):
+        rng = _rng(seed, b)
+        cent = rng.standard_normal((n_centroids, D), dtype=np.float32)
+        which = np.empty(n, dtype=np.int64)
+        t = 0
+        while t < n:
+            run = int(rng.integers(3, 13))
+            which[t:t + run] = int(rng.integers(0, n_centroids))
+            t += run
+        x = cent[which] + np.float32(sigma) * rng.standard_normal((n, D), dtype=np.float32)
+        rows.append(x)
+    return _finish("audio_batch", rows, BF16, P, 0, keep_num, keep_den, ragged=True)
+
+
+def action_batch(seed: int = 0xDA270006, B: int = 32, N: int = 256, D: int = 4096, P: int = 8,
+                 K: int = 56, n_centroids: int = 32, sigma: float = 0.1) -> Workload:
+    """Camera frames of a vision-language-action model: 256 vision tokens kept down to 56
+    (the robot-manipulation study); bf16."""
+    rows = [clustered_tokens(_rng(seed, b), N, D, n_centroids, sigma) for b in range(B)]
+    return _finish("action_batch", rows, BF16, P, K)
+
+
+def wide_image_batch(seed: int = 0xDA270007, B: int = 16, N: int = 576, D: int = 5120,
+                     P: int = 8, K: int = 128, n_centroids: int = 128,
+                     sigma: float = 0.1) -> Workload:
+    """576-token images at the hidden size of a 13B language model (5120); D=8192 gives the
+    72B size.  bf16."""
+    rows = [clustered_tokens(_rng(seed, b), N, D, n_centroids, sigma) for b in range(B)]
+    return _finish("wide_image_batch", rows, BF16, P, K)
+
+
+EXTRA = {"audio": audio_batch, "action": action_batch, "wide13b": wide_image_batch,
+         "wide72b": lambda **kw: wide_image_batch(**{"D": 8192, "B": 8, **kw})}
+
+
+def by_name(name: str, **kw) -> Workload:
+    """Workloads beyond the five benchmark configurations: other modalities and model sizes
+    the paper reports on."""
+    return EXTRA[name](**kw)

@@ -363,6 +363,22 @@ def test_config1_pivot_ablation_four_visual_four_text():
     G.compare(w, G.run_reduce(w, ext=E), refs)
 
 
+@pytest.mark.parametrize("Dc", [1024, 512])
+def test_config2_key_norm_criterion(Dc):
+    """The K-norm criterion at full size with grouped-query shapes: the pivots come from the
+    L1 norms of separate key-state rows (8 or 4 kv heads of 128), the hidden states are read
+    by the score pass only."""
+    w = W.by_index(2)
+    crit_bits = W.key_states(w, Dc, seed=Dc)
+    crit_dev = torch.from_numpy(crit_bits.view(np.int16)).view(torch.bfloat16).cuda()
+    refs = G.oracle_samples(w, crit=crit_bits)
+    assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+    g = G.run_reduce(w, crit=crit_dev)
+    G.compare(w, g, refs)
+    # the pivots differ from those of the hidden-state norms
+    assert not np.array_equal(g.piv, np.stack([r.piv for r in G.oracle_samples(w)]))
+
+
 def test_config2_multicrop_batch():
     check(W.by_index(2))
 
@@ -383,3 +399,46 @@ def test_config4_video_batch():
 
 def test_config3_ragged_batch():
     check(W.by_index(3))
+
+
+# ---- other modalities and model sizes the paper reports on ----------------------------------
+
+@pytest.mark.parametrize("name,kw", [
+    ("audio", dict(keep_num=800)), ("audio", dict(keep_num=700)), ("audio", dict(keep_num=500)),
+    ("action", {}), ("wide13b", {}), ("wide72b", {}), ("wide72b", dict(K=64, P=16)),
+])
+def test_other_modalities_and_hidden_sizes(name, kw):
+    """Audio tokens pruned by 20/30/50 % with 8 pivots (packed utterances), 256 -> 56 tokens of
+    a vision-language-action model, and the hidden sizes of 13B and 72B language models."""
+    check(W.by_name(name, **kw))
+
+
+def test_audio_with_key_norm_criterion_on_spans():
+    """The audio study's setting end to end: K-norm pivots from separate key rows, the audio
+    tokens sitting inside whole sequences, 30 % pruned."""
+    w = W.by_name("audio", B=6)
+    sq = W.sequences_around(w, seed=9)
+    crit_rows = W.key_states(w, 1024, seed=4)
+    crit_full = np.zeros((sq.H.shape[0], 1024), dtype=crit_rows.dtype)
+    for b in range(w.B):  # key rows exist for every row of the sequence; only the span's count
+        crit_full[sq.span_start[b]:sq.span_start[b] + int(w.lengths[b])] = \
+            crit_rows[int(w.cu[b]):int(w.cu[b + 1])]
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    Hd, Cd = dev(sq.H), dev(crit_full)
+    cu_dev, span_dev = torch.from_numpy(w.cu).cuda(), torch.from_numpy(sq.span_start).cuda()
+    desc = D.make_desc(w.B, w.D, w.P, w.dtype, keep_num=w.keep_num, keep_den=w.keep_den,
+                       cu_seqlens=cu_dev, total_N=int(w.cu[-1]), max_N=int(w.lengths.max()),
+                       span_start=span_dev, X_rows=sq.H.shape[0])
+    ws = D.alloc_workspace(desc)
+    total_keep = sum(w.budget(b) for b in range(w.B))
+    keep = torch.empty(total_keep, dtype=torch.int32, device="cuda")
+    piv = torch.empty(w.B * w.P, dtype=torch.int32, device="cuda")
+    D.dart_reduce(desc, Hd, None, keep, ws, crit=Cd, crit_D=1024, crit_ld=1024, piv_out=piv)
+    torch.cuda.synchronize()
+    assert D.dart_device_status(desc, ws) == D.DART_OK
+    k0 = 0
+    for b, r in enumerate(G.oracle_samples(w, crit=crit_rows)):
+        assert oracle.admissible(w.sample(b), r)
+        np.testing.assert_array_equal(piv.cpu().numpy()[b * w.P:(b + 1) * w.P], r.piv)
+        np.testing.assert_array_equal(keep.cpu().numpy()[k0:k0 + w.budget(b)], r.keep)
+        k0 += w.budget(b)
