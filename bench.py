@@ -190,6 +190,11 @@ def main():
                     help="variant, context only: pivots by the L1 norm of separate key-state "
                          "rows of this width (grouped-query shapes, e.g. 1024) instead of the "
                          "hidden states")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="context only: after the headline measurement, run the same number of "
+                         "steps spread over this many HIP streams (independent batches in "
+                         "flight, each with its own workspace and outputs) and report that "
+                         "rate as concurrent_streams")
     ap.add_argument("--sequences", action="store_true",
                     help="context run: spans inside whole sequences and whole-sequence "
                          "compaction (prints its own line)")
@@ -273,6 +278,35 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = total_N * args.steps / wall
 
+    # context: independent batches in flight on several streams (default priority), so that
+    # the on-chip kernels of one batch overlap the streaming passes of another
+    concurrent = None
+    if args.streams > 1:
+        ns = args.streams
+        sts = [torch.cuda.Stream() for _ in range(ns)]
+        wss = [D.alloc_workspace(desc) for _ in range(ns)]
+        Ys = [torch.empty_like(Y) for _ in range(ns)]
+        keeps = [torch.empty_like(keep) for _ in range(ns)]
+        pouts = [torch.empty_like(pos_out) for _ in range(ns)]
+
+        def cstep(i):
+            q = i % ns
+            D.dart_reduce(desc, Xs[i % copies], Ys[q], keeps[q], wss[q], pos=pos,
+                          pos_out=pouts[q], stream=sts[q], **ckw)
+
+        for i in range(args.warmup):
+            cstep(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            cstep(args.warmup + i)
+        torch.cuda.synchronize()
+        cwall = time.perf_counter() - t0
+        same = all(torch.equal(k, keep) for k in keeps)
+        concurrent = {"streams": ns, "ms_per_step": round(cwall * 1e3 / args.steps, 5),
+                      "tokens_per_s": round(total_N * args.steps / cwall, 1),
+                      "outputs_equal_single_stream": bool(same)}
+
     # per-kernel durations: the same steps again, with HIP events between the kernels
     evs = HipEvents(7 * args.steps)
     for i in range(args.steps):
@@ -347,6 +381,7 @@ def main():
         "whole_path_counter_GBps": (None if not headline or measured_traffic("") is None else
                                     round(measured_traffic("") / (ms_per_step * 1e-3) / 1e9, 1)),
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
+        "concurrent_streams": concurrent,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
