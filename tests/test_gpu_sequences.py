@@ -153,3 +153,103 @@ def test_invalid_spans_and_sequences_are_reported():
     bad[2] = bad[1] - 1
     g = run(w, sq, seq_cu=bad, expect=D.DART_ERR_DEVICE)
     assert not g["seq_out"].any()
+
+
+def test_random_combinations_of_the_variants():
+    """Sixteen seeded random batches mixing everything the descriptor offers: spans inside
+    whole sequences, pivots from outside, either retained-set rule, largest / smallest /
+    caller-supplied pivots, a separate criterion tensor, fixed or proportional budgets."""
+    rng = np.random.default_rng(0xDA31)
+    done = 0
+    while done < 16:
+        P = int(rng.choice([2, 4, 8, 16, 24]))
+        P_ext = int(rng.integers(0, P + 1)) if rng.random() < 0.6 else 0
+        P_in = P - P_ext
+        B = int(rng.integers(1, 5))
+        D_ = int(rng.choice([64, 256, 520, 1024]))
+        lengths = [int(rng.integers(max(P, 40), 900)) for _ in range(B)]
+        seed = int(rng.integers(1, 1 << 30))
+        w = W.ragged_batch(seed=seed, B=B, D=D_, P=P, keep_num=int(rng.integers(80, 500)),
+                           keep_den=1000, lengths=lengths)
+        if rng.random() < 0.4:
+            w.K, w.keep_num = int(rng.integers(max(P_in, 1), min(lengths) + 1)), 0
+        if any(w.budget(b) < max(P_in, 1) for b in range(B)):
+            continue
+        agg = int(rng.choice([0, 0, oracle.AGG_MIN, oracle.AGG_MAX]))
+        pmode = int(rng.choice([D.DART_PIVOT_MAX_L1, D.DART_PIVOT_MIN_L1, D.DART_PIVOT_GIVEN]))
+        use_crit = pmode != D.DART_PIVOT_GIVEN and rng.random() < 0.5
+        sq = W.sequences_around(w, seed=seed ^ 5, n_kv=1, kv_width=64)
+        rows = sq.H.shape[0]
+        E = W.text_pivot_rows(w, P_ext, seed=seed ^ 7) if P_ext else None
+        crit_rows = W.key_states(w, 128, seed=seed ^ 9) if use_crit else None
+        given = None
+        if pmode == D.DART_PIVOT_GIVEN:
+            given = np.stack([np.concatenate([rng.permutation(lengths[b])[:P_in],
+                                              np.full(P_ext, -99)]) for b in range(B)]).astype(np.int32)
+        refs = []
+        for b in range(B):
+            lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+            X = w.X[lo:hi]
+            Eb = E[b] if P_ext else np.empty((0, w.D), dtype=X.dtype)
+            if given is not None:
+                r = oracle.reduce_mixed(X, w.dtype, Eb, P_in, w.budget(b), agg=agg,
+                                        given=given[b][:P_in])
+            elif use_crit:
+                # pivots by the criterion rows: rank them with the oracle's own steps
+                c = oracle.l1_norms(crit_rows[lo:hi], w.dtype)
+                ranked = oracle.select_pivots(c, min(hi - lo, P_in + 1), pmode) if P_in else \
+                    np.empty(0, dtype=np.int32)
+                r = oracle.reduce_mixed(X, w.dtype, Eb, P_in, w.budget(b), agg=agg,
+                                        given=ranked[:P_in])
+                r.c = c
+                r.piv_gap = np.array([abs(c[ranked[i]] - c[ranked[i + 1]]) if i + 1 < len(ranked)
+                                      else np.inf for i in range(P_in)])
+            else:
+                r = oracle.reduce_mixed(X, w.dtype, Eb, P_in, w.budget(b), mode=pmode, agg=agg)
+            refs.append(r)
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            continue
+        print(f"[case {done}] B={B} P={P} P_ext={P_ext} D={D_} K={w.K or (w.keep_num, 1000)} "
+              f"agg={agg} pivots={pmode} crit={use_crit} lens={lengths}", flush=True)
+        # ---- GPU
+        Hd = dev(sq.H, w.dtype)
+        cu_dev, span_dev = torch.from_numpy(w.cu).cuda(), torch.from_numpy(sq.span_start).cuda()
+        Ed = dev(np.ascontiguousarray(E.reshape(-1, w.D)), w.dtype) if P_ext else None
+        desc = D.make_desc(B, w.D, P, w.dtype, K=w.K, keep_num=w.keep_num, keep_den=w.keep_den,
+                           cu_seqlens=cu_dev, total_N=int(w.cu[-1]), max_N=max(lengths),
+                           pivot_mode=pmode, score_mode=agg, ext_pivots=Ed, P_ext=P_ext,
+                           span_start=span_dev, X_rows=rows)
+        ws = D.alloc_workspace(desc)
+        total_keep = sum(w.budget(b) for b in range(B))
+        keep = torch.full((max(total_keep, 1),), -1, dtype=torch.int32, device="cuda")
+        piv = (torch.from_numpy(given.reshape(-1)).cuda() if given is not None
+               else torch.full((B * P,), -5, dtype=torch.int32, device="cuda"))
+        kw = {}
+        if use_crit:
+            full = np.zeros((rows, 128), dtype=crit_rows.dtype)
+            for b in range(B):
+                full[sq.span_start[b]:sq.span_start[b] + lengths[b]] = \
+                    crit_rows[int(w.cu[b]):int(w.cu[b + 1])]
+            Cd = dev(full, w.dtype)
+            kw = dict(crit=Cd, crit_D=128, crit_ld=128)
+        D.dart_reduce(desc, Hd, None, keep, ws, piv_out=piv, **kw)
+        out_rows = rows - int(w.cu[-1]) + total_keep
+        row_map = torch.full((max(out_rows, 1),), -7, dtype=torch.int32, device="cuda")
+        seq_out = torch.full((B + 1,), -1, dtype=torch.int32, device="cuda")
+        Hout = torch.zeros((max(out_rows, 1), w.D), dtype=Hd.dtype, device="cuda")
+        D.dart_compact_sequences(desc, torch.from_numpy(sq.seq_cu).cuda(), keep, [(Hd, Hout)],
+                                 seq_out, row_map, ws)
+        torch.cuda.synchronize()
+        assert D.dart_device_status(desc, ws) == D.DART_OK
+        k0, keeps = 0, []
+        for b, r in enumerate(refs):
+            kb = w.budget(b)
+            np.testing.assert_array_equal(piv.cpu().numpy()[b * P:(b + 1) * P], r.piv)
+            np.testing.assert_array_equal(keep.cpu().numpy()[k0:k0 + kb], r.keep)
+            keeps.append(r.keep)
+            k0 += kb
+        want_map, cu_out = oracle.compact_sequences(sq.seq_cu, sq.span_start, w.lengths, keeps)
+        np.testing.assert_array_equal(seq_out.cpu().numpy(), cu_out)
+        np.testing.assert_array_equal(row_map.cpu().numpy()[:out_rows], want_map)
+        assert G.bits(Hout)[:out_rows].tobytes() == oracle.gather_rows(sq.H, want_map).tobytes()
+        done += 1
