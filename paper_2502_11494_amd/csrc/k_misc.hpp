@@ -117,6 +117,8 @@ __global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restri
 
 // Compaction: one wave per retained row.  grid: ceil(rows_bound / 4) blocks of 256.
 // Y rows are packed (stride D); copies are 16 bytes per lane, 1 KiB per wave access.
+// The rows are read once: streaming (non-temporal) loads measured 20 % faster on the
+// largest batch than ordinary ones; streaming stores did not help.
 __global__ __launch_bounds__(256) void k_gather(Geo g, int esz, const void* __restrict__ X,
                                                 const long long* __restrict__ pos,
                                                 const int* __restrict__ keep,
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) void k_gather(Geo g, int esz, const void* __re
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       int t = t0 + u * kWave + lane;
-      v[u] = t < pieces ? in[t] : u32x4{0u, 0u, 0u, 0u};
+      v[u] = t < pieces ? __builtin_nontemporal_load(in + t) : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
