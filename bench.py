@@ -278,6 +278,31 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = total_N * args.steps / wall
 
+    # per-kernel durations: the same steps again, with HIP events between the kernels
+    evs = HipEvents(7 * args.steps)
+    for i in range(args.steps):
+        D.dart_reduce_profiled(desc, Xs[(args.warmup + i) % copies], Y, keep, ws,
+                               evs.handles(7 * i, 7 * i + 7), pos=pos, pos_out=pos_out,
+                               stream=stream, **ckw)
+    torch.cuda.synchronize()
+    stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
+                for s in range(6)]
+    evs.close()
+    dom = max(range(6), key=lambda s: stage_ms[s])
+    # algorithmic bytes of one launch of each streaming kernel
+    alg_bytes = {
+        0: (total_N * args.crit_d * esz if args.crit_d > 0 else x_bytes) + 4 * total_N,  # norms
+        2: x_bytes + 4 * w.P * total_N + w.B * w.P * w.D * esz,     # read X + pivots, write S
+        5: 2 * total_K * w.D * esz + 16 * total_K + 4 * total_K,    # rows + position ids
+    }
+    if dom not in alg_bytes:  # an on-chip stage dominates: report the larger streaming pass
+        dom = 0 if stage_ms[0] >= stage_ms[2] else 2
+    achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(STAGE_KERNELS[dom]) if headline else None,
+                "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
+
     # context: independent batches in flight on several streams (default priority), so that
     # the on-chip kernels of one batch overlap the streaming passes of another
     concurrent = None
@@ -306,31 +331,6 @@ def main():
         concurrent = {"streams": ns, "ms_per_step": round(cwall * 1e3 / args.steps, 5),
                       "tokens_per_s": round(total_N * args.steps / cwall, 1),
                       "outputs_equal_single_stream": bool(same)}
-
-    # per-kernel durations: the same steps again, with HIP events between the kernels
-    evs = HipEvents(7 * args.steps)
-    for i in range(args.steps):
-        D.dart_reduce_profiled(desc, Xs[(args.warmup + i) % copies], Y, keep, ws,
-                               evs.handles(7 * i, 7 * i + 7), pos=pos, pos_out=pos_out,
-                               stream=stream, **ckw)
-    torch.cuda.synchronize()
-    stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
-                for s in range(6)]
-    evs.close()
-    dom = max(range(6), key=lambda s: stage_ms[s])
-    # algorithmic bytes of one launch of each streaming kernel
-    alg_bytes = {
-        0: (total_N * args.crit_d * esz if args.crit_d > 0 else x_bytes) + 4 * total_N,  # norms
-        2: x_bytes + 4 * w.P * total_N + w.B * w.P * w.D * esz,     # read X + pivots, write S
-        5: 2 * total_K * w.D * esz + 16 * total_K + 4 * total_K,    # rows + position ids
-    }
-    if dom not in alg_bytes:  # an on-chip stage dominates: report the larger streaming pass
-        dom = 0 if stage_ms[0] >= stage_ms[2] else 2
-    achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(STAGE_KERNELS[dom]) if headline else None,
-                "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
 
     cpu = None
     if not args.no_cpu_baseline:
