@@ -195,6 +195,8 @@ def main():
                          "steps spread over this many HIP streams (independent batches in "
                          "flight, each with its own workspace and outputs) and report that "
                          "rate as concurrent_streams")
+    ap.add_argument("--graph", action="store_true",
+                    help="context only: also time the steps replayed from captured HIP graphs")
     ap.add_argument("--sequences", action="store_true",
                     help="context run: spans inside whole sequences and whole-sequence "
                          "compaction (prints its own line)")
@@ -332,6 +334,29 @@ def main():
                       "tokens_per_s": round(total_N * args.steps / cwall, 1),
                       "outputs_equal_single_stream": bool(same)}
 
+    # context: the same steps replayed from HIP graphs (one captured step per input copy)
+    graphed = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        graphs = []
+        with torch.cuda.stream(side):
+            for c in range(copies):
+                gph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gph, stream=side):
+                    D.dart_reduce(desc, Xs[c], Y, keep, ws, pos=pos, pos_out=pos_out, **ckw)
+                graphs.append(gph)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % copies].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % copies].replay()
+        torch.cuda.synchronize()
+        gwall = time.perf_counter() - t0
+        graphed = {"ms_per_step": round(gwall * 1e3 / args.steps, 5),
+                   "tokens_per_s": round(total_N * args.steps / gwall, 1)}
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -382,6 +407,7 @@ def main():
                                     round(measured_traffic("") / (ms_per_step * 1e-3) / 1e9, 1)),
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "concurrent_streams": concurrent,
+        "graph_replay": graphed,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
