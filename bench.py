@@ -32,10 +32,12 @@ STAGE_KERNELS = ["k_row_l1", "k_select_pivots", "k_scores_bf16", "k_order_scores
                  "k_gather"]
 
 
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_multicrop_B8_N2880_D4096_bf16.txt")
+TRAFFIC_FILES = {2: "hbm_traffic_multicrop_B8_N2880_D4096_bf16.txt",
+                 3: "hbm_traffic_ragged_B32_D3584_bf16.txt",
+                 4: "hbm_traffic_video_B4_N9216_D3584_bf16.txt"}
 
 
-def measured_traffic(kernel_prefix):
+def measured_traffic(kernel_prefix, config=2):
     """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if the
     kernel sources changed since the counters were taken.  An empty prefix sums all
@@ -43,8 +45,8 @@ def measured_traffic(kernel_prefix):
     import glob
     import hashlib
     try:
-        lines = open(TRAFFIC_FILE).read().splitlines()
-    except OSError:
+        lines = open(os.path.join(ROOT, "profiles", TRAFFIC_FILES[config])).read().splitlines()
+    except (OSError, KeyError):
         return None
     h = hashlib.sha256()
     for path in sorted(glob.glob(os.path.join(ROOT, "paper_2502_11494_amd", "csrc", "*"))):
@@ -226,7 +228,7 @@ def main():
     esz = 2 if w.dtype == W.BF16 else 4
     x_bytes = total_N * w.D * esz
     # the counter figures under profiles/ were taken on the headline run only
-    headline = (args.config == 2 and not args.workload and args.p_ext == 0 and args.crit_d == 0
+    headline = (args.config in TRAFFIC_FILES and not args.workload and args.p_ext == 0 and args.crit_d == 0
                 and args.score_mode == 0 and not args.hot)
 
     if w.dtype == W.BF16:
@@ -302,7 +304,7 @@ def main():
     achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(STAGE_KERNELS[dom]) if headline else None,
+                "traffic": measured_traffic(STAGE_KERNELS[dom], args.config) if headline else None,
                 "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
 
     # context: independent batches in flight on several streams (default priority), so that
@@ -403,8 +405,9 @@ def main():
         "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),
         "whole_path_algorithmic_GBps": round(
             (x_bytes + total_K * w.D * esz + 16 * total_K) / (ms_per_step * 1e-3) / 1e9, 1),
-        "whole_path_counter_GBps": (None if not headline or measured_traffic("") is None else
-                                    round(measured_traffic("") / (ms_per_step * 1e-3) / 1e9, 1)),
+        "whole_path_counter_GBps": (
+            None if not headline or measured_traffic("", args.config) is None else
+            round(measured_traffic("", args.config) / (ms_per_step * 1e-3) / 1e9, 1)),
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "concurrent_streams": concurrent,
         "graph_replay": graphed,
