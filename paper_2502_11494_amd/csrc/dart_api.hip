@@ -238,7 +238,7 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   if (p.tiles_bound == 0) return DART_OK;
   const double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kF32) {
-    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / 16)), dim3(256), 0, st,
+    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
                        p.g, X, piv, S);
   } else {
     // A workgroup of W waves owns a tile of 16*W rows and stages each pivot chunk once:

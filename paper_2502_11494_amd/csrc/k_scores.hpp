@@ -261,65 +261,84 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   }
 }
 
-// fp32 hidden states.  grid: tiles * (tile_rows / 16) blocks of 256; a wave owns 4
-// consecutive token rows of one sample and 8 pivots at a time.
+// fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)
+// blocks of 256: a block owns 4 consecutive token rows of one sample and 8 pivots at a
+// time; its 4 waves split D (piece t of a row goes to wave (t / 64) % 4), so that small
+// batches -- the only ones this path is meant for -- still spread over the chip and a wave's
+// chain of dependent loads is a quarter as long.  The next pieces are requested before the
+// current ones are used.  The 4 partial sums of a dot product are added in wave order, each
+// wave's own sum is a fixed lane-strided order plus butterfly: a score depends only on the
+// two rows' bytes.
+constexpr int kF32Rows = 4, kF32Piv = 8;
 __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restrict__ X,
                                                     const int* __restrict__ piv,
                                                     float* __restrict__ S) {
+  // per wave: dot[4][8], pp[8], xx[4]
+  __shared__ double red[4][kF32Rows * kF32Piv + kF32Piv + kF32Rows];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // rows are grouped per sample: 16 rows per block, dense tiles of the sample
   int b, tl;
-  {
-    // reuse the tile table: block = (tile, 16-row part of the tile)
-    const int parts = g.tile_rows / 16;
-    const int tile = blockIdx.x / parts;
-    if (!locate_tile(g, tile, b, tl)) return;
-    tl = tl * parts + (blockIdx.x - tile * parts);
-  }
+  const int parts = g.tile_rows / kF32Rows;
+  const int tile = blockIdx.x / parts;
+  if (!locate_tile(g, tile, b, tl)) return;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P;
-  const int j0 = tl * 16 + wave * 4;
+  const int j0 = tl * g.tile_rows + (blockIdx.x - tile * parts) * kF32Rows;  // block-uniform
   if (j0 >= n) return;
   const float* Xb = static_cast<const float*>(X) + (long)sm.xrow * g.ld;
   const int pieces = g.D / 4;
-  const f32x4v* xr[4];
+  const f32x4v* xr[kF32Rows];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    int j = j0 + r < n ? j0 + r : n - 1;
+  for (int r = 0; r < kF32Rows; ++r) {
+    const int j = j0 + r < n ? j0 + r : n - 1;  // rows past the end re-read the last; never stored
     xr[r] = reinterpret_cast<const f32x4v*>(Xb + (long)j * g.ld);
   }
   float* Sb = S + (long)P * sm.row0;
-  for (int i0 = 0; i0 < P; i0 += 8) {
-    const f32x4v* pr[8];
+  const f32x4v fz = {0.f, 0.f, 0.f, 0.f};
+  for (int i0 = 0; i0 < P; i0 += kF32Piv) {
+    const f32x4v* pr[kF32Piv];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      int i = i0 + q < P ? i0 + q : P - 1;
+    for (int q = 0; q < kF32Piv; ++q) {
+      const int i = i0 + q < P ? i0 + q : P - 1;
       pr[q] = reinterpret_cast<const f32x4v*>(pivot_row(g, X, 4, sm, b, i, piv));
     }
-    double dot[4][8], xx[4], pp[8];
+    double dot[kF32Rows][kF32Piv], xx[kF32Rows], pp[kF32Piv];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < kF32Rows; ++r) {
       xx[r] = 0.0;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) dot[r][q] = 0.0;
+      for (int q = 0; q < kF32Piv; ++q) dot[r][q] = 0.0;
     }
 #pragma unroll
-    for (int q = 0; q < 8; ++q) pp[q] = 0.0;
-    for (int t = lane; t < pieces; t += kWave) {
-      f32x4v xv[4];
+    for (int q = 0; q < kF32Piv; ++q) pp[q] = 0.0;
+    f32x4v xv[kF32Rows], pv[kF32Piv], xn[kF32Rows], pn[kF32Piv];
+    int t = tid;  // piece index: 256 apart per step
+    auto fetch = [&](int tt, f32x4v (&xo)[kF32Rows], f32x4v (&po)[kF32Piv]) {
+      const bool in = tt < pieces;
+      const int ts = in ? tt : 0;  // a piece past the end re-reads piece 0 and counts as zero
 #pragma unroll
-      for (int r = 0; r < 4; ++r) xv[r] = xr[r][t];
+      for (int r = 0; r < kF32Rows; ++r) {
+        const f32x4v v = xr[r][ts];
+        xo[r] = in ? v : fz;
+      }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        f32x4v pv = pr[q][t];
-        const double p0 = pv.x, p1 = pv.y, p2 = pv.z, p3 = pv.w;
+      for (int q = 0; q < kF32Piv; ++q) {
+        const f32x4v v = pr[q][ts];
+        po[q] = in ? v : fz;
+      }
+    };
+    fetch(t, xv, pv);
+    for (; t < pieces; t += 256) {
+      fetch(t + 256, xn, pn);
+#pragma unroll
+      for (int q = 0; q < kF32Piv; ++q) {
+        const double p0 = pv[q].x, p1 = pv[q].y, p2 = pv[q].z, p3 = pv[q].w;
         pp[q] = fma(p0, p0, pp[q]);
         pp[q] = fma(p1, p1, pp[q]);
         pp[q] = fma(p2, p2, pp[q]);
         pp[q] = fma(p3, p3, pp[q]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < kF32Rows; ++r) {
           dot[r][q] = fma(p0, (double)xv[r].x, dot[r][q]);
           dot[r][q] = fma(p1, (double)xv[r].y, dot[r][q]);
           dot[r][q] = fma(p2, (double)xv[r].z, dot[r][q]);
@@ -327,27 +346,49 @@ __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restric
         }
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < kF32Rows; ++r) {
         const double x0 = xv[r].x, x1 = xv[r].y, x2 = xv[r].z, x3 = xv[r].w;
         xx[r] = fma(x0, x0, xx[r]);
         xx[r] = fma(x1, x1, xx[r]);
         xx[r] = fma(x2, x2, xx[r]);
         xx[r] = fma(x3, x3, xx[r]);
       }
+#pragma unroll
+      for (int r = 0; r < kF32Rows; ++r) xv[r] = xn[r];
+#pragma unroll
+      for (int q = 0; q < kF32Piv; ++q) pv[q] = pn[q];
     }
+    // the wave's sums, then the four waves' partials in wave order
 #pragma unroll
-    for (int q = 0; q < 8; ++q) pp[q] = sqrt(wave_sum(pp[q]));
+    for (int r = 0; r < kF32Rows; ++r) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const double xnorm = sqrt(wave_sum(xx[r]));
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
+      for (int q = 0; q < kF32Piv; ++q) {
         const double d = wave_sum(dot[r][q]);
-        const double den = pp[q] * xnorm;
-        const double s = den > 0.0 ? d / den : 0.0;
-        if (lane == 0 && i0 + q < P && j0 + r < n) Sb[(long)(i0 + q) * n + j0 + r] = (float)s + 0.0f;
+        if (lane == 0) red[wave][r * kF32Piv + q] = d;
       }
+      const double x2 = wave_sum(xx[r]);
+      if (lane == 0) red[wave][kF32Rows * kF32Piv + kF32Piv + r] = x2;
     }
+#pragma unroll
+    for (int q = 0; q < kF32Piv; ++q) {
+      const double p2 = wave_sum(pp[q]);
+      if (lane == 0) red[wave][kF32Rows * kF32Piv + q] = p2;
+    }
+    __syncthreads();
+    if (tid < kF32Rows * kF32Piv) {
+      const int r = tid / kF32Piv, q = tid - r * kF32Piv;
+      double d = 0.0, p2 = 0.0, x2 = 0.0;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        d += red[w][r * kF32Piv + q];
+        p2 += red[w][kF32Rows * kF32Piv + q];
+        x2 += red[w][kF32Rows * kF32Piv + kF32Piv + r];
+      }
+      const double den = sqrt(p2) * sqrt(x2);
+      const double sc = den > 0.0 ? d / den : 0.0;
+      if (i0 + q < P && j0 + r < n) Sb[(long)(i0 + q) * n + j0 + r] = (float)sc + 0.0f;
+    }
+    __syncthreads();  // red is reused by the next group of pivots
   }
 }
 
