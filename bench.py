@@ -208,7 +208,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the reduction step is per-sample work with no "
-              "cross-GPU exchange, and this build runs on one MI355X only (--gpus 1).",
+              "cross-GPU exchange; shard the batch by sample and run one process per GPU "
+              "(use --gpus 1).",
               file=sys.stderr)
         sys.exit(2)
 
