@@ -116,8 +116,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   for (int t = 0; t < LA; ++t) {
     int r = j0 + t * RPI + rowsub;
     r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
-    aptr[t] = Xb + (long)r * rowbytes + col16 * 16;
+    aptr[t] = Xb + (long)r * rowbytes + (TAIL ? 0 : col16 * 16);
   }
+  // With TAIL the lane's column offset is added per chunk instead: a piece past the end of
+  // the row must re-read the row's first 16 bytes, not bytes behind a row shorter than a chunk
+  const int tail_col = TAIL ? col16 * 16 : 0;
   // pivot loads: piece id = tid + THREADS*k -> pivot row id/PC, piece id%PC (== col16);
   // padding slots read the sample's first row and are zeroed after the load
   const unsigned char* pptr[LP];
@@ -126,17 +129,17 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   for (int k = 0; k < LP; ++k) {
     const unsigned char* pr = sh.pivptr[(tid + THREADS * k) / PC];
     preal[k] = pr != nullptr;
-    pptr[k] = (pr != nullptr ? pr : Xb) + col16 * 16;
+    pptr[k] = (pr != nullptr ? pr : Xb) + (TAIL ? 0 : col16 * 16);
   }
 
   u32x4 ra[DEPTH][LA], rp[DEPTH][LP];
-  // With TAIL, a piece past the end of the row re-reads the row's first chunk; it is
+  // With TAIL, a piece past the end of the row re-reads the row's first piece; it is
   // replaced by zeros (as are the padding pivot slots) only when the registers go to LDS:
   // the load stays unconditional and nothing touches its result while it is in flight.
 #define DART_LOAD_A(c, buf)                                                                    \
   {                                                                                            \
     const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
+    const long off_ = in_ ? (long)(c) * (CH * 2) + tail_col : 0;                               \
     _Pragma("unroll") for (int t = 0; t < LA; ++t) ra[buf][t] =                                \
         __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off_));            \
   }
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
 #define DART_LOAD_P(c, rbuf)                                                                   \
   {                                                                                            \
     const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    const long off_ = in_ ? (long)(c) * (CH * 2) : 0;                                          \
+    const long off_ = in_ ? (long)(c) * (CH * 2) + tail_col : 0;                               \
     _Pragma("unroll") for (int k = 0; k < LP; ++k) rp[rbuf][k] =                               \
         *reinterpret_cast<const u32x4*>(pptr[k] + off_);                                       \
   }
