@@ -34,7 +34,11 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
   }
   int first = 0;  // keys of the first sorted run (all of them unless the sort was split)
   collect_sorted(v, n, want, -INFINITY, tid, sh, nullptr, &first);
-  unsigned long long* out = lists + (long)g.P * sm.row0 + sp.list_offset(n, i);
+  // offset of this stage's list = sum of the earlier stages' lengths: lane s of every wave
+  // computes stage s's length, a wave scan adds them up (no loop over the stages)
+  const int len_v = (tid & 63) < g.P ? sp.stage_len(n, tid & 63) : 0;
+  const int off_v = wave_excl_scan(len_v, tid & 63);
+  unsigned long long* out = lists + (long)g.P * sm.row0 + __builtin_amdgcn_readlane(off_v, i);
   for (int t = tid; t < want; t += kSelThreads)
     out[t] = t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)];
 }

@@ -99,16 +99,24 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // fallback sweep
 
   const Split sp(k, P, g.Pin);
+  // stage constants in the lanes of every wave: lane i holds stage i's quota, list
+  // length and list offset (the offsets are the prefix sums of the lengths)
+  int quota_v = 0, len_v = 0;
+  if (lane < P) {
+    quota_v = sp.quota(lane);
+    len_v = sp.stage_len(n, lane);
+  }
+  const int off_v = wave_excl_scan(len_v, lane);
   // Lists of the stages [first, group_hi) that fit in LDS together (the first one maybe
-  // only in part); block-uniform arithmetic, no memory access.
+  // only in part); block-uniform arithmetic on the lane constants, no memory access.
   int group_hi = 0, group_base = 0, staged_total = 0;
   auto plan_group = [&](int first) {
-    group_base = (int)sp.list_offset(n, first);
-    const int l0 = sp.stage_len(n, first);
+    group_base = __builtin_amdgcn_readlane(off_v, first);
+    const int l0 = __builtin_amdgcn_readlane(len_v, first);
     int tot = l0 < kRetList ? l0 : kRetList;
     group_hi = first + 1;
-    while (group_hi < P && tot + sp.stage_len(n, group_hi) <= kRetList)
-      tot += sp.stage_len(n, group_hi++);
+    while (group_hi < P && tot + __builtin_amdgcn_readlane(len_v, group_hi) <= kRetList)
+      tot += __builtin_amdgcn_readlane(len_v, group_hi++);
     staged_total = tot;
   };
   // a group moves in two halves of kStageLoads loads per thread (48 KiB in flight each)
@@ -138,9 +146,9 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
   for (int t = tid; t < (n + 3) / 4; t += kRetThreads)
     reinterpret_cast<uint32_t*>(sh.owner)[t] = 0xffffffffu;
-  if (tid < P) {
-    sh.st_len[tid] = sp.stage_len(n, tid);
-    sh.st_off[tid] = (int)sp.list_offset(n, tid);
+  if (tid < P) {  // wave 0: its lanes hold the stage constants
+    sh.st_len[tid] = len_v;
+    sh.st_off[tid] = off_v;
   }
   store_half(0);
   if (staged_total > kStageLoads * kRetThreads) {
@@ -152,15 +160,6 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     set_bit(sh.R, (uint32_t)my_pivot);
     sh.owner[my_pivot] = kOwnPivot;
   }
-
-  // stage constants in the lanes of every wave: lane i holds stage i's quota, list
-  // length and list offset (the offsets are the prefix sums of the lengths)
-  int quota_v = 0, len_v = 0;
-  if (lane < P) {
-    quota_v = sp.quota(lane);
-    len_v = sp.stage_len(n, lane);
-  }
-  const int off_v = wave_excl_scan(len_v, lane);
 
   int next = 0;  // first stage not yet final (block-uniform)
   while (next < P) {
