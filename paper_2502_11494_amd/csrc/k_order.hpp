@@ -38,7 +38,7 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
   // computes stage s's length, a wave scan adds them up (no loop over the stages)
   const int len_v = (tid & 63) < g.P ? sp.stage_len(n, tid & 63) : 0;
   const int off_v = wave_excl_scan(len_v, tid & 63);
-  unsigned long long* out = lists + (long)g.P * sm.row0 + __builtin_amdgcn_readlane(off_v, i);
+  unsigned long long* out = lists + (long)g.P * sm.row0 + __builtin_amdgcn_readfirstlane(__shfl(off_v, i, kWave));
   for (int t = tid; t < want; t += kSelThreads)
     out[t] = t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)];
 }

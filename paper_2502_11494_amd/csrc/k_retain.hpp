@@ -110,14 +110,21 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   // Lists of the stages [first, group_hi) that fit in LDS together (the first one maybe
   // only in part); block-uniform arithmetic on the lane constants, no memory access.
   int group_hi = 0, group_base = 0, staged_total = 0;
-  auto plan_group = [&](int first) {
-    group_base = __builtin_amdgcn_readlane(off_v, first);
-    const int l0 = __builtin_amdgcn_readlane(len_v, first);
-    int tot = l0 < kRetList ? l0 : kRetList;
-    group_hi = first + 1;
-    while (group_hi < P && tot + __builtin_amdgcn_readlane(len_v, group_hi) <= kRetList)
-      tot += __builtin_amdgcn_readlane(len_v, group_hi++);
-    staged_total = tot;
+  auto plan_group = [&](int first_any) {
+    // (lane broadcasts by shuffle + readfirstlane: a readlane with a computed lane index did
+    // not always compile here)
+    const int first = __builtin_amdgcn_readfirstlane(first_any);  // block-uniform: keep it scalar
+    group_base = __builtin_amdgcn_readfirstlane(__shfl(off_v, first, kWave));
+    const int l0 = __builtin_amdgcn_readfirstlane(__shfl(len_v, first, kWave));
+    const int l0c = l0 < kRetList ? l0 : kRetList;
+    // a later stage s joins the group while everything up to the end of its list fits; the
+    // list ends grow with s, so the stages that fit are the lanes first+1 .. group_hi-1
+    const int rel_end = off_v + len_v - group_base - l0 + l0c;  // staged entries through stage `lane`
+    const bool fits = lane > first && lane < P && rel_end <= kRetList;
+    const int extra = __builtin_amdgcn_readfirstlane(__popcll(__ballot(fits)));
+    group_hi = first + 1 + extra;
+    const int through = __builtin_amdgcn_readfirstlane(__shfl(rel_end, first + extra, kWave));
+    staged_total = extra > 0 ? through : l0c;
   };
   // a group moves in two halves of kStageLoads loads per thread (48 KiB in flight each)
   constexpr int kStageLoads = kRetList / kRetThreads / 2;
@@ -181,10 +188,15 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     if (tid >= next && tid < group_hi) sh.st_kab[tid][1] = kNoKey;
     __syncthreads();
     const int walk_end = group_hi;
+    // The global pointer carries its address space: with a generic one the compiler may fold
+    // the two returns into one flat load from a selected pointer (and its LDS-to-flat cast
+    // did not compile in every context).
+    typedef const unsigned long long __attribute__((address_space(1)))* GlobalList;
+    const GlobalList glist_g = (GlobalList)glist;
     auto entry_of = [&](int i, int p) -> unsigned long long {
       const int o = sh.st_off[i] - group_base + p;  // position in sh.list
       if (o < staged_total) return sh.list[o];
-      return glist[sh.st_off[i] + p];
+      return glist_g[sh.st_off[i] + p];
     };
 
     // ------------------------------------------------------------------ speculative walk
@@ -382,8 +394,10 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     __syncthreads();
 
     // ------------------------------------------------------------------ fp64 scores of the queue
-    const int fb_first = sh.fb_first;
-    const int qn = sh.qn;
+    // block-uniform values read from LDS are made scalar explicitly: they end up as lane
+    // indices of readlane, which must be scalar registers
+    const int fb_first = __builtin_amdgcn_readfirstlane(sh.fb_first);
+    const int qn = __builtin_amdgcn_readfirstlane(sh.qn);
     for (int q = wave; q < qn; q += kRetWaves) {  // a pair per wave: 16 row pairs in flight
       const int st = sh.q_stage[q];
       if (st >= fb_first) continue;  // will be walked again anyway
@@ -423,7 +437,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       if (!pair_less(mt_s, mt_j, mu_s, mu_j) && lane == 0) atomicMin(&sh.bad_first, i);
     }
     __syncthreads();
-    const int bad = sh.bad_first;
+    const int bad = __builtin_amdgcn_readfirstlane(sh.bad_first);
     if (bad >= walk_end && fb_first >= walk_end) {
       next = walk_end;  // everything stands
       continue;
