@@ -15,6 +15,9 @@ namespace dart {
 
 constexpr int kSelPerThread = 16;  // values a thread keeps in registers
 constexpr int kSelBuckets = 1024;
+// Requests for more than kSelCountMin keys are put in order by counting instead of a bitonic
+// sort (measured cross-over), unless one fine histogram bucket holds more than kSelMaxSeg of them (massive ties).
+constexpr int kSelCountMin = 128, kSelMaxSeg = 64;
 
 template <int THREADS>
 struct SelectShared {
@@ -26,6 +29,7 @@ struct SelectShared {
   int count;
   int dstar;
   int count2, dmid, cmid, cstar;  // two-part sort: see collect_sorted
+  int clim;                       // keys selected (ordering by counting)
 };
 
 template <int THREADS>
@@ -51,7 +55,9 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
 // sorted separately (two short sorts instead of one of twice the size; the histogram
 // already orders them by value): the first *part2 keys are at buf[0..), the others at
 // buf[THREADS..).  Otherwise *part2 is the returned count (one run at buf[0..)).
-template <int THREADS>
+// COUNTING: long requests may be ordered by counting (see below); callers that only ever ask for
+// a few keys leave it off and keep the shorter code.
+template <int THREADS, bool COUNTING = false>
 __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
                                               float incl_upto, int tid, SelectShared<THREADS>& sh,
                                               float* left_min = nullptr, int* part2 = nullptr) {
@@ -126,6 +132,104 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     }
   }
   __syncthreads();
+  if (COUNTING && want > kSelCountMin) {
+    // Ordering by counting instead of a sorting network (long requests only).  The selected keys
+    // -- those of the coarse buckets <= dl -- get a second, finer histogram over their own value
+    // range (a bucket is a monotone function of the value, so bucket order is value order);
+    // its prefix sums are the positions where the buckets' keys start; the keys are scattered
+    // there and every key finds its rank inside its bucket's segment.  Six barriers instead of
+    // a bitonic network's dozens.  A segment longer than kSelMaxSeg (massive ties) sends the
+    // list to the network below.
+    constexpr int kCap = kSelThreads * kSelPerThread / 2;  // keys that fit twice in buf
+    int dl = sh.dstar;
+    if (incl_upto > -INFINITY) {
+      const int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
+      dl = d2 > dl ? d2 : dl;
+    }
+    dl = dl < 0 ? 0 : (dl < kSelBuckets ? dl : kSelBuckets - 1);  // (want >= 1 makes it valid anyway)
+    {
+      int through = run;  // count up to and including the thread's last bucket
+#pragma unroll
+      for (int q = kSelBucketsPerThread - 1; q >= 0; --q) {
+        if (tid * kSelBucketsPerThread + q == dl) sh.clim = through;
+        through -= h[q];
+      }
+    }
+    __syncthreads();
+    const int c = __builtin_amdgcn_readfirstlane(sh.clim);  // selected keys
+    if (c <= kCap) {
+      const float scale2 = scale * ((float)kSelBuckets / (float)(dl + 1));
+      auto fine = [&](float x) -> int {
+        const float f = (x - lo) * scale2;
+        int d = f >= (float)(kSelBuckets - 1) ? kSelBuckets - 1 : (int)f;
+        d = d < 0 ? 0 : d;
+        return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
+      };
+#pragma unroll
+      for (int q = 0; q < kSelBucketsPerThread; ++q) sh.hist[tid + q * kSelThreads] = 0;
+      __syncthreads();
+      float rest = INFINITY;
+#pragma unroll
+      for (int e = 0; e < kSelPerThread; ++e)
+        if (e < ne && tid + e * kSelThreads < n) {
+          if (bucket(v[e]) <= dl) atomicAdd(&sh.hist[fine(v[e])], 1);
+          else rest = fminf(rest, v[e]);
+        }
+      if (left_min) {
+        rest = wave_min(rest);
+        if (lane == 0) sh.redg[w] = rest;
+      }
+      __syncthreads();
+      int hh[kSelBucketsPerThread], mine2 = 0, big = 0;
+#pragma unroll
+      for (int q = 0; q < kSelBucketsPerThread; ++q) {
+        hh[q] = sh.hist[tid * kSelBucketsPerThread + q];
+        mine2 += hh[q];
+        big |= hh[q] > kSelMaxSeg ? 1 : 0;
+      }
+      int run2 = wave_excl_scan(mine2, lane);
+      if (lane == 63) sh.redi[w] = run2 + mine2;
+      big = __syncthreads_or(big);
+      if (!big) {
+        if (left_min) {
+#pragma unroll
+          for (int i = 0; i < kSelWaves; ++i) rest = fminf(rest, sh.redg[i]);
+          *left_min = rest;
+        }
+#pragma unroll
+        for (int i = 0; i < kSelWaves; ++i)
+          if (i < w) run2 += sh.redi[i];
+#pragma unroll
+        for (int q = 0; q < kSelBucketsPerThread; ++q) {
+          sh.hist[tid * kSelBucketsPerThread + q] = run2;  // where the bucket's keys start
+          run2 += hh[q];
+        }
+        __syncthreads();
+        unsigned long long* tmp = sh.buf + kCap;
+#pragma unroll
+        for (int e = 0; e < kSelPerThread; ++e) {
+          const int j = tid + e * kSelThreads;
+          if (e < ne && j < n && bucket(v[e]) <= dl) {
+            const int pos = atomicAdd(&sh.hist[fine(v[e])], 1);
+            tmp[pos] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+          }
+        }
+        __syncthreads();
+        // every cell now holds the end of its bucket's segment = the start of the next one
+        for (int t = tid; t < c; t += kSelThreads) {
+          const unsigned long long key = tmp[t];
+          const int d = fine(mono_inv((uint32_t)(key >> 32)));
+          const int start = d > 0 ? sh.hist[d - 1] : 0, end = sh.hist[d];
+          int rank = 0;
+          for (int u = start; u < end; ++u) rank += tmp[u] < key ? 1 : 0;
+          sh.buf[start + rank] = key;
+        }
+        __syncthreads();
+        if (part2) *part2 = c;
+        return c;
+      }
+    }
+  }
   // last bucket whose inclusive count still fits one run (none if bucket 0 alone does not)
   if (part2) {
     int run2 = run;

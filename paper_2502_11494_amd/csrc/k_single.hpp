@@ -80,7 +80,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       v[e] = a;
     }
     const int want = m + 1 < n ? m + 1 : n;
-    int c = collect_sorted(v, n, want, -INFINITY, tid, sh.sel);
+    int c = collect_sorted<1024, true>(v, n, want, -INFINITY, tid, sh.sel);
     const float fa = mono_inv((uint32_t)(sh.sel.buf[m - 1] >> 32));
     float fb = m < c ? mono_inv((uint32_t)(sh.sel.buf[m] >> 32)) : INFINITY;
     if (fb >= 2.0f) fb = INFINITY;  // only pivots are left
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     } else {
       // every token whose aggregate can still be on either side of the boundary
       const float lo = fa - two_tau, hi = fb + two_tau;
-      c = collect_sorted(v, n, want, hi, tid, sh.sel);
+      c = collect_sorted<1024, true>(v, n, want, hi, tid, sh.sel);
       if (tid == 0) {
         sh.below = 0;
         sh.nband = 0;
