@@ -20,6 +20,11 @@ using namespace dart;
 // 4 are 10-30% slower: the kernel runs at the speed of its load stream, which degrades
 // when every wave keeps more of its 16 rows' pieces outstanding).
 constexpr int kScoreDepth = 1;
+// Small batches (at most kScoreSplitRows rows: fewer than 1024 waves of 16 rows) cannot fill
+// the chip with one wave per 16 rows, and a wave's chain over all of D sets the kernel's
+// time; there kScoreSplit workgroups share a tile and split D (see k_scores_bf16).
+constexpr int kScoreSplit = 4;
+constexpr long kScoreSplitRows = 16384;
 
 
 namespace {
@@ -34,7 +39,8 @@ struct Plan {
   int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
-      total;
+      o_part, total;
+  int score_split;  // workgroups that share a score tile (1, or kScoreSplit for small batches)
 };
 
 dart_status make_plan(const dart_desc* d, Plan& p) {
@@ -113,8 +119,15 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   // block and all tiles fit the 256 compute units at once; with more tiles the smaller
   // workgroups (three per compute unit) win, with more pivots too.
   {
+    const int NB = g.Ppad / 16, CH = NB == 1 ? 256 : 128;
+    // (measured: a gain from 4 chunks per slice on -- 576-token images at D = 4096: 30 -> 27 us,
+    // at D = 8192 and half the rows: 50 -> 26 us -- a loss with 3 chunks per slice)
+    p.score_split = (d->dtype == DART_BF16 && total <= kScoreSplitRows &&
+                     d->D / CH >= 4 * kScoreSplit) ? kScoreSplit : 1;
     const long tiles128 = ragged ? total / 128 + d->B : (long)d->B * ((d->N + 127) / 128);
-    g.tile_rows = (d->dtype == DART_BF16 && g.Ppad == 16 && tiles128 <= 256) ? 128 : 64;
+    // (with split tiles the 64-row workgroups, three per compute unit, are all resident at once)
+    g.tile_rows = (d->dtype == DART_BF16 && g.Ppad == 16 && tiles128 <= 256 && p.score_split == 1)
+                      ? 128 : 64;
   }
   p.esz = esz;
   if (!ragged) {
@@ -137,6 +150,14 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   p.o_S = take(sizeof(float) * (size_t)total * d->P);
   p.o_lists = take(sizeof(unsigned long long) * (size_t)total * d->P);
   p.o_scr_f64 = take(sizeof(double) * 2 * (size_t)total);
+  {
+    const int NB = g.Ppad / 16;
+    // partial sums: per tile, slice, wave (tile_rows / 16) and lane, NB*4 + 4 doubles
+    p.o_part = p.score_split > 1
+                   ? take(sizeof(double) * (size_t)p.tiles_bound * p.score_split *
+                          (g.tile_rows / 16) * 64 * (NB * 4 + 4))
+                   : o;
+  }
   p.total = o;
   return DART_OK;
 }
@@ -236,7 +257,7 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
 dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
-  const double* pl2 = at<double>(ws, p.o_pl2);
+  double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kF32) {
     hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
                        p.g, X, piv, S);
@@ -247,12 +268,24 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
 #define DART_LAUNCH_SCORES(NB, CH, W)                                                            \
   do {                                                                                           \
     const dim3 grid(p.tiles_bound), block(64 * (W));                                             \
-    if (p.g.D % (CH) == 0)                                                                       \
+    if (p.score_split > 1) {                                                                     \
+      const dim3 grid_s(p.tiles_bound * kScoreSplit);                                            \
+      double* part = at<double>(ws, p.o_part);                                                   \
+      if (p.g.D % (CH) == 0)                                                                     \
+        hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, kScoreSplit>), grid_s,  \
+                           block, 0, st, p.g, X, piv, pl2, S, part);                             \
+      else                                                                                       \
+        hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, kScoreSplit>), grid_s,   \
+                           block, 0, st, p.g, X, piv, pl2, S, part);                             \
+      DART_LAUNCH_CHECK();                                                                       \
+      hipLaunchKernelGGL((k_scores_finish<NB, W, kScoreSplit>), grid, block, 0, st, p.g, part,   \
+                         pl2, S);                                                                \
+    } else if (p.g.D % (CH) == 0)                                                                \
       hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth>), grid, block, 0, st,     \
-                         p.g, X, piv, pl2, S);                                                   \
+                         p.g, X, piv, pl2, S, nullptr);                                          \
     else                                                                                         \
       hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth>), grid, block, 0, st,      \
-                         p.g, X, piv, pl2, S);                                                   \
+                         p.g, X, piv, pl2, S, nullptr);                                          \
   } while (0)
     switch (p.g.Ppad / 16) {
       case 1:

@@ -70,6 +70,40 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
   return true;
 }
 
+// Scores of one wave's 16 rows from the accumulated dot products and Gram diagonal.
+// Output tile: lane holds column (lane&15) and rows 4*(lane>>4)..+3 of each 16x16 block.
+// With tokens as the A operand, rows are tokens and columns are pivots (Gram: columns are
+// tokens too, so |x_m|^2 sits in lane (m/4)*16+m, slot m%4).
+template <int NB>
+__device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int b, int j0,
+                                             int lane, const double (&acc64)[NB][4],
+                                             const double (&gram64)[4],
+                                             const double* __restrict__ pl2,
+                                             float* __restrict__ S) {
+  const int n = sm.n, P = g.P;
+  const int g4 = lane >> 4;
+  double xn[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) xn[r] = sqrt(__shfl(gram64[r], g4 * 16 + g4 * 4 + r, kWave));
+  float* Sb = S + (long)P * sm.row0;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int i = nb * 16 + (lane & 15);
+    if (i < P) {
+      const double pn = sqrt(pl2[b * g.Ppad + i]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int j = j0 + g4 * 4 + r;
+        if (j < n) {
+          const double den = pn * xn[r];
+          const double s = den > 0.0 ? acc64[nb][r] / den : 0.0;
+          Sb[(long)i * n + j] = (float)s + 0.0f;
+        }
+      }
+    }
+  }
+}
+
 // grid: number of tiles of g.tile_rows = 16*WAVES rows (dense: B*ceil(N/tile_rows);
 // ragged: an upper bound): a workgroup of WAVES waves owns one tile, a wave 16 rows.
 // NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256);
@@ -78,11 +112,16 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
 // traffic) and, requested just before them, the chunk's pivot pieces.  All loads are
 // unconditional straight-line code, so the compiler's wait counts let the prefetched
 // chunks stay in flight.
-template <int NB, int CH, bool TAIL, int WAVES, int DEPTH>
+// SPLIT > 1 (small batches, which cannot fill the chip with one wave per 16 rows): SPLIT
+// workgroups share a tile, each takes a contiguous run of the chunks and leaves its partial
+// sums in `part` ([tile][slice][wave][lane][NB*4 + 4] doubles); k_scores_finish adds them in
+// slice order and stores the scores.  grid: tiles * SPLIT.
+template <int NB, int CH, bool TAIL, int WAVES, int DEPTH, int SPLIT = 1>
 __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv,
                                                      const double* __restrict__ pl2,
-                                                     float* __restrict__ S) {
+                                                     float* __restrict__ S,
+                                                     double* __restrict__ part = nullptr) {
   constexpr int kRowB = CH * 2 + 16;   // LDS row stride, bytes
   constexpr int PC = CH / 8;           // 16-byte pieces per row per chunk
   constexpr int RPI = kWave / PC;      // rows covered by one load instruction
@@ -93,7 +132,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   __shared__ __align__(16) ScoreShared<NB, CH, WAVES> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
-  if (!locate_tile(g, blockIdx.x, b, tl)) return;
+  const int tile = SPLIT == 1 ? blockIdx.x : blockIdx.x / SPLIT;
+  const int slice = SPLIT == 1 ? 0 : blockIdx.x - tile * SPLIT;
+  if (!locate_tile(g, tile, b, tl)) return;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n, P = g.P;
@@ -105,7 +146,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   const long rowbytes = g.ld * 2;
   const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes;
   const int pieces = g.D / 8;  // 16-byte pieces per row
-  const int nchunks = (g.D + CH - 1) / CH;
+  const int chunks_all = (g.D + CH - 1) / CH;
+  // this workgroup's chunks [c_first, nchunks)
+  const int c_first = SPLIT == 1 ? 0 : slice * chunks_all / SPLIT;
+  const int nchunks = SPLIT == 1 ? chunks_all : (slice + 1) * chunks_all / SPLIT;
   const int col16 = lane % PC, rowsub = lane / PC;
   const int j0 = block_row0 + wave * 16;
   const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -217,12 +261,12 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   // the compiler's wait counts at the loop head stay exact)
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) {
-    const int cc = d < nchunks ? d : 0;
+    const int cc = c_first + d < nchunks ? c_first + d : c_first;
     DART_LOAD_P(cc, d);
     DART_LOAD_A(cc, d);
   }
-  DART_STORE_P(0, 0, 0);
-  int c = 0;
+  DART_STORE_P(c_first, 0, c_first & 1);
+  int c = c_first;
   for (; c + 2 * DEPTH - 1 < nchunks; c += DEPTH) {  // steady state: every load is issued
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) DART_CHUNK(c + d, d, (d + 1) % DEPTH, true, true);
@@ -238,30 +282,52 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
 #undef DART_LOAD_P
 #undef DART_STORE_P
 
-  // Output tile: lane holds column (lane&15) and rows 4*(lane>>4)..+3 of each 16x16
-  // block.  With tokens as the A operand, rows are tokens and columns are pivots
-  // (Gram: columns are tokens too, so |x_m|^2 sits in lane (m/4)*16+m, slot m%4).
-  const int g4 = lane >> 4;
-  double xn[4];
+  if (SPLIT == 1) {
+    store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S);
+  } else {
+    double* out = part + (((long)blockIdx.x * WAVES + wave) * kWave + lane) * (NB * 4 + 4);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) xn[r] = sqrt(__shfl(gram64[r], g4 * 16 + g4 * 4 + r, kWave));
-  float* Sb = S + (long)P * sm.row0;
+    for (int r = 0; r < 4; ++r) {
+      out[r] = gram64[r];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    const int i = nb * 16 + (lane & 15);
-    if (i < P) {
-      const double pn = sqrt(pl2[b * g.Ppad + i]);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = j0 + g4 * 4 + r;
-        if (j < n) {
-          const double den = pn * xn[r];
-          const double s = den > 0.0 ? acc64[nb][r] / den : 0.0;
-          Sb[(long)i * n + j] = (float)s + 0.0f;
-        }
-      }
+      for (int nb = 0; nb < NB; ++nb) out[4 + nb * 4 + r] = acc64[nb][r];
     }
   }
+}
+
+// Adds the SPLIT partial sums of every (tile, wave, lane) in slice order and stores the
+// scores.  grid: tiles blocks of WAVES*64 (the same tiles as k_scores_bf16).
+template <int NB, int WAVES, int SPLIT>
+__global__ __launch_bounds__(WAVES * 64) void k_scores_finish(Geo g, const double* __restrict__ part,
+                                                        const double* __restrict__ pl2,
+                                                        float* __restrict__ S) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b, tl;
+  if (!locate_tile(g, blockIdx.x, b, tl)) return;
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0) return;
+  const int block_row0 = tl * (16 * WAVES);
+  if (block_row0 >= sm.n) return;
+  const int j0 = block_row0 + wave * 16;
+  double acc64[NB][4], gram64[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    gram64[r] = 0.0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc64[nb][r] = 0.0;
+  }
+#pragma unroll
+  for (int sl = 0; sl < SPLIT; ++sl) {
+    const double* in =
+        part + ((((long)blockIdx.x * SPLIT + sl) * WAVES + wave) * kWave + lane) * (NB * 4 + 4);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      gram64[r] += in[r];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += in[4 + nb * 4 + r];
+    }
+  }
+  store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S);
 }
 
 // fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)

@@ -41,6 +41,14 @@ SMALL = [
     lambda: W.video_batch(B=1, frames=40, per_frame=64, D=256, P=8, K=1500, n_centroids=8),
     # lists that need several LDS staging groups (32 lists of up to 2049 entries)
     lambda: W.video_batch(B=2, frames=32, per_frame=128, D=128, P=32, K=2048, n_centroids=8),
+    # small batches with long rows: several workgroups share a score tile and split D
+    # (2, 3 and 4 pivot column blocks; row lengths that leave a ragged last chunk)
+    lambda: W.image_batch(B=2, N=300, D=2048, P=20, K=64, n_centroids=16),
+    lambda: W.video_batch(B=1, frames=6, per_frame=50, D=2048, P=40, K=100, n_centroids=8),
+    lambda: W.image_batch(B=1, N=200, D=2048, P=64, K=80, n_centroids=16),
+    lambda: W.image_batch(B=2, N=150, D=2120, P=20, K=40, n_centroids=16),
+    lambda: W.image_batch(B=2, N=150, D=4104, P=8, K=40, n_centroids=16),
+    lambda: W.ragged_batch(B=3, n_lo=200, n_hi=500, D=4096, P=16),
 ]
 
 
