@@ -44,7 +44,9 @@
  *   Non-finite input values give unspecified (but memory-safe) results.
  * Determinism.  Same inputs give bit-identical outputs, call after call, and a
  *   row's score depends only on its bytes and the pivot's bytes, not on where
- *   the row sits in the batch.
+ *   the row sits in the batch.  (Different entry points or pivot modes may take the
+ *   token norms from different passes: their scores agree within
+ *   dart_score_tolerance, not necessarily in the last bit.)
  * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N <= 2^27.
  * Pivots from outside (desc.P_ext > 0).  Tokens are scored against such a pivot and it
  *   has its stage in step (c) like any pivot -- after the pivots that are tokens, in the

@@ -39,7 +39,8 @@ struct Plan {
   int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
-      o_part, total;
+      o_part, o_l2, total;
+  bool norms_given;  // this call's norm pass also leaves the squared token norms (fused path)
   int score_split;  // workgroups that share a score tile (1, or kScoreSplit for small batches)
 };
 
@@ -158,6 +159,8 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
                           (g.tile_rows / 16) * 64 * (NB * 4 + 4))
                    : o;
   }
+  p.o_l2 = take(sizeof(double) * (size_t)total);
+  p.norms_given = false;
   p.total = o;
   return DART_OK;
 }
@@ -195,7 +198,7 @@ dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
 
 // keep_cached: the rows will be read again soon (they are the hidden states themselves).
 dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float* l1,
-                          bool keep_cached, hipStream_t st) {
+                          bool keep_cached, hipStream_t st, double* l2sq = nullptr) {
   constexpr int ROWS = 1;  // one row per wave measured best (more, shorter-lived waves)
   const int rows = p.g.total_N;
   if (rows == 0) return DART_OK;
@@ -208,7 +211,16 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   const bool keep = keep_cached && (double)rows * ldc * p.esz <= 224e6;
 #define DART_LAUNCH_L1(DT)                                                                       \
   do {                                                                                           \
-    if (p.g.span)                                                                                \
+    if (l2sq && p.g.span)                                                                        \
+      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, false, true, true>), dim3(blocks), dim3(256), 0, \
+                         st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
+    else if (l2sq && keep)                                                                       \
+      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, true, false, true>), dim3(blocks), dim3(256), 0, \
+                         st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
+    else if (l2sq)                                                                               \
+      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, false, false, true>), dim3(blocks), dim3(256),   \
+                         0, st, C, Dc, ldc, rows, l1, p.g, l2sq);                                \
+    else if (p.g.span)                                                                                \
       hipLaunchKernelGGL((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,   \
                          Dc, ldc, rows, l1, p.g);                                                \
     else if (keep)                                                                               \
@@ -258,6 +270,7 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
   double* pl2 = at<double>(ws, p.o_pl2);
+  const double* l2sq = p.norms_given ? at<double>(ws, p.o_l2) : nullptr;
   if (p.g.dtype == kF32) {
     hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
                        p.g, X, piv, S);
@@ -268,24 +281,34 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
 #define DART_LAUNCH_SCORES(NB, CH, W)                                                            \
   do {                                                                                           \
     const dim3 grid(p.tiles_bound), block(64 * (W));                                             \
+    const bool tail = p.g.D % (CH) != 0;                                                         \
     if (p.score_split > 1) {                                                                     \
       const dim3 grid_s(p.tiles_bound * kScoreSplit);                                            \
       double* part = at<double>(ws, p.o_part);                                                   \
-      if (p.g.D % (CH) == 0)                                                                     \
-        hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, kScoreSplit>), grid_s,  \
-                           block, 0, st, p.g, X, piv, pl2, S, part);                             \
-      else                                                                                       \
-        hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, kScoreSplit>), grid_s,   \
-                           block, 0, st, p.g, X, piv, pl2, S, part);                             \
+      DART_SCORES_PICK(NB, CH, W, kScoreSplit, grid_s, part);                                    \
       DART_LAUNCH_CHECK();                                                                       \
       hipLaunchKernelGGL((k_scores_finish<NB, W, kScoreSplit>), grid, block, 0, st, p.g, part,   \
-                         pl2, S);                                                                \
-    } else if (p.g.D % (CH) == 0)                                                                \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth>), grid, block, 0, st,     \
-                         p.g, X, piv, pl2, S, nullptr);                                          \
+                         pl2, S, l2sq);                                                          \
+    } else {                                                                                     \
+      double* part = nullptr;                                                                    \
+      DART_SCORES_PICK(NB, CH, W, 1, grid, part);                                                \
+    }                                                                                            \
+  } while (0)
+  // (TAIL, XN) variants of one shape
+#define DART_SCORES_PICK(NB, CH, W, SP, GRID, PART)                                              \
+  do {                                                                                           \
+    if (!tail && l2sq)                                                                           \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, SP, true>), GRID, block,  \
+                         0, st, p.g, X, piv, pl2, S, PART, l2sq);                                \
+    else if (!tail)                                                                              \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, SP, false>), GRID, block, \
+                         0, st, p.g, X, piv, pl2, S, PART, nullptr);                             \
+    else if (l2sq)                                                                               \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, SP, true>), GRID, block,   \
+                         0, st, p.g, X, piv, pl2, S, PART, l2sq);                                \
     else                                                                                         \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth>), grid, block, 0, st,      \
-                         p.g, X, piv, pl2, S, nullptr);                                          \
+      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, SP, false>), GRID, block,  \
+                         0, st, p.g, X, piv, pl2, S, PART, nullptr);                             \
   } while (0)
     switch (p.g.Ppad / 16) {
       case 1:
@@ -296,6 +319,7 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
       default: DART_LAUNCH_SCORES(4, 128, 4); break;
     }
 #undef DART_LAUNCH_SCORES
+#undef DART_SCORES_PICK
   }
   DART_LAUNCH_CHECK();
   return DART_OK;
@@ -312,7 +336,7 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
 
 dart_status launch_retain(const Plan& p, const float* S, const int* piv, const void* X, int* keep,
                           int* cu_keep, void* ws, hipStream_t st) {
-  const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype));
+  const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype, p.norms_given));
   const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   double* scr_f64 = at<double>(ws, p.o_scr_f64);
   if (p.g.score_mode != 0) {  // one threshold for all pivots: no stage lists
@@ -400,7 +424,17 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     DART_TRY(mark(2));
   } else {
     // pivots chosen among the tokens (none if all of them come from outside) ...
-    if (p.g.Pin > 0) DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st));
+    // hidden states as their own criterion: the norm pass also leaves the squared token
+    // norms, and the score pass skips its Gram products
+    // (measured: the extra arithmetic costs the norm pass 1-3 % up to 264 MB and 5 % at
+    // 1.7 GB, where it runs at the memory's speed; with one pivot column block the score pass
+    // gains nothing, with two it gains 5 %, and the tighter error bound saves the retained-set
+    // kernel 10 % on near-duplicate video frames: used for P > 16 up to about 1 GB)
+    p.norms_given = p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 && p.g.Ppad > 16 &&
+                    (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
+    if (p.g.Pin > 0)
+      DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st,
+                             p.norms_given ? at<double>(ws, p.o_l2) : nullptr));
     DART_TRY(mark(1));
     if (p.g.Pin > 0) DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
     // ... then the norms and marks of those from outside

@@ -23,6 +23,16 @@ __device__ __forceinline__ float piece_abs_sum(const u32x4& v) {
   }
 }
 
+// Sum of x^2 over one 16-byte piece of bf16 values: the squares are exact in fp32 (8-bit
+// significands), the pairwise tree rounds three times (relative error <= 3 * 2^-24).
+__device__ __forceinline__ float piece_sq_sum_bf16(const u32x4& v) {
+  const float x0 = bf16_lo(v.x), x1 = bf16_hi(v.x), x2 = bf16_lo(v.y), x3 = bf16_hi(v.y);
+  const float x4 = bf16_lo(v.z), x5 = bf16_hi(v.z), x6 = bf16_lo(v.w), x7 = bf16_hi(v.w);
+  const float a0 = x0 * x0 + x1 * x1, a1 = x2 * x2 + x3 * x3;
+  const float a2 = x4 * x4 + x5 * x5, a3 = x6 * x6 + x7 * x7;
+  return (a0 + a1) + (a2 + a3);
+}
+
 // Relative bound on |fp32 norm - exact norm| for k_row_l1: piece tree, then one
 // add per piece a lane owns, then the 6-step butterfly, each rounding at most
 // 2^-24 relative on a sum of non-negative terms.
@@ -43,9 +53,14 @@ inline double l1_rel_bound(int dtype, int Dc) {
 // SPAN: the samples' rows are spans of C (Geo::span); packed row r belongs to the sample b
 // with cu[b] <= r < cu[b+1] and lives at row span[b] + (r - cu[b]) of C.  Rows of a sample
 // that keeps nothing (skipped: its span may be invalid) are not read.
-template <int DT, int ROWS, bool KEEP, bool SPAN>
+// L2SQ (bf16 only, when the rows are the hidden states themselves): also the squared
+// Euclidean norm of every row, which the score kernel divides by: piece sums in fp32 (see
+// piece_sq_sum_bf16), added in fp64 in a fixed lane-strided order plus butterfly, so the
+// result is a function of the row's bytes with a relative error of at most 3.5 * 2^-24.
+template <int DT, int ROWS, bool KEEP, bool SPAN, bool L2SQ = false>
 __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int Dc, long ldc,
-                                                int rows, float* __restrict__ l1, Geo g) {
+                                                int rows, float* __restrict__ l1, Geo g,
+                                                double* __restrict__ l2sq = nullptr) {
   const int lane = threadIdx.x & 63;
   const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int esz = DT == kBF16 ? 2 : 4;
@@ -55,6 +70,7 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
   const u32x4 zero = {0u, 0u, 0u, 0u};
 
   float acc[ROWS];
+  double sq[ROWS];
   const unsigned char* rp[ROWS];
   bool live[ROWS];
 #pragma unroll
@@ -73,6 +89,7 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
     }
     rp[r] = base + crow * rowbytes;
     acc[r] = 0.f;
+    sq[r] = 0.0;
   }
   for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
     u32x4 v[ROWS][8];
@@ -88,12 +105,19 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
 #pragma unroll
     for (int r = 0; r < ROWS; ++r)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc[r] += piece_abs_sum<DT>(v[r][u]);
+      for (int u = 0; u < 8; ++u) {
+        acc[r] += piece_abs_sum<DT>(v[r][u]);
+        if (L2SQ) sq[r] += (double)piece_sq_sum_bf16(v[r][u]);
+      }
   }
 #pragma unroll
   for (int r = 0; r < ROWS; ++r) {
     float s = wave_sum(acc[r]);
     if (lane == 0 && live[r]) l1[wave * ROWS + r] = s;
+    if (L2SQ) {
+      const double q = wave_sum(sq[r]);
+      if (lane == 0 && live[r]) l2sq[wave * ROWS + r] = q;
+    }
   }
 }
 

@@ -35,10 +35,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // same kind of sum and enters through a square root (half the relative error).
 // Two more units for rounding the quotient to fp32 and the fp64 steps.
 // fp32 inputs: all fp64, only the final rounding to fp32 counts.
+// norms_given: the token norms come from k_row_l1 (relative error 3.5 * 2^-24 on the square,
+// half of it on the norm; 2 units are counted) instead of the Gram diagonal.
 constexpr double kMfmaUlps = 16.0;
-inline double score_abs_bound(int dtype) {
+inline double score_abs_bound(int dtype, bool norms_given = false) {
   const double u = 5.9604644775390625e-08;  // 2^-24
-  return dtype == kBF16 ? (kMfmaUlps * 1.5 + 2.0) * u : 4.0 * u;
+  if (dtype != kBF16) return 4.0 * u;
+  return (norms_given ? kMfmaUlps + 2.0 + 2.0 : kMfmaUlps * 1.5 + 2.0) * u;
 }
 
 // LDS of one workgroup: CH = elements of D per chunk; rows are padded by 16 bytes
@@ -79,12 +82,21 @@ __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int
                                              int lane, const double (&acc64)[NB][4],
                                              const double (&gram64)[4],
                                              const double* __restrict__ pl2,
-                                             float* __restrict__ S) {
+                                             float* __restrict__ S,
+                                             const double* __restrict__ l2sq) {
   const int n = sm.n, P = g.P;
   const int g4 = lane >> 4;
   double xn[4];
+  if (l2sq != nullptr) {  // squared token norms from the norm pass (packed rows)
 #pragma unroll
-  for (int r = 0; r < 4; ++r) xn[r] = sqrt(__shfl(gram64[r], g4 * 16 + g4 * 4 + r, kWave));
+    for (int r = 0; r < 4; ++r) {
+      const int j = j0 + g4 * 4 + r;
+      xn[r] = sqrt(l2sq[sm.row0 + (j < n ? j : n - 1)]);
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) xn[r] = sqrt(__shfl(gram64[r], g4 * 16 + g4 * 4 + r, kWave));
+  }
   float* Sb = S + (long)P * sm.row0;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
@@ -116,12 +128,15 @@ __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int
 // workgroups share a tile, each takes a contiguous run of the chunks and leaves its partial
 // sums in `part` ([tile][slice][wave][lane][NB*4 + 4] doubles); k_scores_finish adds them in
 // slice order and stores the scores.  grid: tiles * SPLIT.
-template <int NB, int CH, bool TAIL, int WAVES, int DEPTH, int SPLIT = 1>
+// XN: the squared token norms are given (l2sq, from the norm pass): the Gram products and
+// their accumulation are left out.
+template <int NB, int CH, bool TAIL, int WAVES, int DEPTH, int SPLIT = 1, bool XN = false>
 __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv,
                                                      const double* __restrict__ pl2,
                                                      float* __restrict__ S,
-                                                     double* __restrict__ part = nullptr) {
+                                                     double* __restrict__ part = nullptr,
+                                                     const double* __restrict__ l2sq = nullptr) {
   constexpr int kRowB = CH * 2 + 16;   // LDS row stride, bytes
   constexpr int PC = CH / 8;           // 16-byte pieces per row per chunk
   constexpr int RPI = kWave / PC;      // rows covered by one load instruction
@@ -239,7 +254,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
     const unsigned char* lp = sh.p + ((c) & 1) * (NB * 16 * kRowB);                            \
     _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                           \
       bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);                    \
-      const f32x4 gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);      \
+      f32x4 gram = fzero;                                                                      \
+      if (!XN) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);         \
       f32x4 acc[NB];                                                                           \
       _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                      \
         bf16x8 pf =                                                                            \
@@ -247,7 +263,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
         acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);             \
       }                                                                                        \
       _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                          \
-        gram64[r] += (double)gram[r];                                                          \
+        if (!XN) gram64[r] += (double)gram[r];                                                 \
         _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];  \
       }                                                                                        \
     }                                                                                          \
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
 #undef DART_STORE_P
 
   if (SPLIT == 1) {
-    store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S);
+    store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S, XN ? l2sq : nullptr);
   } else {
     double* out = part + (((long)blockIdx.x * WAVES + wave) * kWave + lane) * (NB * 4 + 4);
 #pragma unroll
@@ -300,7 +316,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
 template <int NB, int WAVES, int SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void k_scores_finish(Geo g, const double* __restrict__ part,
                                                         const double* __restrict__ pl2,
-                                                        float* __restrict__ S) {
+                                                        float* __restrict__ S,
+                                                        const double* __restrict__ l2sq) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
   if (!locate_tile(g, blockIdx.x, b, tl)) return;
@@ -327,7 +344,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_finish(Geo g, const doubl
       for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += in[4 + nb * 4 + r];
     }
   }
-  store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S);
+  store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S, l2sq);
 }
 
 // fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)
