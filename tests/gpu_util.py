@@ -139,7 +139,10 @@ def compare(w: W.Workload, g: GpuResult, refs: List[oracle.Reduced], check_admis
         err = np.abs(Sg - r.S)
         assert np.all(err <= RTOL[w.dtype] * np.abs(r.S) + ATOL), f"scores of sample {b}"
         worst = max(worst, float(err.max()))
-        assert err.max() <= tau, f"sample {b}: score error {err.max():.3e} exceeds bound {tau:.3e}"
+        # with more than 16 pivots the fused path certifies against a tighter bound (token norms
+        # from the norm pass: 20 instead of 26 units of 2^-24); hold it to that one
+        bound = tau * (20.0 / 26.0 if (w.dtype == W.BF16 and w.P > 16) else 1.0)
+        assert err.max() <= bound, f"sample {b}: score error {err.max():.3e} exceeds bound {bound:.3e}"
         np.testing.assert_array_equal(g.keep[k0:k0 + kb], r.keep, err_msg=f"keep of sample {b}")
         assert g.Y[k0:k0 + kb].tobytes() == r.Y.tobytes(), f"rows of sample {b}"
         np.testing.assert_array_equal(g.pos_out[k0:k0 + kb], r.pos_out)
