@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # load what is built; build only if nothing is (hipcc cross-compiles without a GPU)
+    from paper_2502_11494_amd import binding
+    if not os.path.exists(binding.LIB):
+        from paper_2502_11494_amd import build
+        build.build_hip()
 
 
 def _have_gpu() -> bool:
