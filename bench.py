@@ -387,6 +387,13 @@ def main():
         t0 = time.perf_counter()
         oracle.reduce(w.X[lo:hi], w.dtype, w.P, w.budget(0), pos=w.pos[lo:hi])
         cpu["single_thread_value"] = round((hi - lo) / (time.perf_counter() - t0), 1)
+        try:
+            with open("/proc/cpuinfo") as f:
+                models = [l.split(":", 1)[1].strip() for l in f if l.startswith("model name")]
+            cpu["cpu_model"] = models[0] if models else None
+            cpu["host_logical_cpus"] = os.cpu_count()
+        except OSError:
+            pass
         oracle.set_threads(0)
 
     out = {
