@@ -24,7 +24,6 @@ struct SingleShared {
   int piv[kMaxP];
   int wcnt[16];
   int below, nband;
-  double pair[1024];  // fp64 cosines of (band token, pivot) pairs
 };
 
 // grid: B blocks of 1024.  S: pivot-major scores.  X may be nullptr (scores exact).
@@ -112,33 +111,26 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       }
       __syncthreads();
       const int nband = sh.nband, need = m - sh.below;
-      // fp64 aggregate of every band token from its P cosines, recomputed from the rows
-      if (nband * P <= 1024) {
-        // a (token, pivot) pair per wave at a time, then the aggregate per token
-        for (int t = wave; t < nband * P; t += 16) {
-          const int u = t / P, i = t - u * P;
-          const double s = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv),
-                                              Xb + (long)band_j[u] * rowbytes, g.D, lane);
-          if (lane == 0) sh.pair[t] = s;
+      // fp64 aggregate of every band token, recomputed from the rows: a token per wave.  Only a
+      // pivot whose fp32 score is within 2*tau of the token's fp32 aggregate can hold the
+      // exact minimum (maximum): s64_k >= s32_k - tau > a32 + tau >= s64 of the fp32 argmin for
+      // every other pivot k.  Usually that leaves one or two of the P cosines to compute.
+      for (int u = wave; u < nband; u += 16) {
+        const int j = band_j[u];
+        const unsigned char* xrow = Xb + (long)j * rowbytes;
+        const float none = agg == kAggMin ? INFINITY : -INFINITY;
+        const float s32 = lane < P ? Sb[(long)lane * n + j] + 0.0f : none;  // lane i: pivot i
+        const float a32 = agg == kAggMin ? wave_min(s32) : wave_max(s32);
+        const bool near = lane < P && (agg == kAggMin ? s32 <= a32 + two_tau : s32 >= a32 - two_tau);
+        unsigned long long todo = __ballot(near);
+        double a = agg == kAggMin ? INFINITY : -INFINITY;
+        while (todo != 0ull) {
+          const int i = __ffsll((long long)todo) - 1;
+          todo &= todo - 1ull;
+          const double s = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv), xrow, g.D, lane);
+          a = agg == kAggMin ? fmin(a, s) : fmax(a, s);
         }
-        __syncthreads();
-        for (int u = tid; u < nband; u += 1024) {
-          double a = sh.pair[u * P];
-          for (int i = 1; i < P; ++i)
-            a = agg == kAggMin ? fmin(a, sh.pair[u * P + i]) : fmax(a, sh.pair[u * P + i]);
-          band_v[u] = a;
-        }
-      } else {
-        for (int u = wave; u < nband; u += 16) {  // a large band: one token per wave
-          const unsigned char* xrow = Xb + (long)band_j[u] * rowbytes;
-          double a = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, 0, piv), xrow, g.D, lane);
-          for (int i = 1; i < P; ++i) {
-            const double s =
-                row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv), xrow, g.D, lane);
-            a = agg == kAggMin ? fmin(a, s) : fmax(a, s);
-          }
-          if (lane == 0) band_v[u] = a;
-        }
+        if (lane == 0) band_v[u] = a;
       }
       __syncthreads();
       for (int u = tid; u < nband; u += 1024) {
