@@ -64,19 +64,37 @@ __global__ __launch_bounds__(1024) void k_keep_single(
   if (m > 0) {
     // aggregate of every token; pivots get 2 (above any cosine), so they sort last
     const float* Sb = S + (long)P * sm.row0;
+    // Latency-bound (a few workgroups on the whole chip): 4 slots x 8 pivots = 32 independent
+    // loads per batch.  Indices are clamped instead of predicated so that the loads of a
+    // batch issue together; re-reading an element does not change a minimum or maximum.
     float v[kSelPerThread];
+    const float none = agg == kAggMin ? INFINITY : -INFINITY;
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) v[e] = none;
+    for (int i0 = 0; i0 < P; i0 += 8) {
+#pragma unroll
+      for (int e0 = 0; e0 < kSelPerThread; e0 += 4) {
+        if (e0 * 1024 < n) {
+          float s[4][8];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int j = tid + (e0 + e) * 1024;
+            const float* col = Sb + (j < n ? j : n - 1);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) s[e][q] = col[(long)(i0 + q < P ? i0 + q : P - 1) * n];
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+              v[e0 + e] = agg == kAggMin ? fminf(v[e0 + e], s[e][q] + 0.0f) : fmaxf(v[e0 + e], s[e][q] + 0.0f);
+        }
+      }
+    }
 #pragma unroll
     for (int e = 0; e < kSelPerThread; ++e) {
       const int j = tid + e * 1024;
-      float a = 2.0f;
-      if (e * 1024 < n && j < n && !((sh.R[j >> 5] >> (j & 31)) & 1u)) {
-        a = Sb[j] + 0.0f;
-        for (int i = 1; i < P; ++i) {
-          const float s = Sb[(long)i * n + j] + 0.0f;
-          a = agg == kAggMin ? fminf(a, s) : fmaxf(a, s);
-        }
-      }
-      v[e] = a;
+      if (!(e * 1024 < n && j < n) || ((sh.R[j >> 5] >> (j & 31)) & 1u)) v[e] = 2.0f;
     }
     const int want = m + 1 < n ? m + 1 : n;
     int c = collect_sorted<1024, true>(v, n, want, -INFINITY, tid, sh.sel);
