@@ -296,6 +296,9 @@ def main():
     torch.cuda.synchronize()
     stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
                 for s in range(6)]
+    # one call from its first to its last event: median and minimum over the timed steps
+    call_us = sorted(evs.ms(7 * i, 7 * i + 6) * 1e3 for i in range(args.steps))
+    call_us = {"median": round(call_us[len(call_us) // 2], 2), "min": round(call_us[0], 2)}
     evs.close()
     dom = max(range(6), key=lambda s: stage_ms[s])
     # algorithmic bytes of one launch of each streaming kernel
@@ -420,6 +423,7 @@ def main():
         "whole_path_counter_GBps": (
             None if not headline or measured_traffic("", args.config) is None else
             round(measured_traffic("", args.config) / (ms_per_step * 1e-3) / 1e9, 1)),
+        "call_us_by_events": call_us,
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "concurrent_streams": concurrent,
         "graph_replay": graphed,
