@@ -287,6 +287,20 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = total_N * args.steps / wall
 
+    # spread of the step time: ten further groups of steps, each timed like the region above
+    per = max(1, args.steps // 10)
+    groups = []
+    for gi in range(10):
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for i in range(per):
+            step(args.warmup + gi * per + i)
+        torch.cuda.synchronize()
+        groups.append((time.perf_counter() - tg) * 1e3 / per)
+    groups.sort()
+    spread = {"median": round(groups[5], 5), "min": round(groups[0], 5), "max": round(groups[-1], 5),
+              "groups": 10, "steps_per_group": per}
+
     # per-kernel durations: the same steps again, with HIP events between the kernels
     evs = HipEvents(7 * args.steps)
     for i in range(args.steps):
@@ -296,9 +310,6 @@ def main():
     torch.cuda.synchronize()
     stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
                 for s in range(6)]
-    # one call from its first to its last event: median and minimum over the timed steps
-    call_us = sorted(evs.ms(7 * i, 7 * i + 6) * 1e3 for i in range(args.steps))
-    call_us = {"median": round(call_us[len(call_us) // 2], 2), "min": round(call_us[0], 2)}
     evs.close()
     dom = max(range(6), key=lambda s: stage_ms[s])
     # algorithmic bytes of one launch of each streaming kernel
@@ -423,7 +434,7 @@ def main():
         "whole_path_counter_GBps": (
             None if not headline or measured_traffic("", args.config) is None else
             round(measured_traffic("", args.config) / (ms_per_step * 1e-3) / 1e9, 1)),
-        "call_us_by_events": call_us,
+        "ms_per_step_spread": spread,
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
         "concurrent_streams": concurrent,
         "graph_replay": graphed,
