@@ -8,8 +8,8 @@
 // and max are 1-Lipschitz), so the scheme of the staged kernel applies to the single
 // decision: if the last aggregate taken and the first refused differ by more than
 // 2*tau the fp32 order stands; otherwise every token within 2*tau of the boundary gets
-// its P cosines recomputed in fp64 from the rows and the band is ranked on (fp64
-// aggregate, index).
+// its aggregate recomputed in fp64 from the rows (only the cosines of the pivots that can
+// hold it) and the band is ranked on (fp64 aggregate, index).
 #pragma once
 #include "common.hpp"
 #include "k_select.hpp"
