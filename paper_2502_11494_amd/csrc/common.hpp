@@ -14,6 +14,21 @@ constexpr int kMaxP = 64;        // pivots per sample
 constexpr int kMaxN = 16384;     // tokens per sample
 
 enum { kF32 = 0, kBF16 = 1 };
+
+// The hardware deals the workgroups of a launch to the chip's 8 accelerator dies (XCDs, each
+// with its own L2) round-robin by workgroup id.  For a streaming kernel whose block id
+// selects a contiguous range of rows, this permutation of the ids gives every die one
+// contiguous eighth of the rows instead of every eighth range (measured on the batches of
+// 0.26-1.7 GB: -3..5 % on the norm and score passes, -3 % on the gather).  The grid must
+// be a multiple of 8 blocks (round_up8); ids past the kernel's work fall out at its own
+// bounds check.
+constexpr int kXcds = 8;
+#ifdef __HIPCC__
+__device__ __forceinline__ long xcd_contiguous(unsigned bid, unsigned nblocks) {
+  return (long)(bid % kXcds) * (nblocks / kXcds) + bid / kXcds;
+}
+#endif
+inline long round_up8(long n) { return (n + kXcds - 1) / kXcds * kXcds; }
 enum { kMaxL1 = 0, kMinL1 = 1, kGiven = 2 };
 
 // Shape of one call, passed to every kernel by value.

@@ -202,7 +202,7 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   constexpr int ROWS = 1;  // one row per wave measured best (more, shorter-lived waves)
   const int rows = p.g.total_N;
   if (rows == 0) return DART_OK;
-  const int blocks = (rows + 4 * ROWS - 1) / (4 * ROWS);
+  const int blocks = (int)round_up8((rows + 4 * ROWS - 1) / (4 * ROWS));
   // The 256 MB memory-side cache serves part of the score kernel's second pass if this
   // pass leaves the rows there: measured -12% on that kernel for +8% on this one at 189
   // MB (a net gain), no net gain at 264 MB, a loss for matrices that cannot fit.
@@ -291,7 +291,8 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
                          pl2, S, l2sq);                                                          \
     } else {                                                                                     \
       double* part = nullptr;                                                                    \
-      DART_SCORES_PICK(NB, CH, W, 1, grid, part);                                                \
+      const dim3 grid8((unsigned)round_up8(p.tiles_bound));                                      \
+      DART_SCORES_PICK(NB, CH, W, 1, grid8, part);                                                \
     }                                                                                            \
   } while (0)
   // (TAIL, XN) variants of one shape
@@ -362,7 +363,7 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
 dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, const int* keep,
                           void* Y, int64_t* pos_out, hipStream_t st) {
   if (p.keep_rows_bound == 0) return DART_OK;
-  const int blocks = (int)((p.keep_rows_bound + 3) / 4);
+  const int blocks = (int)round_up8((p.keep_rows_bound + 3) / 4);
   hipLaunchKernelGGL(k_gather, dim3(blocks), dim3(256), 0, st, p.g, p.esz, X,
                      reinterpret_cast<const long long*>(pos), keep, Y,
                      reinterpret_cast<long long*>(pos_out));
@@ -575,7 +576,7 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
       ops.src_ld[i] = t.src_ld_bytes;
       ops.dst_ld[i] = t.dst_ld_bytes;
     }
-    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)((rows_bound + 3) / 4), cnt), dim3(256), 0,
+    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)round_up8((rows_bound + 3) / 4), cnt), dim3(256), 0,
                        st, ops, n_rows, row_map);
     DART_LAUNCH_CHECK();
   }

@@ -115,7 +115,8 @@ __global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restri
   }
 }
 
-// Compaction: one wave per retained row.  grid: ceil(rows_bound / 4) blocks of 256.
+// Compaction: one wave per retained row.  grid: ceil(rows_bound / 4) blocks of 256, rounded up
+// to a multiple of 8 (xcd_contiguous).
 // Y rows are packed (stride D); copies are 16 bytes per lane, 1 KiB per wave access.
 // The rows are read once: streaming (non-temporal) loads measured 20 % faster on the
 // largest batch than ordinary ones; streaming stores did not help.
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256) void k_gather(Geo g, int esz, const void* __re
                                                 void* __restrict__ Y,
                                                 long long* __restrict__ pos_out) {
   const int lane = threadIdx.x & 63;
-  const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long r = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
   int b;
   if (g.cu == nullptr) {
     if (r >= (long)g.B * g.K) return;
@@ -256,11 +257,13 @@ struct SeqOps {
 };
 
 // dst row r = src row row_map[r] for every tensor of ops.  One wave per (row, tensor):
-// grid (ceil(rows_bound / 4), tensors) blocks of 256; 16 bytes per lane, 1 KiB per access.
+// grid (ceil(rows_bound / 4) rounded up to a multiple of 8, tensors) blocks of 256 (with a
+// multiple of 8 in x the die of a block depends on its x only: xcd_contiguous); 16 bytes per
+// lane, 1 KiB per access.
 __global__ __launch_bounds__(256) void k_gather_rows(SeqOps ops, const int* __restrict__ n_rows,
                                                      const int* __restrict__ row_map) {
   const int lane = threadIdx.x & 63, o = blockIdx.y;
-  const long r = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long r = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + (threadIdx.x >> 6);
   if (r >= *n_rows) return;
   const long src = row_map[r];
   const u32x4* in = reinterpret_cast<const u32x4*>(ops.src[o] + src * ops.src_ld[o]);

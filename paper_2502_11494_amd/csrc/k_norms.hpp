@@ -44,7 +44,8 @@ inline double l1_rel_bound(int dtype, int Dc) {
   return (double)(tree + chain + 6 + 1) * 5.9604644775390625e-08;
 }
 
-// grid: ceil(rows / (4 * ROWS)) blocks of 256 threads; wave w of the grid owns
+// grid: ceil(rows / (4 * ROWS)) blocks of 256 threads, rounded up to a multiple of 8; wave w
+// of the grid (after xcd_contiguous) owns
 // rows [w*ROWS, (w+1)*ROWS).  Per row, lane l reads the pieces l, l+64, ... so a
 // wave's loads are 1 KiB contiguous; 8*ROWS loads are in flight per lane.
 // KEEP: ordinary loads, which leave the rows in the memory-side cache for the score
@@ -62,7 +63,9 @@ __global__ __launch_bounds__(256) void k_row_l1(const void* __restrict__ C, int 
                                                 int rows, float* __restrict__ l1, Geo g,
                                                 double* __restrict__ l2sq = nullptr) {
   const int lane = threadIdx.x & 63;
-  const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  // (ordinary loads: the plain order measured faster; streaming loads: a die per eighth)
+  const long blk = KEEP ? (long)blockIdx.x : xcd_contiguous(blockIdx.x, gridDim.x);
+  const long wave = blk * 4 + (threadIdx.x >> 6);
   const int esz = DT == kBF16 ? 2 : 4;
   const int pieces = Dc * esz / 16;
   const long rowbytes = ldc * esz;

@@ -147,7 +147,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* _
   __shared__ __align__(16) ScoreShared<NB, CH, WAVES> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
-  const int tile = SPLIT == 1 ? blockIdx.x : blockIdx.x / SPLIT;
+  // (whole-row tiles: a die per contiguous eighth of the tiles; the grid is a multiple of 8)
+  const int tile = SPLIT == 1 ? (int)xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x / SPLIT;
   const int slice = SPLIT == 1 ? 0 : blockIdx.x - tile * SPLIT;
   if (!locate_tile(g, tile, b, tl)) return;
   const Sample sm = sample_of(g, b);
