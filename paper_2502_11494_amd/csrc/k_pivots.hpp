@@ -48,19 +48,19 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
     int j = tid + e * kSelThreads;
     v[e] = (e * kSelThreads < n && j < n) ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
   }
-  float left_min;
-  int c = collect_sorted(v, n, P, -INFINITY, tid, sh.sel, &left_min);
-  // every token with value <= thr may belong to the exact top P
-  float vP = mono_inv((uint32_t)(sh.sel.buf[P - 1] >> 32));
-  float thr = vP + 2.5f * tau * fabsf(vP);
+  // Candidates: every token that may belong to the exact top P.  With vsel >= the P-th lowest
+  // fp32 value, {v <= vsel + 2.5 tau |vsel|} holds every token within the norm pass's error of
+  // the P-th best: usually P and a handful more.  They are ranked in fp64 below, so neither
+  // their order nor the exact P-th value is needed here.
+  const float vsel = rank_upper_bound<THREADS>(v, n, P, tid, sh.sel);
+  const float thr = vsel + 2.5f * tau * fabsf(vsel);
   if (tid == 0) sh.nU = 0;
   __syncthreads();
-  if (left_min <= thr) c = collect_sorted(v, n, P, thr, tid, sh.sel);  // a rival was left out
-  // the candidates are a prefix of the sorted list: its end is seen by exactly one thread
-  for (int t = tid; t < c; t += kSelThreads) {
-    const bool in = mono_inv((uint32_t)(sh.sel.buf[t] >> 32)) <= thr;
-    const bool next_in = t + 1 < c && mono_inv((uint32_t)(sh.sel.buf[t + 1] >> 32)) <= thr;
-    if (in && !next_in) sh.nU = t + 1;
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e) {
+    const int j = tid + e * kSelThreads;
+    if (e * kSelThreads < n && j < n && v[e] <= thr)
+      sh.sel.buf[atomicAdd(&sh.nU, 1)] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
   }
   __syncthreads();
   const int nU = sh.nU;  // 0 only if the norms are not numbers: then no pivot is written

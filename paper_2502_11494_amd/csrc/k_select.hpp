@@ -46,6 +46,85 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
   return s;
 }
 
+// An upper bound of the want-th lowest of the n values that is itself one of the values: the
+// largest value of the histogram buckets up to the one (d*) that holds the want-th lowest.
+// v[e] belongs to index tid + e*THREADS; the same result on every thread.  For callers that
+// need a superset of the `want` lowest, not their order (five barriers, no sort).
+template <int THREADS>
+__device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread], int n, int want,
+                                                  int tid, SelectShared<THREADS>& sh) {
+  constexpr int kSelWaves = THREADS / kWave;
+  constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
+  const int lane = tid & 63, w = tid >> 6;
+  const int ne = __builtin_amdgcn_readfirstlane((n + THREADS - 1) / THREADS);
+  float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e)
+    if (e < ne && tid + e * THREADS < n) {
+      lo = fminf(lo, v[e]);
+      hi = fmaxf(hi, v[e]);
+    }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  __syncthreads();
+  if (lane == 0) {
+    sh.redf[2 * w] = lo;
+    sh.redf[2 * w + 1] = hi;
+  }
+#pragma unroll
+  for (int q = 0; q < kSelBucketsPerThread; ++q) sh.hist[tid + q * THREADS] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelWaves; ++i) {
+    lo = fminf(lo, sh.redf[2 * i]);
+    hi = fmaxf(hi, sh.redf[2 * i + 1]);
+  }
+  const float range = hi - lo;
+  const float scale = range > 0.f ? (float)kSelBuckets / range : 0.f;
+  auto bucket = [&](float x) -> int {
+    float f = (x - lo) * scale;  // non-finite input lands in a valid bucket too
+    int d = f >= (float)(kSelBuckets - 1) ? kSelBuckets - 1 : (int)f;
+    d = d < 0 ? 0 : d;
+    return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
+  };
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e)
+    if (e < ne && tid + e * THREADS < n) atomicAdd(&sh.hist[bucket(v[e])], 1);
+  __syncthreads();
+  int h[kSelBucketsPerThread], mine = 0;
+#pragma unroll
+  for (int q = 0; q < kSelBucketsPerThread; ++q) {
+    h[q] = sh.hist[tid * kSelBucketsPerThread + q];
+    mine += h[q];
+  }
+  int run = wave_excl_scan(mine, lane);
+  if (lane == 63) sh.redi[w] = run + mine;
+  if (tid == 0) sh.dstar = kSelBuckets - 1;  // (kept if no count crosses: values that are not numbers)
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelWaves; ++i)
+    if (i < w) run += sh.redi[i];
+  const int target = want < n ? want : n;
+#pragma unroll
+  for (int q = 0; q < kSelBucketsPerThread; ++q) {
+    const int before = run;
+    run += h[q];
+    if (before < target && run >= target) sh.dstar = tid * kSelBucketsPerThread + q;
+  }
+  __syncthreads();
+  const int dstar = sh.dstar;
+  float top = -INFINITY;  // largest value of the buckets <= d*
+#pragma unroll
+  for (int e = 0; e < kSelPerThread; ++e)
+    if (e < ne && tid + e * THREADS < n && bucket(v[e]) <= dstar) top = fmaxf(top, v[e]);
+  top = wave_max(top);
+  if (lane == 0) sh.redg[w] = top;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelWaves; ++i) top = fmaxf(top, sh.redg[i]);
+  return top;
+}
+
 // v[e] belongs to index tid + e*THREADS (n <= 16*THREADS); entries with index >= n are ignored.
 // Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
