@@ -46,13 +46,25 @@ __device__ __forceinline__ int block_sum(int v, int tid, int* red) {
   return s;
 }
 
-// An upper bound of the want-th lowest of the n values that is itself one of the values: the
-// largest value of the histogram buckets up to the one (d*) that holds the want-th lowest.
-// v[e] belongs to index tid + e*THREADS; the same result on every thread.  For callers that
-// need a superset of the `want` lowest, not their order (five barriers, no sort).
+// Where the want-th lowest of n values sits in a value-linear histogram of kSelBuckets buckets
+// between the block's minimum and maximum: its bucket d*, and how many values lie in the
+// buckets below d*.  For callers that need a set of lowest values rather than a sorted list:
+// the buckets below d* belong to it outright and only bucket d* needs a closer look.
+struct BucketSplit {
+  float lo, scale;  // bucket(x) = clamp((x - lo) * scale)
+  int dstar, below;
+  __device__ __forceinline__ int bucket(float x) const {
+    float f = (x - lo) * scale;  // non-finite input lands in a valid bucket too
+    int d = f >= (float)(kSelBuckets - 1) ? kSelBuckets - 1 : (int)f;
+    d = d < 0 ? 0 : d;
+    return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
+  }
+};
+
+// v[e] belongs to index tid + e*THREADS; the same result on every thread (four barriers).
 template <int THREADS>
-__device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread], int n, int want,
-                                                  int tid, SelectShared<THREADS>& sh) {
+__device__ __forceinline__ BucketSplit bucket_split(const float (&v)[kSelPerThread], int n, int want,
+                                                    int tid, SelectShared<THREADS>& sh) {
   constexpr int kSelWaves = THREADS / kWave;
   constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
   const int lane = tid & 63, w = tid >> 6;
@@ -80,16 +92,12 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
     hi = fmaxf(hi, sh.redf[2 * i + 1]);
   }
   const float range = hi - lo;
-  const float scale = range > 0.f ? (float)kSelBuckets / range : 0.f;
-  auto bucket = [&](float x) -> int {
-    float f = (x - lo) * scale;  // non-finite input lands in a valid bucket too
-    int d = f >= (float)(kSelBuckets - 1) ? kSelBuckets - 1 : (int)f;
-    d = d < 0 ? 0 : d;
-    return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
-  };
+  BucketSplit bs;
+  bs.lo = lo;
+  bs.scale = range > 0.f ? (float)kSelBuckets / range : 0.f;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e)
-    if (e < ne && tid + e * THREADS < n) atomicAdd(&sh.hist[bucket(v[e])], 1);
+    if (e < ne && tid + e * THREADS < n) atomicAdd(&sh.hist[bs.bucket(v[e])], 1);
   __syncthreads();
   int h[kSelBucketsPerThread], mine = 0;
 #pragma unroll
@@ -99,7 +107,10 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
   }
   int run = wave_excl_scan(mine, lane);
   if (lane == 63) sh.redi[w] = run + mine;
-  if (tid == 0) sh.dstar = kSelBuckets - 1;  // (kept if no count crosses: values that are not numbers)
+  if (tid == 0) {  // (kept if no count crosses the target: values that are not numbers)
+    sh.dstar = kSelBuckets - 1;
+    sh.cstar = 0;
+  }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < kSelWaves; ++i)
@@ -109,14 +120,31 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
   for (int q = 0; q < kSelBucketsPerThread; ++q) {
     const int before = run;
     run += h[q];
-    if (before < target && run >= target) sh.dstar = tid * kSelBucketsPerThread + q;
+    if (before < target && run >= target) {
+      sh.dstar = tid * kSelBucketsPerThread + q;
+      sh.cstar = before;
+    }
   }
   __syncthreads();
-  const int dstar = sh.dstar;
+  bs.dstar = sh.dstar;
+  bs.below = sh.cstar;
+  return bs;
+}
+
+// An upper bound of the want-th lowest of the n values that is itself one of the values: the
+// largest value of the buckets up to d*.  For callers that need a superset of the `want`
+// lowest, not their order (five barriers, no sort).
+template <int THREADS>
+__device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread], int n, int want,
+                                                  int tid, SelectShared<THREADS>& sh) {
+  constexpr int kSelWaves = THREADS / kWave;
+  const int lane = tid & 63, w = tid >> 6;
+  const BucketSplit bs = bucket_split<THREADS>(v, n, want, tid, sh);
   float top = -INFINITY;  // largest value of the buckets <= d*
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e)
-    if (e < ne && tid + e * THREADS < n && bucket(v[e]) <= dstar) top = fmaxf(top, v[e]);
+    if (e * THREADS < n && tid + e * THREADS < n && bs.bucket(v[e]) <= bs.dstar)
+      top = fmaxf(top, v[e]);
   top = wave_max(top);
   if (lane == 0) sh.redg[w] = top;
   __syncthreads();

@@ -96,37 +96,75 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       const int j = tid + e * 1024;
       if (!(e * 1024 < n && j < n) || ((sh.R[j >> 5] >> (j & 31)) & 1u)) v[e] = 2.0f;
     }
+    // Only the set of the m lowest is needed, not their order: the histogram buckets below
+    // the one (d*) that holds the (m+1)-th lowest aggregate belong to it outright; bucket d*
+    // alone is put in order, and its r-th and (r+1)-th keys are the last taken (fa) and the
+    // first refused (fb).
     const int want = m + 1 < n ? m + 1 : n;
-    int c = collect_sorted<1024, true>(v, n, want, -INFINITY, tid, sh.sel);
-    const float fa = mono_inv((uint32_t)(sh.sel.buf[m - 1] >> 32));
-    float fb = m < c ? mono_inv((uint32_t)(sh.sel.buf[m] >> 32)) : INFINITY;
+    const BucketSplit bs = bucket_split<1024>(v, n, want, tid, sh.sel);
+    if (tid == 0) {
+      sh.sel.count = 0;
+      sh.below = 0;
+      sh.nband = 0;
+    }
+    __syncthreads();
+    float max_below = -INFINITY;  // largest aggregate of the buckets below d* (fa if r == 0)
+#pragma unroll
+    for (int e = 0; e < kSelPerThread; ++e) {
+      const int j = tid + e * 1024;
+      if (e * 1024 < n && j < n) {
+        const int d = bs.bucket(v[e]);
+        if (d == bs.dstar)
+          sh.sel.buf[atomicAdd(&sh.sel.count, 1)] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
+        else if (d < bs.dstar)
+          max_below = fmaxf(max_below, v[e]);
+      }
+    }
+    max_below = wave_max(max_below);
+    if (lane == 0) sh.sel.redg[wave] = max_below;
+    __syncthreads();
+    const int hs = __builtin_amdgcn_readfirstlane(sh.sel.count);  // keys of bucket d*
+#pragma unroll
+    for (int i = 0; i < 16; ++i) max_below = fmaxf(max_below, sh.sel.redg[i]);
+    const int np = next_pow2(hs < kWave ? kWave : hs);
+    for (int t = hs + tid; t < np; t += 1024) sh.sel.buf[t] = ~0ull;
+    __syncthreads();
+    block_bitonic_sort<1024>(sh.sel.buf, np, tid);
+    const int r = m - bs.below;  // taken from bucket d*: 0 <= r <= hs
+    const float fa = r > 0 ? mono_inv((uint32_t)(sh.sel.buf[r - 1] >> 32)) : max_below;
+    float fb = r < hs ? mono_inv((uint32_t)(sh.sel.buf[r] >> 32)) : INFINITY;
     if (fb >= 2.0f) fb = INFINITY;  // only pivots are left
     const bool certain = Xb == nullptr || fb - fa > two_tau;
-    __syncthreads();
     if (certain) {
-      for (int t = tid; t < m; t += 1024) {
+#pragma unroll
+      for (int e = 0; e < kSelPerThread; ++e) {
+        const int j = tid + e * 1024;
+        if (e * 1024 < n && j < n && bs.bucket(v[e]) < bs.dstar) atomicOr(&sh.R[j >> 5], 1u << (j & 31));
+      }
+      for (int t = tid; t < r; t += 1024) {
         const uint32_t j = (uint32_t)sh.sel.buf[t];
         atomicOr(&sh.R[j >> 5], 1u << (j & 31));
       }
     } else {
-      // every token whose aggregate can still be on either side of the boundary
+      // every token whose aggregate can still be on either side of the boundary goes to the
+      // band; those certainly below it are taken
       const float lo = fa - two_tau, hi = fb + two_tau;
-      c = collect_sorted<1024, true>(v, n, want, hi, tid, sh.sel);
-      if (tid == 0) {
-        sh.below = 0;
-        sh.nband = 0;
-      }
-      __syncthreads();
-      for (int t = tid; t < c; t += 1024) {
-        const float a = mono_inv((uint32_t)(sh.sel.buf[t] >> 32));
-        const uint32_t j = (uint32_t)sh.sel.buf[t];
-        if (a < lo) {  // certainly among the m lowest
-          atomicOr(&sh.R[j >> 5], 1u << (j & 31));
-          atomicAdd(&sh.below, 1);
-        } else if (a <= hi) {
-          band_j[atomicAdd(&sh.nband, 1)] = (int)j;
+      int taken = 0;
+#pragma unroll
+      for (int e = 0; e < kSelPerThread; ++e) {
+        const int j = tid + e * 1024;
+        if (e * 1024 < n && j < n) {
+          const float a = v[e];
+          if (a < lo) {  // certainly among the m lowest
+            atomicOr(&sh.R[j >> 5], 1u << (j & 31));
+            ++taken;
+          } else if (a <= hi) {
+            band_j[atomicAdd(&sh.nband, 1)] = j;
+          }
         }
       }
+      taken = wave_sum(taken);
+      if (lane == 0 && taken > 0) atomicAdd(&sh.below, taken);
       __syncthreads();
       const int nband = sh.nband, need = m - sh.below;
       // fp64 aggregate of every band token, recomputed from the rows: a token per wave.  Only a
