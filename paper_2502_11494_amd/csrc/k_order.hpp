@@ -33,7 +33,7 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
     v[e] = (e * kSelThreads < n && j < n) ? row[j] + 0.0f : 0.f;
   }
   int first = 0;  // keys of the first sorted run (all of them unless the sort was split)
-  collect_sorted<THREADS, true>(v, n, want, -INFINITY, tid, sh, nullptr, &first);
+  collect_sorted<THREADS, true>(v, n, want, tid, sh, &first);
   // offset of this stage's list = sum of the earlier stages' lengths: lane s of every wave
   // computes stage s's length, a wave scan adds them up (no loop over the stages)
   const int len_v = (tid & 63) < g.P ? sp.stage_len(n, tid & 63) : 0;

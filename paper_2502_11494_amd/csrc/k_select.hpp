@@ -62,6 +62,8 @@ struct BucketSplit {
 };
 
 // v[e] belongs to index tid + e*THREADS; the same result on every thread (four barriers).
+// (collect_sorted below repeats these steps because it goes on to use every thread's own
+// bucket counts.)
 template <int THREADS>
 __device__ __forceinline__ BucketSplit bucket_split(const float (&v)[kSelPerThread], int n, int want,
                                                     int tid, SelectShared<THREADS>& sh) {
@@ -154,10 +156,9 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
 }
 
 // v[e] belongs to index tid + e*THREADS (n <= 16*THREADS); entries with index >= n are ignored.
-// Compacts every entry whose bucket is <= max(d*, bucket(incl_upto)) and sorts;
+// Compacts every entry whose bucket is <= d* and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
-// left_min receives the smallest value NOT compacted (+inf if none is left).
-// part2 (optional, only with incl_upto == -inf): when more than THREADS keys are compacted
+// part2 (optional): when more than THREADS keys are compacted
 // and a bucket boundary cuts them into two runs of at most THREADS keys each, the runs are
 // sorted separately (two short sorts instead of one of twice the size; the histogram
 // already orders them by value): the first *part2 keys are at buf[0..), the others at
@@ -166,8 +167,8 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
 // a few keys leave it off and keep the shorter code.
 template <int THREADS, bool COUNTING = false>
 __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
-                                              float incl_upto, int tid, SelectShared<THREADS>& sh,
-                                              float* left_min = nullptr, int* part2 = nullptr) {
+                                              int tid, SelectShared<THREADS>& sh,
+                                              int* part2 = nullptr) {
   constexpr int kSelThreads = THREADS;
   constexpr int kSelWaves = THREADS / kWave;
   constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
@@ -249,10 +250,6 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     // list to the network below.
     constexpr int kCap = kSelThreads * kSelPerThread / 2;  // keys that fit twice in buf
     int dl = sh.dstar;
-    if (incl_upto > -INFINITY) {
-      const int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
-      dl = d2 > dl ? d2 : dl;
-    }
     dl = dl < 0 ? 0 : (dl < kSelBuckets ? dl : kSelBuckets - 1);  // (want >= 1 makes it valid anyway)
     {
       int through = run;  // count up to and including the thread's last bucket
@@ -275,17 +272,10 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
 #pragma unroll
       for (int q = 0; q < kSelBucketsPerThread; ++q) sh.hist[tid + q * kSelThreads] = 0;
       __syncthreads();
-      float rest = INFINITY;
 #pragma unroll
       for (int e = 0; e < kSelPerThread; ++e)
-        if (e < ne && tid + e * kSelThreads < n) {
-          if (bucket(v[e]) <= dl) atomicAdd(&sh.hist[fine(v[e])], 1);
-          else rest = fminf(rest, v[e]);
-        }
-      if (left_min) {
-        rest = wave_min(rest);
-        if (lane == 0) sh.redg[w] = rest;
-      }
+        if (e < ne && tid + e * kSelThreads < n && bucket(v[e]) <= dl)
+          atomicAdd(&sh.hist[fine(v[e])], 1);
       __syncthreads();
       int hh[kSelBucketsPerThread], mine2 = 0, big = 0;
 #pragma unroll
@@ -298,11 +288,6 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
       if (lane == 63) sh.redi[w] = run2 + mine2;
       big = __syncthreads_or(big);
       if (!big) {
-        if (left_min) {
-#pragma unroll
-          for (int i = 0; i < kSelWaves; ++i) rest = fminf(rest, sh.redg[i]);
-          *left_min = rest;
-        }
 #pragma unroll
         for (int i = 0; i < kSelWaves; ++i)
           if (i < w) run2 += sh.redi[i];
@@ -352,11 +337,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     }
     __syncthreads();
   }
-  int dlim = sh.dstar;
-  if (incl_upto > -INFINITY) {
-    int d2 = incl_upto >= hi ? kSelBuckets - 1 : bucket(incl_upto);
-    dlim = d2 > dlim ? d2 : dlim;
-  }
+  const int dlim = sh.dstar;
   if (part2) {
     const int dmid = sh.dmid, cmid = sh.cmid, cstar = sh.cstar;
     if (cstar > kSelThreads && dmid >= 0 && dmid < dlim && cmid > 0 && cstar - cmid <= kSelThreads) {
@@ -385,29 +366,15 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
       return cstar;
     }
   }
-  float rest = INFINITY;
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     const int j = tid + e * kSelThreads;
-    if (e < ne && j < n) {
-      if (bucket(v[e]) <= dlim) {
-        const int slot = atomicAdd(&sh.count, 1);
-        sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
-      } else {
-        rest = fminf(rest, v[e]);
-      }
+    if (e < ne && j < n && bucket(v[e]) <= dlim) {
+      const int slot = atomicAdd(&sh.count, 1);
+      sh.buf[slot] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
     }
   }
-  if (left_min) {
-    rest = wave_min(rest);
-    if (lane == 0) sh.redg[w] = rest;
-  }
   __syncthreads();
-  if (left_min) {
-#pragma unroll
-    for (int i = 0; i < kSelWaves; ++i) rest = fminf(rest, sh.redg[i]);
-    *left_min = rest;
-  }
   const int c = __builtin_amdgcn_readfirstlane(sh.count);
   const int np = next_pow2(c < kWave ? kWave : c);
   for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
