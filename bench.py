@@ -220,10 +220,8 @@ def main():
     from paper_2502_11494_amd import workloads as W
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    from paper_2502_11494_amd import binding
-    if not os.path.exists(binding.LIB):  # load what is built; build only if nothing is
-        from paper_2502_11494_amd.build import build_hip
-        build_hip()
+    from paper_2502_11494_amd.build import ensure_built
+    ensure_built()  # loads what is built; compiles only a missing or stale library
     if args.sequences:
         return bench_sequences(args)
     torch.cuda.set_device(0)

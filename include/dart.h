@@ -42,6 +42,13 @@
  *   keeps zero tokens -- and a flag is raised in the workspace that
  *   dart_device_status reports.
  *   Non-finite input values give unspecified (but memory-safe) results.
+ * Value range.  The fp32 arithmetic of the bf16 path (exact products of two bf16 values,
+ *   32-term sums of them, row sums of |x| and x^2) must neither overflow nor lose bits to
+ *   underflow, or the rounding bound the decisions are certified against does not hold:
+ *   every non-zero element must satisfy 2^-55 <= |x| <= 2^55 (zeros are fine), for either
+ *   dtype.  Inside that range a common power-of-two factor on a sample changes no output
+ *   bit.  Outside it the retained set may differ from the exact one (memory-safe, not
+ *   detected: the library does not scan its input).
  * Determinism.  Same inputs give bit-identical outputs, call after call, and a
  *   row's score depends only on its bytes and the pivot's bytes, not on where
  *   the row sits in the batch.  (Different entry points or pivot modes may take the
@@ -253,12 +260,24 @@ DART_API dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, 
 
 /* Waits for `stream`, then reports DART_ERR_DEVICE if the last call that used
  * `ws` (with this descriptor) skipped a ragged sample or met an invalid given pivot
- * list, DART_OK otherwise. */
+ * list, DART_OK otherwise.  Every entry point that takes `ws` leaves these flags defined:
+ * with DART_PIVOT_GIVEN, dart_reduce, dart_duplication_scores and dart_topk_keep validate the
+ * piv array they read; an entry point that reads no pivots clears the pivot flag. */
 DART_API dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream);
 
 /* The absolute bound on |fp32 score - exact score| that dart_topk_keep and
  * dart_reduce certify decisions against, for this dtype. */
 DART_API double dart_score_tolerance(int32_t dtype);
+
+/* Diagnostic: the raw 32-term sums of the matrix-core instruction the bf16 score path is built
+ * on (v_mfma_f32_16x16x32_bf16 from a zero accumulator).  A, B: DEVICE bf16 [tiles][16][32]
+ * (k contiguous), out: DEVICE float [tiles][16][16], out[t][i][j] = sum_k A[t][i][k] *
+ * B[t][j][k] as the hardware rounds it.  The bound of dart_score_tolerance assumes that this
+ * sum errs by at most 16 * 2^-24 * sum_k |A B| (the instruction's internal rounding is not
+ * documented); the test-suite checks that assumption through this call on the GPU it runs
+ * on.  tiles >= 0; A, B, out 16-byte aligned. */
+DART_API dart_status dart_probe_mfma_dot32(const void* A, const void* B, float* out,
+                                           int32_t tiles, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 DART_API const char* dart_strerror(dart_status status);

@@ -196,8 +196,8 @@ int oracle_retain(const double* S, int64_t N, const int32_t* piv, int P, int K, 
   return n == K ? 0 : -2;
 }
 
-// Step 4 under ONE threshold common to all pivots (a second reading of Eq. 9-10; the
-// introduction speaks of the tokens "with the lowest similarity to the pivots").  With
+// Step 4 under ONE threshold common to all pivots (a second reading of Eq. 9-10: Section 1
+// describes the retained tokens by a single similarity to the pivot set as a whole).  With
 // the same epsilon for every pivot, Eq. (9)-(10) retain token j iff min_i dup(p_i, x_j)
 // <= epsilon (agg = 1); agg = 2 aggregates with max_i instead (a token counts as a
 // duplicate as soon as it duplicates any pivot).  The budget sets the threshold: R =

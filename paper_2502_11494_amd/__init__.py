@@ -7,5 +7,6 @@ from .binding import (DART_BF16, DART_ERR_ALIGN, DART_ERR_BUDGET, DART_ERR_DEVIC
                       DART_SCORE_PER_PIVOT, DartDesc, DartError, DartRowTensor, alloc_workspace,
                       dart_compact_sequences,
                       dart_device_status, dart_duplication_scores, dart_gather_compact,
-                      dart_reduce, dart_reduce_profiled, dart_select_pivots, dart_topk_keep,
+                      dart_probe_mfma_dot32, dart_reduce,
+                      dart_reduce_profiled, dart_select_pivots, dart_topk_keep,
                       dart_workspace_bytes, make_desc, score_tolerance, strerror)

@@ -24,7 +24,7 @@ DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
            "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
-           "dart_reduce_profiled",
+           "dart_reduce_profiled", "dart_probe_mfma_dot32",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -73,9 +73,10 @@ def lib():
         L.dart_reduce.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dart_reduce_profiled.argtypes = L.dart_reduce.argtypes + [C.POINTER(vp)]
         L.dart_device_status.argtypes = [dp, vp, vp]
+        L.dart_probe_mfma_dot32.argtypes = [vp, vp, vp, i32, vp]
         for name in ("dart_select_pivots", "dart_duplication_scores", "dart_topk_keep",
                      "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
-                     "dart_reduce_profiled", "dart_device_status"):
+                     "dart_reduce_profiled", "dart_device_status", "dart_probe_mfma_dot32"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -193,6 +194,12 @@ def dart_reduce(desc, X, Y, keep, ws, *, crit=None, crit_D=0, crit_ld=0, pos=Non
     _check(lib().dart_reduce(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld, _ptr(pos),
                              _ptr(Y), _ptr(pos_out), _ptr(keep), _ptr(cu_keep), _ptr(piv_out),
                              _ptr(S_out), _ptr(ws), ws.numel(), _stream(stream)), "dart_reduce")
+
+
+def dart_probe_mfma_dot32(A, B, out, *, stream=None):
+    """A, B: bf16 [tiles, 16, 32]; out: float32 [tiles, 16, 16] (raw matrix-core sums)."""
+    _check(lib().dart_probe_mfma_dot32(_ptr(A), _ptr(B), _ptr(out), A.shape[0], _stream(stream)),
+           "dart_probe_mfma_dot32")
 
 
 def dart_reduce_profiled(desc, X, Y, keep, ws, events, *, crit=None, crit_D=0, crit_ld=0,

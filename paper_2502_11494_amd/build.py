@@ -1,16 +1,23 @@
 """Builds libdart_hip.so (the C-ABI library of include/dart.h) for gfx950 with hipcc.
 
 Run as `python -m paper_2502_11494_amd.build`.  hipcc cross-compiles, so no GPU
-is needed to build.
+is needed to build.  A stamp file beside the library records the hash of the
+sources it was built from; `ensure_built()` (what the tests, the smoke check and
+the benchmark call) loads an up-to-date library as it is and rebuilds a missing or
+stale one, so a library older than its sources is never measured as if it were new.
 """
 from __future__ import annotations
 
+import glob
+import hashlib
 import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
+INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB = os.path.join(_HERE, "libdart_hip.so")  # the path binding.py loads
+STAMP = LIB + ".sha256"
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-fvisibility=hidden",
@@ -19,6 +26,18 @@ HIPCC_FLAGS = [
     # against silently wrong results of some of their forms)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
+
+
+def source_hash() -> str:
+    """sha256 over the kernel sources, the public header and the compiler flags."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(CSRC, "*"))) + sorted(
+            glob.glob(os.path.join(INCLUDE, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()
 
 
 def build_hip(verbose: bool = False) -> str:
@@ -34,6 +53,24 @@ def build_hip(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err)
+    with open(STAMP, "w") as f:
+        f.write(source_hash() + "\n")
+    return LIB
+
+
+def is_current() -> bool:
+    """True if the library exists and was built from the sources as they are now."""
+    try:
+        with open(STAMP) as f:
+            return os.path.exists(LIB) and f.read().strip() == source_hash()
+    except OSError:
+        return False
+
+
+def ensure_built(verbose: bool = False) -> str:
+    """The library's path; compiles only if it is missing or older than its sources."""
+    if not is_current():
+        build_hip(verbose=verbose)
     return LIB
 
 

@@ -266,6 +266,19 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
   return DART_OK;
 }
 
+// Leaves the pivot flag of dart_device_status defined for a DART_PIVOT_GIVEN descriptor: the
+// list the entry point reads is validated, or the flag is cleared if it reads none.
+dart_status launch_given_status(const Plan& p, const int* piv, void* ws, hipStream_t st) {
+  if (p.g.mode != kGiven) return DART_OK;
+  if (piv)
+    hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
+                       at<int>(ws, p.o_status));
+  else
+    hipLaunchKernelGGL(k_clear_pivot_status, dim3(1), dim3(1), 0, st, at<int>(ws, p.o_status));
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
 dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
@@ -495,6 +508,7 @@ dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const 
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_given_status(p, piv, ws, st));
   DART_TRY(launch_pivot_norms(p, X, piv, 0, nullptr, ws, st));
   return launch_scores(p, X, piv, S, ws, st);
 }
@@ -510,6 +524,7 @@ dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t*
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_given_status(p, piv, ws, st));
   DART_TRY(launch_order(p, S, ws, st));
   return launch_retain(p, S, piv, X, keep, cu_keep, ws, st);
 }
@@ -525,6 +540,7 @@ dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int6
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_given_status(p, nullptr, ws, st));
   return launch_gather(p, X, pos, keep, Y, pos_out, st);
 }
 
@@ -555,6 +571,7 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
+  DART_TRY(launch_given_status(p, nullptr, ws, st));
   // every sequence loses its pruned vision tokens; at most this many rows remain
   const long rows_bound = (long)p.g.x_rows - p.g.total_N + p.keep_rows_bound;
   hipLaunchKernelGGL(k_seq_offsets, dim3(1), dim3(1024), 0, st, p.g, seq_cu, seq_cu_out,
@@ -626,6 +643,19 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   if (p.g.mode != kGiven) flag[1] = 0;
   if (p.g.span == nullptr) flag[2] = 0;
   return (flag[0] | flag[1] | flag[2]) ? DART_ERR_DEVICE : DART_OK;
+}
+
+dart_status dart_probe_mfma_dot32(const void* A, const void* B, float* out, int32_t tiles,
+                                  void* stream) {
+  if (tiles < 0) return DART_ERR_SHAPE;
+  if (tiles == 0) return DART_OK;
+  if (!A || !B || !out) return DART_ERR_NULL;
+  if (misaligned16(A) || misaligned16(B) || misaligned16(out)) return DART_ERR_ALIGN;
+  hipLaunchKernelGGL(k_probe_mfma_dot32, dim3(tiles), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
+                     out);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
 }
 
 double dart_score_tolerance(int32_t dtype) {

@@ -95,6 +95,28 @@ __global__ __launch_bounds__(1024) void k_check_pivots(Geo g, const int* __restr
   if (threadIdx.x == 0) status[1] = bad ? 1 : 0;
 }
 
+// status[1] = 0: for entry points that read no pivot list (one thread).
+__global__ void k_clear_pivot_status(int* __restrict__ status) { status[1] = 0; }
+
+// The raw matrix-core sums the bf16 score kernel is built on, for the test of its rounding
+// bound: tile t of A and B is [16][32] bf16 (k contiguous); out[t][i][j] = sum_k A[i][k] *
+// B[j][k] from a zero accumulator.  grid: tiles blocks of 64.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(64) void k_probe_mfma_dot32(const unsigned char* __restrict__ A,
+                                                        const unsigned char* __restrict__ B,
+                                                        float* __restrict__ out) {
+  const int lane = threadIdx.x;
+  const long tile = blockIdx.x;
+  const long off = tile * (16 * 32 * 2) + (lane & 15) * 64 + (lane >> 4) * 16;
+  const probe_bf16x8 af = *reinterpret_cast<const probe_bf16x8*>(A + off);
+  const probe_bf16x8 bf = *reinterpret_cast<const probe_bf16x8*>(B + off);
+  const probe_f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+  const probe_f32x4 c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bf, zero, 0, 0, 0);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) out[tile * 256 + ((lane >> 4) * 4 + r) * 16 + (lane & 15)] = c[r];
+}
+
 // Squared Euclidean norms of the rows of pivots first..Ppad-1 in fp64 (0 for padding
 // slots).  piv_mark (optional): entry i of a pivot from outside the sample is set to
 // -1 - (its row in the sample's share of E).  grid: B blocks of 256.

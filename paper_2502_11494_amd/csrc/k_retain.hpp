@@ -1,8 +1,8 @@
 // Retained set of Eq. (9)-(10), one workgroup of 16 waves per sample.
 //
 // R starts as the pivots.  Stage i (pivot order) walks pivot i's ascending score
-// list, skips tokens already in R and takes the first quota_i others -- the
-// per-pivot threshold "determined by the reduction ratio".
+// list, skips tokens already in R and takes the first quota_i others: the threshold of
+// Eq. (9) is set per pivot by the reduction ratio, i.e. by that quota.
 //
 // The scores are fp32 with absolute error <= tau, so a stage's outcome is certain
 // only when the last score taken and the first one refused differ by more than

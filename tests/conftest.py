@@ -10,11 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    # load what is built; build only if nothing is (hipcc cross-compiles without a GPU)
-    from paper_2502_11494_amd import binding
-    if not os.path.exists(binding.LIB):
-        from paper_2502_11494_amd import build
-        build.build_hip()
+    # load what is built if it matches the sources; compile a missing or stale library
+    # (hipcc cross-compiles without a GPU)
+    from paper_2502_11494_amd import build
+    build.ensure_built()
 
 
 def _have_gpu() -> bool:

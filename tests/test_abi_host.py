@@ -180,3 +180,4 @@ def test_status_strings():
     assert all(texts) and len(set(texts)) == 9
     assert D.strerror(-99) not in texts
     assert 0 < D.score_tolerance(D.DART_F32) < D.score_tolerance(D.DART_BF16) < 1e-4
+

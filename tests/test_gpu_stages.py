@@ -203,3 +203,79 @@ def test_stage_entry_points_with_pivots_from_outside():
             np.testing.assert_array_equal(keep_h[k0:k0 + w.budget(b)], r.keep)
             assert Y_h[k0:k0 + w.budget(b)].tobytes() == r.Y.tobytes()
             k0 += w.budget(b)
+
+
+def test_matrix_core_sum_stays_inside_the_assumed_rounding_bound():
+    """The certified score bound assumes that one bf16 matrix-core instruction returns the sum
+    of its 32 exact products with an error of at most 16 * 2^-24 * sum|products| (the
+    instruction's internal rounding is not documented).  Checked here on the GPU the tests run
+    on, against exact fp64 sums, for unit-normal, wide-dynamic-range, all-positive, one-huge-
+    term and cancelling inputs (8.4 million sums)."""
+    rng = np.random.default_rng(0xDA31)
+    tiles = 4096
+    worst = {}
+    for mode in ("normal", "wide", "positive", "huge_term", "cancel"):
+        a = rng.standard_normal((tiles, 16, 32))
+        b = rng.standard_normal((tiles, 16, 32))
+        if mode == "wide":
+            a *= np.exp2(rng.integers(-8, 8, a.shape))
+            b *= np.exp2(rng.integers(-8, 8, b.shape))
+        elif mode == "positive":
+            a, b = np.abs(a), np.abs(b)
+        elif mode == "huge_term":
+            a *= 0.01
+            b *= 0.01
+            a[..., 0] = 4096.0
+            b[..., 0] = 4096.0
+        elif mode == "cancel":
+            a[..., 0] = a[..., 1] = 256.0
+            b[..., 0], b[..., 1] = 256.0, -256.0
+        A = W.f32_to_bf16_bits(a.astype(np.float32))
+        B = W.f32_to_bf16_bits(b.astype(np.float32))
+        dev = lambda bits: torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+        out = torch.empty((tiles, 16, 16), dtype=torch.float32, device="cuda")
+        D.dart_probe_mfma_dot32(dev(A), dev(B), out)
+        torch.cuda.synchronize()
+        Af = (A.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        Bf = (B.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        # products of two bf16 values are exact in fp64; sums of 32 of them to ~1e-16 relative
+        exact = np.einsum("tik,tjk->tij", Af, Bf)
+        mags = np.einsum("tik,tjk->tij", np.abs(Af), np.abs(Bf))
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exact)
+        units = err / (mags * 2.0 ** -24)
+        worst[mode] = float(units.max())
+        assert np.all(err <= 16.0 * 2.0 ** -24 * mags), (mode, worst[mode])
+        # the layout the score kernel relies on: out[t][i][j] pairs row i of A with row j of B
+        assert np.all(err <= 1e-3 * mags + 1e-30)
+    print("worst error in units of 2^-24 * sum|products|:", worst, flush=True)
+
+
+def test_stage_entry_points_leave_the_pivot_flag_defined():
+    """With a caller-supplied-pivots descriptor every entry point that takes the workspace
+    leaves the flag dart_device_status reads in a defined state, whatever the workspace held."""
+    w = W.image_batch(B=2, N=200, D=256, P=8, K=40, n_centroids=8)
+    Xd = G.to_device(w)
+    desc = G.desc_of(w, None, mode=D.DART_PIVOT_GIVEN)
+    ws = D.alloc_workspace(desc)
+    rng = np.random.default_rng(2)
+    piv_h = np.stack([rng.permutation(200)[:w.P] for _ in range(w.B)]).astype(np.int32)
+    piv = torch.from_numpy(piv_h).cuda()
+    S = torch.empty(w.P * 400, dtype=torch.float32, device="cuda")
+    keep = torch.empty(w.B * w.K, dtype=torch.int32, device="cuda")
+    Y = torch.empty((w.B * w.K, w.D), dtype=torch.bfloat16, device="cuda")
+    ws.fill_(0xFF)  # stale flags
+    D.dart_duplication_scores(desc, Xd, piv, S, ws)
+    assert D.dart_device_status(desc, ws) == D.DART_OK
+    ws[:256].fill_(0xFF)
+    D.dart_topk_keep(desc, S, piv, keep, ws, X=Xd)
+    assert D.dart_device_status(desc, ws) == D.DART_OK
+    ws[:256].fill_(0xFF)
+    D.dart_gather_compact(desc, Xd, keep, Y, ws)
+    assert D.dart_device_status(desc, ws) == D.DART_OK
+    # a list with a repeated pivot is reported by the entry points that read it
+    bad = piv_h.copy()
+    bad[1, 3] = bad[1, 2]
+    D.dart_duplication_scores(desc, Xd, torch.from_numpy(bad).cuda(), S, ws)
+    assert D.dart_device_status(desc, ws) == D.DART_ERR_DEVICE
+    D.dart_gather_compact(desc, Xd, keep, Y, ws)  # reads no pivots: clears the flag
+    assert D.dart_device_status(desc, ws) == D.DART_OK

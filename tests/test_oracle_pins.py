@@ -559,3 +559,79 @@ def test_gather_rows_and_packed_batches():
     pos = rng.integers(0, 1000, size=(3, 40)).astype(np.int64)
     got = np.stack([oracle.gather_rows(pos[p].reshape(-1, 1), row_map)[:, 0] for p in range(3)])
     np.testing.assert_array_equal(got, pos[:, mask])
+
+
+# ----------------------------------------------------------------- the admissibility screen
+# oracle.admissible decides which generated inputs count as parity cases; these pins fix both
+# of its answers on inputs whose margins are known by construction.
+
+def _tie_case(third_row):
+    """P = 1, K = 3: the pivot (largest L1 norm) is row 0; stage 0 takes the two lowest
+    cosines among rows 1..4: row 1 (cosine 0), then the tie between row 2 and row 3."""
+    X = rows_f32([[10, 0, 0, 0], [0, 1, 0, 0], [1, 1, 0, 0], third_row, [1, 0, 0, 0]])
+    r = oracle.reduce(X, oracle.F32, 1, 3)
+    assert list(r.piv) == [0] and list(r.keep) == [0, 1, 2]
+    assert r.stage_last[0] == 2 and r.stage_next[0] == 3
+    return X, r
+
+
+def test_admissible_accepts_clear_margins_and_exact_ties_of_identical_rows():
+    w = W.image_batch(B=1, N=120, D=256, P=4, K=24, n_centroids=8)
+    r = oracle.reduce(w.sample(0), w.dtype, w.P, w.K)
+    assert r.stage_gap.min() > 1e-6 and r.piv_gap.min() > 1e-6 * r.c.max()
+    assert oracle.admissible(w.sample(0), r)
+    # the stage boundary falls between two bit-identical rows: margin exactly 0, and the
+    # lowest index is the true answer
+    X, r = _tie_case([1, 1, 0, 0])
+    assert r.stage_gap[0] == 0.0
+    assert oracle.admissible(X, r)
+
+
+def test_admissible_rejects_zero_and_tiny_stage_margins_between_different_rows():
+    # row 3 = 2 * row 2: the same cosine exactly (a power-of-two scale is exact), other bits
+    X, r = _tie_case([2, 2, 0, 0])
+    assert r.stage_gap[0] == 0.0 and not np.array_equal(X[2], X[3])
+    assert not oracle.admissible(X, r)
+    # cosines 1 - t^2/2 with t = 2^-12 and t(1 + 2^-23): 7e-15 apart, below the screen's 1e-9
+    t = np.float32(2.0 ** -12)
+    X = rows_f32([[10, 0, 0, 0], [1, 0, 0, 0], [1, np.nextafter(t, np.float32(1)), 0, 0],
+                  [1, t, 0, 0], [1, 0.5, 0, 0]])
+    r = oracle.reduce(X, oracle.F32, 1, 2)  # stage 0 takes one token: the lowest cosine
+    assert list(r.keep) == [0, 4]
+    r = oracle.reduce(X, oracle.F32, 1, 3)
+    assert r.stage_last[0] == 2 and r.stage_next[0] == 3 and 0.0 <= r.stage_gap[0] < 1e-13
+    assert not oracle.admissible(X, r)
+    # a margin of 1e-12 reported for different rows is refused whatever produced it
+    w = W.image_batch(B=1, N=120, D=256, P=4, K=24, n_centroids=8)
+    r = oracle.reduce(w.sample(0), w.dtype, w.P, w.K)
+    for i in range(w.P):
+        bad = oracle.reduce(w.sample(0), w.dtype, w.P, w.K)
+        bad.stage_gap[i] = 1e-12
+        assert not oracle.admissible(w.sample(0), bad), i
+    # ... and 2e-9 passes: the screen's threshold is 1e-9 absolute on a cosine
+    r.stage_gap[2] = 2e-9
+    assert oracle.admissible(w.sample(0), r)
+
+
+def test_admissible_pivot_rank_ties():
+    # rows 0 and 1 have the same L1 norm (3) and differ: neither rank order is safe
+    X = rows_f32([[3, 0, 0, 0], [0, 3, 0, 0], [1, 1, 0, 0], [0.5, 0, 0, 0]])
+    r = oracle.reduce(X, oracle.F32, 1, 2)  # the tie is between the pivot and the runner-up
+    assert list(r.piv) == [0] and r.piv_gap[0] == 0.0
+    assert not oracle.admissible(X, r)
+    r = oracle.reduce(X, oracle.F32, 2, 3)  # the tie is between two pivots: their order
+    assert list(r.piv) == [0, 1] and r.piv_gap[0] == 0.0
+    assert not oracle.admissible(X, r)
+    # the same ties between bit-identical rows fall to the index rule: accepted
+    X = rows_f32([[3, 0, 0, 0], [3, 0, 0, 0], [1, 1, 0, 0], [0.5, 0, 0, 0]])
+    r = oracle.reduce(X, oracle.F32, 1, 2)
+    assert list(r.piv) == [0] and r.piv_gap[0] == 0.0 and oracle.admissible(X, r)
+    r = oracle.reduce(X, oracle.F32, 2, 3)
+    assert list(r.piv) == [0, 1] and r.piv_gap[0] == 0.0 and oracle.admissible(X, r)
+    # a relative norm margin below 1e-9 between different rows is refused, above it accepted
+    w = W.image_batch(B=1, N=120, D=256, P=4, K=24, n_centroids=8)
+    r = oracle.reduce(w.sample(0), w.dtype, w.P, w.K)
+    r.piv_gap[1] = 1e-12 * r.c[r.piv[1]]
+    assert not oracle.admissible(w.sample(0), r)
+    r.piv_gap[1] = 1e-8 * r.c[r.piv[1]]
+    assert oracle.admissible(w.sample(0), r)
