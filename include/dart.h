@@ -90,8 +90,10 @@ typedef enum dart_status {
   DART_ERR_WORKSPACE = -5, /* ws NULL, misaligned or smaller than required         */
   DART_ERR_ALIGN = -6,     /* a row start would not be 16-byte aligned             */
   DART_ERR_HIP = -7,       /* a HIP call or kernel launch failed                   */
-  DART_ERR_DEVICE = -8     /* dart_device_status: a ragged sample or a given pivot
+  DART_ERR_DEVICE = -8,    /* dart_device_status: a ragged sample or a given pivot
                               list was rejected on the device                      */
+  DART_ERR_STATIC_LIMIT = -9 /* dart_reduce_static: the problem needs more scratch than
+                              the library's built-in buffer holds                  */
 } dart_status;
 
 typedef enum dart_dtype {
@@ -210,6 +212,31 @@ DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const voi
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* dart_reduce for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and kernels as dart_reduce, but the scratch memory is a buffer built
+ * into the library (a file-scope device array of dart_static_scratch_bytes() bytes -- 32 MiB
+ * -- that every GPU the library runs on holds until the process ends) instead of `ws`.  The
+ * call allocates and frees nothing.
+ *   - A descriptor whose dart_workspace_bytes() exceeds dart_static_scratch_bytes() is
+ *     refused with DART_ERR_STATIC_LIMIT and nothing is enqueued (the five benchmark shapes
+ *     except the 1.7 GB ragged batch fit).
+ *   - All calls on one GPU share that GPU's buffer: two calls whose work overlaps in time on
+ *     the same GPU (different streams, or threads) race on it.  Calls on one stream are safe.
+ *   - dart_device_status for such a call: pass ws = NULL to dart_device_status_static.
+ * The buffer keeps the previous call's contents; the kernels initialise every word they
+ * read. */
+DART_API dart_status dart_reduce_static(const dart_desc* desc, const void* X, const void* crit,
+                               int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
+                               int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                               int32_t* piv_out, float* S_out, void* stream);
+
+/* Size of the built-in scratch buffer of dart_reduce_static (host arithmetic only). */
+DART_API size_t dart_static_scratch_bytes(void);
+
+/* dart_device_status for the last dart_reduce_static call on the current GPU. */
+DART_API dart_status dart_device_status_static(const dart_desc* desc, void* stream);
 
 /* One per-token tensor for dart_compact_sequences: rows of row_bytes bytes (a multiple of
  * 16), row r of src at src + r*src_ld_bytes, likewise dst; bases and strides multiples of

@@ -18,13 +18,15 @@ LIB = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdart_hip.so")
 DART_OK = 0
 DART_ERR_NULL, DART_ERR_SHAPE, DART_ERR_BUDGET, DART_ERR_DTYPE = -1, -2, -3, -4
 DART_ERR_WORKSPACE, DART_ERR_ALIGN, DART_ERR_HIP, DART_ERR_DEVICE = -5, -6, -7, -8
+DART_ERR_STATIC_LIMIT = -9
 DART_F32, DART_BF16 = 0, 1
 DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN = 0, 1, 2
 DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
            "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
-           "dart_reduce_profiled", "dart_probe_mfma_dot32",
+           "dart_reduce_profiled", "dart_reduce_static", "dart_static_scratch_bytes",
+           "dart_device_status_static", "dart_probe_mfma_dot32",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -73,10 +75,15 @@ def lib():
         L.dart_reduce.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dart_reduce_profiled.argtypes = L.dart_reduce.argtypes + [C.POINTER(vp)]
         L.dart_device_status.argtypes = [dp, vp, vp]
+        L.dart_reduce_static.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.dart_static_scratch_bytes.argtypes = []
+        L.dart_static_scratch_bytes.restype = sz
+        L.dart_device_status_static.argtypes = [dp, vp]
         L.dart_probe_mfma_dot32.argtypes = [vp, vp, vp, i32, vp]
         for name in ("dart_select_pivots", "dart_duplication_scores", "dart_topk_keep",
                      "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
-                     "dart_reduce_profiled", "dart_device_status", "dart_probe_mfma_dot32"):
+                     "dart_reduce_profiled", "dart_device_status", "dart_reduce_static",
+                     "dart_device_status_static", "dart_probe_mfma_dot32"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -194,6 +201,23 @@ def dart_reduce(desc, X, Y, keep, ws, *, crit=None, crit_D=0, crit_ld=0, pos=Non
     _check(lib().dart_reduce(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld, _ptr(pos),
                              _ptr(Y), _ptr(pos_out), _ptr(keep), _ptr(cu_keep), _ptr(piv_out),
                              _ptr(S_out), _ptr(ws), ws.numel(), _stream(stream)), "dart_reduce")
+
+
+def dart_reduce_static(desc, X, Y, keep, *, crit=None, crit_D=0, crit_ld=0, pos=None,
+                       pos_out=None, cu_keep=None, piv_out=None, S_out=None, stream=None):
+    """dart_reduce on the library's built-in scratch buffer: no workspace, no allocation."""
+    _check(lib().dart_reduce_static(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld,
+                                    _ptr(pos), _ptr(Y), _ptr(pos_out), _ptr(keep),
+                                    _ptr(cu_keep), _ptr(piv_out), _ptr(S_out), _stream(stream)),
+           "dart_reduce_static")
+
+
+def dart_static_scratch_bytes() -> int:
+    return int(lib().dart_static_scratch_bytes())
+
+
+def dart_device_status_static(desc, *, stream=None) -> int:
+    return int(lib().dart_device_status_static(C.byref(desc), _stream(stream)))
 
 
 def dart_probe_mfma_dot32(A, B, out, *, stream=None):

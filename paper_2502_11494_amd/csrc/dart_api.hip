@@ -3,6 +3,8 @@
 // dart_device_status.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/dart.h"
 #include "common.hpp"
 #include "k_misc.hpp"
@@ -26,6 +28,11 @@ constexpr int kScoreDepth = 1;
 constexpr int kScoreSplit = 4;
 constexpr long kScoreSplitRows = 16384;
 
+
+// Scratch of dart_reduce_static: one copy per GPU, at an address of its own on each.  In host
+// code this name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -466,6 +473,25 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   return DART_OK;
 }
 
+// Device address of `scratch` on the current GPU, resolved once per GPU with that GPU current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+dart_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DART_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+      return DART_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DART_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -627,6 +653,27 @@ dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const voi
                      S_out, ws, ws_bytes, stream, events);
 }
 
+size_t dart_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+dart_status dart_reduce_static(const dart_desc* desc, const void* X, const void* crit,
+                               int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
+                               int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                               int32_t* piv_out, float* S_out, void* stream) {
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  if (p.total > kStaticScratchBytes) return DART_ERR_STATIC_LIMIT;
+  void* ws = nullptr;
+  DART_TRY(static_scratch(&ws));
+  return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
+                     S_out, ws, kStaticScratchBytes, stream, nullptr);
+}
+
+dart_status dart_device_status_static(const dart_desc* desc, void* stream) {
+  void* ws = nullptr;
+  DART_TRY(static_scratch(&ws));
+  return dart_device_status(desc, ws, stream);
+}
+
 dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stream) {
   Plan p;
   DART_TRY(make_plan(desc, p));
@@ -672,6 +719,9 @@ const char* dart_strerror(dart_status status) {
     case DART_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case DART_ERR_ALIGN: return "row starts are not 16-byte aligned";
     case DART_ERR_HIP: return "a HIP call or kernel launch failed";
+    case DART_ERR_STATIC_LIMIT:
+      return "the problem needs more scratch than the built-in buffer of dart_reduce_static "
+             "holds (dart_static_scratch_bytes); use dart_reduce with a workspace";
     case DART_ERR_DEVICE:
       return "a ragged sample violated the size or budget limits, a span or sequence is invalid, "
              "or a given pivot list is invalid";

@@ -181,3 +181,25 @@ def test_status_strings():
     assert D.strerror(-99) not in texts
     assert 0 < D.score_tolerance(D.DART_F32) < D.score_tolerance(D.DART_BF16) < 1e-4
 
+
+def test_static_entry_refuses_what_its_buffer_cannot_hold():
+    """dart_reduce_static checks the descriptor against the built-in buffer on the host, before
+    anything touches a device."""
+    limit = D.dart_static_scratch_bytes()
+    assert limit == 32 << 20
+    fits = D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320)
+    assert D.dart_workspace_bytes(fits) <= limit
+    video = D.make_desc(4, 3584, 32, D.DART_BF16, N=9216, K=1024)
+    assert D.dart_workspace_bytes(video) <= limit
+    big = D.make_desc(32, 3584, 16, D.DART_BF16, keep_num=111, keep_den=1000, total_N=250000,
+                      max_N=16384)
+    big.cu_seqlens = 0x1000  # never dereferenced on the host
+    assert D.dart_workspace_bytes(big) > limit
+    L = binding.lib()
+    rc = L.dart_reduce_static(C.byref(big), 0x1000, None, 0, 0, None, 0x1000, None, 0x1000, None,
+                              None, None, None)
+    assert rc == D.DART_ERR_STATIC_LIMIT
+    assert "built-in buffer" in D.strerror(rc)
+    bad = D.make_desc(1, 4096, 0, D.DART_BF16, N=576, K=64)
+    assert L.dart_reduce_static(C.byref(bad), 0x1000, None, 0, 0, None, 0x1000, None, 0x1000,
+                                None, None, None, None) == D.DART_ERR_SHAPE
