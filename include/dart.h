@@ -54,7 +54,8 @@
  *   the row sits in the batch.  (Different entry points or pivot modes may take the
  *   token norms from different passes: their scores agree within
  *   dart_score_tolerance, not necessarily in the last bit.)
- * Limits.  1 <= P <= 64, N_b <= 16384, D <= 65536, total_N <= 2^27.
+ * Limits.  B <= 2^20, 1 <= P <= 64, N_b <= 16384, D <= 65536, total_N <= 2^27, row strides (ld, crit_ld,
+ *   ext_ld) <= 2^24 elements.
  * Pivots from outside (desc.P_ext > 0).  Tokens are scored against such a pivot and it
  *   has its stage in step (c) like any pivot -- after the pivots that are tokens, in the
  *   order of its rows -- but it is no token: it is never retained and holds no slot of

@@ -31,6 +31,18 @@ def build(force: bool = True) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """Compile the oracle together with oracle/sanitize_check.cpp under AddressSanitizer and
+    UndefinedBehaviorSanitizer (no recovery: the first finding aborts) and return the path of
+    the executable, which runs every oracle function on exactly sized buffers."""
+    exe = os.path.join(_HERE, "sanitize_check")
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-fopenmp", "-Wall", "-Wextra",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+           _SRC, os.path.join(_HERE, "sanitize_check.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def lib():
     global _lib
     if _lib is None:

@@ -58,6 +58,33 @@ def build_hip(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(outdir: str) -> str:
+    """The same library with AddressSanitizer and UndefinedBehaviorSanitizer on its HOST code
+    (argument checks, workspace arithmetic, launches), written to `outdir` as
+    libdart_hip_san.so; rebuilt only when the sources changed.  For the CPU test that sweeps
+    the ABI with invalid arguments; never loaded by the product."""
+    os.makedirs(outdir, exist_ok=True)
+    out = os.path.join(outdir, "libdart_hip_san.so")
+    stamp = out + ".sha256"
+    try:
+        with open(stamp) as f:
+            if os.path.exists(out) and f.read().strip() == source_hash():
+                return out
+    except OSError:
+        pass
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + ["-O1", "-g"]
+    for san in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all"):
+        flags += ["-Xarch_host", san]
+    res = subprocess.run([hipcc, *flags, os.path.join(CSRC, "dart_api.hip"), "-o", out],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc (host sanitizers) failed ({res.returncode}):\n{res.stderr}")
+    with open(stamp, "w") as f:
+        f.write(source_hash() + "\n")
+    return out
+
+
 def is_current() -> bool:
     """True if the library exists and was built from the sources as they are now."""
     try:

@@ -37,6 +37,10 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 namespace {
 
 constexpr size_t kAlign = 256;
+// Row strides (elements) are bounded so that rows * stride * element size stays far inside 64
+// bits on the host and in the kernels' byte offsets.
+constexpr int64_t kMaxLd = int64_t(1) << 24;
+constexpr int kMaxB = 1 << 20;  // samples per call (grids and offset tables are sized by B)
 inline size_t up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
@@ -57,8 +61,8 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   if (d->pivot_mode != DART_PIVOT_MAX_L1 && d->pivot_mode != DART_PIVOT_MIN_L1 &&
       d->pivot_mode != DART_PIVOT_GIVEN)
     return DART_ERR_DTYPE;
-  if (d->B < 0 || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
-      d->score_mode < 0 || d->score_mode > 2 || d->P_ext < 0 || d->P_ext > d->P)
+  if (d->B < 0 || d->B > kMaxB || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
+      d->ld > kMaxLd || d->score_mode < 0 || d->score_mode > 2 || d->P_ext < 0 || d->P_ext > d->P)
     return DART_ERR_SHAPE;
   const int Pin = d->P - d->P_ext;  // pivots that are tokens of the sample
   const bool ragged = d->cu_seqlens != nullptr;
@@ -93,7 +97,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   if (((long)d->ld * esz) % 16 != 0 || ((long)d->D * esz) % 16 != 0) return DART_ERR_ALIGN;
   if (d->P_ext > 0) {
     if (!d->ext_pivots) return DART_ERR_NULL;
-    if (d->ext_ld < d->D) return DART_ERR_SHAPE;
+    if (d->ext_ld < d->D || d->ext_ld > kMaxLd) return DART_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(d->ext_pivots) & 15u) != 0 || ((long)d->ext_ld * esz) % 16 != 0)
       return DART_ERR_ALIGN;
   }
@@ -405,7 +409,7 @@ dart_status check_crit(const Plan& p, const void* X, const void*& crit, int32_t&
     crit_ld = p.g.ld;
     return DART_OK;
   }
-  if (crit_D <= 0 || crit_D > 65536 || crit_ld < crit_D) return DART_ERR_SHAPE;
+  if (crit_D <= 0 || crit_D > 65536 || crit_ld < crit_D || crit_ld > kMaxLd) return DART_ERR_SHAPE;
   if (misaligned16(crit) || (crit_ld * p.esz) % 16 != 0 || ((long)crit_D * p.esz) % 16 != 0)
     return DART_ERR_ALIGN;
   return DART_OK;
