@@ -202,6 +202,9 @@ def main():
     ap.add_argument("--sequences", action="store_true",
                     help="context run: spans inside whole sequences and whole-sequence "
                          "compaction (prints its own line)")
+    ap.add_argument("--fused", action="store_true",
+                    help="context run: the one-launch persistent kernel (DART_FUSED=1) instead of "
+                         "the default kernel-per-step path")
     ap.add_argument("--hot", action="store_true",
                     help="context run: the same input buffer every step (cache-hot), not the "
                          "headline measurement")
@@ -213,6 +216,8 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.fused:
+        os.environ["DART_FUSED"] = "1"
     import numpy as np
     import torch
 
@@ -232,7 +237,7 @@ def main():
     x_bytes = total_N * w.D * esz
     # the counter figures under profiles/ were taken on the headline run only
     headline = (args.config in TRAFFIC_FILES and not args.workload and args.p_ext == 0 and args.crit_d == 0
-                and args.score_mode == 0 and not args.hot)
+                and args.score_mode == 0 and not args.hot and not args.fused)
 
     if w.dtype == W.BF16:
         X0 = torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).cuda()
@@ -419,6 +424,8 @@ def main():
                                f"{w.name}: B={w.B} "
                                f"N={'ragged' if w.ragged else int(lens[0])} D={w.D} P={w.P} "
                                f"K={w.K if w.K else f'floor({w.keep_num}/{w.keep_den} N)'}",
+                   "path": ("one persistent kernel (DART_FUSED=1)" if args.fused
+                            else "one kernel per step"),
                    "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
                                   "one threshold on the maximum"][args.score_mode],
                    "pivots_from_outside": args.p_ext,

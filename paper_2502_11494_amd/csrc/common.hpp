@@ -31,6 +31,28 @@ __device__ __forceinline__ long xcd_contiguous(unsigned bid, unsigned nblocks) {
 inline long round_up8(long n) { return (n + kXcds - 1) / kXcds * kXcds; }
 enum { kMaxL1 = 0, kMinL1 = 1, kGiven = 2 };
 
+// ---- memory that another workgroup of the same launch wrote ------------------------------
+// The chip has eight L2 caches (one per accelerator die) that are not kept coherent for
+// ordinary loads and stores inside one kernel, and a cache-wide fence (write back and
+// invalidate a whole L2) costs tens of microseconds under streaming load.  The one-launch
+// path therefore moves everything one workgroup hands to another through device-scope
+// accesses (`sc1` loads and stores: written through to memory, read past the caches), the
+// same instructions the atomics use, one value at a time.  COH = false gives the plain
+// access for kernels whose inputs were written by an earlier launch.
+template <bool COH, typename T>
+__device__ __forceinline__ T ld_dev(const T* p) {
+  if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return *p;
+}
+template <bool COH, typename T>
+__device__ __forceinline__ void st_dev(T* p, T v) {
+  if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+// Every store this thread has issued has reached the point where other dies read it.  With
+// a workgroup barrier after it, one thread may then raise a flag for other workgroups.
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Shape of one call, passed to every kernel by value.
 struct Geo {
   int B, D, P, Ppad;
@@ -99,12 +121,14 @@ __device__ __forceinline__ Sample sample_of(const Geo& g, int b) {
 
 // Row of pivot i of sample b: a token of the sample (index piv[b*P + i], clamped so that a
 // caller's bad index cannot leave X) or, for the last Pe pivots, a row of E.
+// (COH: piv was written by another workgroup of this launch)
+template <bool COH = false>
 __device__ __forceinline__ const unsigned char* pivot_row(const Geo& g, const void* X, int esz,
                                                           const Sample& sm, int b, int i,
-                                                          const int* __restrict__ piv) {
+                                                          const int* piv) {
   if (i >= g.Pin)
     return static_cast<const unsigned char*>(g.E) + ((long)b * g.Pe + (i - g.Pin)) * g.lde * esz;
-  int p = piv[b * g.P + i];
+  int p = ld_dev<COH>(&piv[b * g.P + i]);
   p = p < 0 ? 0 : (p < sm.n ? p : sm.n - 1);
   return static_cast<const unsigned char*>(X) + ((long)sm.xrow + p) * g.ld * esz;
 }

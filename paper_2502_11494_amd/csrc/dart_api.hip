@@ -3,10 +3,12 @@
 // dart_device_status.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <mutex>
 
 #include "../../include/dart.h"
 #include "common.hpp"
+#include "k_fused.hpp"
 #include "k_misc.hpp"
 #include "k_norms.hpp"
 #include "k_order.hpp"
@@ -50,7 +52,8 @@ struct Plan {
   int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
-      o_part, o_l2, total;
+      o_part, o_l2, o_sync, o_nstart, o_sstart, o_gstart, total;
+  bool fusable;  // the shape and modes the one-launch path covers (see reduce_impl)
   bool norms_given;  // this call's norm pass also leaves the squared token norms (fused path)
   int score_split;  // workgroups that share a score tile (1, or kScoreSplit for small batches)
 };
@@ -171,6 +174,17 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
                    : o;
   }
   p.o_l2 = take(sizeof(double) * (size_t)total);
+  // one-launch path: bf16, pivots chosen among the tokens, the staged rule, packed samples
+  p.fusable = d->dtype == DART_BF16 && d->pivot_mode != DART_PIVOT_GIVEN && d->P_ext == 0 &&
+              d->score_mode == 0 && d->span_start == nullptr && d->B <= kFuMaxB;
+  if (d->B <= kFuMaxB) {  // (the same workspace size whatever the modes)
+    p.o_sync = take(sizeof(int) * (size_t)fused_sync_ints(d->B, d->P));
+    p.o_nstart = take(sizeof(int) * ((size_t)d->B + 1));
+    p.o_sstart = take(sizeof(int) * ((size_t)d->B + 1));
+    p.o_gstart = take(sizeof(int) * ((size_t)d->B + 1));
+  } else {
+    p.o_sync = p.o_nstart = p.o_sstart = p.o_gstart = o;
+  }
   p.norms_given = false;
   p.total = o;
   return DART_OK;
@@ -395,6 +409,83 @@ dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, cons
   return DART_OK;
 }
 
+// Compute units of the current GPU (one persistent workgroup each), looked up once per GPU.
+int compute_units() {
+  static std::mutex m;
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(m);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// The whole step as one persistent kernel (after a one-workgroup set-up kernel).
+dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, int64_t* pos_out,
+                         int32_t* keep, int32_t* cu_keep, int* piv, float* S, void* ws,
+                         hipStream_t st) {
+  const int NB = p.g.Ppad / 16;
+  const int score_rows = NB <= 2 ? FusedScoreCfg<1>::ROWS : FusedScoreCfg<3>::ROWS;
+  int* sync = at<int>(ws, p.o_sync);
+  int* nstart = at<int>(ws, p.o_nstart);
+  int* sstart = at<int>(ws, p.o_sstart);
+  int* gstart = at<int>(ws, p.o_gstart);
+  hipLaunchKernelGGL(k_fused_init, dim3(1), dim3(1024), 0, st, p.g, score_rows, Y ? 1 : 0, sync,
+                     nstart, sstart, gstart, cu_keep, at<int>(ws, p.o_status));
+  DART_LAUNCH_CHECK();
+  FusedArgs a;
+  a.X = X;
+  a.pos = reinterpret_cast<const long long*>(pos);
+  a.Y = Y;
+  a.pos_out = reinterpret_cast<long long*>(pos_out);
+  a.keep = keep;
+  a.piv = piv;
+  a.S = S;
+  a.l1 = at<float>(ws, p.o_l1);
+  a.l2sq = at<double>(ws, p.o_l2);
+  a.pl2 = at<double>(ws, p.o_pl2);
+  a.lists = at<unsigned long long>(ws, p.o_lists);
+  a.scr = at<double>(ws, p.o_scr_f64);
+  a.sync = sync;
+  a.norm_start = nstart;
+  a.score_start = sstart;
+  a.gather_start = gstart;
+  a.status = at<int>(ws, p.o_status);
+  a.tau_l1 = (float)l1_rel_bound(p.g.dtype, p.g.D);
+  a.two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype, true));
+  a.keep_cached = (double)p.g.total_N * p.g.ld * p.esz <= 224e6 ? 1 : 0;
+  a.spin_limit = 1 << 20;
+  const dim3 grid(compute_units()), block(kFuThreads);
+  const bool tail = p.g.D % kFuCH != 0;
+#define DART_LAUNCH_FUSED(NBV)                                                        \
+  do {                                                                                \
+    if (tail) hipLaunchKernelGGL((k_fused<NBV, true>), grid, block, 0, st, p.g, a);   \
+    else hipLaunchKernelGGL((k_fused<NBV, false>), grid, block, 0, st, p.g, a);       \
+  } while (0)
+  switch (NB) {
+    case 1: DART_LAUNCH_FUSED(1); break;
+    case 2: DART_LAUNCH_FUSED(2); break;
+    case 3: DART_LAUNCH_FUSED(3); break;
+    default: DART_LAUNCH_FUSED(4); break;
+  }
+#undef DART_LAUNCH_FUSED
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+// DART_FUSED=1 in the environment sends dart_reduce through the one-launch kernel where it
+// applies (a switch between two complete implementations of the same step; the kernel-per-step
+// path is the default because it measured faster on every benchmark shape).
+bool fused_enabled() {
+  const char* v = std::getenv("DART_FUSED");
+  return v && v[0] == '1';
+}
+
 #define DART_TRY(expr)                    \
   do {                                    \
     dart_status _s = (expr);              \
@@ -439,6 +530,8 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   float* l1 = at<float>(ws, p.o_l1);
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(mark(0));
+  if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
+    return launch_fused(p, X, pos, Y, pos_out, keep, cu_keep, piv, S, ws, st);
   if (p.g.mode == kGiven) {
     // the caller's pivots: check them, compute their norms; no pass over the criterion
     hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
@@ -682,9 +775,10 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   Plan p;
   DART_TRY(make_plan(desc, p));
   if (!ws) return DART_ERR_WORKSPACE;
-  if (p.g.B == 0 || (p.g.cu == nullptr && p.g.mode != kGiven)) return DART_OK;
-  // [0] ragged offsets / budgets / spans, [1] given pivots, [2] sequences around the spans
-  int flag[3] = {0, 0, 0};
+  if (p.g.B == 0 || (p.g.cu == nullptr && p.g.mode != kGiven && !p.fusable)) return DART_OK;
+  // [0] ragged offsets / budgets / spans, [1] given pivots, [2] sequences around the spans,
+  // [3] the one-launch path gave up a bounded wait (its outputs are then unspecified)
+  int flag[4] = {0, 0, 0, 0};
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hipMemcpyAsync(flag, static_cast<const unsigned char*>(ws) + p.o_status, sizeof(flag),
                      hipMemcpyDeviceToHost, st) != hipSuccess)
@@ -693,7 +787,8 @@ dart_status dart_device_status(const dart_desc* desc, const void* ws, void* stre
   if (p.g.cu == nullptr) flag[0] = 0;
   if (p.g.mode != kGiven) flag[1] = 0;
   if (p.g.span == nullptr) flag[2] = 0;
-  return (flag[0] | flag[1] | flag[2]) ? DART_ERR_DEVICE : DART_OK;
+  flag[3] = (p.fusable && flag[3] == kFuAborted) ? 1 : 0;
+  return (flag[0] | flag[1] | flag[2] | flag[3]) ? DART_ERR_DEVICE : DART_OK;
 }
 
 dart_status dart_probe_mfma_dot32(const void* A, const void* B, float* out, int32_t tiles,

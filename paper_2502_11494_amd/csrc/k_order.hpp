@@ -8,17 +8,17 @@
 
 namespace dart {
 
-// grid: B*P blocks of THREADS (1024); block (b, i).
+// The list of stage i of sample b, by one workgroup of THREADS (1024) threads.
 // S: pivot-major scores.  lists: 64-bit (score image << 32 | index) entries; the
 // region of sample b starts at P*row0(b) and holds the stage lists back to back
 // (see list_offset).
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void k_order_scores(
-    Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
+// COH: S was written, and lists will be read, by other workgroups of this launch.
+template <int THREADS, bool COH>
+__device__ __forceinline__ void order_scores_body(const Geo& g, int b, int i, const float* S,
+                                                  unsigned long long* lists,
+                                                  SelectShared<THREADS>& sh) {
   constexpr int kSelThreads = THREADS;
-  __shared__ SelectShared<THREADS> sh;
   const int tid = threadIdx.x;
-  const int b = blockIdx.x / g.P, i = blockIdx.x % g.P;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0) return;
   const int n = sm.n;
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     int j = tid + e * kSelThreads;
-    v[e] = (e * kSelThreads < n && j < n) ? row[j] + 0.0f : 0.f;
+    v[e] = (e * kSelThreads < n && j < n) ? ld_dev<COH>(&row[j]) + 0.0f : 0.f;
   }
   int first = 0;  // keys of the first sorted run (all of them unless the sort was split)
   collect_sorted<THREADS, true>(v, n, want, tid, sh, &first);
@@ -40,7 +40,15 @@ __global__ __launch_bounds__(THREADS) void k_order_scores(
   const int off_v = wave_excl_scan(len_v, tid & 63);
   unsigned long long* out = lists + (long)g.P * sm.row0 + __builtin_amdgcn_readfirstlane(__shfl(off_v, i, kWave));
   for (int t = tid; t < want; t += kSelThreads)
-    out[t] = t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)];
+    st_dev<COH>(&out[t], t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)]);
+}
+
+// grid: B*P blocks of THREADS (1024); block (b, i).
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void k_order_scores(
+    Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
+  __shared__ SelectShared<THREADS> sh;
+  order_scores_body<THREADS, false>(g, blockIdx.x / g.P, blockIdx.x % g.P, S, lists, sh);
 }
 
 }  // namespace dart

@@ -22,23 +22,23 @@ struct PivotShared {
   int nU;
 };
 
-// grid: B blocks of THREADS (1024).
+// Pivot selection of sample b by one workgroup of THREADS (1024) threads.
 // l1 [total_N] fp32 criterion norms; piv [B*P] (the first Pin entries of a sample are
 // written); pl2 [B*Ppad] squared L2 norms of the pivots' hidden-state rows (0 for the
 // other slots); scr [2*total_N] doubles.
-template <int DT, int THREADS>
-__global__ __launch_bounds__(THREADS) void k_select_pivots(
-    Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
-    const float* __restrict__ l1, int* __restrict__ piv, double* __restrict__ pl2,
-    double* __restrict__ scr, float tau) {
+// COH: l1 was written, and piv / pl2 will be read, by other workgroups of this launch.
+template <int DT, int THREADS, bool COH>
+__device__ __forceinline__ void select_pivots_body(
+    const Geo& g, int b, const void* X, const void* C, int Dc, long ldc, const float* l1,
+    int* piv, double* pl2, double* scr, float tau, PivotShared<THREADS>& sh) {
   constexpr int kSelThreads = THREADS;
   constexpr int kSelWaves = THREADS / kWave;
-  __shared__ PivotShared<THREADS> sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
-  if (tid < g.Ppad) pl2[b * g.Ppad + tid] = 0.0;
+  if (tid < g.Ppad) st_dev<COH>(&pl2[b * g.Ppad + tid], 0.0);
   if (sm.k == 0) return;
+  if (COH) stores_done();
+  __syncthreads();  // the zeros are ordered before the pivots' norms below
   const int n = sm.n, P = g.Pin;  // pivots chosen among the tokens; stride of piv is g.P
   const float sign = g.mode == kMaxL1 ? -1.f : 1.f;  // "lowest" of -norm = largest norm
 
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
 #pragma unroll
   for (int e = 0; e < kSelPerThread; ++e) {
     int j = tid + e * kSelThreads;
-    v[e] = (e * kSelThreads < n && j < n) ? sign * l1[sm.row0 + j] + 0.0f : 0.f;
+    v[e] = (e * kSelThreads < n && j < n) ? sign * ld_dev<COH>(&l1[sm.row0 + j]) + 0.0f : 0.f;
   }
   // Candidates: every token that may belong to the exact top P.  With vsel >= the P-th lowest
   // fp32 value, {v <= vsel + 2.5 tau |vsel|} holds every token within the norm pass's error of
@@ -109,8 +109,8 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
       const int ju = (int)(uint32_t)sh.sel.buf[u];
       const int cnt = __popcll(__ballot(on && (co < cu || (co == cu && jo < ju))));
       if (lane == 0 && cnt < P) {
-        piv[b * g.P + cnt] = ju;
-        pl2[b * g.Ppad + cnt] = l2s[u];
+        st_dev<COH>(&piv[b * g.P + cnt], ju);
+        st_dev<COH>(&pl2[b * g.Ppad + cnt], l2s[u]);
       }
     }
     return;
@@ -125,10 +125,20 @@ __global__ __launch_bounds__(THREADS) void k_select_pivots(
       cnt += (co < cu || (co == cu && jo < ju)) ? 1 : 0;
     }
     if (cnt < P) {
-      piv[b * g.P + cnt] = ju;
-      pl2[b * g.Ppad + cnt] = l2s[u];
+      st_dev<COH>(&piv[b * g.P + cnt], ju);
+      st_dev<COH>(&pl2[b * g.Ppad + cnt], l2s[u]);
     }
   }
+}
+
+// grid: B blocks of THREADS (1024): block b selects the pivots of sample b.
+template <int DT, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_select_pivots(
+    Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
+    const float* __restrict__ l1, int* __restrict__ piv, double* __restrict__ pl2,
+    double* __restrict__ scr, float tau) {
+  __shared__ PivotShared<THREADS> sh;
+  select_pivots_body<DT, THREADS, false>(g, blockIdx.x, X, C, Dc, ldc, l1, piv, pl2, scr, tau, sh);
 }
 
 }  // namespace dart

@@ -68,20 +68,20 @@ __device__ __forceinline__ bool pair_less(double sa, int ja, double sb, int jb) 
   return sa < sb || (sa == sb && ja < jb);
 }
 
-// grid: B blocks of kRetThreads.
+// The retained set of sample b by one workgroup of kRetThreads threads.
 // lists: per sample at P*row0, stage lists back to back (see k_order_scores).
 // S: pivot-major scores.  X may be nullptr: then scores are taken as exact.
 // keep: packed, ascending per sample.  cu_keep_out (optional) [B+1].
 // scr_f64 [2*total_N] doubles: per-sample scratch at row0 (fallback sweep only).
-template <int DT>
-__global__ __launch_bounds__(kRetThreads) void k_retain(
-    Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
-    const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
-    int* __restrict__ cu_keep_out, double* __restrict__ scr_f64, float two_tau) {
-  __shared__ RetainShared sh;
+// COH: S, lists and piv were written, and keep will be read, by other workgroups of this
+// launch.
+template <int DT, bool COH>
+__device__ __forceinline__ void retain_body(
+    const Geo& g, int b, const float* S, const unsigned long long* lists, const int* piv,
+    const void* X, int* keep, int* cu_keep_out, double* scr_f64, float two_tau,
+    RetainShared& sh) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
-  const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
   if (cu_keep_out && tid == 0) {
     cu_keep_out[b] = sm.keep0;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
 #pragma unroll
     for (int u = 0; u < kStageLoads; ++u) {
       const int t = (h * kStageLoads + u) * kRetThreads + tid;
-      staged[u] = t < staged_total ? glist[group_base + t] : 0ull;
+      staged[u] = t < staged_total ? ld_dev<COH>(&glist[group_base + t]) : 0ull;
     }
   };
   auto store_half = [&](int h) {
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
   plan_group(0);
   load_half(0);
   int my_pivot = -1;
-  if (tid < g.Pin) my_pivot = piv[b * P + tid];  // pivots from outside hold no slot
+  if (tid < g.Pin) my_pivot = ld_dev<COH>(&piv[b * P + tid]);  // pivots from outside hold no slot
   for (int t = tid; t < words; t += kRetThreads) sh.R[t] = 0u;
   for (int t = tid; t < (n + 3) / 4; t += kRetThreads)
     reinterpret_cast<uint32_t*>(sh.owner)[t] = 0xffffffffu;
@@ -196,6 +196,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     auto entry_of = [&](int i, int p) -> unsigned long long {
       const int o = sh.st_off[i] - group_base + p;  // position in sh.list
       if (o < staged_total) return sh.list[o];
+      if (COH) return ld_dev<true>(&glist[sh.st_off[i] + p]);
       return glist_g[sh.st_off[i] + p];
     };
 
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     for (int q = wave; q < qn; q += kRetWaves) {  // a pair per wave: 16 row pairs in flight
       const int st = sh.q_stage[q];
       if (st >= fb_first) continue;  // will be walked again anyway
-      const double s0 = row_cosine_f64<DT>(pivot_row(g, X, esz, sm, b, st, piv),
+      const double s0 = row_cosine_f64<DT>(pivot_row<COH>(g, X, esz, sm, b, st, piv),
                                            Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
       if (lane == 0) sh.q_s64[q] = s0;
     }
@@ -497,7 +498,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
       int n_in = 0;
       for (int j = tid; j < n; j += kRetThreads) {
         if (bit_of(sh.R, (uint32_t)j)) continue;
-        const float s = Srow[j] + 0.0f;
+        const float s = ld_dev<COH>(&Srow[j]) + 0.0f;
         if (s < lo) {  // below the band: certainly among the quota lowest
           set_bit(sh.R, (uint32_t)j);
           sh.owner[j] = (unsigned char)i;
@@ -513,7 +514,7 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
 #pragma unroll
       for (int w = 0; w < kRetWaves; ++w) need -= sh.wcnt[w];
       const int nU = sh.cnt;
-      const unsigned char* prow = pivot_row(g, X, esz, sm, b, i, piv);
+      const unsigned char* prow = pivot_row<COH>(g, X, esz, sm, b, i, piv);
       for (int u = wave; u < nU; u += kRetWaves) {
         const double s64 =
             row_cosine_f64<DT>(prow, Xb + (long)sweep_idx[u] * rowbytes, g.D, lane);
@@ -553,10 +554,20 @@ __global__ __launch_bounds__(kRetThreads) void k_retain(
     uint32_t m = sh.R[t];
     while (m) {
       int bit = __ffs(m) - 1;
-      *out++ = t * 32 + bit;
+      st_dev<COH>(out++, t * 32 + bit);
       m &= m - 1;
     }
   }
+}
+
+// grid: B blocks of kRetThreads: block b builds the retained set of sample b.
+template <int DT>
+__global__ __launch_bounds__(kRetThreads) void k_retain(
+    Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
+    const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
+    int* __restrict__ cu_keep_out, double* __restrict__ scr_f64, float two_tau) {
+  __shared__ RetainShared sh;
+  retain_body<DT, false>(g, blockIdx.x, S, lists, piv, X, keep, cu_keep_out, scr_f64, two_tau, sh);
 }
 
 }  // namespace dart

@@ -77,13 +77,12 @@ __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int&
 // Output tile: lane holds column (lane&15) and rows 4*(lane>>4)..+3 of each 16x16 block.
 // With tokens as the A operand, rows are tokens and columns are pivots (Gram: columns are
 // tokens too, so |x_m|^2 sits in lane (m/4)*16+m, slot m%4).
-template <int NB>
+// COH: pl2 and l2sq were written, and S will be read, by other workgroups of this launch.
+template <int NB, bool COH = false>
 __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int b, int j0,
                                              int lane, const double (&acc64)[NB][4],
-                                             const double (&gram64)[4],
-                                             const double* __restrict__ pl2,
-                                             float* __restrict__ S,
-                                             const double* __restrict__ l2sq) {
+                                             const double (&gram64)[4], const double* pl2,
+                                             float* S, const double* l2sq) {
   const int n = sm.n, P = g.P;
   const int g4 = lane >> 4;
   double xn[4];
@@ -91,7 +90,7 @@ __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int j = j0 + g4 * 4 + r;
-      xn[r] = sqrt(l2sq[sm.row0 + (j < n ? j : n - 1)]);
+      xn[r] = sqrt(ld_dev<COH>(&l2sq[sm.row0 + (j < n ? j : n - 1)]));
     }
   } else {
 #pragma unroll
@@ -102,14 +101,14 @@ __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int
   for (int nb = 0; nb < NB; ++nb) {
     const int i = nb * 16 + (lane & 15);
     if (i < P) {
-      const double pn = sqrt(pl2[b * g.Ppad + i]);
+      const double pn = sqrt(ld_dev<COH>(&pl2[b * g.Ppad + i]));
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int j = j0 + g4 * 4 + r;
         if (j < n) {
           const double den = pn * xn[r];
           const double s = den > 0.0 ? acc64[nb][r] / den : 0.0;
-          Sb[(long)i * n + j] = (float)s + 0.0f;
+          st_dev<COH>(&Sb[(long)i * n + j], (float)s + 0.0f);
         }
       }
     }
