@@ -8,9 +8,11 @@ P=16 pivots, keep 320.  Inputs are resident in HBM before the timed region and
 rotate through enough distinct copies (> 1 GB) that every step reads HBM-cold
 data rather than the 256 MB last-level cache.
 
-Prints ONE JSON line: throughput in input vision tokens per second, the
-roofline position of the dominant kernel (timed with HIP events inside this
-process) and the CPU oracle timed on the host cores as a baseline.
+Prints ONE JSON line: throughput in input vision tokens per second; the roofline
+position of the whole call (the bytes the method must move over the HIP-event
+duration of one dart_reduce) with every streaming kernel's own figure beside it;
+the same measurement for the video and the ragged batch (other_configs); and the
+CPU oracle timed on the host cores as a baseline.
 """
 from __future__ import annotations
 
@@ -73,6 +75,7 @@ class HipEvents:
         self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
         self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.hip.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
         self.ev = []
         for _ in range(n):
             e = C.c_void_p()
@@ -172,72 +175,33 @@ def bench_sequences(args):
                                "rotated and fit the memory-side cache"}}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 0..4 (2 is the headline)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--score-mode", type=int, default=0, choices=[0, 1, 2],
-                    help="0 = a threshold per pivot (the headline), 1/2 = one threshold on the "
-                         "min/max aggregate (variant, context only)")
-    ap.add_argument("--p-ext", type=int, default=0,
-                    help="variant, context only: the last P_EXT of the workload's pivots are "
-                         "synthetic text-token rows from outside the samples")
-    ap.add_argument("--workload", default="", choices=["", "audio", "action", "wide13b", "wide72b"],
-                    help="context only: a shape beyond the five configurations (audio tokens, "
-                         "a vision-language-action model, 13B / 72B hidden sizes)")
-    ap.add_argument("--crit-d", type=int, default=0,
-                    help="variant, context only: pivots by the L1 norm of separate key-state "
-                         "rows of this width (grouped-query shapes, e.g. 1024) instead of the "
-                         "hidden states")
-    ap.add_argument("--streams", type=int, default=2,
-                    help="context only: after the headline measurement, run the same number of "
-                         "steps spread over this many HIP streams (independent batches in "
-                         "flight, each with its own workspace and outputs) and report that "
-                         "rate as concurrent_streams")
-    ap.add_argument("--graph", action="store_true",
-                    help="context only: also time the steps replayed from captured HIP graphs")
-    ap.add_argument("--sequences", action="store_true",
-                    help="context run: spans inside whole sequences and whole-sequence "
-                         "compaction (prints its own line)")
-    ap.add_argument("--fused", action="store_true",
-                    help="context run: the one-launch persistent kernel (DART_FUSED=1) instead of "
-                         "the default kernel-per-step path")
-    ap.add_argument("--hot", action="store_true",
-                    help="context run: the same input buffer every step (cache-hot), not the "
-                         "headline measurement")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the reduction step is per-sample work with no "
-              "cross-GPU exchange; shard the batch by sample and run one process per GPU "
-              "(use --gpus 1).",
-              file=sys.stderr)
-        sys.exit(2)
+def whole_call_bytes(total_N, total_K, D_, esz):
+    """Algorithmic HBM bytes of one dart_reduce call: what the method must move (read every
+    hidden-state row once, write the retained rows, read and write their position ids), and
+    what the two-pass schedule moves (the pivots are not known before every norm is, so X is
+    read twice; the gather reads the retained rows once more)."""
+    x_bytes = total_N * D_ * esz
+    compulsory = x_bytes + total_K * D_ * esz + 16 * total_K
+    two_pass = 2 * x_bytes + 2 * total_K * D_ * esz + 16 * total_K
+    return x_bytes, compulsory, two_pass
 
-    if args.fused:
-        os.environ["DART_FUSED"] = "1"
+
+def measure(w, args, config_index, steps, warmup, variants=True):
+    """Times dart_reduce on one workload (HBM-cold inputs: the batch rotates through more
+    than 1 GB of copies).  Returns the figures of the bench line for that workload."""
     import numpy as np
     import torch
 
     import paper_2502_11494_amd as D
     from paper_2502_11494_amd import workloads as W
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    from paper_2502_11494_amd.build import ensure_built
-    ensure_built()  # loads what is built; compiles only a missing or stale library
-    if args.sequences:
-        return bench_sequences(args)
-    torch.cuda.set_device(0)
-    w = W.by_name(args.workload) if args.workload else W.by_index(args.config)
     total_N = int(w.cu[-1])
     total_K = sum(w.budget(b) for b in range(w.B))
     esz = 2 if w.dtype == W.BF16 else 4
-    x_bytes = total_N * w.D * esz
-    # the counter figures under profiles/ were taken on the headline run only
-    headline = (args.config in TRAFFIC_FILES and not args.workload and args.p_ext == 0 and args.crit_d == 0
-                and args.score_mode == 0 and not args.hot and not args.fused)
+    x_bytes, compulsory, two_pass = whole_call_bytes(total_N, total_K, w.D, esz)
+    # the counter figures under profiles/ were taken on the plain run of this workload only
+    plain = (config_index in TRAFFIC_FILES and not args.workload and args.p_ext == 0
+             and args.crit_d == 0 and args.score_mode == 0 and not args.hot and not args.fused)
 
     if w.dtype == W.BF16:
         X0 = torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).cuda()
@@ -279,55 +243,106 @@ def main():
         D.dart_reduce(desc, Xs[i % copies], Y, keep, ws, pos=pos, pos_out=pos_out, stream=stream,
                       **ckw)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for i in range(steps):
+        step(warmup + i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    tokens_per_s = total_N * args.steps / wall
+    ms_per_step = wall * 1e3 / steps
+    tokens_per_s = total_N * steps / wall
 
     # spread of the step time: ten further groups of steps, each timed like the region above
-    per = max(1, args.steps // 10)
+    per = max(1, steps // 10)
     groups = []
     for gi in range(10):
         torch.cuda.synchronize()
         tg = time.perf_counter()
         for i in range(per):
-            step(args.warmup + gi * per + i)
+            step(warmup + gi * per + i)
         torch.cuda.synchronize()
         groups.append((time.perf_counter() - tg) * 1e3 / per)
     groups.sort()
     spread = {"median": round(groups[5], 5), "min": round(groups[0], 5), "max": round(groups[-1], 5),
               "groups": 10, "steps_per_group": per}
 
-    # per-kernel durations: the same steps again, with HIP events between the kernels
-    evs = HipEvents(7 * args.steps)
-    for i in range(args.steps):
-        D.dart_reduce_profiled(desc, Xs[(args.warmup + i) % copies], Y, keep, ws,
+    # per-kernel durations: the same steps again, with HIP events between the kernels on the
+    # stream they are launched on (the kernel-per-step path; events bracket a kernel plus its
+    # launch gap)
+    evs = HipEvents(7 * steps)
+    was_fused = os.environ.pop("DART_FUSED", None)
+    for i in range(steps):
+        D.dart_reduce_profiled(desc, Xs[(warmup + i) % copies], Y, keep, ws,
                                evs.handles(7 * i, 7 * i + 7), pos=pos, pos_out=pos_out,
                                stream=stream, **ckw)
     torch.cuda.synchronize()
-    stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(args.steps)) / args.steps
+    if was_fused is not None:
+        os.environ["DART_FUSED"] = was_fused
+    stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(steps)) / steps
                 for s in range(6)]
     evs.close()
-    dom = max(range(6), key=lambda s: stage_ms[s])
+    # the whole call: one event pair around each plain dart_reduce (no events inside it)
+    evs = HipEvents(2 * steps)
+    for i in range(steps):
+        assert evs.hip.hipEventRecord(evs.ev[2 * i], C.c_void_p(stream.cuda_stream)) == 0
+        step(warmup + i)
+        assert evs.hip.hipEventRecord(evs.ev[2 * i + 1], C.c_void_p(stream.cuda_stream)) == 0
+    torch.cuda.synchronize()
+    call_ms = sum(evs.ms(2 * i, 2 * i + 1) for i in range(steps)) / steps
+    evs.close()
     # algorithmic bytes of one launch of each streaming kernel
     alg_bytes = {
         0: (total_N * args.crit_d * esz if args.crit_d > 0 else x_bytes) + 4 * total_N,  # norms
         2: x_bytes + 4 * w.P * total_N + w.B * w.P * w.D * esz,     # read X + pivots, write S
         5: 2 * total_K * w.D * esz + 16 * total_K + 4 * total_K,    # rows + position ids
     }
-    if dom not in alg_bytes:  # an on-chip stage dominates: report the larger streaming pass
-        dom = 0 if stage_ms[0] >= stage_ms[2] else 2
-    achieved = alg_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": ("k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]), "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(STAGE_KERNELS[dom], args.config) if headline else None,
-                "stage_us": {STAGES[s]: round(stage_ms[s] * 1e3, 2) for s in range(6)}}
+    kernels = {}
+    for s_, name in ((0, STAGE_KERNELS[0]),
+                     (2, "k_scores_f32" if w.dtype != W.BF16 else STAGE_KERNELS[2]),
+                     (5, STAGE_KERNELS[5])):
+        gbps = alg_bytes[s_] / (stage_ms[s_] * 1e-3) / 1e9
+        kernels[name] = {"algorithmic_bytes": alg_bytes[s_], "event_us": round(stage_ms[s_] * 1e3, 2),
+                         "achieved": round(gbps, 1), "frac": round(gbps / HBM_PEAK_GBS, 4),
+                         "traffic": measured_traffic(STAGE_KERNELS[s_], config_index) if plain else None}
+    dom = max((0, 2, 5), key=lambda s_: stage_ms[s_])
+    dom_name = "k_scores_f32" if dom == 2 and w.dtype != W.BF16 else STAGE_KERNELS[dom]
+    counter_bytes = measured_traffic("", config_index) if plain else None
+    achieved = compulsory / (call_ms * 1e-3) / 1e9
+    roofline = {
+        # the whole call: the bytes the method must move over the event-timed duration of one
+        # dart_reduce (all of its kernels, on the stream they run on)
+        "bound": "hbm", "scope": "whole dart_reduce call (6 kernels; 7 with ragged offsets)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes": compulsory, "call_event_us": round(call_ms * 1e3, 2),
+        "traffic": counter_bytes,
+        "traffic_source": (("profiles/" + TRAFFIC_FILES[config_index] + " (rocprofv3 FETCH_SIZE + "
+                            "WRITE_SIZE of an earlier run of this command on the same sources; "
+                            "not a counter of this run)") if counter_bytes is not None else None),
+        "two_pass_schedule": {"bytes": two_pass,
+                              "achieved": round(two_pass / (call_ms * 1e-3) / 1e9, 1),
+                              "frac": round(two_pass / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "counter_frac": (None if counter_bytes is None else
+                         round(counter_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)),
+        "dominant_kernel": dom_name,
+        "kernels": kernels,
+        "stage_us": {STAGES[s_]: round(stage_ms[s_] * 1e3, 2) for s_ in range(6)},
+        "on_chip_us": round((stage_ms[1] + stage_ms[3] + stage_ms[4]) * 1e3, 2),
+    }
+    out = {
+        "ms_per_step": round(ms_per_step, 5), "tokens_per_s": round(tokens_per_s, 1),
+        "tokens_removed_per_s": round((total_N - total_K) * steps / wall, 1),
+        "steps": steps, "warmup": warmup, "total_tokens": total_N, "retained_tokens": total_K,
+        "input_copies_rotated": copies,
+        "whole_path_algorithmic_GBps": round(compulsory / (ms_per_step * 1e-3) / 1e9, 1),
+        "whole_path_counter_GBps": (None if counter_bytes is None else
+                                    round(counter_bytes / (ms_per_step * 1e-3) / 1e9, 1)),
+        "ms_per_step_spread": spread, "roofline": roofline,
+    }
+    if not variants:
+        return out
 
     # context: independent batches in flight on several streams (default priority), so that
     # the on-chip kernels of one batch overlap the streaming passes of another
@@ -345,17 +360,17 @@ def main():
             D.dart_reduce(desc, Xs[i % copies], Ys[q], keeps[q], wss[q], pos=pos,
                           pos_out=pouts[q], stream=sts[q], **ckw)
 
-        for i in range(args.warmup):
+        for i in range(warmup):
             cstep(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            cstep(args.warmup + i)
+        for i in range(steps):
+            cstep(warmup + i)
         torch.cuda.synchronize()
         cwall = time.perf_counter() - t0
         same = all(torch.equal(k, keep) for k in keeps)
-        concurrent = {"streams": ns, "ms_per_step": round(cwall * 1e3 / args.steps, 5),
-                      "tokens_per_s": round(total_N * args.steps / cwall, 1),
+        concurrent = {"streams": ns, "ms_per_step": round(cwall * 1e3 / steps, 5),
+                      "tokens_per_s": round(total_N * steps / cwall, 1),
                       "outputs_equal_single_stream": bool(same)}
 
     # context: the same steps replayed from HIP graphs (one captured step per input copy)
@@ -370,16 +385,104 @@ def main():
                     D.dart_reduce(desc, Xs[c], Y, keep, ws, pos=pos, pos_out=pos_out, **ckw)
                 graphs.append(gph)
         torch.cuda.synchronize()
-        for i in range(args.warmup):
+        for i in range(warmup):
             graphs[i % copies].replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            graphs[(args.warmup + i) % copies].replay()
+        for i in range(steps):
+            graphs[(warmup + i) % copies].replay()
         torch.cuda.synchronize()
         gwall = time.perf_counter() - t0
-        graphed = {"ms_per_step": round(gwall * 1e3 / args.steps, 5),
-                   "tokens_per_s": round(total_N * args.steps / gwall, 1)}
+        graphed = {"ms_per_step": round(gwall * 1e3 / steps, 5),
+                   "tokens_per_s": round(total_N * steps / gwall, 1)}
+    out["concurrent_streams"] = concurrent
+    out["graph_replay"] = graphed
+    return out
+
+
+def workload_label(w, index, extra):
+    lens = w.lengths
+    return (f"{'extra' if extra else f'configs[{index}]'} {w.name}: B={w.B} "
+            f"N={'ragged' if w.ragged else int(lens[0])} D={w.D} P={w.P} "
+            f"K={w.K if w.K else f'floor({w.keep_num}/{w.keep_den} N)'}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 0..4 (2 is the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the video and ragged batches that the default run times after "
+                         "the headline shape (other_configs in the output)")
+    ap.add_argument("--score-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0 = a threshold per pivot (the headline), 1/2 = one threshold on the "
+                         "min/max aggregate (variant, context only)")
+    ap.add_argument("--p-ext", type=int, default=0,
+                    help="variant, context only: the last P_EXT of the workload's pivots are "
+                         "synthetic text-token rows from outside the samples")
+    ap.add_argument("--workload", default="", choices=["", "audio", "action", "wide13b", "wide72b"],
+                    help="context only: a shape beyond the five configurations (audio tokens, "
+                         "a vision-language-action model, 13B / 72B hidden sizes)")
+    ap.add_argument("--crit-d", type=int, default=0,
+                    help="variant, context only: pivots by the L1 norm of separate key-state "
+                         "rows of this width (grouped-query shapes, e.g. 1024) instead of the "
+                         "hidden states")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="context only: after the headline measurement, run the same number of "
+                         "steps spread over this many HIP streams (independent batches in "
+                         "flight, each with its own workspace and outputs) and report that "
+                         "rate as concurrent_streams")
+    ap.add_argument("--graph", action="store_true",
+                    help="context only: also time the steps replayed from captured HIP graphs")
+    ap.add_argument("--sequences", action="store_true",
+                    help="context run: spans inside whole sequences and whole-sequence "
+                         "compaction (prints its own line)")
+    ap.add_argument("--fused", action="store_true",
+                    help="context run: the one-launch persistent kernel (DART_FUSED=1) instead of "
+                         "the default kernel-per-step path")
+    ap.add_argument("--hot", action="store_true",
+                    help="context run: the same input buffer every step (cache-hot), not the "
+                         "headline measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the reduction step is per-sample work with no "
+              "cross-GPU exchange; shard the batch by sample and run one process per GPU "
+              "(use --gpus 1).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    if args.fused:
+        os.environ["DART_FUSED"] = "1"
+    import torch
+
+    from paper_2502_11494_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    from paper_2502_11494_amd.build import ensure_built
+    ensure_built()  # loads what is built; compiles only a missing or stale library
+    if args.sequences:
+        return bench_sequences(args)
+    torch.cuda.set_device(0)
+    w = W.by_name(args.workload) if args.workload else W.by_index(args.config)
+    m = measure(w, args, args.config, args.steps, args.warmup)
+    total_N = m["total_tokens"]
+
+    # the other two shapes the bandwidth target names, timed the same way in this process
+    default_run = (args.config == 2 and not args.workload and args.p_ext == 0 and args.crit_d == 0
+                   and args.score_mode == 0 and not args.hot and not args.fused)
+    others = None
+    if default_run and not args.no_other_configs:
+        others = {}
+        for idx, steps in ((4, max(20, args.steps // 2)), (3, max(10, args.steps // 5))):
+            wo = W.by_index(idx)
+            mo = measure(wo, args, idx, steps, max(3, args.warmup // 4), variants=False)
+            mo["workload"] = workload_label(wo, idx, False)
+            others[f"configs[{idx}]"] = mo
+            del wo
+            torch.cuda.empty_cache()
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -416,14 +519,11 @@ def main():
     out = {
         "metric": "vision tokens reduced/sec (input tokens per dart_reduce call), "
                   "N=2880 D=4096 bf16",
-        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": m["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == W.BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{'extra' if args.workload else f'configs[{args.config}]'} "
-                               f"{w.name}: B={w.B} "
-                               f"N={'ragged' if w.ragged else int(lens[0])} D={w.D} P={w.P} "
-                               f"K={w.K if w.K else f'floor({w.keep_num}/{w.keep_den} N)'}",
+        "config": {"workload": workload_label(w, args.config, bool(args.workload)),
                    "path": ("one persistent kernel (DART_FUSED=1)" if args.fused
                             else "one kernel per step"),
                    "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
@@ -431,19 +531,17 @@ def main():
                    "pivots_from_outside": args.p_ext,
                    "criterion": (f"separate key-state rows of width {args.crit_d}"
                                  if args.crit_d > 0 else "the hidden states themselves"),
-                   "total_tokens": total_N, "retained_tokens": total_K,
-                   "input_copies_rotated": copies},
-        "tokens_removed_per_s": round((total_N - total_K) * args.steps / wall, 1),
-        "whole_path_algorithmic_GBps": round(
-            (x_bytes + total_K * w.D * esz + 16 * total_K) / (ms_per_step * 1e-3) / 1e9, 1),
-        "whole_path_counter_GBps": (
-            None if not headline or measured_traffic("", args.config) is None else
-            round(measured_traffic("", args.config) / (ms_per_step * 1e-3) / 1e9, 1)),
-        "ms_per_step_spread": spread,
+                   "total_tokens": total_N, "retained_tokens": m["retained_tokens"],
+                   "input_copies_rotated": m["input_copies_rotated"]},
+        "tokens_removed_per_s": m["tokens_removed_per_s"],
+        "whole_path_algorithmic_GBps": m["whole_path_algorithmic_GBps"],
+        "whole_path_counter_GBps": m["whole_path_counter_GBps"],
+        "ms_per_step_spread": m["ms_per_step_spread"],
         "inputs": "cache-hot (same buffer every step)" if args.hot else "HBM-cold (rotating copies)",
-        "concurrent_streams": concurrent,
-        "graph_replay": graphed,
-        "roofline": roofline,
+        "concurrent_streams": m.get("concurrent_streams"),
+        "graph_replay": m.get("graph_replay"),
+        "roofline": m["roofline"],
+        "other_configs": others,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -3,6 +3,8 @@
 // dart_device_status.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <mutex>
 
@@ -55,6 +57,7 @@ struct Plan {
       o_part, o_l2, o_sync, o_nstart, o_sstart, o_gstart, total;
   bool fusable;  // the shape and modes the one-launch path covers (see reduce_impl)
   bool norms_given;  // this call's norm pass also leaves the squared token norms (fused path)
+  int ks_waves, ks_split;  // K-split score kernel: waves per workgroup and groups (0: not used)
   int score_split;  // workgroups that share a score tile (1, or kScoreSplit for small batches)
 };
 
@@ -144,6 +147,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
     g.tile_rows = (d->dtype == DART_BF16 && g.Ppad == 16 && tiles128 <= 256 && p.score_split == 1)
                       ? 128 : 64;
   }
+  p.ks_waves = p.ks_split = 0;
   p.esz = esz;
   if (!ragged) {
     p.keep_rows_bound = (long)d->B * K;
@@ -304,11 +308,133 @@ dart_status launch_given_status(const Plan& p, const int* piv, void* ws, hipStre
   return DART_OK;
 }
 
+// Compute units of the current GPU looked up once per GPU.
+int compute_units() {
+  static std::mutex m;
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(m);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// ---- tile shape of the score kernel when the norm pass delivers the token norms -----------
+// k_scores_ksplit takes any number of waves W per workgroup and splits the D-chunks over KS
+// groups of them, so a tile has R = 16*W/KS rows.  Measured on the benchmark shapes the kernel
+// runs at the speed of the busiest compute unit: about 6 TB/s for the chip as a whole (pivot
+// chunks, served by L2, count about a fifth of their bytes), plus 48 GB/s for whatever rows
+// the busiest unit holds beyond the average (the units take ceil(tiles/256) or one fewer tiles
+// each), and never faster than a wave's chain of chunks (0.55 us each).  Tile heights that
+// divide the batch evenly over the 256 units therefore win: 9 waves (144 rows) for four
+// samples of 9216 tokens (47 us against 55 with 64-row tiles), 12 waves in 4 groups (48 rows)
+// for sixteen of 576 (18 us against 27 for the four-workgroup split plus its finishing pass).
+// The candidates are the shapes instantiated below.
+struct KsChoice { int waves, split; };
+#define DART_KS_SHAPES(X_)                                                                   \
+  X_(3, 1) X_(4, 1) X_(5, 1) X_(6, 1) X_(7, 1) X_(8, 1) X_(9, 1) X_(10, 1) X_(11, 1) X_(12, 1) \
+  X_(4, 2) X_(6, 2) X_(8, 2) X_(12, 2) X_(16, 2) X_(6, 3) X_(9, 3) X_(12, 3)                  \
+  X_(8, 4) X_(12, 4) X_(16, 4)
+
+KsChoice choose_score_tiles(const Plan& p, int units) {
+  static const KsChoice shapes[] = {
+#define DART_KS_ENTRY(W, KS) {W, KS},
+      DART_KS_SHAPES(DART_KS_ENTRY)
+#undef DART_KS_ENTRY
+  };
+  const Geo& g = p.g;
+  const int NB = g.Ppad / 16;
+  const double rowbytes = (double)g.D * 2;
+  const int chunks = (g.D + kKsCH - 1) / kKsCH;
+  KsChoice best = {4, 1};
+  double best_t = 1e30;
+  for (const KsChoice& c : shapes) {
+    const int R = 16 * c.waves / c.split;
+    const size_t lds = (size_t)(c.waves * 16 + c.split * 2 * NB * 16) * (kKsCH * 2 + 16) + NB * 128;
+    if (lds > 150 * 1024) continue;
+    const double tiles = g.cu == nullptr ? (double)g.B * ((g.N + R - 1) / R)
+                                         : (double)g.total_N / R + 0.5 * g.B;
+    const double per_unit = std::ceil(tiles / units);
+    const double rows_busiest = per_unit * R;
+    const double rows_avg = (double)g.total_N / units;
+    const double weight = 1.0 + 0.2 * NB * 16 / R;  // pivot chunks come from L2
+    double t = g.total_N * rowbytes * weight / 6.0e12;
+    if (rows_busiest > rows_avg) t += (rows_busiest - rows_avg) * rowbytes * weight / 48e9;
+    const int resident = (int)std::max<size_t>(1, std::min<size_t>(150 * 1024 / lds, 16 / c.waves));
+    const double chain = std::ceil(per_unit / resident) * ((chunks + c.split - 1) / c.split) * 0.55e-6 + 4e-6;
+    t = std::max(t, chain);
+    t += 1e-9 * (256 - R) / 256;  // ties: the taller tile (less pivot traffic)
+    if (t < best_t) {
+      best_t = t;
+      best = c;
+    }
+  }
+  return best;
+}
+
+// Switches the plan to k_scores_ksplit with the tile shape chosen for this batch.  Called when
+// this call's norm pass can deliver the squared token norms (bf16 hidden states that are their
+// own criterion, up to about 1 GB: see reduce_impl).
+void plan_score_tiles(Plan& p) {
+  const KsChoice c = choose_score_tiles(p, compute_units());
+  p.ks_waves = c.waves;
+  p.ks_split = c.split;
+  p.score_split = 1;
+  p.g.tile_rows = 16 * c.waves / c.split;
+  p.tiles_bound = p.g.cu == nullptr
+                      ? p.g.B * ((p.g.N + p.g.tile_rows - 1) / p.g.tile_rows)
+                      : p.g.total_N / p.g.tile_rows + p.g.B;
+}
+
+template <int NB, bool TAIL>
+dart_status launch_scores_ksplit_nb(const Plan& p, const void* X, const int* piv,
+                                    const double* pl2, const double* l2sq, float* S,
+                                    hipStream_t st) {
+  const dim3 grid((unsigned)round_up8(p.tiles_bound)), block(64 * p.ks_waves);
+#define DART_KS_LAUNCH(W, KS)                                                                  \
+  if (p.ks_waves == W && p.ks_split == KS) {                                                   \
+    if constexpr ((size_t)(W * 16 + KS * 2 * NB * 16) * (kKsCH * 2 + 16) + NB * 128 <= 150 * 1024) { \
+      hipLaunchKernelGGL((k_scores_ksplit<NB, KS, W, TAIL>), grid, block, 0, st, p.g, X, piv,  \
+                         pl2, l2sq, S);                                                        \
+      DART_LAUNCH_CHECK();                                                                     \
+      return DART_OK;                                                                          \
+    }                                                                                          \
+  }
+  DART_KS_SHAPES(DART_KS_LAUNCH)
+#undef DART_KS_LAUNCH
+  return DART_ERR_SHAPE;
+}
+
+dart_status launch_scores_ksplit(const Plan& p, const void* X, const int* piv, const double* pl2,
+                                 const double* l2sq, float* S, hipStream_t st) {
+  if (p.tiles_bound == 0) return DART_OK;
+  const bool tail = p.g.D % kKsCH != 0;
+  switch (p.g.Ppad / 16) {
+    case 1: return tail ? launch_scores_ksplit_nb<1, true>(p, X, piv, pl2, l2sq, S, st)
+                        : launch_scores_ksplit_nb<1, false>(p, X, piv, pl2, l2sq, S, st);
+    case 2: return tail ? launch_scores_ksplit_nb<2, true>(p, X, piv, pl2, l2sq, S, st)
+                        : launch_scores_ksplit_nb<2, false>(p, X, piv, pl2, l2sq, S, st);
+    case 3: return tail ? launch_scores_ksplit_nb<3, true>(p, X, piv, pl2, l2sq, S, st)
+                        : launch_scores_ksplit_nb<3, false>(p, X, piv, pl2, l2sq, S, st);
+    default: return tail ? launch_scores_ksplit_nb<4, true>(p, X, piv, pl2, l2sq, S, st)
+                         : launch_scores_ksplit_nb<4, false>(p, X, piv, pl2, l2sq, S, st);
+  }
+}
+
 dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
   double* pl2 = at<double>(ws, p.o_pl2);
   const double* l2sq = p.norms_given ? at<double>(ws, p.o_l2) : nullptr;
+  if (p.ks_waves > 0) {
+    if (l2sq == nullptr) return DART_ERR_SHAPE;  // (plan_score_tiles asks for them)
+    return launch_scores_ksplit(p, X, piv, pl2, l2sq, S, st);
+  }
   if (p.g.dtype == kF32) {
     hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
                        p.g, X, piv, S);
@@ -409,22 +535,6 @@ dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, cons
   return DART_OK;
 }
 
-// Compute units of the current GPU (one persistent workgroup each), looked up once per GPU.
-int compute_units() {
-  static std::mutex m;
-  static int cached[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  std::lock_guard<std::mutex> lock(m);
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
 // The whole step as one persistent kernel (after a one-workgroup set-up kernel).
 dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, int64_t* pos_out,
                          int32_t* keep, int32_t* cu_keep, int* piv, float* S, void* ws,
@@ -461,7 +571,7 @@ dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, in
   a.keep_cached = (double)p.g.total_N * p.g.ld * p.esz <= 224e6 ? 1 : 0;
   a.spin_limit = 1 << 20;
   const dim3 grid(compute_units()), block(kFuThreads);
-  const bool tail = p.g.D % kFuCH != 0;
+  const bool tail = p.g.D % kKsCH != 0;
 #define DART_LAUNCH_FUSED(NBV)                                                        \
   do {                                                                                \
     if (tail) hipLaunchKernelGGL((k_fused<NBV, true>), grid, block, 0, st, p.g, a);   \
@@ -528,6 +638,15 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   int* piv = piv_out ? piv_out : at<int>(ws, p.o_piv);
   float* S = S_out ? S_out : at<float>(ws, p.o_S);
   float* l1 = at<float>(ws, p.o_l1);
+  // hidden states as their own criterion: the norm pass also leaves the squared token norms
+  // and the score pass takes the tile shape that spreads this batch evenly over the chip
+  // (measured: the extra arithmetic costs the norm pass 1-3 % up to 264 MB and 5 % at 1.7 GB,
+  // where it runs at the memory's speed and the gain of the score pass does not pay for it;
+  // the tighter error bound also saves the retained-set kernel 10 % on near-duplicate video
+  // frames)
+  p.norms_given = p.g.mode != kGiven && p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 &&
+                  (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
+  if (p.norms_given) plan_score_tiles(p);
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(mark(0));
   if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
@@ -542,14 +661,6 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     DART_TRY(mark(2));
   } else {
     // pivots chosen among the tokens (none if all of them come from outside) ...
-    // hidden states as their own criterion: the norm pass also leaves the squared token
-    // norms, and the score pass skips its Gram products
-    // (measured: the extra arithmetic costs the norm pass 1-3 % up to 264 MB and 5 % at
-    // 1.7 GB, where it runs at the memory's speed; with one pivot column block the score pass
-    // gains nothing, with two it gains 5 %, and the tighter error bound saves the retained-set
-    // kernel 10 % on near-duplicate video frames: used for P > 16 up to about 1 GB)
-    p.norms_given = p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 && p.g.Ppad > 16 &&
-                    (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
     if (p.g.Pin > 0)
       DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st,
                              p.norms_given ? at<double>(ws, p.o_l2) : nullptr));

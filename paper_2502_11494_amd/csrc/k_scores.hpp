@@ -347,6 +347,188 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_finish(Geo g, const doubl
   store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S, l2sq);
 }
 
+// ---- score tiles with the D-chunks split inside the workgroup ---------------------------------
+// The WAVES waves of a workgroup form KS groups that share the same 16*WAVES/KS token rows;
+// group gk walks the D-chunks [gk*chunks/KS, (gk+1)*chunks/KS) with its own pivot chunks, and
+// the groups' partial sums are added in group order at the end.  A tile of few rows (many tiles:
+// every compute unit busy, a sample's scores done early) then still has WAVES waves' worth of
+// loads in flight, at the pivot traffic of its row count.  The token norms come from the norm
+// pass (l2sq); the arithmetic is that of k_scores_bf16 (exact bf16 products, 32-term sums on
+// the matrix cores, fp64 accumulation).
+constexpr int kKsCH = 128;  // elements of D per chunk
+
+// LDS: token chunks of the waves, pivot chunks of the KS groups (double buffered), the
+// pivots' row addresses.  Rows padded by 16 bytes as in ScoreShared.
+template <int NB, int KS, int WAVES>
+struct KSplitShared {
+  static constexpr int kRowB = kKsCH * 2 + 16;
+  unsigned char a[WAVES * 16 * kRowB];
+  unsigned char p[KS * 2 * NB * 16 * kRowB];
+  const unsigned char* pivptr[NB * 16];
+};
+
+// Tile tl (16*WAVES/KS rows) of sample b.  COH: piv, pl2 and l2sq were written, and S will be
+// read, by other workgroups of this launch.
+template <int NB, int KS, int WAVES, bool TAIL, bool COH>
+__device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm, int b, int tl,
+                                                  const void* X, const int* piv, const double* pl2,
+                                                  const double* l2sq, float* S,
+                                                  KSplitShared<NB, KS, WAVES>& sh) {
+  constexpr int ROWS = 16 * WAVES / KS;
+  constexpr int WG = WAVES / KS;        // waves per group
+  constexpr int TG = WG * kWave;        // threads per group
+  constexpr int kRowB = kKsCH * 2 + 16;
+  constexpr int PC = kKsCH / 8;         // 16-byte pieces per row per chunk
+  constexpr int RPI = kWave / PC;       // rows covered by one load instruction
+  constexpr int LA = 16 / RPI;          // token loads per lane per chunk
+  constexpr int PP = NB * 16 * PC;      // pivot pieces per chunk
+  constexpr int LP = (PP + TG - 1) / TG;
+  constexpr int KSTEPS = kKsCH / 32;    // matrix-core steps per chunk
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int gk = wave / WG, wi = wave - gk * WG, tg = tid - gk * TG;
+  const int n = sm.n, P = g.P;
+  if (tid < NB * 16) sh.pivptr[tid] = tid < P ? pivot_row<COH>(g, X, 2, sm, b, tid, piv) : nullptr;
+  __syncthreads();
+
+  const long rowbytes = g.ld * 2;
+  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes;
+  const int pieces = g.D / 8;
+  const int chunks_all = (g.D + kKsCH - 1) / kKsCH;
+  const int c_first = gk * chunks_all / KS, c_end = (gk + 1) * chunks_all / KS;
+  const int my_cnt = c_end - c_first;
+  const int max_cnt = (chunks_all + KS - 1) / KS;  // every group runs this many rounds
+  const int col16 = lane % PC, rowsub = lane / PC;
+  const int j0 = tl * ROWS + wi * 16;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+
+  const unsigned char* aptr[LA];
+#pragma unroll
+  for (int t = 0; t < LA; ++t) {
+    int r = j0 + t * RPI + rowsub;
+    r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
+    aptr[t] = Xb + (long)r * rowbytes + (TAIL ? 0 : col16 * 16);
+  }
+  const int tail_col = TAIL ? col16 * 16 : 0;
+  const unsigned char* pptr[LP];
+  bool preal[LP], pmine[LP];
+#pragma unroll
+  for (int k = 0; k < LP; ++k) {
+    const int pid = tg + TG * k;
+    pmine[k] = pid < PP;
+    const unsigned char* pr = pmine[k] ? sh.pivptr[pid / PC] : nullptr;
+    preal[k] = pr != nullptr;
+    pptr[k] = (pr != nullptr ? pr : Xb) + (TAIL ? 0 : col16 * 16);
+  }
+  unsigned char* la = sh.a + wave * (16 * kRowB);
+  unsigned char* lpg = sh.p + gk * (2 * NB * 16 * kRowB);
+  const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
+  const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
+
+  double acc64[NB][4];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc64[nb][r] = 0.0;
+
+  u32x4 ra[LA], rp[LP];
+  // chunk c of this group (clamped to a chunk it owns, so that every load is unconditional
+  // and in bounds; the surplus rounds of a group with fewer chunks compute nothing)
+  auto load_chunk = [&](int c) {
+    const bool in = !TAIL || c * PC + col16 < pieces;
+    const long off = in ? (long)c * (kKsCH * 2) + tail_col : 0;
+#pragma unroll
+    for (int k = 0; k < LP; ++k) rp[k] = *reinterpret_cast<const u32x4*>(pptr[k] + off);
+#pragma unroll
+    for (int t = 0; t < LA; ++t)
+      ra[t] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off));
+  };
+  auto store_p = [&](int c, int buf) {
+    const bool in = !TAIL || c * PC + col16 < pieces;
+#pragma unroll
+    for (int k = 0; k < LP; ++k)
+      if (pmine[k])
+        *reinterpret_cast<u32x4*>(lpg + buf * (NB * 16 * kRowB) + ((tg + TG * k) / PC) * kRowB +
+                                  col16 * 16) = (in && preal[k]) ? rp[k] : zero;
+  };
+  const int c_last = my_cnt > 0 ? c_end - 1 : 0;
+  load_chunk(my_cnt > 0 ? c_first : 0);
+  store_p(c_first, 0);
+  for (int it = 0; it < max_cnt; ++it) {
+    const int c = c_first + it;
+    const bool live = it < my_cnt;
+    {
+      const bool in = !TAIL || c * PC + col16 < pieces;
+#pragma unroll
+      for (int t = 0; t < LA; ++t)
+        *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) =
+            (in && live) ? ra[t] : zero;
+    }
+    const bool more = it + 1 < my_cnt;
+    if (it + 1 < max_cnt) load_chunk(more ? c + 1 : c_last);
+    __syncthreads();  // pivot buffer it%2 is complete; buffer (it+1)%2 is no longer read
+    const unsigned char* lp = lpg + (it & 1) * (NB * 16 * kRowB);
+    if (live) {
+#pragma unroll
+      for (int s = 0; s < KSTEPS; ++s) {
+        const bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);
+        f32x4 acc[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const bf16x8 pf =
+              *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);
+          acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
+      }
+    }
+    if (it + 1 < max_cnt) store_p(more ? c + 1 : c_last, (it + 1) & 1);
+  }
+  // the groups' partial sums: groups 1.. leave theirs in LDS (over the token chunks, which
+  // nobody reads any more), group 0 adds them in group order and stores the scores
+  __syncthreads();
+  double* part = reinterpret_cast<double*>(sh.a);
+  if (KS > 1 && gk > 0) {
+    double* out = part + ((long)((gk - 1) * WG + wi) * kWave + lane) * (NB * 4);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) out[nb * 4 + r] = acc64[nb][r];
+  }
+  __syncthreads();
+  if (gk == 0) {
+#pragma unroll
+    for (int o = 1; o < KS; ++o) {
+      const double* in = part + ((long)((o - 1) * WG + wi) * kWave + lane) * (NB * 4);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc64[nb][r] += in[nb * 4 + r];
+    }
+    const double gram_unused[4] = {0.0, 0.0, 0.0, 0.0};
+    if (j0 < n) store_scores<NB, COH>(g, sm, b, j0, lane, acc64, gram_unused, pl2, S, l2sq);
+  }
+}
+
+// grid: the tiles of 16*WAVES/KS rows (dense: B*ceil(N/rows); ragged: an upper bound), rounded
+// up to a multiple of 8 blocks (a die per contiguous eighth of the tiles); WAVES*64 threads.
+template <int NB, int KS, int WAVES, bool TAIL>
+__global__ __launch_bounds__(WAVES * 64) void k_scores_ksplit(Geo g, const void* __restrict__ X,
+                                                       const int* __restrict__ piv,
+                                                       const double* __restrict__ pl2,
+                                                       const double* __restrict__ l2sq,
+                                                       float* __restrict__ S) {
+  __shared__ __align__(16) KSplitShared<NB, KS, WAVES> sh;
+  int b, tl;
+  const int tile = (int)xcd_contiguous(blockIdx.x, gridDim.x);
+  if (!locate_tile(g, tile, b, tl)) return;
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0 || tl * (16 * WAVES / KS) >= sm.n) return;
+  score_tile_ksplit<NB, KS, WAVES, TAIL, false>(g, sm, b, tl, X, piv, pl2, l2sq, S, sh);
+}
+
 // fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)
 // blocks of 256: a block owns 4 consecutive token rows of one sample and 8 pivots at a
 // time; its 4 waves split D (piece t of a row goes to wave (t / 64) % 4), so that small
