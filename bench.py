@@ -30,7 +30,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 STAGES = ["row_l1_norms", "select_pivots", "duplication_scores", "order_scores", "retain",
           "gather_compact"]
-STAGE_KERNELS = ["k_row_l1", "k_select_pivots", "k_scores_bf16", "k_order_scores", "k_retain",
+# (the score pass is k_scores_ksplit when the norm pass delivers the token norms, k_scores_bf16
+# otherwise: the prefix covers both)
+STAGE_KERNELS = ["k_row_l1", "k_select_pivots", "k_scores", "k_order_scores", "k_retain",
                  "k_gather"]
 
 
