@@ -229,6 +229,9 @@ def measure(w, args, config_index, steps, warmup, variants=True):
     else:
         desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K, **more)
     ws = D.alloc_workspace(desc)
+    tile_w, tile_ks = D.dart_score_tile_shape(desc)
+    score_tile = (None if tile_w == 0 else
+                  {"waves": tile_w, "groups": tile_ks, "rows": 16 * tile_w // tile_ks})
     Y = torch.empty((total_K, w.D), dtype=X0.dtype, device="cuda")
     keep = torch.empty(total_K, dtype=torch.int32, device="cuda")
     pos_out = torch.empty(total_K, dtype=torch.int64, device="cuda")
@@ -337,7 +340,7 @@ def measure(w, args, config_index, steps, warmup, variants=True):
         "ms_per_step": round(ms_per_step, 5), "tokens_per_s": round(tokens_per_s, 1),
         "tokens_removed_per_s": round((total_N - total_K) * steps / wall, 1),
         "steps": steps, "warmup": warmup, "total_tokens": total_N, "retained_tokens": total_K,
-        "input_copies_rotated": copies,
+        "input_copies_rotated": copies, "score_tile": score_tile,
         "whole_path_algorithmic_GBps": round(compulsory / (ms_per_step * 1e-3) / 1e9, 1),
         "whole_path_counter_GBps": (None if counter_bytes is None else
                                     round(counter_bytes / (ms_per_step * 1e-3) / 1e9, 1)),
@@ -534,7 +537,8 @@ def main():
                    "criterion": (f"separate key-state rows of width {args.crit_d}"
                                  if args.crit_d > 0 else "the hidden states themselves"),
                    "total_tokens": total_N, "retained_tokens": m["retained_tokens"],
-                   "input_copies_rotated": m["input_copies_rotated"]},
+                   "input_copies_rotated": m["input_copies_rotated"],
+                   "score_tile": m["score_tile"]},
         "tokens_removed_per_s": m["tokens_removed_per_s"],
         "whole_path_algorithmic_GBps": m["whole_path_algorithmic_GBps"],
         "whole_path_counter_GBps": m["whole_path_counter_GBps"],

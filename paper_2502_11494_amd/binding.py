@@ -26,7 +26,7 @@ DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
            "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
            "dart_reduce_profiled", "dart_reduce_static", "dart_static_scratch_bytes",
-           "dart_device_status_static", "dart_probe_mfma_dot32",
+           "dart_device_status_static", "dart_probe_mfma_dot32", "dart_score_tile_shape",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -76,6 +76,7 @@ def lib():
         L.dart_reduce_profiled.argtypes = L.dart_reduce.argtypes + [C.POINTER(vp)]
         L.dart_device_status.argtypes = [dp, vp, vp]
         L.dart_reduce_static.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.dart_score_tile_shape.argtypes = [dp, C.POINTER(i32), C.POINTER(i32)]
         L.dart_static_scratch_bytes.argtypes = []
         L.dart_static_scratch_bytes.restype = sz
         L.dart_device_status_static.argtypes = [dp, vp]
@@ -83,7 +84,8 @@ def lib():
         for name in ("dart_select_pivots", "dart_duplication_scores", "dart_topk_keep",
                      "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
                      "dart_reduce_profiled", "dart_device_status", "dart_reduce_static",
-                     "dart_device_status_static", "dart_probe_mfma_dot32"):
+                     "dart_device_status_static", "dart_probe_mfma_dot32",
+                     "dart_score_tile_shape"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -210,6 +212,15 @@ def dart_reduce_static(desc, X, Y, keep, *, crit=None, crit_D=0, crit_ld=0, pos=
                                     _ptr(pos), _ptr(Y), _ptr(pos_out), _ptr(keep),
                                     _ptr(cu_keep), _ptr(piv_out), _ptr(S_out), _stream(stream)),
            "dart_reduce_static")
+
+
+def dart_score_tile_shape(desc) -> tuple:
+    """(waves per workgroup, groups of them) of the score kernel for this descriptor; (0, 0)
+    for fp32."""
+    w, ks = C.c_int32(0), C.c_int32(0)
+    _check(lib().dart_score_tile_shape(C.byref(desc), C.byref(w), C.byref(ks)),
+           "dart_score_tile_shape")
+    return int(w.value), int(ks.value)
 
 
 def dart_static_scratch_bytes() -> int:

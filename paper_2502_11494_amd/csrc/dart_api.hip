@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <mutex>
 
@@ -20,18 +21,6 @@
 #include "k_single.hpp"
 
 using namespace dart;
-
-// Chunks a wave of the score kernel requests ahead of the one it is computing on.
-// Measured on the B=8 N=2880 D=4096 and B=4 N=9216 D=3584 shapes: 1 is fastest (2, 3 and
-// 4 are 10-30% slower: the kernel runs at the speed of its load stream, which degrades
-// when every wave keeps more of its 16 rows' pieces outstanding).
-constexpr int kScoreDepth = 1;
-// Small batches (at most kScoreSplitRows rows: fewer than 1024 waves of 16 rows) cannot fill
-// the chip with one wave per 16 rows, and a wave's chain over all of D sets the kernel's
-// time; there kScoreSplit workgroups share a tile and split D (see k_scores_bf16).
-constexpr int kScoreSplit = 4;
-constexpr long kScoreSplitRows = 16384;
-
 
 // Scratch of dart_reduce_static: one copy per GPU, at an address of its own on each.  In host
 // code this name is only a handle for hipGetSymbolAddress, never a device address.
@@ -54,12 +43,99 @@ struct Plan {
   int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
-      o_part, o_l2, o_sync, o_nstart, o_sstart, o_gstart, total;
+      o_l2, o_sync, o_nstart, o_sstart, o_gstart, total;
   bool fusable;  // the shape and modes the one-launch path covers (see reduce_impl)
-  bool norms_given;  // this call's norm pass also leaves the squared token norms (fused path)
-  int ks_waves, ks_split;  // K-split score kernel: waves per workgroup and groups (0: not used)
-  int score_split;  // workgroups that share a score tile (1, or kScoreSplit for small batches)
+  bool norms_given;  // this call's norm pass also leaves the squared token norms
+  int ks_waves, ks_split;  // bf16 score kernel: waves per workgroup and groups of them (fp32: 0)
 };
+
+// Compute units of the current GPU looked up once per GPU.
+int compute_units() {
+  static std::mutex m;
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(m);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// ---- tile shape of the bf16 score kernel ----------------------------------------------------
+// k_scores_ksplit takes any number of waves W per workgroup and splits the D-chunks over KS
+// groups of them, so a tile has R = 16*W/KS rows.  Measured on the benchmark shapes the kernel
+// runs at the speed of the busiest compute unit: about 6 TB/s for the chip as a whole (pivot
+// chunks, served by L2, count about a fifth of their bytes), plus 48 GB/s for whatever rows
+// the busiest unit holds beyond the average (the units take ceil(tiles/256) or one fewer tiles
+// each), and never faster than a wave's chain of chunks (0.55 us each).  Tile heights that
+// divide the batch evenly over the 256 units therefore win: 9 waves (144 rows) for four
+// samples of 9216 tokens (47 us against 55 with 64-row tiles), 12 waves in 4 groups (48 rows)
+// for sixteen of 576 (18 us against 27 for four workgroups per tile and a finishing pass).
+// The candidates are the shapes instantiated below.
+struct KsChoice { int waves, split; };
+#define DART_KS_SHAPES(X_)                                                                   \
+  X_(3, 1) X_(4, 1) X_(5, 1) X_(6, 1) X_(8, 1) X_(9, 1) X_(10, 1) X_(11, 1) X_(12, 1)        \
+  X_(4, 2) X_(6, 2) X_(8, 2) X_(12, 2) X_(6, 3) X_(9, 3) X_(12, 3)                          \
+  X_(8, 4) X_(12, 4) X_(16, 4)
+constexpr KsChoice kKsShapes[] = {
+#define DART_KS_ENTRY(W, KS) {W, KS},
+    DART_KS_SHAPES(DART_KS_ENTRY)
+#undef DART_KS_ENTRY
+};
+constexpr size_t kKsLdsLimit = 150 * 1024;  // of the 160 KB of a compute unit
+
+KsChoice choose_score_tiles(const Geo& g, int units) {
+  const int NB = g.Ppad / 16;
+  const double rowbytes = (double)g.D * 2;
+  const int chunks = (g.D + kKsCH - 1) / kKsCH;
+  KsChoice best = {4, 1};
+  double best_t = 1e30;
+  for (const KsChoice& c : kKsShapes) {
+    const int R = 16 * c.waves / c.split;
+    const size_t lds = ksplit_lds_bytes(NB, c.split, c.waves);
+    if (lds > kKsLdsLimit) continue;
+    const double tiles = g.cu == nullptr ? (double)g.B * ((g.N + R - 1) / R)
+                                         : (double)g.total_N / R + 0.5 * g.B;
+    const double per_unit = std::ceil(tiles / units);
+    const double rows_busiest = per_unit * R;
+    const double rows_avg = (double)g.total_N / units;
+    const double weight = 1.0 + 0.2 * NB * 16 / R;  // pivot chunks come from L2
+    double t = g.total_N * rowbytes * weight / 6.0e12;
+    if (rows_busiest > rows_avg) t += (rows_busiest - rows_avg) * rowbytes * weight / 48e9;
+    const int resident = (int)std::max<size_t>(1, std::min<size_t>(kKsLdsLimit / lds, 16 / c.waves));
+    const double chain = std::ceil(per_unit / resident) * ((chunks + c.split - 1) / c.split) * 0.55e-6 + 4e-6;
+    t = std::max(t, chain);
+    t += 1e-9 * (256 - R) / 256;  // ties: the taller tile (less pivot traffic)
+    if (t < best_t) {
+      best_t = t;
+      best = c;
+    }
+  }
+  return best;
+}
+
+// DART_SCORE_TILE="W,KS" in the environment names the shape instead (for tuning, and for the
+// tests that run every instantiated shape); a value that is not one of the shapes above, or
+// does not fit the LDS with this many pivots, is an error of the call.
+dart_status plan_score_tiles(Plan& p) {
+  KsChoice c = choose_score_tiles(p.g, compute_units());
+  if (const char* v = std::getenv("DART_SCORE_TILE")) {
+    int w = 0, ks = 0;
+    bool known = false;
+    if (std::sscanf(v, "%d,%d", &w, &ks) == 2)
+      for (const KsChoice& k : kKsShapes) known = known || (k.waves == w && k.split == ks);
+    if (!known || ksplit_lds_bytes(p.g.Ppad / 16, ks, w) > kKsLdsLimit) return DART_ERR_SHAPE;
+    c = {w, ks};
+  }
+  p.ks_waves = c.waves;
+  p.ks_split = c.split;
+  p.g.tile_rows = 16 * c.waves / c.split;
+  return DART_OK;
+}
 
 dart_status make_plan(const dart_desc* d, Plan& p) {
   if (!d) return DART_ERR_NULL;
@@ -132,22 +208,14 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.E = d->P_ext > 0 ? d->ext_pivots : nullptr;
   g.span = d->span_start;
   g.x_rows = d->span_start ? d->X_rows : (int)total;
-  // 8-wave score workgroups (128 rows share a pivot chunk; 84 KB of LDS, one workgroup per
-  // compute unit) measured 10% faster than 4-wave ones when the pivots fill one 16-column
-  // block and all tiles fit the 256 compute units at once; with more tiles the smaller
-  // workgroups (three per compute unit) win, with more pivots too.
-  {
-    const int NB = g.Ppad / 16, CH = NB == 1 ? 256 : 128;
-    // (measured: a gain from 4 chunks per slice on -- 576-token images at D = 4096: 30 -> 27 us,
-    // at D = 8192 and half the rows: 50 -> 26 us -- a loss with 3 chunks per slice)
-    p.score_split = (d->dtype == DART_BF16 && total <= kScoreSplitRows &&
-                     d->D / CH >= 4 * kScoreSplit) ? kScoreSplit : 1;
-    const long tiles128 = ragged ? total / 128 + d->B : (long)d->B * ((d->N + 127) / 128);
-    // (with split tiles the 64-row workgroups, three per compute unit, are all resident at once)
-    g.tile_rows = (d->dtype == DART_BF16 && g.Ppad == 16 && tiles128 <= 256 && p.score_split == 1)
-                      ? 128 : 64;
-  }
+  // score tiles: fp32 rows are scored 4 to a block, counted in tiles of 64; bf16 tiles take
+  // the shape chosen for this batch
+  g.tile_rows = 64;
   p.ks_waves = p.ks_split = 0;
+  if (d->dtype == DART_BF16) {
+    const dart_status ts = plan_score_tiles(p);
+    if (ts != DART_OK) return ts;
+  }
   p.esz = esz;
   if (!ragged) {
     p.keep_rows_bound = (long)d->B * K;
@@ -169,14 +237,6 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   p.o_S = take(sizeof(float) * (size_t)total * d->P);
   p.o_lists = take(sizeof(unsigned long long) * (size_t)total * d->P);
   p.o_scr_f64 = take(sizeof(double) * 2 * (size_t)total);
-  {
-    const int NB = g.Ppad / 16;
-    // partial sums: per tile, slice, wave (tile_rows / 16) and lane, NB*4 + 4 doubles
-    p.o_part = p.score_split > 1
-                   ? take(sizeof(double) * (size_t)p.tiles_bound * p.score_split *
-                          (g.tile_rows / 16) * 64 * (NB * 4 + 4))
-                   : o;
-  }
   p.o_l2 = take(sizeof(double) * (size_t)total);
   // one-launch path: bf16, pivots chosen among the tokens, the staged rule, packed samples
   p.fusable = d->dtype == DART_BF16 && d->pivot_mode != DART_PIVOT_GIVEN && d->P_ext == 0 &&
@@ -308,186 +368,56 @@ dart_status launch_given_status(const Plan& p, const int* piv, void* ws, hipStre
   return DART_OK;
 }
 
-// Compute units of the current GPU looked up once per GPU.
-int compute_units() {
-  static std::mutex m;
-  static int cached[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  std::lock_guard<std::mutex> lock(m);
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
-// ---- tile shape of the score kernel when the norm pass delivers the token norms -----------
-// k_scores_ksplit takes any number of waves W per workgroup and splits the D-chunks over KS
-// groups of them, so a tile has R = 16*W/KS rows.  Measured on the benchmark shapes the kernel
-// runs at the speed of the busiest compute unit: about 6 TB/s for the chip as a whole (pivot
-// chunks, served by L2, count about a fifth of their bytes), plus 48 GB/s for whatever rows
-// the busiest unit holds beyond the average (the units take ceil(tiles/256) or one fewer tiles
-// each), and never faster than a wave's chain of chunks (0.55 us each).  Tile heights that
-// divide the batch evenly over the 256 units therefore win: 9 waves (144 rows) for four
-// samples of 9216 tokens (47 us against 55 with 64-row tiles), 12 waves in 4 groups (48 rows)
-// for sixteen of 576 (18 us against 27 for the four-workgroup split plus its finishing pass).
-// The candidates are the shapes instantiated below.
-struct KsChoice { int waves, split; };
-#define DART_KS_SHAPES(X_)                                                                   \
-  X_(3, 1) X_(4, 1) X_(5, 1) X_(6, 1) X_(7, 1) X_(8, 1) X_(9, 1) X_(10, 1) X_(11, 1) X_(12, 1) \
-  X_(4, 2) X_(6, 2) X_(8, 2) X_(12, 2) X_(16, 2) X_(6, 3) X_(9, 3) X_(12, 3)                  \
-  X_(8, 4) X_(12, 4) X_(16, 4)
-
-KsChoice choose_score_tiles(const Plan& p, int units) {
-  static const KsChoice shapes[] = {
-#define DART_KS_ENTRY(W, KS) {W, KS},
-      DART_KS_SHAPES(DART_KS_ENTRY)
-#undef DART_KS_ENTRY
-  };
-  const Geo& g = p.g;
-  const int NB = g.Ppad / 16;
-  const double rowbytes = (double)g.D * 2;
-  const int chunks = (g.D + kKsCH - 1) / kKsCH;
-  KsChoice best = {4, 1};
-  double best_t = 1e30;
-  for (const KsChoice& c : shapes) {
-    const int R = 16 * c.waves / c.split;
-    const size_t lds = (size_t)(c.waves * 16 + c.split * 2 * NB * 16) * (kKsCH * 2 + 16) + NB * 128;
-    if (lds > 150 * 1024) continue;
-    const double tiles = g.cu == nullptr ? (double)g.B * ((g.N + R - 1) / R)
-                                         : (double)g.total_N / R + 0.5 * g.B;
-    const double per_unit = std::ceil(tiles / units);
-    const double rows_busiest = per_unit * R;
-    const double rows_avg = (double)g.total_N / units;
-    const double weight = 1.0 + 0.2 * NB * 16 / R;  // pivot chunks come from L2
-    double t = g.total_N * rowbytes * weight / 6.0e12;
-    if (rows_busiest > rows_avg) t += (rows_busiest - rows_avg) * rowbytes * weight / 48e9;
-    const int resident = (int)std::max<size_t>(1, std::min<size_t>(150 * 1024 / lds, 16 / c.waves));
-    const double chain = std::ceil(per_unit / resident) * ((chunks + c.split - 1) / c.split) * 0.55e-6 + 4e-6;
-    t = std::max(t, chain);
-    t += 1e-9 * (256 - R) / 256;  // ties: the taller tile (less pivot traffic)
-    if (t < best_t) {
-      best_t = t;
-      best = c;
-    }
-  }
-  return best;
-}
-
-// Switches the plan to k_scores_ksplit with the tile shape chosen for this batch.  Called when
-// this call's norm pass can deliver the squared token norms (bf16 hidden states that are their
-// own criterion, up to about 1 GB: see reduce_impl).
-void plan_score_tiles(Plan& p) {
-  const KsChoice c = choose_score_tiles(p, compute_units());
-  p.ks_waves = c.waves;
-  p.ks_split = c.split;
-  p.score_split = 1;
-  p.g.tile_rows = 16 * c.waves / c.split;
-  p.tiles_bound = p.g.cu == nullptr
-                      ? p.g.B * ((p.g.N + p.g.tile_rows - 1) / p.g.tile_rows)
-                      : p.g.total_N / p.g.tile_rows + p.g.B;
-}
-
-template <int NB, bool TAIL>
+template <int NB, bool TAIL, bool XN>
 dart_status launch_scores_ksplit_nb(const Plan& p, const void* X, const int* piv,
                                     const double* pl2, const double* l2sq, float* S,
                                     hipStream_t st) {
   const dim3 grid((unsigned)round_up8(p.tiles_bound)), block(64 * p.ks_waves);
-#define DART_KS_LAUNCH(W, KS)                                                                  \
-  if (p.ks_waves == W && p.ks_split == KS) {                                                   \
-    if constexpr ((size_t)(W * 16 + KS * 2 * NB * 16) * (kKsCH * 2 + 16) + NB * 128 <= 150 * 1024) { \
-      hipLaunchKernelGGL((k_scores_ksplit<NB, KS, W, TAIL>), grid, block, 0, st, p.g, X, piv,  \
-                         pl2, l2sq, S);                                                        \
-      DART_LAUNCH_CHECK();                                                                     \
-      return DART_OK;                                                                          \
-    }                                                                                          \
+#define DART_KS_LAUNCH(W, KS)                                                                   \
+  if (p.ks_waves == W && p.ks_split == KS) {                                                    \
+    if constexpr (ksplit_lds_bytes(NB, KS, W) <= kKsLdsLimit) {                                 \
+      hipLaunchKernelGGL((k_scores_ksplit<NB, KS, W, TAIL, XN>), grid, block, 0, st, p.g, X,    \
+                         piv, pl2, l2sq, S);                                                    \
+      DART_LAUNCH_CHECK();                                                                      \
+      return DART_OK;                                                                           \
+    }                                                                                           \
   }
   DART_KS_SHAPES(DART_KS_LAUNCH)
 #undef DART_KS_LAUNCH
   return DART_ERR_SHAPE;
 }
 
-dart_status launch_scores_ksplit(const Plan& p, const void* X, const int* piv, const double* pl2,
-                                 const double* l2sq, float* S, hipStream_t st) {
-  if (p.tiles_bound == 0) return DART_OK;
+template <int NB>
+dart_status launch_scores_ksplit_tx(const Plan& p, const void* X, const int* piv,
+                                    const double* pl2, const double* l2sq, float* S,
+                                    hipStream_t st) {
   const bool tail = p.g.D % kKsCH != 0;
-  switch (p.g.Ppad / 16) {
-    case 1: return tail ? launch_scores_ksplit_nb<1, true>(p, X, piv, pl2, l2sq, S, st)
-                        : launch_scores_ksplit_nb<1, false>(p, X, piv, pl2, l2sq, S, st);
-    case 2: return tail ? launch_scores_ksplit_nb<2, true>(p, X, piv, pl2, l2sq, S, st)
-                        : launch_scores_ksplit_nb<2, false>(p, X, piv, pl2, l2sq, S, st);
-    case 3: return tail ? launch_scores_ksplit_nb<3, true>(p, X, piv, pl2, l2sq, S, st)
-                        : launch_scores_ksplit_nb<3, false>(p, X, piv, pl2, l2sq, S, st);
-    default: return tail ? launch_scores_ksplit_nb<4, true>(p, X, piv, pl2, l2sq, S, st)
-                         : launch_scores_ksplit_nb<4, false>(p, X, piv, pl2, l2sq, S, st);
-  }
+  if (l2sq)
+    return tail ? launch_scores_ksplit_nb<NB, true, true>(p, X, piv, pl2, l2sq, S, st)
+                : launch_scores_ksplit_nb<NB, false, true>(p, X, piv, pl2, l2sq, S, st);
+  return tail ? launch_scores_ksplit_nb<NB, true, false>(p, X, piv, pl2, l2sq, S, st)
+              : launch_scores_ksplit_nb<NB, false, false>(p, X, piv, pl2, l2sq, S, st);
 }
 
+// l2sq: the squared token norms if this call's norm pass left them (else the score kernel
+// takes them from its own Gram products).
 dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S, void* ws,
                           hipStream_t st) {
   if (p.tiles_bound == 0) return DART_OK;
-  double* pl2 = at<double>(ws, p.o_pl2);
+  const double* pl2 = at<double>(ws, p.o_pl2);
   const double* l2sq = p.norms_given ? at<double>(ws, p.o_l2) : nullptr;
-  if (p.ks_waves > 0) {
-    if (l2sq == nullptr) return DART_ERR_SHAPE;  // (plan_score_tiles asks for them)
-    return launch_scores_ksplit(p, X, piv, pl2, l2sq, S, st);
-  }
   if (p.g.dtype == kF32) {
     hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
                        p.g, X, piv, S);
-  } else {
-    // A workgroup of W waves owns a tile of 16*W rows and stages each pivot chunk once:
-    // 1- and 2-wave workgroups re-read the pivot chunks too often (no faster at P=16, much
-    // slower at P=32); 8 waves halve that traffic again and win at P<=16.
-#define DART_LAUNCH_SCORES(NB, CH, W)                                                            \
-  do {                                                                                           \
-    const dim3 grid(p.tiles_bound), block(64 * (W));                                             \
-    const bool tail = p.g.D % (CH) != 0;                                                         \
-    if (p.score_split > 1) {                                                                     \
-      const dim3 grid_s(p.tiles_bound * kScoreSplit);                                            \
-      double* part = at<double>(ws, p.o_part);                                                   \
-      DART_SCORES_PICK(NB, CH, W, kScoreSplit, grid_s, part);                                    \
-      DART_LAUNCH_CHECK();                                                                       \
-      hipLaunchKernelGGL((k_scores_finish<NB, W, kScoreSplit>), grid, block, 0, st, p.g, part,   \
-                         pl2, S, l2sq);                                                          \
-    } else {                                                                                     \
-      double* part = nullptr;                                                                    \
-      const dim3 grid8((unsigned)round_up8(p.tiles_bound));                                      \
-      DART_SCORES_PICK(NB, CH, W, 1, grid8, part);                                                \
-    }                                                                                            \
-  } while (0)
-  // (TAIL, XN) variants of one shape
-#define DART_SCORES_PICK(NB, CH, W, SP, GRID, PART)                                              \
-  do {                                                                                           \
-    if (!tail && l2sq)                                                                           \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, SP, true>), GRID, block,  \
-                         0, st, p.g, X, piv, pl2, S, PART, l2sq);                                \
-    else if (!tail)                                                                              \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, false, W, kScoreDepth, SP, false>), GRID, block, \
-                         0, st, p.g, X, piv, pl2, S, PART, nullptr);                             \
-    else if (l2sq)                                                                               \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, SP, true>), GRID, block,   \
-                         0, st, p.g, X, piv, pl2, S, PART, l2sq);                                \
-    else                                                                                         \
-      hipLaunchKernelGGL((k_scores_bf16<NB, CH, true, W, kScoreDepth, SP, false>), GRID, block,  \
-                         0, st, p.g, X, piv, pl2, S, PART, nullptr);                             \
-  } while (0)
-    switch (p.g.Ppad / 16) {
-      case 1:
-        if (p.g.tile_rows == 128) DART_LAUNCH_SCORES(1, 256, 8); else DART_LAUNCH_SCORES(1, 256, 4);
-        break;
-      case 2: DART_LAUNCH_SCORES(2, 128, 4); break;
-      case 3: DART_LAUNCH_SCORES(3, 128, 4); break;
-      default: DART_LAUNCH_SCORES(4, 128, 4); break;
-    }
-#undef DART_LAUNCH_SCORES
-#undef DART_SCORES_PICK
+    DART_LAUNCH_CHECK();
+    return DART_OK;
   }
-  DART_LAUNCH_CHECK();
-  return DART_OK;
+  switch (p.g.Ppad / 16) {
+    case 1: return launch_scores_ksplit_tx<1>(p, X, piv, pl2, l2sq, S, st);
+    case 2: return launch_scores_ksplit_tx<2>(p, X, piv, pl2, l2sq, S, st);
+    case 3: return launch_scores_ksplit_tx<3>(p, X, piv, pl2, l2sq, S, st);
+    default: return launch_scores_ksplit_tx<4>(p, X, piv, pl2, l2sq, S, st);
+  }
 }
 
 dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st) {
@@ -638,15 +568,13 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   int* piv = piv_out ? piv_out : at<int>(ws, p.o_piv);
   float* S = S_out ? S_out : at<float>(ws, p.o_S);
   float* l1 = at<float>(ws, p.o_l1);
-  // hidden states as their own criterion: the norm pass also leaves the squared token norms
-  // and the score pass takes the tile shape that spreads this batch evenly over the chip
-  // (measured: the extra arithmetic costs the norm pass 1-3 % up to 264 MB and 5 % at 1.7 GB,
-  // where it runs at the memory's speed and the gain of the score pass does not pay for it;
-  // the tighter error bound also saves the retained-set kernel 10 % on near-duplicate video
-  // frames)
+  // hidden states as their own criterion: the norm pass also leaves the squared token norms,
+  // which saves the score pass its Gram products (measured: the extra arithmetic costs the
+  // norm pass 1-3 % up to 264 MB and 5 % at 1.7 GB, where it runs at the memory's speed and
+  // the gain of the score pass does not pay for it; the tighter error bound also saves the
+  // retained-set kernel 10 % on near-duplicate video frames)
   p.norms_given = p.g.mode != kGiven && p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 &&
                   (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
-  if (p.norms_given) plan_score_tiles(p);
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(mark(0));
   if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
@@ -708,6 +636,15 @@ size_t dart_workspace_bytes(const dart_desc* desc) {
   Plan p;
   if (make_plan(desc, p) != DART_OK) return 0;
   return p.total;
+}
+
+dart_status dart_score_tile_shape(const dart_desc* desc, int32_t* waves, int32_t* split) {
+  if (!waves || !split) return DART_ERR_NULL;
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  *waves = p.ks_waves;
+  *split = p.ks_split;
+  return DART_OK;
 }
 
 dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,

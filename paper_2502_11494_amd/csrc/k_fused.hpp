@@ -353,7 +353,7 @@ template <int NB, bool TAIL>
 __device__ __attribute__((noinline)) void fused_do_score(int b_in, int i_in) {
   DART_FUSED_PARAMS(b_in, i_in);
   DART_FUSED_PREFETCH_BEGIN();
-  score_tile_ksplit<NB, FusedScoreCfg<NB>::KS, kFuWaves, TAIL, true>(
+  score_tile_ksplit<NB, FusedScoreCfg<NB>::KS, kFuWaves, TAIL, true, true>(
       g, sample_of(g, b), b, idx, a.X, a.piv, a.pl2, a.l2sq, a.S, fused_score_lds<NB>());
   stores_done();
   DART_FUSED_PREFETCH_END();

@@ -2,18 +2,20 @@
 // and every token of its sample.
 //
 // bf16 hidden states: the tokens x pivots x D contraction runs on the matrix
-// cores (v_mfma_f32_16x16x32_bf16).  A workgroup of 4 or 8 waves owns 64 or 128 token
-// rows; a wave owns 16 of them and walks D in chunks of 128 or 256 elements:
-//   HBM -> registers (two or four rows per load instruction, 256-512 B contiguous
-//       each, two chunks ahead) -> LDS (row-padded) -> MFMA A fragments
-//       (ds_read_b128, conflict-free).
-// The pivot rows of the chunk are staged once per workgroup in LDS (double
-// buffered) and serve as B fragments.  Feeding the token fragment as both
-// operands yields the tile's Gram matrix, whose diagonal is |x_j|^2, at no extra
-// memory traffic.  Every MFMA starts from a zero accumulator and its 32-term sums
-// are added up in fp64 on the vector ALU.  bf16 x bf16 products are exact in fp32,
-// so the only rounding is inside the matrix core's 32-term sum: see
-// score_abs_bound().
+// cores (v_mfma_f32_16x16x32_bf16).  A workgroup of W waves in KS groups owns
+// 16*W/KS token rows; a wave owns 16 of them and walks its group's share of D in
+// chunks of 128 elements:
+//   HBM -> registers (four rows per load instruction, 256 B contiguous each, one
+//       chunk ahead) -> LDS (row-padded) -> MFMA A fragments (ds_read_b128,
+//       conflict-free).
+// The pivot rows of the chunk are staged once per group in LDS (double buffered)
+// and serve as B fragments.  The squared token norms come from the norm pass
+// when it has read the same rows; otherwise the token fragment is fed as both
+// operands, which yields the tile's Gram matrix, whose diagonal is |x_j|^2, at
+// no extra memory traffic.  Every MFMA starts from a zero accumulator and its
+// 32-term sums are added up in fp64 on the vector ALU.  bf16 x bf16 products are
+// exact in fp32, so the only rounding is inside the matrix core's 32-term sum:
+// see score_abs_bound().
 //
 // fp32 hidden states: plain fp64 arithmetic on the vector ALU (products of two
 // floats are exact in fp64).
@@ -43,16 +45,6 @@ inline double score_abs_bound(int dtype, bool norms_given = false) {
   if (dtype != kBF16) return 4.0 * u;
   return (norms_given ? kMfmaUlps + 2.0 + 2.0 : kMfmaUlps * 1.5 + 2.0) * u;
 }
-
-// LDS of one workgroup: CH = elements of D per chunk; rows are padded by 16 bytes
-// so that the 16-row x 64-byte fragment reads hit distinct banks.
-template <int NB, int CH, int WAVES>
-struct ScoreShared {
-  static constexpr int kRowB = CH * 2 + 16;
-  unsigned char a[WAVES * 16 * kRowB];   // per-wave token chunk
-  unsigned char p[2 * NB * 16 * kRowB];  // pivot chunk, double buffered
-  const unsigned char* pivptr[NB * 16];  // pivot rows (nullptr: padding slot)
-};
 
 // Tile -> (sample, tile inside the sample).  Returns false for surplus blocks.
 __device__ __forceinline__ bool locate_tile(const Geo& g, int tile, int& b, int& tl) {
@@ -115,261 +107,41 @@ __device__ __forceinline__ void store_scores(const Geo& g, const Sample& sm, int
   }
 }
 
-// grid: number of tiles of g.tile_rows = 16*WAVES rows (dense: B*ceil(N/tile_rows);
-// ragged: an upper bound): a workgroup of WAVES waves owns one tile, a wave 16 rows.
-// NB = Ppad/16 pivot column blocks; CH = elements of D per chunk (128 or 256);
-// TAIL = D is not a multiple of CH (then the last chunk's missing pieces are zeroed).
-// DEPTH chunks per wave are in flight in registers: the token pieces (the only HBM
-// traffic) and, requested just before them, the chunk's pivot pieces.  All loads are
-// unconditional straight-line code, so the compiler's wait counts let the prefetched
-// chunks stay in flight.
-// SPLIT > 1 (small batches, which cannot fill the chip with one wave per 16 rows): SPLIT
-// workgroups share a tile, each takes a contiguous run of the chunks and leaves its partial
-// sums in `part` ([tile][slice][wave][lane][NB*4 + 4] doubles); k_scores_finish adds them in
-// slice order and stores the scores.  grid: tiles * SPLIT.
-// XN: the squared token norms are given (l2sq, from the norm pass): the Gram products and
-// their accumulation are left out.
-template <int NB, int CH, bool TAIL, int WAVES, int DEPTH, int SPLIT = 1, bool XN = false>
-__global__ __launch_bounds__(WAVES * 64) void k_scores_bf16(Geo g, const void* __restrict__ X,
-                                                     const int* __restrict__ piv,
-                                                     const double* __restrict__ pl2,
-                                                     float* __restrict__ S,
-                                                     double* __restrict__ part = nullptr,
-                                                     const double* __restrict__ l2sq = nullptr) {
-  constexpr int kRowB = CH * 2 + 16;   // LDS row stride, bytes
-  constexpr int PC = CH / 8;           // 16-byte pieces per row per chunk
-  constexpr int RPI = kWave / PC;      // rows covered by one load instruction
-  constexpr int LA = 16 / RPI;         // token loads per lane per chunk
-  constexpr int THREADS = WAVES * 64;
-  constexpr int LP = NB * 16 * PC / THREADS;  // pivot loads per thread per chunk
-  constexpr int KS = CH / 32;          // MFMA k-steps per chunk
-  __shared__ __align__(16) ScoreShared<NB, CH, WAVES> sh;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int b, tl;
-  // (whole-row tiles: a die per contiguous eighth of the tiles; the grid is a multiple of 8)
-  const int tile = SPLIT == 1 ? (int)xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x / SPLIT;
-  const int slice = SPLIT == 1 ? 0 : blockIdx.x - tile * SPLIT;
-  if (!locate_tile(g, tile, b, tl)) return;
-  const Sample sm = sample_of(g, b);
-  if (sm.k == 0) return;
-  const int n = sm.n, P = g.P;
-  const int block_row0 = tl * (16 * WAVES);
-  if (block_row0 >= n) return;
-  if (tid < NB * 16) sh.pivptr[tid] = tid < P ? pivot_row(g, X, 2, sm, b, tid, piv) : nullptr;
-  __syncthreads();
-
-  const long rowbytes = g.ld * 2;
-  const unsigned char* Xb = static_cast<const unsigned char*>(X) + (long)sm.xrow * rowbytes;
-  const int pieces = g.D / 8;  // 16-byte pieces per row
-  const int chunks_all = (g.D + CH - 1) / CH;
-  // this workgroup's chunks [c_first, nchunks)
-  const int c_first = SPLIT == 1 ? 0 : slice * chunks_all / SPLIT;
-  const int nchunks = SPLIT == 1 ? chunks_all : (slice + 1) * chunks_all / SPLIT;
-  const int col16 = lane % PC, rowsub = lane / PC;
-  const int j0 = block_row0 + wave * 16;
-  const u32x4 zero = {0u, 0u, 0u, 0u};
-
-  // token loads: instruction t covers rows t*RPI .. t*RPI+RPI-1 of the wave's 16
-  const unsigned char* aptr[LA];
-#pragma unroll
-  for (int t = 0; t < LA; ++t) {
-    int r = j0 + t * RPI + rowsub;
-    r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
-    aptr[t] = Xb + (long)r * rowbytes + (TAIL ? 0 : col16 * 16);
-  }
-  // With TAIL the lane's column offset is added per chunk instead: a piece past the end of
-  // the row must re-read the row's first 16 bytes, not bytes behind a row shorter than a chunk
-  const int tail_col = TAIL ? col16 * 16 : 0;
-  // pivot loads: piece id = tid + THREADS*k -> pivot row id/PC, piece id%PC (== col16);
-  // padding slots read the sample's first row and are zeroed after the load
-  const unsigned char* pptr[LP];
-  bool preal[LP];
-#pragma unroll
-  for (int k = 0; k < LP; ++k) {
-    const unsigned char* pr = sh.pivptr[(tid + THREADS * k) / PC];
-    preal[k] = pr != nullptr;
-    pptr[k] = (pr != nullptr ? pr : Xb) + (TAIL ? 0 : col16 * 16);
-  }
-
-  u32x4 ra[DEPTH][LA], rp[DEPTH][LP];
-  // With TAIL, a piece past the end of the row re-reads the row's first piece; it is
-  // replaced by zeros (as are the padding pivot slots) only when the registers go to LDS:
-  // the load stays unconditional and nothing touches its result while it is in flight.
-#define DART_LOAD_A(c, buf)                                                                    \
-  {                                                                                            \
-    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    const long off_ = in_ ? (long)(c) * (CH * 2) + tail_col : 0;                               \
-    _Pragma("unroll") for (int t = 0; t < LA; ++t) ra[buf][t] =                                \
-        __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aptr[t] + off_));            \
-  }
-#define DART_STORE_A(c, buf)                                                                   \
-  {                                                                                            \
-    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    _Pragma("unroll") for (int t = 0; t < LA; ++t)                                             \
-        *reinterpret_cast<u32x4*>(la + (t * RPI + rowsub) * kRowB + col16 * 16) =              \
-            in_ ? ra[buf][t] : zero;                                                           \
-  }
-#define DART_LOAD_P(c, rbuf)                                                                   \
-  {                                                                                            \
-    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    const long off_ = in_ ? (long)(c) * (CH * 2) + tail_col : 0;                               \
-    _Pragma("unroll") for (int k = 0; k < LP; ++k) rp[rbuf][k] =                               \
-        *reinterpret_cast<const u32x4*>(pptr[k] + off_);                                       \
-  }
-#define DART_STORE_P(c, rbuf, buf)                                                             \
-  {                                                                                            \
-    const bool in_ = !TAIL || (c) * PC + col16 < pieces;                                       \
-    _Pragma("unroll") for (int k = 0; k < LP; ++k)                                             \
-        *reinterpret_cast<u32x4*>(sh.p + (buf) * (NB * 16 * kRowB) +                           \
-                                  ((tid + THREADS * k) / PC) * kRowB + col16 * 16) =           \
-            (in_ && preal[k]) ? rp[rbuf][k] : zero;                                            \
-  }
-
-  double acc64[NB][4], gram64[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    gram64[r] = 0.0;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc64[nb][r] = 0.0;
-  }
-
-  unsigned char* la = sh.a + wave * (16 * kRowB);
-  const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
-  const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
-
-  // One chunk c (register slot buf = c % DEPTH): the wave's rows go registers -> its own
-  // LDS region (in-order LDS ops within a wave make that safe); the freed slot takes the
-  // pivot and token pieces of chunk c + DEPTH (vector loads return in order: each chunk's
-  // pivot pieces are requested just before its token pieces, so waiting for the pivots of
-  // chunk c + 1 leaves the younger chunks in flight); MFMAs on chunk c; then the pivot
-  // registers of chunk c + 1 go to the other LDS pivot buffer.
-#define DART_CHUNK(c, buf, nbuf, DO_P, DO_A)                                                   \
-  {                                                                                            \
-    DART_STORE_A(c, buf);                                                                      \
-    if (DO_A) {                                                                                \
-      DART_LOAD_P((c) + DEPTH, buf);                                                           \
-      DART_LOAD_A((c) + DEPTH, buf);                                                           \
-    }                                                                                          \
-    __syncthreads(); /* pivot buffer c%2 is complete; buffer (c+1)%2 is no longer read */      \
-    const unsigned char* lp = sh.p + ((c) & 1) * (NB * 16 * kRowB);                            \
-    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                           \
-      bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);                    \
-      f32x4 gram = fzero;                                                                      \
-      if (!XN) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);         \
-      f32x4 acc[NB];                                                                           \
-      _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) {                                      \
-        bf16x8 pf =                                                                            \
-            *reinterpret_cast<const bf16x8*>(lp + nb * (16 * kRowB) + frag_off + s * 64);      \
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);             \
-      }                                                                                        \
-      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                          \
-        if (!XN) gram64[r] += (double)gram[r];                                                 \
-        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];  \
-      }                                                                                        \
-    }                                                                                          \
-    if (DO_P) DART_STORE_P((c) + 1, nbuf, ((c) + 1) & 1);                                               \
-  }
-
-  // DEPTH chunks (pivot and token pieces) are in flight per wave (register ring, static
-  // indices)
-  // (a row shorter than DEPTH chunks re-reads chunk 0 into the unused slots: the loads
-  // stay unconditional, so every path into the loop has the same loads outstanding and
-  // the compiler's wait counts at the loop head stay exact)
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d) {
-    const int cc = c_first + d < nchunks ? c_first + d : c_first;
-    DART_LOAD_P(cc, d);
-    DART_LOAD_A(cc, d);
-  }
-  DART_STORE_P(c_first, 0, c_first & 1);
-  int c = c_first;
-  for (; c + 2 * DEPTH - 1 < nchunks; c += DEPTH) {  // steady state: every load is issued
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) DART_CHUNK(c + d, d, (d + 1) % DEPTH, true, true);
-  }
-#pragma unroll
-  for (int r = 0; r < 2 * DEPTH - 1; ++r) {  // the last chunks: loads only while chunks remain
-    if (c + r < nchunks)
-      DART_CHUNK(c + r, r % DEPTH, (r + 1) % DEPTH, c + r + 1 < nchunks, c + r + DEPTH < nchunks);
-  }
-#undef DART_CHUNK
-#undef DART_LOAD_A
-#undef DART_STORE_A
-#undef DART_LOAD_P
-#undef DART_STORE_P
-
-  if (SPLIT == 1) {
-    store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S, XN ? l2sq : nullptr);
-  } else {
-    double* out = part + (((long)blockIdx.x * WAVES + wave) * kWave + lane) * (NB * 4 + 4);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      out[r] = gram64[r];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) out[4 + nb * 4 + r] = acc64[nb][r];
-    }
-  }
-}
-
-// Adds the SPLIT partial sums of every (tile, wave, lane) in slice order and stores the
-// scores.  grid: tiles blocks of WAVES*64 (the same tiles as k_scores_bf16).
-template <int NB, int WAVES, int SPLIT>
-__global__ __launch_bounds__(WAVES * 64) void k_scores_finish(Geo g, const double* __restrict__ part,
-                                                        const double* __restrict__ pl2,
-                                                        float* __restrict__ S,
-                                                        const double* __restrict__ l2sq) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int b, tl;
-  if (!locate_tile(g, blockIdx.x, b, tl)) return;
-  const Sample sm = sample_of(g, b);
-  if (sm.k == 0) return;
-  const int block_row0 = tl * (16 * WAVES);
-  if (block_row0 >= sm.n) return;
-  const int j0 = block_row0 + wave * 16;
-  double acc64[NB][4], gram64[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    gram64[r] = 0.0;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc64[nb][r] = 0.0;
-  }
-#pragma unroll
-  for (int sl = 0; sl < SPLIT; ++sl) {
-    const double* in =
-        part + ((((long)blockIdx.x * SPLIT + sl) * WAVES + wave) * kWave + lane) * (NB * 4 + 4);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      gram64[r] += in[r];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += in[4 + nb * 4 + r];
-    }
-  }
-  store_scores<NB>(g, sm, b, j0, lane, acc64, gram64, pl2, S, l2sq);
-}
-
-// ---- score tiles with the D-chunks split inside the workgroup ---------------------------------
+// ---- bf16 score tiles ------------------------------------------------------------------------
 // The WAVES waves of a workgroup form KS groups that share the same 16*WAVES/KS token rows;
 // group gk walks the D-chunks [gk*chunks/KS, (gk+1)*chunks/KS) with its own pivot chunks, and
 // the groups' partial sums are added in group order at the end.  A tile of few rows (many tiles:
 // every compute unit busy, a sample's scores done early) then still has WAVES waves' worth of
-// loads in flight, at the pivot traffic of its row count.  The token norms come from the norm
-// pass (l2sq); the arithmetic is that of k_scores_bf16 (exact bf16 products, 32-term sums on
-// the matrix cores, fp64 accumulation).
+// loads in flight, at the pivot traffic of its row count.  KS = 1 is the plain tile of 16*WAVES
+// rows.
 constexpr int kKsCH = 128;  // elements of D per chunk
 
 // LDS: token chunks of the waves, pivot chunks of the KS groups (double buffered), the
-// pivots' row addresses.  Rows padded by 16 bytes as in ScoreShared.
+// pivots' row addresses.  Rows are padded by 16 bytes so that the 16-row x 64-byte fragment
+// reads hit distinct banks.  After the last chunk the groups' partial sums (kPartB bytes per
+// wave of the groups 1..KS-1) overlay a and, for the widest shapes, the start of p.
 template <int NB, int KS, int WAVES>
 struct KSplitShared {
   static constexpr int kRowB = kKsCH * 2 + 16;
+  static constexpr int kPartB = kWave * (NB * 4 + 4) * 8;
   unsigned char a[WAVES * 16 * kRowB];
   unsigned char p[KS * 2 * NB * 16 * kRowB];
   const unsigned char* pivptr[NB * 16];
+  static_assert((WAVES - WAVES / KS) * kPartB <= WAVES * 16 * kRowB + KS * 2 * NB * 16 * kRowB,
+                "the groups' partial sums must fit in the token and pivot chunks they overlay");
 };
 
-// Tile tl (16*WAVES/KS rows) of sample b.  COH: piv, pl2 and l2sq were written, and S will be
-// read, by other workgroups of this launch.
-template <int NB, int KS, int WAVES, bool TAIL, bool COH>
+// LDS bytes of a shape (host side: which shapes fit a compute unit).
+constexpr size_t ksplit_lds_bytes(int NB, int KS, int WAVES) {
+  return (size_t)(WAVES * 16 + KS * 2 * NB * 16) * (kKsCH * 2 + 16) + (size_t)NB * 16 * 8;
+}
+
+// Tile tl (16*WAVES/KS rows) of sample b.
+// TAIL: D is not a multiple of the chunk (the last chunk's missing pieces are zeroed).
+// XN: the squared token norms are given (l2sq, from the norm pass): the Gram products and
+// their accumulation are left out.
+// COH: piv, pl2 and l2sq were written, and S will be read, by other workgroups of this launch.
+template <int NB, int KS, int WAVES, bool TAIL, bool XN, bool COH>
 __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm, int b, int tl,
                                                   const void* X, const int* piv, const double* pl2,
                                                   const double* l2sq, float* S,
@@ -384,6 +156,7 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
   constexpr int PP = NB * 16 * PC;      // pivot pieces per chunk
   constexpr int LP = (PP + TG - 1) / TG;
   constexpr int KSTEPS = kKsCH / 32;    // matrix-core steps per chunk
+  constexpr int PV = NB * 4 + (XN ? 0 : 4);  // partial sums per lane
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int gk = wave / WG, wi = wave - gk * WG, tg = tid - gk * TG;
   const int n = sm.n, P = g.P;
@@ -408,7 +181,11 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
     r = r < n ? r : n - 1;  // rows past the sample's end re-read its last row; never stored
     aptr[t] = Xb + (long)r * rowbytes + (TAIL ? 0 : col16 * 16);
   }
+  // With TAIL the lane's column offset is added per chunk instead: a piece past the end of
+  // the row must re-read the row's first 16 bytes, not bytes behind a row shorter than a chunk
   const int tail_col = TAIL ? col16 * 16 : 0;
+  // pivot pieces: piece id = tg + TG*k -> pivot row id/PC, piece id%PC (== col16); padding
+  // slots read the sample's first row and are zeroed when the registers go to LDS
   const unsigned char* pptr[LP];
   bool preal[LP], pmine[LP];
 #pragma unroll
@@ -424,15 +201,19 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
   const int frag_off = (lane & 15) * kRowB + (lane >> 4) * 16;
   const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
 
-  double acc64[NB][4];
+  double acc64[NB][4], gram64[4];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int r = 0; r < 4; ++r) {
+    gram64[r] = 0.0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) acc64[nb][r] = 0.0;
+    for (int nb = 0; nb < NB; ++nb) acc64[nb][r] = 0.0;
+  }
 
   u32x4 ra[LA], rp[LP];
   // chunk c of this group (clamped to a chunk it owns, so that every load is unconditional
-  // and in bounds; the surplus rounds of a group with fewer chunks compute nothing)
+  // and in bounds; the surplus rounds of a group with fewer chunks compute nothing).  The
+  // chunk's pivot pieces are requested just before its token pieces (vector loads return in
+  // order), and nothing touches a load's result while it is in flight.
   auto load_chunk = [&](int c) {
     const bool in = !TAIL || c * PC + col16 < pieces;
     const long off = in ? (long)c * (kKsCH * 2) + tail_col : 0;
@@ -457,6 +238,8 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
     const int c = c_first + it;
     const bool live = it < my_cnt;
     {
+      // the wave's rows go registers -> its own LDS region (LDS operations of one wave
+      // complete in order, so the fragment reads below need no barrier of their own)
       const bool in = !TAIL || c * PC + col16 < pieces;
 #pragma unroll
       for (int t = 0; t < LA; ++t)
@@ -471,6 +254,8 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
 #pragma unroll
       for (int s = 0; s < KSTEPS; ++s) {
         const bf16x8 af = *reinterpret_cast<const bf16x8*>(la + frag_off + s * 64);
+        f32x4 gram = fzero;
+        if (!XN) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, af, fzero, 0, 0, 0);
         f32x4 acc[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -479,42 +264,55 @@ __device__ __forceinline__ void score_tile_ksplit(const Geo& g, const Sample& sm
           acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, pf, fzero, 0, 0, 0);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 4; ++r) {
+          if (!XN) gram64[r] += (double)gram[r];
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc64[nb][r] += (double)acc[nb][r];
+        }
       }
     }
     if (it + 1 < max_cnt) store_p(more ? c + 1 : c_last, (it + 1) & 1);
   }
-  // the groups' partial sums: groups 1.. leave theirs in LDS (over the token chunks, which
-  // nobody reads any more), group 0 adds them in group order and stores the scores
-  __syncthreads();
-  double* part = reinterpret_cast<double*>(sh.a);
-  if (KS > 1 && gk > 0) {
-    double* out = part + ((long)((gk - 1) * WG + wi) * kWave + lane) * (NB * 4);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) out[nb * 4 + r] = acc64[nb][r];
-  }
-  __syncthreads();
-  if (gk == 0) {
-#pragma unroll
-    for (int o = 1; o < KS; ++o) {
-      const double* in = part + ((long)((o - 1) * WG + wi) * kWave + lane) * (NB * 4);
+  if (KS > 1) {
+    // the groups' partial sums: groups 1.. leave theirs in LDS (over the chunks, which nobody
+    // reads any more), group 0 adds them in group order
+    __syncthreads();
+    double* part = reinterpret_cast<double*>(sh.a);
+    if (gk > 0) {
+      double* out = part + ((long)((gk - 1) * WG + wi) * kWave + lane) * PV;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc64[nb][r] += in[nb * 4 + r];
+        for (int r = 0; r < 4; ++r) out[nb * 4 + r] = acc64[nb][r];
+      if (!XN) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) out[NB * 4 + r] = gram64[r];
+      }
     }
-    const double gram_unused[4] = {0.0, 0.0, 0.0, 0.0};
-    if (j0 < n) store_scores<NB, COH>(g, sm, b, j0, lane, acc64, gram_unused, pl2, S, l2sq);
+    __syncthreads();
+    if (gk == 0) {
+#pragma unroll
+      for (int o = 1; o < KS; ++o) {
+        const double* in = part + ((long)((o - 1) * WG + wi) * kWave + lane) * PV;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc64[nb][r] += in[nb * 4 + r];
+        if (!XN) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) gram64[r] += in[NB * 4 + r];
+        }
+      }
+    }
   }
+  if (gk == 0 && j0 < n)
+    store_scores<NB, COH>(g, sm, b, j0, lane, acc64, gram64, pl2, S, XN ? l2sq : nullptr);
 }
 
-// grid: the tiles of 16*WAVES/KS rows (dense: B*ceil(N/rows); ragged: an upper bound), rounded
-// up to a multiple of 8 blocks (a die per contiguous eighth of the tiles); WAVES*64 threads.
-template <int NB, int KS, int WAVES, bool TAIL>
+// grid: the tiles of g.tile_rows = 16*WAVES/KS rows (dense: B*ceil(N/rows); ragged: an upper
+// bound), rounded up to a multiple of 8 blocks (a die per contiguous eighth of the tiles);
+// WAVES*64 threads.  NB = Ppad/16 pivot column blocks.
+template <int NB, int KS, int WAVES, bool TAIL, bool XN>
 __global__ __launch_bounds__(WAVES * 64) void k_scores_ksplit(Geo g, const void* __restrict__ X,
                                                        const int* __restrict__ piv,
                                                        const double* __restrict__ pl2,
@@ -526,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_ksplit(Geo g, const void*
   if (!locate_tile(g, tile, b, tl)) return;
   const Sample sm = sample_of(g, b);
   if (sm.k == 0 || tl * (16 * WAVES / KS) >= sm.n) return;
-  score_tile_ksplit<NB, KS, WAVES, TAIL, false>(g, sm, b, tl, X, piv, pl2, l2sq, S, sh);
+  score_tile_ksplit<NB, KS, WAVES, TAIL, XN, false>(g, sm, b, tl, X, piv, pl2, l2sq, S, sh);
 }
 
 // fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)

@@ -203,3 +203,51 @@ def test_static_entry_refuses_what_its_buffer_cannot_hold():
     bad = D.make_desc(1, 4096, 0, D.DART_BF16, N=576, K=64)
     assert L.dart_reduce_static(C.byref(bad), 0x1000, None, 0, 0, None, 0x1000, None, 0x1000,
                                 None, None, None, None) == D.DART_ERR_SHAPE
+
+
+def _built_tile_shapes(P):
+    """Every (waves, groups) the library accepts from DART_SCORE_TILE for P pivots."""
+    desc = D.make_desc(4, 1024, P, D.DART_BF16, N=600, K=max(P, 64))
+    found = []
+    try:
+        for w in range(1, 17):
+            for ks in range(1, 5):
+                os.environ["DART_SCORE_TILE"] = f"{w},{ks}"
+                try:
+                    assert D.dart_score_tile_shape(desc) == (w, ks)
+                    found.append((w, ks))
+                except D.DartError as e:
+                    assert e.status == D.DART_ERR_SHAPE
+    finally:
+        del os.environ["DART_SCORE_TILE"]
+    return found
+
+
+def test_score_tile_shape_follows_the_batch_and_the_override():
+    """The tile chooser is host arithmetic: the benchmark shapes get the tiles that spread
+    their rows evenly over 256 compute units, fp32 has no choice, and the environment override
+    is honoured for built shapes and refused (by every entry point) for anything else."""
+    assert "DART_SCORE_TILE" not in os.environ
+    # 8 x 2880 rows: 96-row tiles = 240 tiles, every unit at most one
+    assert D.dart_score_tile_shape(D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320)) == (6, 1)
+    # 4 x 9216 rows: 144-row tiles = 256 tiles, one per unit
+    assert D.dart_score_tile_shape(D.make_desc(4, 3584, 32, D.DART_BF16, N=9216, K=1024)) == (9, 1)
+    # 16 x 576 rows: 48-row tiles, the hidden dimension split over two groups of waves
+    w, ks = D.dart_score_tile_shape(D.make_desc(16, 4096, 8, D.DART_BF16, N=576, K=64))
+    assert ks > 1 and 16 * w // ks == 48
+    assert D.dart_score_tile_shape(D.make_desc(1, 4096, 8, D.DART_F32, N=576, K=64)) == (0, 0)
+    shapes = _built_tile_shapes(8)
+    assert len(shapes) >= 15 and (6, 1) in shapes and (9, 1) in shapes and (1, 1) not in shapes
+    assert all(w % ks == 0 for w, ks in shapes)
+    # with 64 pivots the widest split shapes do not fit the LDS and are refused
+    assert set(_built_tile_shapes(64)) < set(shapes)
+    desc = D.make_desc(2, 1024, 8, D.DART_BF16, N=300, K=32)
+    os.environ["DART_SCORE_TILE"] = "7,5"
+    try:
+        assert D.dart_workspace_bytes(desc) == 0
+        with pytest.raises(D.DartError) as e:
+            D.dart_score_tile_shape(desc)
+        assert e.value.status == D.DART_ERR_SHAPE
+    finally:
+        del os.environ["DART_SCORE_TILE"]
+    assert D.dart_workspace_bytes(desc) > 0
