@@ -118,6 +118,17 @@ def test_zero_rows_score_zero():
     assert np.all(S[:, [5, 77, 100]] == 0.0) and not np.any(np.signbit(S[:, [5, 77, 100]]))
 
 
+@pytest.mark.parametrize("make", [
+    lambda: W.image_batch(B=2, N=150, D=8, P=4, K=30, n_centroids=8),       # one 16-byte piece
+    lambda: W.image_batch(B=2, N=150, D=16, P=4, K=30, n_centroids=8),
+    lambda: W.single_image(N=150, D=4, P=4, K=30, n_centroids=8),           # fp32, one piece
+    lambda: W.image_batch(B=2, N=90, D=65536, P=8, K=24, n_centroids=8),    # the widest rows
+    lambda: W.single_image(N=70, D=65536, P=8, K=20, n_centroids=8),        # fp32, widest
+], ids=["bf16-D8", "bf16-D16", "f32-D4", "bf16-D65536", "f32-D65536"])
+def test_narrowest_and_widest_rows(make):
+    check(make())
+
+
 def test_many_pivots_and_longest_sample():
     w = W.ragged_batch(B=2, D=256, P=64, lengths=[16384, 4100], keep_num=1, keep_den=8)
     check(w)
