@@ -30,8 +30,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 STAGES = ["row_l1_norms", "select_pivots", "duplication_scores", "order_scores", "retain",
           "gather_compact"]
-# (the score pass is k_scores_ksplit when the norm pass delivers the token norms, k_scores_bf16
-# otherwise: the prefix covers both)
+# (the score pass is k_scores_ksplit for bf16 and k_scores_f32 for fp32 rows: the prefix covers both)
 STAGE_KERNELS = ["k_row_l1", "k_select_pivots", "k_scores", "k_order_scores", "k_retain",
                  "k_gather"]
 
