@@ -1,6 +1,8 @@
 """Parity of the fused HIP path (dart_reduce through the C ABI) with the CPU
 oracle: pivots, retained indices, gathered rows and position ids bit for bit,
 scores within tolerance."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -41,7 +43,7 @@ SMALL = [
     lambda: W.video_batch(B=1, frames=40, per_frame=64, D=256, P=8, K=1500, n_centroids=8),
     # lists that need several LDS staging groups (32 lists of up to 2049 entries)
     lambda: W.video_batch(B=2, frames=32, per_frame=128, D=128, P=32, K=2048, n_centroids=8),
-    # small batches with long rows: several workgroups share a score tile and split D
+    # small batches with long rows: groups of waves share a score tile and split D
     # (2, 3 and 4 pivot column blocks; row lengths that leave a ragged last chunk)
     lambda: W.image_batch(B=2, N=300, D=2048, P=20, K=64, n_centroids=16),
     lambda: W.video_batch(B=1, frames=6, per_frame=50, D=2048, P=40, K=100, n_centroids=8),
@@ -236,6 +238,62 @@ def test_random_shapes_sweep():
             continue  # a margin below the oracle's own resolution: not a parity case
         check(w)
         done += 1
+
+
+def test_random_everything_sweep():
+    """Seeded random draws over all batch recipes (fp32 and bf16, dense and packed, with and
+    without separate criterion rows), hidden sizes with and without partial chunks and 1 to 64
+    pivots, each compared bit for bit.  DART_SWEEP_CASES / DART_SWEEP_SEED in the environment
+    make it as long as wanted (3000 cases take about three minutes)."""
+    cases = int(os.environ.get("DART_SWEEP_CASES", "80"))
+    rng = np.random.default_rng(int(os.environ.get("DART_SWEEP_SEED", "20261128")))
+    done = skipped = 0
+    while done < cases:
+        kind = int(rng.integers(0, 5))
+        P = int(rng.choice([1, 2, 5, 8, 13, 16, 17, 24, 32, 33, 48, 49, 64]))
+        N = int(rng.integers(max(P, 8), 4000))
+        K = int(rng.integers(P, N + 1)) if rng.random() < 0.2 else int(
+            rng.integers(P, max(P + 1, N // 3)))
+        D_ = int(rng.choice([8, 64, 136, 256, 520, 1024, 1096, 2048, 3584, 4096]))
+        B = int(rng.integers(1, 6))
+        if B * N * D_ > 3e7:
+            continue
+        seed = int(rng.integers(1, 1 << 30))
+        if kind == 0:
+            w = W.single_image(seed=seed, N=N, D=(D_ + 3) // 4 * 4, P=P, K=K, n_centroids=16)
+        elif kind == 1:
+            w = W.image_batch(seed=seed, B=B, N=N, D=D_, P=P, K=K, n_centroids=24)
+        elif kind == 2:
+            w = W.multicrop_batch(seed=seed, B=B, N=N, D=D_, P=P, K=K, n_centroids=32)
+        elif kind == 3:
+            frames = int(rng.integers(2, 12))
+            per = max(N // frames, P // frames + 1)
+            if frames * per < max(P, K):
+                continue
+            w = W.video_batch(seed=seed, B=B, frames=frames, per_frame=per, D=D_, P=P,
+                              K=min(K, frames * per), n_centroids=8)
+        else:
+            num = int(rng.integers(60, 600))
+            n_min = -(-P * 1000 // num) + 1
+            lengths = [int(rng.integers(n_min, n_min + 2500)) for _ in range(B)]
+            if sum(lengths) * D_ > 3e7:
+                continue
+            w = W.ragged_batch(seed=seed, B=B, D=D_, P=P, keep_num=num, keep_den=1000,
+                               lengths=lengths)
+        use_crit = w.dtype == W.BF16 and rng.random() < 0.35
+        crit_bits = (W.key_states(w, int(rng.choice([64, 128, 512])), seed=seed & 0xffff)
+                     if use_crit else None)
+        refs = G.oracle_samples(w, crit=crit_bits)
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            skipped += 1
+            continue  # a margin below the oracle's own resolution: not a parity case
+        print(f"[case {done}] {w.name} B={w.B} D={w.D} P={w.P} K={w.K} "
+              f"lens={w.lengths[:5].tolist()} crit={use_crit}", flush=True)
+        crit_dev = (None if crit_bits is None else
+                    torch.from_numpy(crit_bits.view(np.int16)).view(torch.bfloat16).cuda())
+        G.compare(w, G.run_reduce(w, crit=crit_dev), refs)
+        done += 1
+    assert skipped <= cases // 4, f"{skipped} inadmissible draws for {cases} cases"
 
 
 def test_caller_supplied_pivots():
