@@ -47,6 +47,7 @@ struct Plan {
   bool fusable;  // the shape and modes the one-launch path covers (see reduce_impl)
   bool norms_given;  // this call's norm pass also leaves the squared token norms
   int ks_waves, ks_split;  // bf16 score kernel: waves per workgroup and groups of them (fp32: 0)
+  bool retain_packed;      // the largest sample's stage lists need the 6-byte LDS layout
 };
 
 // Compute units of the current GPU looked up once per GPU.
@@ -137,6 +138,20 @@ dart_status plan_score_tiles(Plan& p) {
   return DART_OK;
 }
 
+// Entries of all stage lists of a sample of n tokens that keeps k of them with P pivots, Pin
+// of them among the tokens (the sum of Split::stage_len over the stages).
+long retain_list_entries(int n, int k, int P, int Pin) {
+  if (k <= Pin) return 0;
+  const int q = (k - Pin) / P, r = (k - Pin) % P;
+  long total = 0;
+  for (int i = 0; i < P; ++i) {
+    if (q + (i < r ? 1 : 0) == 0) continue;
+    const int filled = Pin + q * (i + 1) + (i + 1 < r ? i + 1 : r);
+    total += std::min(filled + 1, n);
+  }
+  return total;
+}
+
 dart_status make_plan(const dart_desc* d, Plan& p) {
   if (!d) return DART_ERR_NULL;
   if (d->dtype != DART_F32 && d->dtype != DART_BF16) return DART_ERR_DTYPE;
@@ -217,6 +232,11 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
     if (ts != DART_OK) return ts;
   }
   p.esz = esz;
+  {
+    const int n_big = ragged ? maxn : d->N;
+    const int k_big = ragged ? (d->K > 0 ? d->K : (int)(((long)maxn * d->keep_num) / g.keep_den)) : K;
+    p.retain_packed = retain_list_entries(n_big, k_big, d->P, Pin) > kRetList;
+  }
   if (!ragged) {
     p.keep_rows_bound = (long)d->B * K;
     p.tiles_bound = d->B * ((d->N + g.tile_rows - 1) / g.tile_rows);
@@ -444,12 +464,15 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
     DART_LAUNCH_CHECK();
     return DART_OK;
   }
-  if (p.g.dtype == kBF16)
-    hipLaunchKernelGGL((k_retain<kBF16>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,
-                       piv, X, keep, cu_keep, scr_f64, two_tau);
-  else
-    hipLaunchKernelGGL((k_retain<kF32>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists, piv,
-                       X, keep, cu_keep, scr_f64, two_tau);
+#define DART_LAUNCH_RETAIN(DT, PK)                                                               \
+  hipLaunchKernelGGL((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,   \
+                     piv, X, keep, cu_keep, scr_f64, two_tau)
+  if (p.g.dtype == kBF16) {
+    if (p.retain_packed) DART_LAUNCH_RETAIN(kBF16, true); else DART_LAUNCH_RETAIN(kBF16, false);
+  } else {
+    if (p.retain_packed) DART_LAUNCH_RETAIN(kF32, true); else DART_LAUNCH_RETAIN(kF32, false);
+  }
+#undef DART_LAUNCH_RETAIN
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

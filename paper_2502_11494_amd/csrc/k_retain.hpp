@@ -30,13 +30,26 @@ namespace dart {
 constexpr int kRetThreads = 1024;  // 16 waves for staging, the band phase and the fp64 re-scoring
 constexpr int kRetWaves = kRetThreads / kWave;
 constexpr int kRetWords = kMaxN / 32;
-constexpr int kRetList = 12288;  // list entries staged in LDS at a time
+// List entries staged in LDS at a time.  Two layouts of the same LDS region: whole 8-byte
+// entries (one LDS read each) when the lists of the batch's largest sample fit kRetList of
+// them, else a 32-bit score image and a 16-bit token index per entry (6 bytes, two LDS reads:
+// measured 0.5 us slower on a 2880-token sample), so that the 32 lists of a 9216-token video
+// sample (17424 entries) or the 16 lists of a 16384-token sample at one ninth (15.6 K) are
+// still staged in one go instead of two (measured: -3 and -5 us).
+constexpr int kRetList = 12288;
+constexpr int kRetListPacked = 18432;
 constexpr int kRetQ = 1024;      // band candidates awaiting an fp64 score
 constexpr unsigned char kOwnNone = 0xff, kOwnPivot = 0xfe;
 constexpr unsigned long long kNoKey = ~0ull;  // no list entry looks like this (index < 2^14)
 
 struct RetainShared {
-  unsigned long long list[kRetList];
+  union {
+    unsigned long long list[kRetList];
+    struct {
+      uint32_t lkey[kRetListPacked];        // score images of the staged entries
+      unsigned short lidx[kRetListPacked];  // their token indices (< kMaxN = 2^14)
+    } pk;
+  };
   uint32_t R[kRetWords];
   unsigned char owner[kMaxN];  // stage that took the token (kOwnPivot, kOwnNone)
   double q_s64[kRetQ];
@@ -74,8 +87,8 @@ __device__ __forceinline__ bool pair_less(double sa, int ja, double sb, int jb) 
 // keep: packed, ascending per sample.  cu_keep_out (optional) [B+1].
 // scr_f64 [2*total_N] doubles: per-sample scratch at row0 (fallback sweep only).
 // COH: S, lists and piv were written, and keep will be read, by other workgroups of this
-// launch.
-template <int DT, bool COH>
+// launch.  PACKED: the 6-byte layout of the staged lists (see kRetList).
+template <int DT, bool COH, bool PACKED = false>
 __device__ __forceinline__ void retain_body(
     const Geo& g, int b, const float* S, const unsigned long long* lists, const int* piv,
     const void* X, int* keep, int* cu_keep_out, double* scr_f64, float two_tau,
@@ -99,6 +112,12 @@ __device__ __forceinline__ void retain_body(
   int* sweep_idx = reinterpret_cast<int*>(scr_f64 + g.total_N + sm.row0);  // fallback sweep
 
   const Split sp(k, P, g.Pin);
+  constexpr int kCap = PACKED ? kRetListPacked : kRetList;  // staged entries at a time
+  // staged entry o in the form of the global lists (score image << 32 | index)
+  auto staged_entry = [&](int o) -> unsigned long long {
+    if (PACKED) return ((unsigned long long)sh.pk.lkey[o] << 32) | sh.pk.lidx[o];
+    return sh.list[o];
+  };
   // stage constants in the lanes of every wave: lane i holds stage i's quota, list
   // length and list offset (the offsets are the prefix sums of the lengths)
   int quota_v = 0, len_v = 0;
@@ -116,18 +135,18 @@ __device__ __forceinline__ void retain_body(
     const int first = __builtin_amdgcn_readfirstlane(first_any);  // block-uniform: keep it scalar
     group_base = __builtin_amdgcn_readfirstlane(__shfl(off_v, first, kWave));
     const int l0 = __builtin_amdgcn_readfirstlane(__shfl(len_v, first, kWave));
-    const int l0c = l0 < kRetList ? l0 : kRetList;
+    const int l0c = l0 < kCap ? l0 : kCap;
     // a later stage s joins the group while everything up to the end of its list fits; the
     // list ends grow with s, so the stages that fit are the lanes first+1 .. group_hi-1
     const int rel_end = off_v + len_v - group_base - l0 + l0c;  // staged entries through stage `lane`
-    const bool fits = lane > first && lane < P && rel_end <= kRetList;
+    const bool fits = lane > first && lane < P && rel_end <= kCap;
     const int extra = __builtin_amdgcn_readfirstlane(__popcll(__ballot(fits)));
     group_hi = first + 1 + extra;
     const int through = __builtin_amdgcn_readfirstlane(__shfl(rel_end, first + extra, kWave));
     staged_total = extra > 0 ? through : l0c;
   };
-  // a group moves in two halves of kStageLoads loads per thread (48 KiB in flight each)
-  constexpr int kStageLoads = kRetList / kRetThreads / 2;
+  // a group moves in two halves of kStageLoads loads per thread (48 or 72 KiB in flight each)
+  constexpr int kStageLoads = kCap / kRetThreads / 2;
   unsigned long long staged[kStageLoads];
   auto load_half = [&](int h) {
 #pragma unroll
@@ -140,7 +159,14 @@ __device__ __forceinline__ void retain_body(
 #pragma unroll
     for (int u = 0; u < kStageLoads; ++u) {
       const int t = (h * kStageLoads + u) * kRetThreads + tid;
-      if (t < staged_total) sh.list[t] = staged[u];
+      if (t < staged_total) {
+        if (PACKED) {
+          sh.pk.lkey[t] = (uint32_t)(staged[u] >> 32);
+          sh.pk.lidx[t] = (unsigned short)staged[u];
+        } else {
+          sh.list[t] = staged[u];
+        }
+      }
     }
   };
 
@@ -194,8 +220,8 @@ __device__ __forceinline__ void retain_body(
     typedef const unsigned long long __attribute__((address_space(1)))* GlobalList;
     const GlobalList glist_g = (GlobalList)glist;
     auto entry_of = [&](int i, int p) -> unsigned long long {
-      const int o = sh.st_off[i] - group_base + p;  // position in sh.list
-      if (o < staged_total) return sh.list[o];
+      const int o = sh.st_off[i] - group_base + p;  // position among the staged entries
+      if (o < staged_total) return staged_entry(o);
       if (COH) return ld_dev<true>(&glist[sh.st_off[i] + p]);
       return glist_g[sh.st_off[i] + p];
     };
@@ -212,8 +238,8 @@ __device__ __forceinline__ void retain_body(
         const int len = __builtin_amdgcn_readlane(len_v, st);
         const int off = __builtin_amdgcn_readlane(off_v, st) - group_base;
         int idx = tid < len ? off + tid : 0;
-        idx = idx < kRetList ? idx : 0;
-        return sh.list[idx];
+        idx = idx < kCap ? idx : 0;
+        return staged_entry(idx);
       };
       const int wv = __builtin_amdgcn_readfirstlane(wave);
       unsigned long long e_pre = first_entries(next);
@@ -282,8 +308,8 @@ __device__ __forceinline__ void retain_body(
           const int t = pos + tid;
           const bool in = t < len;
           unsigned long long e;
-          if (staged_all) e = sh.list[in ? off + t : 0];
-          else e = in ? entry_of(i, t) : sh.list[0];  // a list longer than the LDS region
+          if (staged_all) e = staged_entry(in ? off + t : 0);
+          else e = in ? entry_of(i, t) : staged_entry(0);  // a list longer than the LDS region
           const uint32_t j = (uint32_t)e;
           const uint32_t rw = sh.R[j >> 5];
           const bool cand = in && ((rw >> (j & 31)) & 1u) == 0u;
@@ -561,13 +587,14 @@ __device__ __forceinline__ void retain_body(
 }
 
 // grid: B blocks of kRetThreads: block b builds the retained set of sample b.
-template <int DT>
+template <int DT, bool PACKED>
 __global__ __launch_bounds__(kRetThreads) void k_retain(
     Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
     const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
     int* __restrict__ cu_keep_out, double* __restrict__ scr_f64, float two_tau) {
   __shared__ RetainShared sh;
-  retain_body<DT, false>(g, blockIdx.x, S, lists, piv, X, keep, cu_keep_out, scr_f64, two_tau, sh);
+  retain_body<DT, false, PACKED>(g, blockIdx.x, S, lists, piv, X, keep, cu_keep_out, scr_f64,
+                                 two_tau, sh);
 }
 
 }  // namespace dart
