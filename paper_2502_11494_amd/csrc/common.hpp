@@ -367,9 +367,11 @@ __device__ __forceinline__ void rows_l1_l2_f64(const void* const (&row)[R], int 
 }
 
 // Cosine of Eq. (7) between rows p and x in fp64; 0 if either norm is 0.
-template <int DT>
+// PPG: the squared norm of p is given (pp_given, an fp64 sum over the same row) and its
+// products are left out (a sixth of the arithmetic).
+template <int DT, bool PPG = false>
 __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* xrow, int D,
-                                                 int lane) {
+                                                 int lane, double pp_given = 0.0) {
   const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
   const u32x4* p = reinterpret_cast<const u32x4*>(prow);
   const u32x4* x = reinterpret_cast<const u32x4*>(xrow);
@@ -391,13 +393,13 @@ __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* x
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         dot = fma(pe[e], xe[e], dot);
-        pp = fma(pe[e], pe[e], pp);
+        if (!PPG) pp = fma(pe[e], pe[e], pp);
         xx = fma(xe[e], xe[e], xx);
       }
     }
   }
   dot = wave_sum(dot);
-  pp = wave_sum(pp);
+  pp = PPG ? pp_given : wave_sum(pp);
   xx = wave_sum(xx);
   double den = sqrt(pp) * sqrt(xx);
   return den > 0.0 ? dot / den : 0.0;

@@ -312,9 +312,10 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   const int rows = p.g.total_N;
   if (rows == 0) return DART_OK;
   const int blocks = (int)round_up8((rows + 4 * ROWS - 1) / (4 * ROWS));
-  // The 256 MB memory-side cache serves part of the score kernel's second pass if this
-  // pass leaves the rows there: measured -12% on that kernel for +8% on this one at 189
-  // MB (a net gain), no net gain at 264 MB, a loss for matrices that cannot fit.
+  // The 256 MB memory-side cache serves the score kernel's second pass if this pass leaves
+  // the rows there: measured 31 instead of 38 us on that kernel for 0.7 us more on this one
+  // at 189 MB; at 264 MB this pass loses 7 us and that one gains 0.7; a loss for matrices
+  // that cannot fit.
   // With spans the caller moves whole sequences afterwards, which sweeps that cache anyway:
   // measured slower with ordinary loads there.
   const bool keep = keep_cached && (double)rows * ldc * p.esz <= 224e6;
@@ -449,8 +450,10 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
   return DART_OK;
 }
 
+// pivot_norms_ready: this call has left the pivots' fp64 squared norms in the workspace.
 dart_status launch_retain(const Plan& p, const float* S, const int* piv, const void* X, int* keep,
-                          int* cu_keep, void* ws, hipStream_t st) {
+                          int* cu_keep, void* ws, hipStream_t st, bool pivot_norms_ready) {
+  const double* pl2 = pivot_norms_ready ? at<double>(ws, p.o_pl2) : nullptr;
   const float two_tau = (float)(2.0 * 1.01 * score_abs_bound(p.g.dtype, p.norms_given));
   const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   double* scr_f64 = at<double>(ws, p.o_scr_f64);
@@ -466,7 +469,7 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
   }
 #define DART_LAUNCH_RETAIN(DT, PK)                                                               \
   hipLaunchKernelGGL((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,   \
-                     piv, X, keep, cu_keep, scr_f64, two_tau)
+                     piv, X, keep, cu_keep, scr_f64, two_tau, pl2)
   if (p.g.dtype == kBF16) {
     if (p.retain_packed) DART_LAUNCH_RETAIN(kBF16, true); else DART_LAUNCH_RETAIN(kBF16, false);
   } else {
@@ -625,7 +628,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   DART_TRY(mark(3));
   DART_TRY(launch_order(p, S, ws, st));
   DART_TRY(mark(4));
-  DART_TRY(launch_retain(p, S, piv, X, keep, cu_keep, ws, st));
+  DART_TRY(launch_retain(p, S, piv, X, keep, cu_keep, ws, st, true));
   DART_TRY(mark(5));
   if (Y) DART_TRY(launch_gather(p, X, pos, keep, Y, pos_out, st));  // NULL: the caller compacts
   DART_TRY(mark(6));
@@ -720,7 +723,7 @@ dart_status dart_topk_keep(const dart_desc* desc, const float* S, const int32_t*
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(launch_given_status(p, piv, ws, st));
   DART_TRY(launch_order(p, S, ws, st));
-  return launch_retain(p, S, piv, X, keep, cu_keep, ws, st);
+  return launch_retain(p, S, piv, X, keep, cu_keep, ws, st, false);
 }
 
 dart_status dart_gather_compact(const dart_desc* desc, const void* X, const int64_t* pos,

@@ -368,8 +368,8 @@ __device__ __attribute__((noinline)) void fused_do_order(int b_in, int i_in) {
 __device__ __attribute__((noinline)) void fused_do_retain(int b_in, int i_in) {
   DART_FUSED_PARAMS(b_in, i_in);
   DART_FUSED_PREFETCH_BEGIN();
-  retain_body<kBF16, true>(g, b, a.S, a.lists, a.piv, a.X, a.keep, nullptr, a.scr, a.two_tau,
-                           fu_sh.ret);
+  retain_body<kBF16, true, false>(g, b, a.S, a.lists, a.piv, a.X, a.keep, nullptr, a.scr,
+                                  a.two_tau, fu_sh.ret, a.pl2);
   stores_done();
   DART_FUSED_PREFETCH_END();
 }

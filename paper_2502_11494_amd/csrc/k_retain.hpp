@@ -84,6 +84,8 @@ __device__ __forceinline__ bool pair_less(double sa, int ja, double sb, int jb) 
 // The retained set of sample b by one workgroup of kRetThreads threads.
 // lists: per sample at P*row0, stage lists back to back (see k_order_scores).
 // S: pivot-major scores.  X may be nullptr: then scores are taken as exact.
+// pl2 [B*Ppad] (optional): fp64 squared norms of the pivots' rows, if this call computed them
+// (the fp64 re-scoring then skips those products).
 // keep: packed, ascending per sample.  cu_keep_out (optional) [B+1].
 // scr_f64 [2*total_N] doubles: per-sample scratch at row0 (fallback sweep only).
 // COH: S, lists and piv were written, and keep will be read, by other workgroups of this
@@ -92,7 +94,7 @@ template <int DT, bool COH, bool PACKED = false>
 __device__ __forceinline__ void retain_body(
     const Geo& g, int b, const float* S, const unsigned long long* lists, const int* piv,
     const void* X, int* keep, int* cu_keep_out, double* scr_f64, float two_tau,
-    RetainShared& sh) {
+    RetainShared& sh, const double* pl2 = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   const Sample sm = sample_of(g, b);
@@ -428,8 +430,11 @@ __device__ __forceinline__ void retain_body(
     for (int q = wave; q < qn; q += kRetWaves) {  // a pair per wave: 16 row pairs in flight
       const int st = sh.q_stage[q];
       if (st >= fb_first) continue;  // will be walked again anyway
-      const double s0 = row_cosine_f64<DT>(pivot_row<COH>(g, X, esz, sm, b, st, piv),
-                                           Xb + (long)sh.q_idx[q] * rowbytes, g.D, lane);
+      const unsigned char* prow = pivot_row<COH>(g, X, esz, sm, b, st, piv);
+      const unsigned char* xrow = Xb + (long)sh.q_idx[q] * rowbytes;
+      const double s0 =
+          pl2 ? row_cosine_f64<DT, true>(prow, xrow, g.D, lane, ld_dev<COH>(&pl2[b * g.Ppad + st]))
+              : row_cosine_f64<DT>(prow, xrow, g.D, lane);
       if (lane == 0) sh.q_s64[q] = s0;
     }
     __syncthreads();
@@ -541,9 +546,11 @@ __device__ __forceinline__ void retain_body(
       for (int w = 0; w < kRetWaves; ++w) need -= sh.wcnt[w];
       const int nU = sh.cnt;
       const unsigned char* prow = pivot_row<COH>(g, X, esz, sm, b, i, piv);
+      const double pp_i = pl2 ? ld_dev<COH>(&pl2[b * g.Ppad + i]) : 0.0;
       for (int u = wave; u < nU; u += kRetWaves) {
-        const double s64 =
-            row_cosine_f64<DT>(prow, Xb + (long)sweep_idx[u] * rowbytes, g.D, lane);
+        const unsigned char* xrow = Xb + (long)sweep_idx[u] * rowbytes;
+        const double s64 = pl2 ? row_cosine_f64<DT, true>(prow, xrow, g.D, lane, pp_i)
+                               : row_cosine_f64<DT>(prow, xrow, g.D, lane);
         if (lane == 0) sweep_s64[u] = s64;
       }
       __syncthreads();
@@ -591,10 +598,11 @@ template <int DT, bool PACKED>
 __global__ __launch_bounds__(kRetThreads) void k_retain(
     Geo g, const float* __restrict__ S, const unsigned long long* __restrict__ lists,
     const int* __restrict__ piv, const void* __restrict__ X, int* __restrict__ keep,
-    int* __restrict__ cu_keep_out, double* __restrict__ scr_f64, float two_tau) {
+    int* __restrict__ cu_keep_out, double* __restrict__ scr_f64, float two_tau,
+    const double* __restrict__ pl2) {
   __shared__ RetainShared sh;
   retain_body<DT, false, PACKED>(g, blockIdx.x, S, lists, piv, X, keep, cu_keep_out, scr_f64,
-                                 two_tau, sh);
+                                 two_tau, sh, pl2);
 }
 
 }  // namespace dart
