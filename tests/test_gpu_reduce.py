@@ -131,6 +131,15 @@ def test_narrowest_and_widest_rows(make):
     check(make())
 
 
+def test_thousands_of_tiny_samples():
+    """Grids of thousands of workgroups with almost no work each: 3000 dense samples of 24
+    tokens, and 2500 packed samples of 10 to 59 tokens."""
+    check(W.image_batch(B=3000, N=24, D=64, P=2, K=6, n_centroids=6))
+    lengths = [int(x) for x in np.random.default_rng(1).integers(10, 60, 2500)]
+    check(W.ragged_batch(seed=101, B=2500, D=64, P=3, keep_num=300, keep_den=1000,
+                         lengths=lengths))
+
+
 def test_many_pivots_and_longest_sample():
     w = W.ragged_batch(B=2, D=256, P=64, lengths=[16384, 4100], keep_num=1, keep_den=8)
     check(w)
