@@ -33,6 +33,7 @@ CASES = [
     lambda: W.image_batch(B=1, N=64, D=8, P=64, K=64, n_centroids=4),            # one D-chunk
     lambda: W.image_batch(B=40, N=130, D=256, P=8, K=30, n_centroids=8),         # many samples
     lambda: W.ragged_batch(B=2, D=256, P=64, lengths=[16384, 4100], keep_num=1, keep_den=8),
+    lambda: W.image_batch(B=3000, N=24, D=64, P=2, K=6, n_centroids=6),          # thousands of chains
 ]
 
 
