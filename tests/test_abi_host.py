@@ -251,3 +251,9 @@ def test_score_tile_shape_follows_the_batch_and_the_override():
     finally:
         del os.environ["DART_SCORE_TILE"]
     assert D.dart_workspace_bytes(desc) > 0
+    L = binding.lib()
+    w = C.c_int32(7)
+    assert L.dart_score_tile_shape(C.byref(desc), None, C.byref(w)) == D.DART_ERR_NULL
+    assert L.dart_score_tile_shape(C.byref(desc), C.byref(w), None) == D.DART_ERR_NULL
+    assert L.dart_score_tile_shape(None, C.byref(w), C.byref(w)) == D.DART_ERR_NULL
+    assert w.value == 7  # nothing is written on an error
