@@ -428,8 +428,13 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   const double* pl2 = at<double>(ws, p.o_pl2);
   const double* l2sq = p.norms_given ? at<double>(ws, p.o_l2) : nullptr;
   if (p.g.dtype == kF32) {
-    hipLaunchKernelGGL(k_scores_f32, dim3(p.tiles_bound * (p.g.tile_rows / kF32Rows)), dim3(256), 0, st,
-                       p.g, X, piv, S);
+    // two rows per block while four would not give every compute unit two blocks
+    if (p.g.total_N <= 4 * 2 * compute_units())
+      hipLaunchKernelGGL(k_scores_f32<2>, dim3(p.tiles_bound * (p.g.tile_rows / 2)), dim3(256), 0,
+                         st, p.g, X, piv, S);
+    else
+      hipLaunchKernelGGL(k_scores_f32<4>, dim3(p.tiles_bound * (p.g.tile_rows / 4)), dim3(256), 0,
+                         st, p.g, X, piv, S);
     DART_LAUNCH_CHECK();
     return DART_OK;
   }

@@ -327,19 +327,21 @@ __global__ __launch_bounds__(WAVES * 64) void k_scores_ksplit(Geo g, const void*
   score_tile_ksplit<NB, KS, WAVES, TAIL, XN, false>(g, sm, b, tl, X, piv, pl2, l2sq, S, sh);
 }
 
-// fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / 4)
-// blocks of 256: a block owns 4 consecutive token rows of one sample and 8 pivots at a
-// time; its 4 waves split D (piece t of a row goes to wave (t / 64) % 4), so that small
+// fp32 hidden states, fp64 arithmetic on the vector ALU.  grid: tiles * (tile_rows / ROWS)
+// blocks of 256: a block owns ROWS (4 or 2) consecutive token rows of one sample and 8 pivots
+// at a time; its 4 waves split D (piece t of a row goes to wave (t / 64) % 4), so that small
 // batches -- the only ones this path is meant for -- still spread over the chip and a wave's
 // chain of dependent loads is a quarter as long.  The next pieces are requested before the
 // current ones are used.  The 4 partial sums of a dot product are added in wave order, each
 // wave's own sum is a fixed lane-strided order plus butterfly: a score depends only on the
-// two rows' bytes.
-constexpr int kF32Rows = 4, kF32Piv = 8;
+// two rows' bytes.  (Rows per block, measured on one 576-token image: 1, 2, 4, 8 rows give
+// 19.4, 15.6, 16.3, 26.8 us by events; 2 rows where 4 would leave compute units idle.)
+constexpr int kF32Piv = 8;
+template <int kF32Rows>
 __global__ __launch_bounds__(256) void k_scores_f32(Geo g, const void* __restrict__ X,
                                                     const int* __restrict__ piv,
                                                     float* __restrict__ S) {
-  // per wave: dot[4][8], pp[8], xx[4]
+  // per wave: dot[ROWS][8], pp[8], xx[ROWS]
   __shared__ double red[4][kF32Rows * kF32Piv + kF32Piv + kF32Rows];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, tl;
