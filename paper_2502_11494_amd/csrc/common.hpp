@@ -12,6 +12,7 @@ typedef float f32x4v __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kMaxP = 64;        // pivots per sample
 constexpr int kMaxN = 16384;     // tokens per sample
+constexpr int kMaxBySize = 256;  // samples a ragged batch may have to be ordered by length
 
 enum { kF32 = 0, kBF16 = 1 };
 
@@ -69,6 +70,9 @@ struct Geo {
   // ragged only, filled by k_prepare: packed offsets of keep and of score tiles
   const int* cu_keep;
   const int* tile_start;
+  // ragged batches of at most kMaxBySize samples, filled by k_prepare: the samples from the
+  // longest to the shortest (nullptr: batch order)
+  const int* by_size;
   // Pivots from outside the scored tokens (text-token pivots): the last Pe of the P pivots
   // of every sample are rows of E (sample b, outside pivot e at row b*Pe + e, stride lde
   // elements); the first Pin = P - Pe are tokens of the sample.

@@ -43,7 +43,7 @@ struct Plan {
   int tiles_bound;       // upper bound of the number of score tiles (g.tile_rows rows each)
   // workspace offsets
   size_t o_status, o_cu_keep, o_tile_start, o_l1, o_piv, o_pl2, o_S, o_lists, o_scr_f64,
-      o_l2, o_sync, o_nstart, o_sstart, o_gstart, total;
+      o_l2, o_sync, o_nstart, o_sstart, o_gstart, o_by_size, total;
   bool fusable;  // the shape and modes the one-launch path covers (see reduce_impl)
   bool norms_given;  // this call's norm pass also leaves the squared token norms
   int ks_waves, ks_split;  // bf16 score kernel: waves per workgroup and groups of them (fp32: 0)
@@ -217,6 +217,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.cu = d->cu_seqlens;
   g.cu_keep = nullptr;
   g.tile_start = nullptr;
+  g.by_size = nullptr;
   g.Pe = d->P_ext;
   g.Pin = Pin;
   g.lde = d->P_ext > 0 ? d->ext_ld : 0;
@@ -269,6 +270,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   } else {
     p.o_sync = p.o_nstart = p.o_sstart = p.o_gstart = o;
   }
+  p.o_by_size = take(sizeof(int) * kMaxBySize);
   p.norms_given = false;
   p.total = o;
   return DART_OK;
@@ -297,11 +299,15 @@ dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
   if (p.g.cu == nullptr) return DART_OK;
   int* cu_keep = at<int>(ws, p.o_cu_keep);
   int* tile_start = at<int>(ws, p.o_tile_start);
+  // (only where the ordering kernel's B*P workgroups, one per compute unit, need several rounds)
+  int* by_size = p.g.B <= kMaxBySize && (long)p.g.B * p.g.P > compute_units()
+                     ? at<int>(ws, p.o_by_size) : nullptr;
   hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1024), 0, st, p.g, cu_keep, tile_start,
-                     at<int>(ws, p.o_status));
+                     at<int>(ws, p.o_status), by_size);
   DART_LAUNCH_CHECK();
   p.g.cu_keep = cu_keep;
   p.g.tile_start = tile_start;
+  p.g.by_size = by_size;
   return DART_OK;
 }
 

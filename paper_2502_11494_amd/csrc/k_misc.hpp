@@ -12,11 +12,17 @@ namespace dart {
 // 1 if a non-empty sample was rejected (its sizes or budget, or a span that leaves X), 2 if
 // cu_seqlens itself is not a non-decreasing sequence from 0 to total_N (then every sample
 // is skipped).
+// by_size (optional, B <= kMaxBySize): the samples ordered from the longest to the shortest
+// (ties in batch order).  The ordering kernel runs one workgroup per compute unit, a list's
+// time grows with its sample's length, and workgroups start in id order: with the long
+// samples first the short ones fill the gaps at the end instead of the other way round.
 __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_keep,
                                                   int* __restrict__ tile_start,
-                                                  int* __restrict__ status) {
+                                                  int* __restrict__ status,
+                                                  int* __restrict__ by_size) {
   __shared__ int red[2][16];
   __shared__ int carry[2];
+  __shared__ int len_of[kMaxBySize];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   int broken = 0;
   for (int b = tid; b < g.B; b += 1024) broken |= g.cu[b + 1] < g.cu[b] ? 1 : 0;
@@ -69,6 +75,16 @@ __global__ __launch_bounds__(1024) void k_prepare(Geo g, int* __restrict__ cu_ke
     __syncthreads();
   }
   bad = __syncthreads_or(bad);
+  if (by_size != nullptr) {  // (block-uniform; g.B <= kMaxBySize)
+    const int n = tid < g.B && !broken ? g.cu[tid + 1] - g.cu[tid] : 0;
+    if (tid < g.B) len_of[tid] = n;
+    __syncthreads();
+    if (tid < g.B) {
+      int rank = 0;
+      for (int o = 0; o < g.B; ++o) rank += (len_of[o] > n || (len_of[o] == n && o < tid)) ? 1 : 0;
+      by_size[rank] = tid;
+    }
+  }
   if (tid == 0) {
     cu_keep[g.B] = carry[0];
     tile_start[g.B] = carry[1];

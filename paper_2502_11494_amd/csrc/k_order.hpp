@@ -43,12 +43,15 @@ __device__ __forceinline__ void order_scores_body(const Geo& g, int b, int i, co
     st_dev<COH>(&out[t], t < first ? sh.buf[t] : sh.buf[kSelThreads + (t - first)]);
 }
 
-// grid: B*P blocks of THREADS (1024); block (b, i).
+// grid: B*P blocks of THREADS (1024); block (b, i), the samples from the longest to the
+// shortest where g.by_size says so.
 template <int THREADS>
 __global__ __launch_bounds__(THREADS) void k_order_scores(
     Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
   __shared__ SelectShared<THREADS> sh;
-  order_scores_body<THREADS, false>(g, blockIdx.x / g.P, blockIdx.x % g.P, S, lists, sh);
+  const int slot = blockIdx.x / g.P;
+  const int b = g.by_size ? g.by_size[slot] : slot;
+  order_scores_body<THREADS, false>(g, b, blockIdx.x % g.P, S, lists, sh);
 }
 
 }  // namespace dart
