@@ -352,16 +352,43 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   return DART_OK;
 }
 
+// Values a thread of the selection kernels keeps in registers: 1024 threads times this many
+// cover the longest sample (see k_select.hpp); instantiated for 1, 2, 3, 4, 6, 8, 10, 12, 16.
+int values_per_thread(int max_n) {
+  const int need = (max_n + 1023) / 1024;
+  for (int per : {1, 2, 3, 4, 6, 8, 10, 12, 16})
+    if (per >= need) return per;
+  return 16;
+}
+#define DART_FOR_VALUES_PER_THREAD(per, LAUNCH)                                                  \
+  switch (per) {                                                                                 \
+    case 1: LAUNCH(1); break;                                                                    \
+    case 2: LAUNCH(2); break;                                                                    \
+    case 3: LAUNCH(3); break;                                                                    \
+    case 4: LAUNCH(4); break;                                                                    \
+    case 6: LAUNCH(6); break;                                                                    \
+    case 8: LAUNCH(8); break;                                                                    \
+    case 10: LAUNCH(10); break;                                                                  \
+    case 12: LAUNCH(12); break;                                                                  \
+    default: LAUNCH(16); break;                                                                  \
+  }
+
 dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, int Dc, long ldc,
                                  const float* l1, int* piv, void* ws, hipStream_t st) {
   const float tau = (float)l1_rel_bound(p.g.dtype, Dc);
   double* pl2 = at<double>(ws, p.o_pl2);
   double* scr = at<double>(ws, p.o_scr_f64);
   // 1024 threads: a 256-thread variant measured slower even for short samples
-#define DART_LAUNCH_PIVOTS(DT)                                                                   \
-  hipLaunchKernelGGL((k_select_pivots<DT, 1024>), dim3(p.g.B), dim3(1024), 0, st, p.g, X, C, Dc,   \
-                     ldc, l1, piv, pl2, scr, tau)
-  if (p.g.dtype == kBF16) DART_LAUNCH_PIVOTS(kBF16); else DART_LAUNCH_PIVOTS(kF32);
+#define DART_LAUNCH_PIVOTS(PER)                                                                  \
+  do {                                                                                           \
+    if (p.g.dtype == kBF16)                                                                      \
+      hipLaunchKernelGGL((k_select_pivots<kBF16, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,    \
+                         p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_select_pivots<kF32, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,     \
+                         p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
+  } while (0)
+  DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_PIVOTS);
 #undef DART_LAUNCH_PIVOTS
   DART_LAUNCH_CHECK();
   return DART_OK;
@@ -456,7 +483,11 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
   if (p.g.score_mode != 0) return DART_OK;  // the single-threshold rule orders nothing per pivot
   unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   // 1024 threads: a 256-thread variant measured slower even for short samples
-  hipLaunchKernelGGL(k_order_scores<1024>, dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, lists);
+#define DART_LAUNCH_ORDER(PER)                                                                   \
+  hipLaunchKernelGGL((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, \
+                     lists)
+  DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_ORDER);
+#undef DART_LAUNCH_ORDER
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -469,12 +500,23 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
   const unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   double* scr_f64 = at<double>(ws, p.o_scr_f64);
   if (p.g.score_mode != 0) {  // one threshold for all pivots: no stage lists
-    if (p.g.dtype == kBF16)
-      hipLaunchKernelGGL((k_keep_single<kBF16>), dim3(p.g.B), dim3(1024), 0, st, p.g, S, piv, X,
-                         keep, cu_keep, scr_f64, two_tau, p.g.score_mode);
-    else
-      hipLaunchKernelGGL((k_keep_single<kF32>), dim3(p.g.B), dim3(1024), 0, st, p.g, S, piv, X,
-                         keep, cu_keep, scr_f64, two_tau, p.g.score_mode);
+#define DART_LAUNCH_SINGLE(PER)                                                                  \
+  do {                                                                                           \
+    if (p.g.dtype == kBF16)                                                                      \
+      hipLaunchKernelGGL((k_keep_single<kBF16, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,    \
+                         piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_keep_single<kF32, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,     \
+                         piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
+  } while (0)
+    {
+      const int per = values_per_thread(p.g.max_N);
+      if (per <= 4) DART_LAUNCH_SINGLE(4);
+      else if (per <= 8) DART_LAUNCH_SINGLE(8);
+      else if (per <= 12) DART_LAUNCH_SINGLE(12);
+      else DART_LAUNCH_SINGLE(16);
+    }
+#undef DART_LAUNCH_SINGLE
     DART_LAUNCH_CHECK();
     return DART_OK;
   }

@@ -13,10 +13,10 @@ namespace dart {
 // region of sample b starts at P*row0(b) and holds the stage lists back to back
 // (see list_offset).
 // COH: S was written, and lists will be read, by other workgroups of this launch.
-template <int THREADS, bool COH>
+template <int THREADS, bool COH, int PER = kSelPerThread>
 __device__ __forceinline__ void order_scores_body(const Geo& g, int b, int i, const float* S,
                                                   unsigned long long* lists,
-                                                  SelectShared<THREADS>& sh) {
+                                                  SelectShared<THREADS, PER>& sh) {
   constexpr int kSelThreads = THREADS;
   const int tid = threadIdx.x;
   const Sample sm = sample_of(g, b);
@@ -26,14 +26,14 @@ __device__ __forceinline__ void order_scores_body(const Geo& g, int b, int i, co
   const int want = sp.stage_len(n, i);
   if (want == 0) return;  // the stage takes nothing
   const float* row = S + (long)g.P * sm.row0 + (long)i * n;
-  float v[kSelPerThread];
+  float v[PER];
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e) {
+  for (int e = 0; e < PER; ++e) {
     int j = tid + e * kSelThreads;
     v[e] = (e * kSelThreads < n && j < n) ? ld_dev<COH>(&row[j]) + 0.0f : 0.f;
   }
   int first = 0;  // keys of the first sorted run (all of them unless the sort was split)
-  collect_sorted<THREADS, true>(v, n, want, tid, sh, &first);
+  collect_sorted<THREADS, true, PER>(v, n, want, tid, sh, &first);
   // offset of this stage's list = sum of the earlier stages' lengths: lane s of every wave
   // computes stage s's length, a wave scan adds them up (no loop over the stages)
   const int len_v = (tid & 63) < g.P ? sp.stage_len(n, tid & 63) : 0;
@@ -44,14 +44,14 @@ __device__ __forceinline__ void order_scores_body(const Geo& g, int b, int i, co
 }
 
 // grid: B*P blocks of THREADS (1024); block (b, i), the samples from the longest to the
-// shortest where g.by_size says so.
-template <int THREADS>
+// shortest where g.by_size says so.  PER*THREADS >= the longest sample.
+template <int THREADS, int PER>
 __global__ __launch_bounds__(THREADS) void k_order_scores(
     Geo g, const float* __restrict__ S, unsigned long long* __restrict__ lists) {
-  __shared__ SelectShared<THREADS> sh;
+  __shared__ SelectShared<THREADS, PER> sh;
   const int slot = blockIdx.x / g.P;
   const int b = g.by_size ? g.by_size[slot] : slot;
-  order_scores_body<THREADS, false>(g, b, blockIdx.x % g.P, S, lists, sh);
+  order_scores_body<THREADS, false, PER>(g, b, blockIdx.x % g.P, S, lists, sh);
 }
 
 }  // namespace dart

@@ -14,9 +14,9 @@ namespace dart {
 
 constexpr int kPivLdsCand = 512;  // candidates whose fp64 norms fit in LDS
 
-template <int THREADS>
+template <int THREADS, int PER = kSelPerThread>
 struct PivotShared {
-  SelectShared<THREADS> sel;
+  SelectShared<THREADS, PER> sel;
   double c64[kPivLdsCand];
   double l2[kPivLdsCand];
   int nU;
@@ -27,10 +27,10 @@ struct PivotShared {
 // written); pl2 [B*Ppad] squared L2 norms of the pivots' hidden-state rows (0 for the
 // other slots); scr [2*total_N] doubles.
 // COH: l1 was written, and piv / pl2 will be read, by other workgroups of this launch.
-template <int DT, int THREADS, bool COH>
+template <int DT, int THREADS, bool COH, int PER = kSelPerThread>
 __device__ __forceinline__ void select_pivots_body(
     const Geo& g, int b, const void* X, const void* C, int Dc, long ldc, const float* l1,
-    int* piv, double* pl2, double* scr, float tau, PivotShared<THREADS>& sh) {
+    int* piv, double* pl2, double* scr, float tau, PivotShared<THREADS, PER>& sh) {
   constexpr int kSelThreads = THREADS;
   constexpr int kSelWaves = THREADS / kWave;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -42,9 +42,9 @@ __device__ __forceinline__ void select_pivots_body(
   const int n = sm.n, P = g.Pin;  // pivots chosen among the tokens; stride of piv is g.P
   const float sign = g.mode == kMaxL1 ? -1.f : 1.f;  // "lowest" of -norm = largest norm
 
-  float v[kSelPerThread];
+  float v[PER];
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e) {
+  for (int e = 0; e < PER; ++e) {
     int j = tid + e * kSelThreads;
     v[e] = (e * kSelThreads < n && j < n) ? sign * ld_dev<COH>(&l1[sm.row0 + j]) + 0.0f : 0.f;
   }
@@ -52,12 +52,12 @@ __device__ __forceinline__ void select_pivots_body(
   // fp32 value, {v <= vsel + 2.5 tau |vsel|} holds every token within the norm pass's error of
   // the P-th best: usually P and a handful more.  They are ranked in fp64 below, so neither
   // their order nor the exact P-th value is needed here.
-  const float vsel = rank_upper_bound<THREADS>(v, n, P, tid, sh.sel);
+  const float vsel = rank_upper_bound<THREADS, PER>(v, n, P, tid, sh.sel);
   const float thr = vsel + 2.5f * tau * fabsf(vsel);
   if (tid == 0) sh.nU = 0;
   __syncthreads();
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e) {
+  for (int e = 0; e < PER; ++e) {
     const int j = tid + e * kSelThreads;
     if (e * kSelThreads < n && j < n && v[e] <= thr)
       sh.sel.buf[atomicAdd(&sh.nU, 1)] = ((unsigned long long)mono_of(v[e]) << 32) | (unsigned)j;
@@ -132,13 +132,15 @@ __device__ __forceinline__ void select_pivots_body(
 }
 
 // grid: B blocks of THREADS (1024): block b selects the pivots of sample b.
-template <int DT, int THREADS>
+// PER*THREADS >= the longest sample.
+template <int DT, int THREADS, int PER>
 __global__ __launch_bounds__(THREADS) void k_select_pivots(
     Geo g, const void* __restrict__ X, const void* __restrict__ C, int Dc, long ldc,
     const float* __restrict__ l1, int* __restrict__ piv, double* __restrict__ pl2,
     double* __restrict__ scr, float tau) {
-  __shared__ PivotShared<THREADS> sh;
-  select_pivots_body<DT, THREADS, false>(g, blockIdx.x, X, C, Dc, ldc, l1, piv, pl2, scr, tau, sh);
+  __shared__ PivotShared<THREADS, PER> sh;
+  select_pivots_body<DT, THREADS, false, PER>(g, blockIdx.x, X, C, Dc, ldc, l1, piv, pl2, scr, tau,
+                                              sh);
 }
 
 }  // namespace dart

@@ -6,22 +6,28 @@
 // compacted and bitonic-sorted.  Ties need no special care: the composite key is
 // unique, so the sort alone yields (value ascending, index ascending).
 //
-// A thread keeps up to 16 values in registers, so a block of THREADS threads
-// handles n <= 16*THREADS values (1024 threads for the 16384-token limit).
+// A thread keeps PER values in registers (at most 16), so a block of THREADS threads handles
+// n <= PER*THREADS values (1024 threads and PER = 16 for the 16384-token limit).  PER is a
+// template parameter chosen by the host from the longest sample: the loops over a thread's
+// values are unrolled and a slot past the sample's end still issues its instructions with
+// every lane switched off (measured on 2880-token samples: PER = 4 instead of 16 takes 1.9 us
+// off pivot selection and 1.7 us off the ordering kernel).
 #pragma once
 #include "common.hpp"
 
 namespace dart {
 
-constexpr int kSelPerThread = 16;  // values a thread keeps in registers
+constexpr int kSelPerThread = 16;  // most values a thread keeps in registers
+constexpr int pow2_at_least(int v) { int p = 1; while (p < v) p <<= 1; return p; }
 constexpr int kSelBuckets = 1024;
 // Requests for more than kSelCountMin keys are put in order by counting instead of a bitonic
 // sort (measured cross-over), unless one fine histogram bucket holds more than kSelMaxSeg of them (massive ties).
 constexpr int kSelCountMin = 128, kSelMaxSeg = 64;
 
-template <int THREADS>
+template <int THREADS, int PER = kSelPerThread>
 struct SelectShared {
-  unsigned long long buf[THREADS * kSelPerThread];  // compacted keys, then sorted
+  static constexpr int kBuf = pow2_at_least(THREADS * PER);  // (the sorts pad to a power of two)
+  unsigned long long buf[kBuf];  // compacted keys, then sorted
   int hist[kSelBuckets];
   float redf[2 * (THREADS / kWave)];
   float redg[THREADS / kWave];
@@ -64,16 +70,16 @@ struct BucketSplit {
 // v[e] belongs to index tid + e*THREADS; the same result on every thread (four barriers).
 // (collect_sorted below repeats these steps because it goes on to use every thread's own
 // bucket counts.)
-template <int THREADS>
-__device__ __forceinline__ BucketSplit bucket_split(const float (&v)[kSelPerThread], int n, int want,
-                                                    int tid, SelectShared<THREADS>& sh) {
+template <int THREADS, int PER>
+__device__ __forceinline__ BucketSplit bucket_split(const float (&v)[PER], int n, int want,
+                                                    int tid, SelectShared<THREADS, PER>& sh) {
   constexpr int kSelWaves = THREADS / kWave;
   constexpr int kSelBucketsPerThread = kSelBuckets / THREADS;
   const int lane = tid & 63, w = tid >> 6;
   const int ne = __builtin_amdgcn_readfirstlane((n + THREADS - 1) / THREADS);
   float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e)
+  for (int e = 0; e < PER; ++e)
     if (e < ne && tid + e * THREADS < n) {
       lo = fminf(lo, v[e]);
       hi = fmaxf(hi, v[e]);
@@ -98,7 +104,7 @@ __device__ __forceinline__ BucketSplit bucket_split(const float (&v)[kSelPerThre
   bs.lo = lo;
   bs.scale = range > 0.f ? (float)kSelBuckets / range : 0.f;
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e)
+  for (int e = 0; e < PER; ++e)
     if (e < ne && tid + e * THREADS < n) atomicAdd(&sh.hist[bs.bucket(v[e])], 1);
   __syncthreads();
   int h[kSelBucketsPerThread], mine = 0;
@@ -136,15 +142,15 @@ __device__ __forceinline__ BucketSplit bucket_split(const float (&v)[kSelPerThre
 // An upper bound of the want-th lowest of the n values that is itself one of the values: the
 // largest value of the buckets up to d*.  For callers that need a superset of the `want`
 // lowest, not their order (five barriers, no sort).
-template <int THREADS>
-__device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread], int n, int want,
-                                                  int tid, SelectShared<THREADS>& sh) {
+template <int THREADS, int PER>
+__device__ __forceinline__ float rank_upper_bound(const float (&v)[PER], int n, int want,
+                                                  int tid, SelectShared<THREADS, PER>& sh) {
   constexpr int kSelWaves = THREADS / kWave;
   const int lane = tid & 63, w = tid >> 6;
-  const BucketSplit bs = bucket_split<THREADS>(v, n, want, tid, sh);
+  const BucketSplit bs = bucket_split<THREADS, PER>(v, n, want, tid, sh);
   float top = -INFINITY;  // largest value of the buckets <= d*
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e)
+  for (int e = 0; e < PER; ++e)
     if (e * THREADS < n && tid + e * THREADS < n && bs.bucket(v[e]) <= bs.dstar)
       top = fmaxf(top, v[e]);
   top = wave_max(top);
@@ -155,7 +161,7 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
   return top;
 }
 
-// v[e] belongs to index tid + e*THREADS (n <= 16*THREADS); entries with index >= n are ignored.
+// v[e] belongs to index tid + e*THREADS (n <= PER*THREADS); entries with index >= n are ignored.
 // Compacts every entry whose bucket is <= d* and sorts;
 // returns how many were compacted (>= min(want, n)); the same value on every thread.
 // part2 (optional): when more than THREADS keys are compacted
@@ -165,9 +171,9 @@ __device__ __forceinline__ float rank_upper_bound(const float (&v)[kSelPerThread
 // buf[THREADS..).  Otherwise *part2 is the returned count (one run at buf[0..)).
 // COUNTING: long requests may be ordered by counting (see below); callers that only ever ask for
 // a few keys leave it off and keep the shorter code.
-template <int THREADS, bool COUNTING = false>
-__device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], int n, int want,
-                                              int tid, SelectShared<THREADS>& sh,
+template <int THREADS, bool COUNTING = false, int PER = kSelPerThread>
+__device__ __forceinline__ int collect_sorted(const float (&v)[PER], int n, int want,
+                                              int tid, SelectShared<THREADS, PER>& sh,
                                               int* part2 = nullptr) {
   constexpr int kSelThreads = THREADS;
   constexpr int kSelWaves = THREADS / kWave;
@@ -177,7 +183,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
   // block min / max
   float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e)
+  for (int e = 0; e < PER; ++e)
     if (e < ne && tid + e * kSelThreads < n) {
       lo = fminf(lo, v[e]);
       hi = fmaxf(hi, v[e]);
@@ -206,7 +212,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     return d > kSelBuckets - 1 ? kSelBuckets - 1 : d;
   };
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e)
+  for (int e = 0; e < PER; ++e)
     if (e < ne && tid + e * kSelThreads < n) atomicAdd(&sh.hist[bucket(v[e])], 1);
   __syncthreads();
   // inclusive scan of the histogram: thread t owns kSelBucketsPerThread consecutive buckets
@@ -248,7 +254,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     // there and every key finds its rank inside its bucket's segment.  Six barriers instead of
     // a bitonic network's dozens.  A segment longer than kSelMaxSeg (massive ties) sends the
     // list to the network below.
-    constexpr int kCap = kSelThreads * kSelPerThread / 2;  // keys that fit twice in buf
+    constexpr int kCap = SelectShared<THREADS, PER>::kBuf / 2;  // keys that fit twice in buf
     int dl = sh.dstar;
     dl = dl < 0 ? 0 : (dl < kSelBuckets ? dl : kSelBuckets - 1);  // (want >= 1 makes it valid anyway)
     {
@@ -273,7 +279,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
       for (int q = 0; q < kSelBucketsPerThread; ++q) sh.hist[tid + q * kSelThreads] = 0;
       __syncthreads();
 #pragma unroll
-      for (int e = 0; e < kSelPerThread; ++e)
+      for (int e = 0; e < PER; ++e)
         if (e < ne && tid + e * kSelThreads < n && bucket(v[e]) <= dl)
           atomicAdd(&sh.hist[fine(v[e])], 1);
       __syncthreads();
@@ -299,7 +305,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
         __syncthreads();
         unsigned long long* tmp = sh.buf + kCap;
 #pragma unroll
-        for (int e = 0; e < kSelPerThread; ++e) {
+        for (int e = 0; e < PER; ++e) {
           const int j = tid + e * kSelThreads;
           if (e < ne && j < n && bucket(v[e]) <= dl) {
             const int pos = atomicAdd(&sh.hist[fine(v[e])], 1);
@@ -343,7 +349,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     if (cstar > kSelThreads && dmid >= 0 && dmid < dlim && cmid > 0 && cstar - cmid <= kSelThreads) {
       // two runs: buckets <= dmid (cmid keys) and (dmid, dlim] (cstar - cmid keys)
 #pragma unroll
-      for (int e = 0; e < kSelPerThread; ++e) {
+      for (int e = 0; e < PER; ++e) {
         const int j = tid + e * kSelThreads;
         if (e < ne && j < n) {
           const int d = bucket(v[e]);
@@ -367,7 +373,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[kSelPerThread], i
     }
   }
 #pragma unroll
-  for (int e = 0; e < kSelPerThread; ++e) {
+  for (int e = 0; e < PER; ++e) {
     const int j = tid + e * kSelThreads;
     if (e < ne && j < n && bucket(v[e]) <= dlim) {
       const int slot = atomicAdd(&sh.count, 1);

@@ -18,8 +18,9 @@ namespace dart {
 
 enum { kAggMin = 1, kAggMax = 2 };
 
+template <int PER>
 struct SingleShared {
-  SelectShared<1024> sel;
+  SelectShared<1024, PER> sel;
   uint32_t R[kMaxN / 32];
   int piv[kMaxP];
   int wcnt[16];
@@ -27,14 +28,16 @@ struct SingleShared {
 };
 
 // grid: B blocks of 1024.  S: pivot-major scores.  X may be nullptr (scores exact).
+// PER (a multiple of 4): values per thread, PER*1024 >= the longest sample.
 // scr_f64 [2*total_N]: per sample, fp64 aggregates of the band at row0 and their
 // indices (as ints) at total_N + row0.
-template <int DT>
+template <int DT, int PER>
 __global__ __launch_bounds__(1024) void k_keep_single(
     Geo g, const float* __restrict__ S, const int* __restrict__ piv, const void* __restrict__ X,
     int* __restrict__ keep, int* __restrict__ cu_keep_out, double* __restrict__ scr_f64,
     float two_tau, int agg) {
-  __shared__ SingleShared sh;
+  static_assert(PER % 4 == 0, "the score loads go four slots at a time");
+  __shared__ SingleShared<PER> sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.x;
   const Sample sm = sample_of(g, b);
@@ -67,13 +70,13 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     // Latency-bound (a few workgroups on the whole chip): 4 slots x 8 pivots = 32 independent
     // loads per batch.  Indices are clamped instead of predicated so that the loads of a
     // batch issue together; re-reading an element does not change a minimum or maximum.
-    float v[kSelPerThread];
+    float v[PER];
     const float none = agg == kAggMin ? INFINITY : -INFINITY;
 #pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) v[e] = none;
+    for (int e = 0; e < PER; ++e) v[e] = none;
     for (int i0 = 0; i0 < P; i0 += 8) {
 #pragma unroll
-      for (int e0 = 0; e0 < kSelPerThread; e0 += 4) {
+      for (int e0 = 0; e0 < PER; e0 += 4) {
         if (e0 * 1024 < n) {
           float s[4][8];
 #pragma unroll
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       }
     }
 #pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int j = tid + e * 1024;
       if (!(e * 1024 < n && j < n) || ((sh.R[j >> 5] >> (j & 31)) & 1u)) v[e] = 2.0f;
     }
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     // alone is put in order, and its r-th and (r+1)-th keys are the last taken (fa) and the
     // first refused (fb).
     const int want = m + 1 < n ? m + 1 : n;
-    const BucketSplit bs = bucket_split<1024>(v, n, want, tid, sh.sel);
+    const BucketSplit bs = bucket_split<1024, PER>(v, n, want, tid, sh.sel);
     if (tid == 0) {
       sh.sel.count = 0;
       sh.below = 0;
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     __syncthreads();
     float max_below = -INFINITY;  // largest aggregate of the buckets below d* (fa if r == 0)
 #pragma unroll
-    for (int e = 0; e < kSelPerThread; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int j = tid + e * 1024;
       if (e * 1024 < n && j < n) {
         const int d = bs.bucket(v[e]);
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
     const bool certain = Xb == nullptr || fb - fa > two_tau;
     if (certain) {
 #pragma unroll
-      for (int e = 0; e < kSelPerThread; ++e) {
+      for (int e = 0; e < PER; ++e) {
         const int j = tid + e * 1024;
         if (e * 1024 < n && j < n && bs.bucket(v[e]) < bs.dstar) atomicOr(&sh.R[j >> 5], 1u << (j & 31));
       }
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(1024) void k_keep_single(
       const float lo = fa - two_tau, hi = fb + two_tau;
       int taken = 0;
 #pragma unroll
-      for (int e = 0; e < kSelPerThread; ++e) {
+      for (int e = 0; e < PER; ++e) {
         const int j = tid + e * 1024;
         if (e * 1024 < n && j < n) {
           const float a = v[e];
