@@ -486,7 +486,13 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
 #define DART_LAUNCH_ORDER(PER)                                                                   \
   hipLaunchKernelGGL((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, \
                      lists)
-  DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_ORDER);
+  // samples of at most 1024 tokens: 512 threads with two values each (measured on 576-token
+  // samples: 8.9 against 9.6 us; pivot selection is slower that way, 3072-token samples too)
+  if (p.g.max_N <= 1024)
+    hipLaunchKernelGGL((k_order_scores<512, 2>), dim3(p.g.B * p.g.P), dim3(512), 0, st, p.g, S,
+                       lists);
+  else
+    DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_ORDER);
 #undef DART_LAUNCH_ORDER
   DART_LAUNCH_CHECK();
   return DART_OK;
