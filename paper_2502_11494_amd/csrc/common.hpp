@@ -373,7 +373,9 @@ __device__ __forceinline__ void rows_l1_l2_f64(const void* const (&row)[R], int 
 // Cosine of Eq. (7) between rows p and x in fp64; 0 if either norm is 0.
 // PPG: the squared norm of p is given (pp_given, an fp64 sum over the same row) and its
 // products are left out (a sixth of the arithmetic).
-template <int DT, bool PPG = false>
+// INF: 16-byte pieces of each row a lane keeps in flight (8: a whole 8 KiB row pair at once;
+// fewer where registers are short).  The sums run in piece order whatever INF is.
+template <int DT, bool PPG = false, int INF = 8>
 __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* xrow, int D,
                                                  int lane, double pp_given = 0.0) {
   const int pieces = D * (DT == kBF16 ? 2 : 4) / 16;
@@ -381,16 +383,16 @@ __device__ __forceinline__ double row_cosine_f64(const void* prow, const void* x
   const u32x4* x = reinterpret_cast<const u32x4*>(xrow);
   const u32x4 zero = {0u, 0u, 0u, 0u};
   double dot = 0.0, pp = 0.0, xx = 0.0;
-  for (int t0 = 0; t0 < pieces; t0 += kWave * 8) {
-    u32x4 pv[8], xv[8];  // a whole 8 KiB row pair is in flight at once
+  for (int t0 = 0; t0 < pieces; t0 += kWave * INF) {
+    u32x4 pv[INF], xv[INF];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < INF; ++u) {
       int t = t0 + u * kWave + lane;
       pv[u] = t < pieces ? p[t] : zero;
       xv[u] = t < pieces ? x[t] : zero;
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < INF; ++u) {
       double pe[8], xe[8];
       piece_to_f64<DT>(pv[u], pe);
       piece_to_f64<DT>(xv[u], xe);
@@ -541,15 +543,40 @@ __device__ __forceinline__ void block_bitonic_sort_lds(unsigned long long* s, in
 }
 
 // n: power of two, n >= 64, identical on every thread; s holds n keys (LDS).
-template <int THREADS>
+// MAXM: the caller's n never exceeds MAXM*THREADS (the larger variants, which need the most
+// registers, are then not compiled into its kernel).
+template <int THREADS, int MAXM = 16>
 __device__ __forceinline__ void block_bitonic_sort(unsigned long long* s, int n, int tid) {
   n = __builtin_amdgcn_readfirstlane(n);
-  if (n <= THREADS) block_bitonic_sort_m<THREADS, 1>(s, n, tid);
-  else if (n == 2 * THREADS) block_bitonic_sort_m<THREADS, 2>(s, n, tid);
-  else if (n == 4 * THREADS) block_bitonic_sort_m<THREADS, 4>(s, n, tid);
-  else if (n == 8 * THREADS) block_bitonic_sort_m<THREADS, 8>(s, n, tid);
-  else if (n == 16 * THREADS) block_bitonic_sort_m<THREADS, 16>(s, n, tid);
-  else block_bitonic_sort_lds<THREADS>(s, n, tid);
+  if (n <= THREADS) {
+    block_bitonic_sort_m<THREADS, 1>(s, n, tid);
+    return;
+  }
+  if constexpr (MAXM >= 2) {
+    if (n == 2 * THREADS) {
+      block_bitonic_sort_m<THREADS, 2>(s, n, tid);
+      return;
+    }
+  }
+  if constexpr (MAXM >= 4) {
+    if (n == 4 * THREADS) {
+      block_bitonic_sort_m<THREADS, 4>(s, n, tid);
+      return;
+    }
+  }
+  if constexpr (MAXM >= 8) {
+    if (n == 8 * THREADS) {
+      block_bitonic_sort_m<THREADS, 8>(s, n, tid);
+      return;
+    }
+  }
+  if constexpr (MAXM >= 16) {
+    if (n == 16 * THREADS) {
+      block_bitonic_sort_m<THREADS, 16>(s, n, tid);
+      return;
+    }
+  }
+  block_bitonic_sort_lds<THREADS>(s, n, tid);
 }
 
 __device__ __forceinline__ int next_pow2(int v) {

@@ -39,6 +39,7 @@ constexpr int kRetWords = kMaxN / 32;
 constexpr int kRetList = 12288;
 constexpr int kRetListPacked = 18432;
 constexpr int kRetQ = 1024;      // band candidates awaiting an fp64 score
+constexpr int kRetInFlight = 4;  // 16-byte pieces per row and lane in flight in the fp64 re-scoring
 constexpr unsigned char kOwnNone = 0xff, kOwnPivot = 0xfe;
 constexpr unsigned long long kNoKey = ~0ull;  // no list entry looks like this (index < 2^14)
 
@@ -433,8 +434,8 @@ __device__ __forceinline__ void retain_body(
       const unsigned char* prow = pivot_row<COH>(g, X, esz, sm, b, st, piv);
       const unsigned char* xrow = Xb + (long)sh.q_idx[q] * rowbytes;
       const double s0 =
-          pl2 ? row_cosine_f64<DT, true>(prow, xrow, g.D, lane, ld_dev<COH>(&pl2[b * g.Ppad + st]))
-              : row_cosine_f64<DT>(prow, xrow, g.D, lane);
+          pl2 ? row_cosine_f64<DT, true, kRetInFlight>(prow, xrow, g.D, lane, ld_dev<COH>(&pl2[b * g.Ppad + st]))
+              : row_cosine_f64<DT, false, kRetInFlight>(prow, xrow, g.D, lane);
       if (lane == 0) sh.q_s64[q] = s0;
     }
     __syncthreads();
@@ -549,8 +550,8 @@ __device__ __forceinline__ void retain_body(
       const double pp_i = pl2 ? ld_dev<COH>(&pl2[b * g.Ppad + i]) : 0.0;
       for (int u = wave; u < nU; u += kRetWaves) {
         const unsigned char* xrow = Xb + (long)sweep_idx[u] * rowbytes;
-        const double s64 = pl2 ? row_cosine_f64<DT, true>(prow, xrow, g.D, lane, pp_i)
-                               : row_cosine_f64<DT>(prow, xrow, g.D, lane);
+        const double s64 = pl2 ? row_cosine_f64<DT, true, kRetInFlight>(prow, xrow, g.D, lane, pp_i)
+                               : row_cosine_f64<DT, false, kRetInFlight>(prow, xrow, g.D, lane);
         if (lane == 0) sweep_s64[u] = s64;
       }
       __syncthreads();

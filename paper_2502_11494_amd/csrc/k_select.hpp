@@ -366,8 +366,8 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[PER], int n, int 
       for (int t = c1 + tid; t < np1; t += kSelThreads) sh.buf[t] = ~0ull;
       for (int t = c2 + tid; t < np2; t += kSelThreads) sh.buf[kSelThreads + t] = ~0ull;
       __syncthreads();
-      block_bitonic_sort<kSelThreads>(sh.buf, np1, tid);
-      block_bitonic_sort<kSelThreads>(sh.buf + kSelThreads, np2, tid);
+      block_bitonic_sort<kSelThreads, SelectShared<THREADS, PER>::kBuf / THREADS>(sh.buf, np1, tid);
+      block_bitonic_sort<kSelThreads, SelectShared<THREADS, PER>::kBuf / THREADS>(sh.buf + kSelThreads, np2, tid);
       *part2 = c1;
       return cstar;
     }
@@ -385,7 +385,7 @@ __device__ __forceinline__ int collect_sorted(const float (&v)[PER], int n, int 
   const int np = next_pow2(c < kWave ? kWave : c);
   for (int t = c + tid; t < np; t += kSelThreads) sh.buf[t] = ~0ull;
   __syncthreads();
-  block_bitonic_sort<kSelThreads>(sh.buf, np, tid);
+  block_bitonic_sort<kSelThreads, SelectShared<THREADS, PER>::kBuf / THREADS>(sh.buf, np, tid);
   if (part2) *part2 = c;
   return c;
 }
