@@ -72,6 +72,10 @@ def lib():
         L.oracle_reduce.argtypes = [vp, i32, i64, i64, i64, vp, i64, i64, vp, i32, i32, i32,
                                     vp, vp, dp, dp, vp, vp, dp, vp, vp, dp]
         L.oracle_reduce.restype = i32
+        L.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_random_pivots.argtypes = [C.c_uint64, i64, i64, i32, vp]
+        L.oracle_random_pivots.restype = i32
         _lib = L
     return _lib
 
@@ -253,6 +257,25 @@ def reduce_given(X: np.ndarray, dtype: int, piv: np.ndarray, K: int,
     r.Y, r.pos_out = gather(X, dtype, pos, r.keep)
     r.piv_gap = np.full(r.piv.shape[0], np.inf)  # no ranking decision was taken
     return r
+
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    """One Philox4x32-10 block: counter (4 words), key (2 words) -> 4 words."""
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def random_pivots(seed: int, b: int, n: int, P: int, want_draws: bool = False):
+    """The P pivots sample b of n tokens draws at random from `seed` (see
+    oracle_random_pivots); with want_draws also the number of draws it took."""
+    piv = np.empty(P, dtype=np.int32)
+    t = int(lib().oracle_random_pivots(C.c_uint64(seed & (2**64 - 1)), b, n, P, _p(piv)))
+    assert t >= 0
+    return (piv, t) if want_draws else piv
 
 
 def reduce_mixed(X: np.ndarray, dtype: int, E: np.ndarray, P_in: int, K: int,

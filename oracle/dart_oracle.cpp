@@ -281,6 +281,66 @@ void oracle_gather_rows(const void* src, int64_t row_bytes, int64_t src_ld_bytes
                 static_cast<size_t>(row_bytes));
 }
 
+// One block of the Philox4x32 counter-based generator with 10 rounds (Salmon, Moraes, Dror,
+// Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11): a round replaces the counter
+// words (c0, c1, c2, c3) by (hi(M1*c2) ^ c1 ^ k0, lo(M1*c2), hi(M0*c0) ^ c3 ^ k1, lo(M0*c0))
+// and the key words grow by the Weyl constants between rounds.
+void oracle_philox4x32_10(const uint32_t* counter, const uint32_t* key, uint32_t* out) {
+  const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  uint32_t c0 = counter[0], c1 = counter[1], c2 = counter[2], c3 = counter[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint64_t p0 = M0 * c0, p1 = M1 * c2;
+    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    c1 = static_cast<uint32_t>(p1);
+    c3 = static_cast<uint32_t>(p0);
+    c0 = n0;
+    c2 = n2;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+// Pivots drawn at random (the random rows of the pivot ablation, Sec. 4.3 / Table 8; the
+// paper names no generator, so the draw is defined here): sample b draws tokens
+// d_t = floor(w_t * N / 2^32), t = 0, 1, ..., where w_t is word t mod 4 of the Philox4x32-10
+// block with counter (t div 4, b, 0, 0) and key (low, high half of seed); its pivots are the
+// first P distinct draws, in the order they appear.  After 4096 draws (never reached in
+// practice) the lowest unused tokens fill the list.  Returns the number of draws used.
+int oracle_random_pivots(uint64_t seed, int64_t b, int64_t N, int P, int32_t* piv) {
+  const int kMaxDraws = 4096;
+  if (P < 0 || N < P) return -1;
+  const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
+  std::vector<char> used(N, 0);
+  int have = 0, t = 0;
+  uint32_t words[4] = {0, 0, 0, 0};
+  for (; t < kMaxDraws && have < P; ++t) {
+    if (t % 4 == 0) {
+      const uint32_t counter[4] = {static_cast<uint32_t>(t / 4), static_cast<uint32_t>(b), 0u, 0u};
+      oracle_philox4x32_10(counter, key, words);
+    }
+    const int64_t d = static_cast<int64_t>((static_cast<uint64_t>(words[t % 4]) *
+                                            static_cast<uint64_t>(N)) >> 32);
+    if (!used[d]) {
+      used[d] = 1;
+      piv[have++] = static_cast<int32_t>(d);
+    }
+  }
+  for (int64_t j = 0; j < N && have < P; ++j)
+    if (!used[j]) {
+      used[j] = 1;
+      piv[have++] = static_cast<int32_t>(j);
+    }
+  return t;
+}
+
 // Steps 1-5 for one sample.  crit == NULL means the hidden-state rows are their
 // own criterion.  Optional outputs may be NULL: c [N], S [P*N], Y, pos_out,
 // piv_gap [P] (c[piv[i]] - c[next in rank], sign-corrected for kMinL1),

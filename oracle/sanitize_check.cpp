@@ -3,8 +3,8 @@
 // with -fsanitize=address,undefined -fno-sanitize-recover=all and executed by the CPU test
 // suite: every oracle function runs on exactly sized heap buffers over a set of shapes that
 // covers both element types, padded row strides, single-token samples, keep-everything and
-// pivots-only budgets, the remainder rule, pivots from outside the sample and whole-sequence
-// maps.  Any out-of-bounds access, use of uninitialised size arithmetic that overflows, or
+// pivots-only budgets, the remainder rule, pivots from outside the sample, pivots drawn at
+// random and whole-sequence maps.  Any out-of-bounds access, use of uninitialised size arithmetic that overflows, or
 // other undefined behaviour aborts the program; on success it prints "sanitize ok".
 #include <cstdint>
 #include <cstdio>
@@ -35,6 +35,8 @@ int oracle_reduce(const void* X, int dtype, int64_t N, int64_t D, int64_t ld, co
                   int32_t* piv, int32_t* keep, double* c_out, double* S_out, void* Y,
                   int64_t* pos_out, double* piv_gap, int32_t* stage_last, int32_t* stage_next,
                   double* stage_gap);
+void oracle_philox4x32_10(const uint32_t* counter, const uint32_t* key, uint32_t* out);
+int oracle_random_pivots(uint64_t seed, int64_t b, int64_t N, int P, int32_t* piv);
 }
 
 namespace {
@@ -143,6 +145,15 @@ int main(int argc, char** argv) {
   CHECK(oracle_retain(s1, 4, p1, 1, 5, k1, nullptr, nullptr, nullptr) == -1);
   CHECK(oracle_retain(s1, 4, p1, 1, 0, k1, nullptr, nullptr, nullptr) == -1);
   CHECK(oracle_retain_single(s1, 4, p1, 1, 2, 3, k1, nullptr, nullptr, nullptr) == -1);
+  // random pivots: exactly sized lists, every token drawn, the largest seed and sample index
+  for (int n : {1, 2, 64, 1000}) {
+    for (int P : {0, 1, n < 64 ? n : 64}) {
+      std::vector<int32_t> piv(static_cast<size_t>(P));
+      CHECK(oracle_random_pivots(~0ull, (1 << 20) - 1, n, P, piv.data()) >= P);
+      for (int32_t j : piv) CHECK(j >= 0 && j < n);
+    }
+  }
+  CHECK(oracle_random_pivots(1, 0, 3, 4, p1) == -1);
   if (failures) return 1;
   std::puts("sanitize ok");
   return 0;

@@ -635,3 +635,63 @@ def test_admissible_pivot_rank_ties():
     assert not oracle.admissible(w.sample(0), r)
     r.piv_gap[1] = 1e-8 * r.c[r.piv[1]]
     assert oracle.admissible(w.sample(0), r)
+
+
+# ---- pivots drawn at random (the random rows of the pivot ablation, Sec. 4.3 / Table 8) ----
+
+def test_philox_known_answers():
+    """The oracle's Philox4x32-10 against the published known-answer vectors."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_known_answers.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for f in rows:
+        v = [int(x, 16) for x in f]
+        out = oracle.philox4x32_10(v[0:4], v[4:6])
+        assert [int(x) for x in out] == v[6:10], f
+
+
+def test_random_pivots_follow_the_first_known_answer_block():
+    """seed 0, sample 0: the first four draws come from the all-zero known-answer block
+    6627e8d5 e169c58d bc57ac4c 9b00dbd8, word by word, scaled by N / 2^32 and rounded down
+    (0.39904, 0.88052, 0.73571, 0.60548 of the range)."""
+    assert list(oracle.random_pivots(0, 0, 1000, 4)) == [399, 880, 735, 605]
+    assert list(oracle.random_pivots(0, 0, 7, 4)) == [2, 6, 5, 4]
+    # the second draw of N = 2 repeats the first token only if both words fall in one half:
+    # 0.399 -> 0, 0.880 -> 1
+    assert list(oracle.random_pivots(0, 0, 2, 2)) == [0, 1]
+    # a repeated draw is skipped: with N = 3 the draws are 1, 2, 2, 1 and then the next block
+    piv, draws = oracle.random_pivots(0, 0, 3, 3, want_draws=True)
+    assert list(piv[:2]) == [1, 2] and piv[2] == 0 and draws > 4
+
+
+def test_random_pivots_are_distinct_in_range_and_reproducible():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 3000))
+        P = int(rng.integers(0, min(n, 64) + 1))
+        seed = int(rng.integers(0, 2**63))
+        b = int(rng.integers(0, 1 << 20))
+        piv, draws = oracle.random_pivots(seed, b, n, P, want_draws=True)
+        assert len(set(piv.tolist())) == P and (P == 0 or (piv.min() >= 0 and piv.max() < n))
+        assert P <= draws <= 4096
+        np.testing.assert_array_equal(piv, oracle.random_pivots(seed, b, n, P))
+        if P >= 4 and n >= 64:
+            assert list(piv) != list(oracle.random_pivots(seed, b + 1, n, P))
+            assert list(piv) != list(oracle.random_pivots(seed + 1, b, n, P))
+            assert list(piv) != list(oracle.random_pivots(seed + (1 << 32), b, n, P))
+    # every token of a sample is drawn when P = N: a permutation
+    piv = oracle.random_pivots(11, 3, 64, 64)
+    assert sorted(piv.tolist()) == list(range(64))
+    # a prefix of a longer list is the shorter list (the draws do not depend on P)
+    np.testing.assert_array_equal(oracle.random_pivots(9, 2, 500, 16)[:5],
+                                  oracle.random_pivots(9, 2, 500, 5))
+
+
+def test_random_pivots_are_uniform():
+    """First pivots over 20000 samples of one seed spread evenly over 16 tokens
+    (chi-square with 15 degrees of freedom: 99.9 % quantile 37.7)."""
+    counts = np.zeros(16)
+    for b in range(20000):
+        counts[oracle.random_pivots(123456789, b, 16, 1)[0]] += 1
+    chi2 = float(((counts - 1250.0) ** 2 / 1250.0).sum())
+    assert chi2 < 37.7, chi2
