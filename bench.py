@@ -222,6 +222,8 @@ def measure(w, args, config_index, steps, warmup, variants=True):
         ext = (torch.from_numpy(E.view(np.int16)).view(torch.bfloat16) if w.dtype == W.BF16
                else torch.from_numpy(E)).cuda()
     more = dict(score_mode=args.score_mode, ext_pivots=ext, P_ext=args.p_ext)
+    if args.random_pivots >= 0:
+        more.update(pivot_mode=D.DART_PIVOT_RANDOM, seed=args.random_pivots)
     if w.ragged:
         desc = D.make_desc(w.B, w.D, w.P, w.dtype, keep_num=w.keep_num, keep_den=w.keep_den,
                            cu_seqlens=cu_dev, total_N=total_N, max_N=int(lens.max()), **more)
@@ -427,6 +429,9 @@ def main():
     ap.add_argument("--p-ext", type=int, default=0,
                     help="variant, context only: the last P_EXT of the workload's pivots are "
                          "synthetic text-token rows from outside the samples")
+    ap.add_argument("--random-pivots", type=int, default=-1, metavar="SEED",
+                    help="context run: pivots drawn at random from SEED (DART_PIVOT_RANDOM, the "
+                         "random rows of the pivot ablation) instead of the largest norms")
     ap.add_argument("--workload", default="", choices=["", "audio", "action", "wide13b", "wide72b"],
                     help="context only: a shape beyond the five configurations (audio tokens, "
                          "a vision-language-action model, 13B / 72B hidden sizes)")
@@ -533,7 +538,9 @@ def main():
                    "score_mode": ["per-pivot thresholds", "one threshold on the minimum",
                                   "one threshold on the maximum"][args.score_mode],
                    "pivots_from_outside": args.p_ext,
-                   "criterion": (f"separate key-state rows of width {args.crit_d}"
+                   "criterion": (f"none: pivots drawn at random from seed {args.random_pivots}"
+                                 if args.random_pivots >= 0 else
+                                 f"separate key-state rows of width {args.crit_d}"
                                  if args.crit_d > 0 else "the hidden states themselves"),
                    "total_tokens": total_N, "retained_tokens": m["retained_tokens"],
                    "input_copies_rotated": m["input_copies_rotated"],

@@ -105,8 +105,18 @@ typedef enum dart_dtype {
 typedef enum dart_pivot_mode {
   DART_PIVOT_MAX_L1 = 0, /* largest criterion L1 norm first (Table 1 caption)      */
   DART_PIVOT_MIN_L1 = 1, /* smallest first (the "heart" rows of the pivot ablation) */
-  DART_PIVOT_GIVEN = 2   /* dart_reduce only: the caller supplies the pivots (e.g. drawn at
-                            random, the random rows of the pivot ablation); see dart_reduce */
+  DART_PIVOT_GIVEN = 2,  /* dart_reduce only: the caller supplies the pivots; see dart_reduce */
+  DART_PIVOT_RANDOM = 3  /* dart_select_pivots and dart_reduce: drawn at random from desc.seed
+                            (the random rows of the pivot ablation, Section 4.3 / Table 8).
+                            The paper names no generator; the draw is defined here: sample
+                            b draws tokens d_t = floor(w_t * N_b / 2^32), t = 0, 1, ..., where
+                            w_t is word t mod 4 of the Philox4x32-10 block (Salmon et al.,
+                            SC'11) with counter (t div 4, b, 0, 0) and key (low, high 32 bits
+                            of seed); the sample's P - P_ext pivots are its first distinct
+                            draws, in the order they appear, which is also their stage order
+                            in step (c).  (After 4096 draws, which 64 pivots among 64 tokens
+                            reach with probability below 1e-25, the lowest unused tokens
+                            complete the list.)  No criterion is read: crit is ignored.     */
 } dart_pivot_mode;
 
 typedef enum dart_score_mode {
@@ -147,6 +157,7 @@ typedef struct dart_desc {
    * sample a skipped one (see Errors).  NULL: the samples are packed back to back.        */
   const int32_t* span_start; /* DEVICE int32[B], or NULL                                   */
   int32_t X_rows;            /* rows of X when span_start != NULL (>= total_N)             */
+  uint64_t seed;             /* DART_PIVOT_RANDOM: the seed of the draw (ignored otherwise) */
 } dart_desc;
 
 /* Bytes of workspace every entry point below accepts for this descriptor
@@ -168,6 +179,8 @@ DART_API dart_status dart_score_tile_shape(const dart_desc* desc, int32_t* waves
  * Table 1 caption.  crit: criterion rows [total_N, crit_D] with row stride
  * crit_ld (same dtype as X, e.g. the layer's key states), or NULL to use the
  * hidden-state rows themselves (then crit_D/crit_ld are ignored).
+ * DART_PIVOT_RANDOM: the pivots are drawn from desc.seed instead (see dart_pivot_mode), in
+ * draw order; crit is ignored and l1_out is not written.
  * Output piv[b*P + i] = index, local to sample b, of its i-th pivot, ordered by
  * (L1 norm descending, index ascending) -- ascending norm for DART_PIVOT_MIN_L1.
  * Norms are accumulated in fp32 and every token whose fp32 norm could still
@@ -219,7 +232,9 @@ DART_API dart_status dart_gather_compact(const dart_desc* desc, const void* X, c
  * is the index, local to sample b, of the pivot of stage i; crit is ignored.  The P
  * indices of a sample must be distinct and inside the sample: a list that is not makes
  * dart_device_status report DART_ERR_DEVICE and leaves that call's outputs unspecified
- * (nothing is read or written out of bounds). */
+ * (nothing is read or written out of bounds).
+ * DART_PIVOT_RANDOM: step (a) draws the pivots from desc.seed (see dart_pivot_mode) instead
+ * of ranking norms; piv_out, if given, receives them; crit is ignored. */
 DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,

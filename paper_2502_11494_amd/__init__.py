@@ -4,7 +4,7 @@ from .binding import (DART_BF16, DART_ERR_ALIGN, DART_ERR_BUDGET, DART_ERR_DEVIC
                       DART_ERR_DTYPE, DART_ERR_HIP, DART_ERR_NULL, DART_ERR_SHAPE,
                       DART_ERR_STATIC_LIMIT,
                       DART_ERR_WORKSPACE, DART_F32, DART_OK, DART_PIVOT_MAX_L1,
-                      DART_PIVOT_GIVEN, DART_PIVOT_MIN_L1, DART_SCORE_MAX, DART_SCORE_MIN,
+                      DART_PIVOT_GIVEN, DART_PIVOT_MIN_L1, DART_PIVOT_RANDOM, DART_SCORE_MAX, DART_SCORE_MIN,
                       DART_SCORE_PER_PIVOT, DartDesc, DartError, DartRowTensor, alloc_workspace,
                       dart_compact_sequences,
                       dart_device_status, dart_duplication_scores, dart_gather_compact,

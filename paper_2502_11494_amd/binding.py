@@ -20,7 +20,7 @@ DART_ERR_NULL, DART_ERR_SHAPE, DART_ERR_BUDGET, DART_ERR_DTYPE = -1, -2, -3, -4
 DART_ERR_WORKSPACE, DART_ERR_ALIGN, DART_ERR_HIP, DART_ERR_DEVICE = -5, -6, -7, -8
 DART_ERR_STATIC_LIMIT = -9
 DART_F32, DART_BF16 = 0, 1
-DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN = 0, 1, 2
+DART_PIVOT_MAX_L1, DART_PIVOT_MIN_L1, DART_PIVOT_GIVEN, DART_PIVOT_RANDOM = 0, 1, 2, 3
 DART_SCORE_PER_PIVOT, DART_SCORE_MIN, DART_SCORE_MAX = 0, 1, 2
 
 EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_scores",
@@ -37,7 +37,8 @@ class DartDesc(C.Structure):
                 ("ld", C.c_int64), ("dtype", C.c_int32), ("K", C.c_int32),
                 ("keep_num", C.c_int32), ("keep_den", C.c_int32), ("pivot_mode", C.c_int32),
                 ("score_mode", C.c_int32), ("P_ext", C.c_int32), ("ext_ld", C.c_int64),
-                ("ext_pivots", C.c_void_p), ("span_start", C.c_void_p), ("X_rows", C.c_int32)]
+                ("ext_pivots", C.c_void_p), ("span_start", C.c_void_p), ("X_rows", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 class DartRowTensor(C.Structure):
@@ -120,7 +121,7 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
               score_mode: int = DART_SCORE_PER_PIVOT,
               ext_pivots: Optional[torch.Tensor] = None, P_ext: int = 0,
               ext_ld: Optional[int] = None, span_start: Optional[torch.Tensor] = None,
-              X_rows: int = 0) -> DartDesc:
+              X_rows: int = 0, seed: int = 0) -> DartDesc:
     d = DartDesc()
     d.B, d.D, d.P, d.N = B, D, P, N
     d.cu_seqlens = None if cu_seqlens is None else cu_seqlens.data_ptr()
@@ -136,6 +137,7 @@ def make_desc(B: int, D: int, P: int, dtype: int, *, N: int = 0, K: int = 0, kee
         d.span_start = (span_start.data_ptr() if hasattr(span_start, "data_ptr")
                         else int(span_start))
     d.X_rows = X_rows
+    d.seed = seed & (2**64 - 1)
     # the descriptor holds raw device addresses: keep their tensors alive with it
     d._keepalive = (cu_seqlens, ext_pivots, span_start)
     return d

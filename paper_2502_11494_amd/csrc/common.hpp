@@ -30,7 +30,7 @@ __device__ __forceinline__ long xcd_contiguous(unsigned bid, unsigned nblocks) {
 }
 #endif
 inline long round_up8(long n) { return (n + kXcds - 1) / kXcds * kXcds; }
-enum { kMaxL1 = 0, kMinL1 = 1, kGiven = 2 };
+enum { kMaxL1 = 0, kMinL1 = 1, kGiven = 2, kRandom = 3 };
 
 // ---- memory that another workgroup of the same launch wrote ------------------------------
 // The chip has eight L2 caches (one per accelerator die) that are not kept coherent for

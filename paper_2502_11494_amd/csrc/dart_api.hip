@@ -48,6 +48,7 @@ struct Plan {
   bool norms_given;  // this call's norm pass also leaves the squared token norms
   int ks_waves, ks_split;  // bf16 score kernel: waves per workgroup and groups of them (fp32: 0)
   bool retain_packed;      // the largest sample's stage lists need the 6-byte LDS layout
+  unsigned long long seed; // DART_PIVOT_RANDOM: the seed of the draw
 };
 
 // Compute units of the current GPU looked up once per GPU.
@@ -156,7 +157,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   if (!d) return DART_ERR_NULL;
   if (d->dtype != DART_F32 && d->dtype != DART_BF16) return DART_ERR_DTYPE;
   if (d->pivot_mode != DART_PIVOT_MAX_L1 && d->pivot_mode != DART_PIVOT_MIN_L1 &&
-      d->pivot_mode != DART_PIVOT_GIVEN)
+      d->pivot_mode != DART_PIVOT_GIVEN && d->pivot_mode != DART_PIVOT_RANDOM)
     return DART_ERR_DTYPE;
   if (d->B < 0 || d->B > kMaxB || d->D <= 0 || d->D > 65536 || d->P < 1 || d->P > kMaxP || d->ld < d->D ||
       d->ld > kMaxLd || d->score_mode < 0 || d->score_mode > 2 || d->P_ext < 0 || d->P_ext > d->P)
@@ -212,6 +213,7 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.keep_den = d->keep_den > 0 ? d->keep_den : 1;
   g.dtype = d->dtype;
   g.mode = d->pivot_mode;
+  p.seed = d->seed;
   g.score_mode = d->score_mode;
   g.ld = d->ld;
   g.cu = d->cu_seqlens;
@@ -260,7 +262,8 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   p.o_scr_f64 = take(sizeof(double) * 2 * (size_t)total);
   p.o_l2 = take(sizeof(double) * (size_t)total);
   // one-launch path: bf16, pivots chosen among the tokens, the staged rule, packed samples
-  p.fusable = d->dtype == DART_BF16 && d->pivot_mode != DART_PIVOT_GIVEN && d->P_ext == 0 &&
+  p.fusable = d->dtype == DART_BF16 && d->pivot_mode != DART_PIVOT_GIVEN &&
+              d->pivot_mode != DART_PIVOT_RANDOM && d->P_ext == 0 &&
               d->score_mode == 0 && d->span_start == nullptr && d->B <= kFuMaxB;
   if (d->B <= kFuMaxB) {  // (the same workspace size whatever the modes)
     p.o_sync = take(sizeof(int) * (size_t)fused_sync_ints(d->B, d->P));
@@ -405,6 +408,14 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
   else
     hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
                        pl2, piv_mark);
+  DART_LAUNCH_CHECK();
+  return DART_OK;
+}
+
+// The pivots of DART_PIVOT_RANDOM, drawn on the device (the first Pin entries of every sample).
+dart_status launch_random_pivots(const Plan& p, int* piv, hipStream_t st) {
+  if (p.g.Pin == 0) return DART_OK;
+  hipLaunchKernelGGL(k_random_pivots, dim3(p.g.B), dim3(64), 0, st, p.g, p.seed, piv);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -641,6 +652,10 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   if (!X || !keep || (Y && (pos != nullptr) != (pos_out != nullptr))) return DART_ERR_NULL;
   if (p.g.mode == kGiven && !piv_out) return DART_ERR_NULL;
   if (misaligned16(X) || (Y && misaligned16(Y))) return DART_ERR_ALIGN;
+  // pivots drawn at random: the library writes the list, then the step runs as with a
+  // caller's list (no pass over a criterion, no check of a list that is valid by construction)
+  const bool random = p.g.mode == kRandom;
+  if (random) p.g.mode = kGiven;
   if (p.g.mode == kGiven) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
@@ -666,9 +681,13 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     return launch_fused(p, X, pos, Y, pos_out, keep, cu_keep, piv, S, ws, st);
   if (p.g.mode == kGiven) {
     // the caller's pivots: check them, compute their norms; no pass over the criterion
-    hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
-                       at<int>(ws, p.o_status));
-    DART_LAUNCH_CHECK();
+    if (random) {
+      DART_TRY(launch_random_pivots(p, piv, st));
+    } else {
+      hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
+                         at<int>(ws, p.o_status));
+      DART_LAUNCH_CHECK();
+    }
     DART_TRY(mark(1));
     DART_TRY(launch_pivot_norms(p, X, piv, 0, piv, ws, st));
     DART_TRY(mark(2));
@@ -741,12 +760,15 @@ dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void*
   if (p.g.B == 0) return DART_OK;
   if (!X || !piv) return DART_ERR_NULL;
   if (misaligned16(X)) return DART_ERR_ALIGN;
+  if (p.g.mode == kRandom) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
   float* l1 = l1_out ? l1_out : at<float>(ws, p.o_l1);
   DART_TRY(launch_prepare(p, ws, st));
-  if (p.g.Pin > 0) {
+  if (p.g.mode == kRandom) {  // no criterion is read and l1_out is left as it is
+    DART_TRY(launch_random_pivots(p, piv, st));
+  } else if (p.g.Pin > 0) {
     DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, false, st));
     DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
   }

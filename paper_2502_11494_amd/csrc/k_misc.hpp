@@ -111,6 +111,77 @@ __global__ __launch_bounds__(1024) void k_check_pivots(Geo g, const int* __restr
   if (threadIdx.x == 0) status[1] = bad ? 1 : 0;
 }
 
+// Pivots drawn at random (the random rows of the pivot ablation, Section 4.3 / Table 8).
+// The generator is Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): a round maps
+// the counter words (c0, c1, c2, c3) to (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1,
+// lo(M0 c0)); the key words grow by the two Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+
+// Sample b draws tokens d_t = floor(w_t * N_b / 2^32), t = 0, 1, ..., with w_t word t mod 4 of
+// the Philox block of counter (t div 4, b, 0, 0) and key (low, high half of the seed); its
+// Pin pivots are the first Pin distinct draws in the order they appear.  After kRandomDraws
+// draws (a bound for the loop; 64 pivots among 64 tokens need about 300) the lowest unused
+// tokens fill the list.  grid: B blocks of one wave: the lanes compute 256 draws at a time,
+// lane 0 walks them.
+constexpr int kRandomDraws = 4096;
+__global__ __launch_bounds__(64) void k_random_pivots(Geo g, unsigned long long seed,
+                                                      int* __restrict__ piv) {
+  __shared__ uint32_t used[kMaxN / 32];
+  __shared__ int draws[256];
+  __shared__ int have_sh;
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const Sample sm = sample_of(g, b);
+  if (sm.k == 0 || g.Pin == 0) return;
+  const int n = sm.n, want = g.Pin;
+  int* out = piv + (long)b * g.P;
+  for (int t = lane; t < (n + 31) / 32; t += 64) used[t] = 0u;
+  int have = 0;
+  for (int base = 0; base < kRandomDraws && have < want; base += 256) {
+    uint32_t w[4];
+    philox4x32_10((uint32_t)(base / 4 + lane), (uint32_t)b, 0u, 0u, (uint32_t)seed,
+                  (uint32_t)(seed >> 32), w);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) draws[4 * lane + u] = (int)__umulhi(w[u], (uint32_t)n);
+    __syncthreads();
+    if (lane == 0) {
+      for (int t = 0; t < 256 && have < want; ++t) {
+        const int d = draws[t];
+        const uint32_t bit = 1u << (d & 31);
+        if ((used[d >> 5] & bit) == 0u) {
+          used[d >> 5] |= bit;
+          out[have++] = d;
+        }
+      }
+      have_sh = have;
+    }
+    __syncthreads();
+    have = have_sh;
+  }
+  if (lane == 0)
+    for (int j = 0; j < n && have < want; ++j)
+      if ((used[j >> 5] & (1u << (j & 31))) == 0u) out[have++] = j;
+}
+
 // status[1] = 0: for entry points that read no pivot list (one thread).
 __global__ void k_clear_pivot_status(int* __restrict__ status) { status[1] = 0; }
 

@@ -35,11 +35,11 @@ def to_device(w: W.Workload, ld: Optional[int] = None) -> torch.Tensor:
 def desc_of(w: W.Workload, cu_dev: Optional[torch.Tensor], ld: Optional[int] = None,
             mode: int = D.DART_PIVOT_MAX_L1, K: Optional[int] = None,
             score_mode: int = D.DART_SCORE_PER_PIVOT, ext: Optional[torch.Tensor] = None,
-            P_ext: int = 0) -> D.DartDesc:
+            P_ext: int = 0, seed: int = 0) -> D.DartDesc:
     """ext [B*P_ext, D] device rows: the last P_ext of the w.P pivots come from outside."""
     lens = w.lengths
     more = dict(ld=ld, pivot_mode=mode, score_mode=score_mode, ext_pivots=ext, P_ext=P_ext,
-                ext_ld=None if ext is None else ext.stride(0))
+                ext_ld=None if ext is None else ext.stride(0), seed=seed)
     if w.ragged:
         return D.make_desc(w.B, w.D, w.P, w.dtype, K=w.K if K is None else K,
                            keep_num=w.keep_num, keep_den=w.keep_den, cu_seqlens=cu_dev,
@@ -70,10 +70,11 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
                crit: Optional[torch.Tensor] = None, Xd: Optional[torch.Tensor] = None,
                given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK,
                score_mode: int = D.DART_SCORE_PER_PIVOT,
-               ext: Optional[np.ndarray] = None, ext_ld: Optional[int] = None) -> GpuResult:
+               ext: Optional[np.ndarray] = None, ext_ld: Optional[int] = None,
+               seed: int = 0) -> GpuResult:
     """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots.
     ext [B, P_ext, D] element bits: pivot rows from outside the samples (the last P_ext
-    of the w.P pivots)."""
+    of the w.P pivots).  seed: of the draw, with mode DART_PIVOT_RANDOM."""
     Xd = to_device(w, ld) if Xd is None else Xd
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
     ext_dev, P_ext = None, 0
@@ -85,7 +86,8 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
         ext_dev = torch.zeros((max(flat.shape[0], 1), ext_ld or w.D), dtype=t.dtype, device="cuda")
         ext_dev[:flat.shape[0], :w.D] = t.cuda()
         ext_dev = ext_dev[:, :w.D]  # rows keep the padded stride
-    desc = desc_of(w, cu_dev, ld, mode, score_mode=score_mode, ext=ext_dev, P_ext=P_ext)
+    desc = desc_of(w, cu_dev, ld, mode, score_mode=score_mode, ext=ext_dev, P_ext=P_ext,
+                   seed=seed)
     ws = D.alloc_workspace(desc)
     total_keep = sum(w.budget(b) for b in range(w.B))
     total_N = int(w.cu[-1])

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_descriptor_layout_matches_the_header():
-    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode), offsetof(dart_desc, P_ext), offsetof(dart_desc, ext_ld), offsetof(dart_desc, ext_pivots), offsetof(dart_desc, span_start), offsetof(dart_desc, X_rows), sizeof(dart_row_tensor));return 0;}\n'
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "dart.h"\nint main(){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu", sizeof(dart_desc), offsetof(dart_desc, cu_seqlens), offsetof(dart_desc, ld), offsetof(dart_desc, K), offsetof(dart_desc, score_mode), offsetof(dart_desc, P_ext), offsetof(dart_desc, ext_ld), offsetof(dart_desc, ext_pivots), offsetof(dart_desc, span_start), offsetof(dart_desc, X_rows), offsetof(dart_desc, seed), sizeof(dart_row_tensor));return 0;}\n'
     with tempfile.TemporaryDirectory() as td:
         c = os.path.join(td, "t.c")
         open(c, "w").write(src)
@@ -42,7 +42,7 @@ def test_descriptor_layout_matches_the_header():
     assert list(map(int, out)) == [C.sizeof(T), T.cu_seqlens.offset, T.ld.offset, T.K.offset,
                                    T.score_mode.offset, T.P_ext.offset, T.ext_ld.offset,
                                    T.ext_pivots.offset, T.span_start.offset, T.X_rows.offset,
-                                   C.sizeof(binding.DartRowTensor)]
+                                   T.seed.offset, C.sizeof(binding.DartRowTensor)]
 
 
 def test_workspace_grows_with_the_problem():
@@ -63,6 +63,8 @@ BAD = [
     (dict(B=2, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, total_N=1000), D.DART_ERR_SHAPE),
     (dict(B=1, D=4096, P=8, dtype=7, N=576, K=64), D.DART_ERR_DTYPE),
     (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, pivot_mode=5), D.DART_ERR_DTYPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, pivot_mode=4), D.DART_ERR_DTYPE),
+    (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=64, pivot_mode=-1), D.DART_ERR_DTYPE),
     (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=7), D.DART_ERR_BUDGET),
     (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=576, K=577), D.DART_ERR_BUDGET),
     (dict(B=1, D=4096, P=8, dtype=D.DART_BF16, N=4, K=4), D.DART_ERR_BUDGET),
@@ -129,6 +131,12 @@ def test_null_and_workspace_errors_need_no_device():
     assert rc == D.DART_ERR_NULL
     rc = L.dart_select_pivots(C.byref(dg), fake, None, 0, 0, fake, None, fake, need, None)
     assert rc == D.DART_ERR_DTYPE
+    # pivots drawn at random: a valid descriptor whatever the seed, the same workspace
+    dr = D.make_desc(1, 4096, 8, D.DART_BF16, N=576, K=64, pivot_mode=D.DART_PIVOT_RANDOM,
+                     seed=2**64 - 1)
+    assert D.dart_workspace_bytes(dr) == need
+    assert L.dart_select_pivots(C.byref(dr), fake, None, 0, 0, None, None, fake, need,
+                                None) == D.DART_ERR_NULL  # the list it would write is missing
     # an empty batch is a valid no-op and needs nothing else
     d0 = D.make_desc(0, 4096, 8, D.DART_BF16, N=576, K=64)
     assert L.dart_reduce(C.byref(d0), None, None, 0, 0, None, None, None, None, None, None,

@@ -1,0 +1,110 @@
+"""DART_PIVOT_RANDOM: pivots drawn on the GPU from a seed (the random rows of the pivot
+ablation, Section 4.3 / Table 8) against the oracle's own Philox4x32-10 draw, and the step
+that follows them against the oracle run with those pivots."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_11494_amd as D
+from paper_2502_11494_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _refs(w, seed, E=None, P_ext=0, agg=0):
+    out = []
+    for b in range(w.B):
+        lo, hi = int(w.cu[b]), int(w.cu[b + 1])
+        piv = oracle.random_pivots(seed, b, hi - lo, w.P - P_ext)
+        if E is None:
+            out.append(oracle.reduce_given(w.sample(b), w.dtype, piv, w.budget(b),
+                                           pos=w.pos[lo:hi]))
+        else:
+            out.append(oracle.reduce_mixed(w.sample(b), w.dtype, E[b], w.P - P_ext, w.budget(b),
+                                           pos=w.pos[lo:hi], agg=agg, given=piv))
+    return out
+
+
+CASES = [
+    (1, lambda: W.multicrop_batch(B=3, N=700, D=1024, P=16, K=120, n_centroids=64)),
+    (2**40 + 5, lambda: W.image_batch(B=2, N=333, D=520, P=5, K=64, n_centroids=32)),
+    (7, lambda: W.single_image(N=300, D=256, P=8, K=50, n_centroids=16)),            # fp32
+    (2**64 - 1, lambda: W.ragged_batch(B=4, n_lo=300, n_hi=1200, D=512, P=16)),
+    (99, lambda: W.image_batch(B=3, N=64, D=64, P=64, K=64, n_centroids=8)),         # P = N: ~300-500 draws
+    (5, lambda: W.image_batch(B=2, N=70, D=64, P=64, K=66, n_centroids=8)),
+    (123, lambda: W.image_batch(B=40, N=130, D=256, P=1, K=30, n_centroids=8)),
+    (31, lambda: W.video_batch(B=2, frames=8, per_frame=60, D=1024, P=32, K=96, n_centroids=8)),
+]
+
+
+def test_random_pivots_and_the_step_after_them_match_the_oracle():
+    compared = 0
+    for seed, make in CASES:
+        w = make()
+        print(f"[case] random pivots seed={seed} {w.name} B={w.B} D={w.D} P={w.P} K={w.K}",
+              flush=True)
+        refs = _refs(w, seed)
+        g = G.run_reduce(w, mode=D.DART_PIVOT_RANDOM, seed=seed)
+        for b, r in enumerate(refs):  # the draw itself is integer work: always compared
+            np.testing.assert_array_equal(g.piv[b], r.piv, err_msg=f"pivots of sample {b}")
+        if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            continue  # a margin below the oracle's own resolution: not a parity case
+        G.compare(w, g, refs)
+        compared += 1
+    assert compared >= len(CASES) - 1, f"only {compared} of {len(CASES)} cases were admissible"
+
+
+def test_select_pivots_draws_the_same_lists():
+    """The stage entry point returns the list dart_reduce uses; another seed or another
+    sample index gives another list; l1_out is left alone."""
+    w = W.ragged_batch(B=5, n_lo=100, n_hi=3000, D=256, P=24)
+    Xd = G.to_device(w)
+    cu_dev = torch.from_numpy(w.cu).cuda()
+    lists = {}
+    for seed in (0, 1, 2**33):
+        desc = G.desc_of(w, cu_dev, mode=D.DART_PIVOT_RANDOM, seed=seed)
+        ws = D.alloc_workspace(desc)
+        piv = torch.full((w.B * w.P,), -1, dtype=torch.int32, device="cuda")
+        l1 = torch.full((int(w.cu[-1]),), -3.0, dtype=torch.float32, device="cuda")
+        D.dart_select_pivots(desc, Xd, piv, ws, l1_out=l1)
+        torch.cuda.synchronize()
+        got = piv.cpu().numpy().reshape(w.B, w.P)
+        for b in range(w.B):
+            np.testing.assert_array_equal(
+                got[b], oracle.random_pivots(seed, b, int(w.lengths[b]), w.P), err_msg=f"{seed} {b}")
+        assert float(l1.min()) == -3.0 and float(l1.max()) == -3.0
+        lists[seed] = got
+    assert not np.array_equal(lists[0], lists[1]) and not np.array_equal(lists[0], lists[2**33])
+
+
+def test_random_pivots_with_pivots_from_outside_and_one_threshold():
+    """4 random vision pivots + 4 text pivots (the mixed rows of the ablation), the staged and
+    the single-threshold rule."""
+    w = W.multicrop_batch(B=3, N=700, D=1024, P=8, K=128, n_centroids=64)
+    E = W.text_pivot_rows(w, 4, seed=3)
+    compared = 0
+    for agg, mode in ((0, D.DART_SCORE_PER_PIVOT), (oracle.AGG_MIN, D.DART_SCORE_MIN),
+                      (oracle.AGG_MAX, D.DART_SCORE_MAX)):
+        refs = _refs(w, 17, E=E, P_ext=4, agg=agg)
+        g = G.run_reduce(w, mode=D.DART_PIVOT_RANDOM, seed=17, ext=E, score_mode=mode)
+        for b, r in enumerate(refs):
+            np.testing.assert_array_equal(g.piv[b], r.piv)
+        if all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
+            G.compare(w, g, refs)
+            compared += 1
+    assert compared >= 2
+
+
+def test_random_pivots_at_full_size():
+    """The headline batch with random pivots: the ablation's shape of use."""
+    w = W.by_index(2)
+    refs = _refs(w, 2025)
+    assert all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs))
+    g = G.run_reduce(w, mode=D.DART_PIVOT_RANDOM, seed=2025)
+    G.compare(w, g, refs)
+    again = G.run_reduce(w, mode=D.DART_PIVOT_RANDOM, seed=2025)
+    for f in ("piv", "keep", "S", "Y", "pos_out"):
+        np.testing.assert_array_equal(getattr(g, f), getattr(again, f), err_msg=f)
