@@ -251,9 +251,10 @@ def test_random_shapes_sweep():
 
 def test_random_everything_sweep():
     """Seeded random draws over all batch recipes (fp32 and bf16, dense and packed, with and
-    without separate criterion rows), hidden sizes with and without partial chunks and 1 to 64
-    pivots, each compared bit for bit.  DART_SWEEP_CASES / DART_SWEEP_SEED in the environment
-    make it as long as wanted (3000 cases take about three minutes)."""
+    without separate criterion rows, pivots ranked by norm or drawn at random), hidden sizes with
+    and without partial chunks and 1 to 64 pivots, each compared bit for bit.  DART_SWEEP_CASES /
+    DART_SWEEP_SEED in the environment make it as long as wanted (3000 cases take about three
+    minutes)."""
     cases = int(os.environ.get("DART_SWEEP_CASES", "80"))
     rng = np.random.default_rng(int(os.environ.get("DART_SWEEP_SEED", "20261128")))
     done = skipped = 0
@@ -290,17 +291,28 @@ def test_random_everything_sweep():
             w = W.ragged_batch(seed=seed, B=B, D=D_, P=P, keep_num=num, keep_den=1000,
                                lengths=lengths)
         use_crit = w.dtype == W.BF16 and rng.random() < 0.35
+        drawn = rng.random() < 0.12  # pivots drawn at random on the device instead of ranked
+        draw_seed = int(rng.integers(0, 2**63))
         crit_bits = (W.key_states(w, int(rng.choice([64, 128, 512])), seed=seed & 0xffff)
                      if use_crit else None)
-        refs = G.oracle_samples(w, crit=crit_bits)
+        if drawn:
+            refs = [oracle.reduce_given(
+                w.sample(b), w.dtype, oracle.random_pivots(draw_seed, b, int(w.lengths[b]), w.P),
+                w.budget(b), pos=w.pos[int(w.cu[b]):int(w.cu[b + 1])]) for b in range(w.B)]
+        else:
+            refs = G.oracle_samples(w, crit=crit_bits)
         if not all(oracle.admissible(w.sample(b), r) for b, r in enumerate(refs)):
             skipped += 1
             continue  # a margin below the oracle's own resolution: not a parity case
         print(f"[case {done}] {w.name} B={w.B} D={w.D} P={w.P} K={w.K} "
-              f"lens={w.lengths[:5].tolist()} crit={use_crit}", flush=True)
+              f"lens={w.lengths[:5].tolist()} crit={use_crit} drawn={drawn}", flush=True)
         crit_dev = (None if crit_bits is None else
                     torch.from_numpy(crit_bits.view(np.int16)).view(torch.bfloat16).cuda())
-        G.compare(w, G.run_reduce(w, crit=crit_dev), refs)
+        if drawn:  # (a criterion tensor, if passed, is ignored)
+            g = G.run_reduce(w, crit=crit_dev, mode=D.DART_PIVOT_RANDOM, seed=draw_seed)
+        else:
+            g = G.run_reduce(w, crit=crit_dev)
+        G.compare(w, g, refs)
         done += 1
     assert skipped <= cases // 4, f"{skipped} inadmissible draws for {cases} cases"
 
