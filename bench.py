@@ -86,9 +86,13 @@ class HipEvents:
     def handles(self, lo, hi):
         return [e.value for e in self.ev[lo:hi]]
 
-    def ms(self, a, b):
+    def ms(self, a, b, missing=None):
+        """Elapsed time between two events; `missing` (if given) for a pair that was never
+        recorded (a stage without a kernel)."""
         out = C.c_float()
         rc = self.hip.hipEventElapsedTime(C.byref(out), self.ev[a], self.ev[b])
+        if rc != 0 and missing is not None:
+            return missing
         assert rc == 0, rc
         return out.value
 
@@ -274,20 +278,17 @@ def measure(w, args, config_index, steps, warmup, variants=True):
     spread = {"median": round(groups[5], 5), "min": round(groups[0], 5), "max": round(groups[-1], 5),
               "groups": 10, "steps_per_group": per}
 
-    # per-kernel durations: the same steps again, with HIP events between the kernels on the
-    # stream they are launched on (the kernel-per-step path; events bracket a kernel plus its
-    # launch gap)
-    evs = HipEvents(7 * steps)
-    was_fused = os.environ.pop("DART_FUSED", None)
+    # per-kernel durations: the same steps again (the kernel-per-step path), every stage's
+    # kernels stamping a pair of HIP events with their own begin and end on the stream they
+    # run on (start/stop events of the launch: no packets between the kernels)
+    evs = HipEvents(12 * steps)
     for i in range(steps):
         D.dart_reduce_profiled(desc, Xs[(warmup + i) % copies], Y, keep, ws,
-                               evs.handles(7 * i, 7 * i + 7), pos=pos, pos_out=pos_out,
+                               evs.handles(12 * i, 12 * i + 12), pos=pos, pos_out=pos_out,
                                stream=stream, **ckw)
     torch.cuda.synchronize()
-    if was_fused is not None:
-        os.environ["DART_FUSED"] = was_fused
-    stage_ms = [sum(evs.ms(7 * i + s, 7 * i + s + 1) for i in range(steps)) / steps
-                for s in range(6)]
+    stage_ms = [sum(evs.ms(12 * i + 2 * s, 12 * i + 2 * s + 1, missing=0.0)
+                    for i in range(steps)) / steps for s in range(6)]
     evs.close()
     # the whole call: one event pair around each plain dart_reduce (no events inside it)
     evs = HipEvents(2 * steps)

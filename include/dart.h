@@ -302,10 +302,15 @@ DART_API dart_status dart_compact_sequences(const dart_desc* desc, const int32_t
                                    int64_t pos_out_plane_stride, int32_t* seq_cu_out,
                                    int32_t* row_map, void* ws, size_t ws_bytes, void* stream);
 
-/* dart_reduce that also records the caller's HIP events around its kernels:
- * events is a HOST array of 7 hipEvent_t (as void*); events[k] is recorded
- * before kernel stage k (0 row norms, 1 pivot selection, 2 scores, 3 score
- * ordering, 4 retained set, 5 compaction) and events[6] after the last. */
+/* dart_reduce that also stamps the caller's HIP events with the begin and end of its
+ * kernels: events is a HOST array of 12 hipEvent_t (as void*, created with timing enabled);
+ * events[2k] takes the begin of the first kernel of stage k and events[2k+1] the end of its
+ * last kernel (0 row norms, 1 pivot selection, 2 scores, 3 score ordering, 4 retained set,
+ * 5 compaction), so hipEventElapsedTime(events[2k], events[2k+1]) is the stage's duration as
+ * a kernel trace shows it: the times are the dispatches' own and nothing is enqueued between
+ * the kernels.  A stage that launches no kernel for this descriptor (e.g. the ordering under
+ * the single-threshold rule, the gather with Y == NULL) leaves its two events untouched.
+ * The one-launch path (DART_FUSED=1) is not taken. */
 DART_API dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const void* crit,
                                  int32_t crit_D, int64_t crit_ld, const int64_t* pos, void* Y,
                                  int64_t* pos_out, int32_t* keep, int32_t* cu_keep,

@@ -242,8 +242,9 @@ def dart_probe_mfma_dot32(A, B, out, *, stream=None):
 def dart_reduce_profiled(desc, X, Y, keep, ws, events, *, crit=None, crit_D=0, crit_ld=0,
                          pos=None, pos_out=None, cu_keep=None, piv_out=None, S_out=None,
                          stream=None):
-    """events: 7 raw hipEvent_t handles (ints)."""
-    arr = (C.c_void_p * 7)(*[C.c_void_p(int(e)) for e in events])
+    """events: 12 raw hipEvent_t handles (ints): begin and end of the six stages."""
+    assert len(events) == 12
+    arr = (C.c_void_p * 12)(*[C.c_void_p(int(e)) for e in events])
     _check(lib().dart_reduce_profiled(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld,
                                       _ptr(pos), _ptr(Y), _ptr(pos_out), _ptr(keep),
                                       _ptr(cu_keep), _ptr(piv_out), _ptr(S_out), _ptr(ws),

@@ -1,6 +1,7 @@
 // Host side of the DART C ABI (include/dart.h): argument checks, workspace
 // carving and kernel launches.  No allocation, no synchronisation except in
 // dart_device_status.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -297,6 +298,27 @@ inline T* at(void* ws, size_t off) {
     if (hipGetLastError() != hipSuccess) return DART_ERR_HIP; \
   } while (0)
 
+// Stage events of dart_reduce_profiled.  While they are set, every kernel this thread launches
+// stamps them with its own begin and end (the start/stop events of hipExtLaunchKernel: the
+// times are the dispatch's, and no marker packet goes between the kernels, so a stage's
+// elapsed time is what a kernel trace shows for it); the first kernel of a stage takes the
+// start event, every kernel of the stage the stop event (the last one's time stays).
+struct StageEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+thread_local StageEvents t_stage;
+
+#define DART_LAUNCH(kernel, grid, block, shmem, st, ...)                                        \
+  do {                                                                                          \
+    if (t_stage.stop != nullptr) {                                                              \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, st, t_stage.start, t_stage.stop, 0,     \
+                            __VA_ARGS__);                                                       \
+      t_stage.start = nullptr;                                                                  \
+    } else {                                                                                    \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                          \
+    }                                                                                           \
+  } while (0)
+
 // Fills the ragged offsets (no-op for dense batches) and points g at them.
 dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
   if (p.g.cu == nullptr) return DART_OK;
@@ -305,7 +327,7 @@ dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
   // (only where the ordering kernel's B*P workgroups, one per compute unit, need several rounds)
   int* by_size = p.g.B <= kMaxBySize && (long)p.g.B * p.g.P > compute_units()
                      ? at<int>(ws, p.o_by_size) : nullptr;
-  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(1024), 0, st, p.g, cu_keep, tile_start,
+  DART_LAUNCH(k_prepare, dim3(1), dim3(1024), 0, st, p.g, cu_keep, tile_start,
                      at<int>(ws, p.o_status), by_size);
   DART_LAUNCH_CHECK();
   p.g.cu_keep = cu_keep;
@@ -328,26 +350,27 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
   // With spans the caller moves whole sequences afterwards, which sweeps that cache anyway:
   // measured slower with ordinary loads there.
   const bool keep = keep_cached && (double)rows * ldc * p.esz <= 224e6;
+  double* const no_l2sq = nullptr;
 #define DART_LAUNCH_L1(DT)                                                                       \
   do {                                                                                           \
     if (l2sq && p.g.span)                                                                        \
-      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, false, true, true>), dim3(blocks), dim3(256), 0, \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, true, true>), dim3(blocks), dim3(256), 0, \
                          st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
     else if (l2sq && keep)                                                                       \
-      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, true, false, true>), dim3(blocks), dim3(256), 0, \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, true, false, true>), dim3(blocks), dim3(256), 0, \
                          st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
     else if (l2sq)                                                                               \
-      hipLaunchKernelGGL((k_row_l1<kBF16, ROWS, false, false, true>), dim3(blocks), dim3(256),   \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, false, true>), dim3(blocks), dim3(256),   \
                          0, st, C, Dc, ldc, rows, l1, p.g, l2sq);                                \
     else if (p.g.span)                                                                                \
-      hipLaunchKernelGGL((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,   \
-                         Dc, ldc, rows, l1, p.g);                                                \
+      DART_LAUNCH((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,   \
+                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
     else if (keep)                                                                               \
-      hipLaunchKernelGGL((k_row_l1<DT, ROWS, true, false>), dim3(blocks), dim3(256), 0, st, C,   \
-                         Dc, ldc, rows, l1, p.g);                                                \
+      DART_LAUNCH((k_row_l1<DT, ROWS, true, false>), dim3(blocks), dim3(256), 0, st, C,   \
+                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
     else                                                                                         \
-      hipLaunchKernelGGL((k_row_l1<DT, ROWS, false, false>), dim3(blocks), dim3(256), 0, st, C,  \
-                         Dc, ldc, rows, l1, p.g);                                                \
+      DART_LAUNCH((k_row_l1<DT, ROWS, false, false>), dim3(blocks), dim3(256), 0, st, C,  \
+                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
   } while (0)
   if (p.g.dtype == kBF16) DART_LAUNCH_L1(kBF16); else DART_LAUNCH_L1(kF32);
 #undef DART_LAUNCH_L1
@@ -385,10 +408,10 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
 #define DART_LAUNCH_PIVOTS(PER)                                                                  \
   do {                                                                                           \
     if (p.g.dtype == kBF16)                                                                      \
-      hipLaunchKernelGGL((k_select_pivots<kBF16, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,    \
+      DART_LAUNCH((k_select_pivots<kBF16, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,    \
                          p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
     else                                                                                         \
-      hipLaunchKernelGGL((k_select_pivots<kF32, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,     \
+      DART_LAUNCH((k_select_pivots<kF32, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,     \
                          p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
   } while (0)
   DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_PIVOTS);
@@ -403,10 +426,10 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
                                int* piv_mark, void* ws, hipStream_t st) {
   double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kBF16)
-    hipLaunchKernelGGL((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
+    DART_LAUNCH((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
                        pl2, piv_mark);
   else
-    hipLaunchKernelGGL((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
+    DART_LAUNCH((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
                        pl2, piv_mark);
   DART_LAUNCH_CHECK();
   return DART_OK;
@@ -415,7 +438,7 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
 // The pivots of DART_PIVOT_RANDOM, drawn on the device (the first Pin entries of every sample).
 dart_status launch_random_pivots(const Plan& p, int* piv, hipStream_t st) {
   if (p.g.Pin == 0) return DART_OK;
-  hipLaunchKernelGGL(k_random_pivots, dim3(p.g.B), dim3(64), 0, st, p.g, p.seed, piv);
+  DART_LAUNCH(k_random_pivots, dim3(p.g.B), dim3(64), 0, st, p.g, p.seed, piv);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -425,10 +448,10 @@ dart_status launch_random_pivots(const Plan& p, int* piv, hipStream_t st) {
 dart_status launch_given_status(const Plan& p, const int* piv, void* ws, hipStream_t st) {
   if (p.g.mode != kGiven) return DART_OK;
   if (piv)
-    hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
+    DART_LAUNCH(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
                        at<int>(ws, p.o_status));
   else
-    hipLaunchKernelGGL(k_clear_pivot_status, dim3(1), dim3(1), 0, st, at<int>(ws, p.o_status));
+    DART_LAUNCH(k_clear_pivot_status, dim3(1), dim3(1), 0, st, at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -441,7 +464,7 @@ dart_status launch_scores_ksplit_nb(const Plan& p, const void* X, const int* piv
 #define DART_KS_LAUNCH(W, KS)                                                                   \
   if (p.ks_waves == W && p.ks_split == KS) {                                                    \
     if constexpr (ksplit_lds_bytes(NB, KS, W) <= kKsLdsLimit) {                                 \
-      hipLaunchKernelGGL((k_scores_ksplit<NB, KS, W, TAIL, XN>), grid, block, 0, st, p.g, X,    \
+      DART_LAUNCH((k_scores_ksplit<NB, KS, W, TAIL, XN>), grid, block, 0, st, p.g, X,    \
                          piv, pl2, l2sq, S);                                                    \
       DART_LAUNCH_CHECK();                                                                      \
       return DART_OK;                                                                           \
@@ -474,10 +497,10 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
   if (p.g.dtype == kF32) {
     // two rows per block while four would not give every compute unit two blocks
     if (p.g.total_N <= 4 * 2 * compute_units())
-      hipLaunchKernelGGL(k_scores_f32<2>, dim3(p.tiles_bound * (p.g.tile_rows / 2)), dim3(256), 0,
+      DART_LAUNCH(k_scores_f32<2>, dim3(p.tiles_bound * (p.g.tile_rows / 2)), dim3(256), 0,
                          st, p.g, X, piv, S);
     else
-      hipLaunchKernelGGL(k_scores_f32<4>, dim3(p.tiles_bound * (p.g.tile_rows / 4)), dim3(256), 0,
+      DART_LAUNCH(k_scores_f32<4>, dim3(p.tiles_bound * (p.g.tile_rows / 4)), dim3(256), 0,
                          st, p.g, X, piv, S);
     DART_LAUNCH_CHECK();
     return DART_OK;
@@ -495,12 +518,12 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
   unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   // 1024 threads: a 256-thread variant measured slower even for short samples
 #define DART_LAUNCH_ORDER(PER)                                                                   \
-  hipLaunchKernelGGL((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, \
+  DART_LAUNCH((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, \
                      lists)
   // samples of at most 1024 tokens: 512 threads with two values each (measured on 576-token
   // samples: 8.9 against 9.6 us; pivot selection is slower that way, 3072-token samples too)
   if (p.g.max_N <= 1024)
-    hipLaunchKernelGGL((k_order_scores<512, 2>), dim3(p.g.B * p.g.P), dim3(512), 0, st, p.g, S,
+    DART_LAUNCH((k_order_scores<512, 2>), dim3(p.g.B * p.g.P), dim3(512), 0, st, p.g, S,
                        lists);
   else
     DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_ORDER);
@@ -520,10 +543,10 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
 #define DART_LAUNCH_SINGLE(PER)                                                                  \
   do {                                                                                           \
     if (p.g.dtype == kBF16)                                                                      \
-      hipLaunchKernelGGL((k_keep_single<kBF16, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,    \
+      DART_LAUNCH((k_keep_single<kBF16, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,    \
                          piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
     else                                                                                         \
-      hipLaunchKernelGGL((k_keep_single<kF32, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,     \
+      DART_LAUNCH((k_keep_single<kF32, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,     \
                          piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
   } while (0)
     {
@@ -538,7 +561,7 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
     return DART_OK;
   }
 #define DART_LAUNCH_RETAIN(DT, PK)                                                               \
-  hipLaunchKernelGGL((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,   \
+  DART_LAUNCH((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,   \
                      piv, X, keep, cu_keep, scr_f64, two_tau, pl2)
   if (p.g.dtype == kBF16) {
     if (p.retain_packed) DART_LAUNCH_RETAIN(kBF16, true); else DART_LAUNCH_RETAIN(kBF16, false);
@@ -554,7 +577,7 @@ dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, cons
                           void* Y, int64_t* pos_out, hipStream_t st) {
   if (p.keep_rows_bound == 0) return DART_OK;
   const int blocks = (int)round_up8((p.keep_rows_bound + 3) / 4);
-  hipLaunchKernelGGL(k_gather, dim3(blocks), dim3(256), 0, st, p.g, p.esz, X,
+  DART_LAUNCH(k_gather, dim3(blocks), dim3(256), 0, st, p.g, p.esz, X,
                      reinterpret_cast<const long long*>(pos), keep, Y,
                      reinterpret_cast<long long*>(pos_out));
   DART_LAUNCH_CHECK();
@@ -571,7 +594,7 @@ dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, in
   int* nstart = at<int>(ws, p.o_nstart);
   int* sstart = at<int>(ws, p.o_sstart);
   int* gstart = at<int>(ws, p.o_gstart);
-  hipLaunchKernelGGL(k_fused_init, dim3(1), dim3(1024), 0, st, p.g, score_rows, Y ? 1 : 0, sync,
+  DART_LAUNCH(k_fused_init, dim3(1), dim3(1024), 0, st, p.g, score_rows, Y ? 1 : 0, sync,
                      nstart, sstart, gstart, cu_keep, at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
   FusedArgs a;
@@ -600,8 +623,8 @@ dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, in
   const bool tail = p.g.D % kKsCH != 0;
 #define DART_LAUNCH_FUSED(NBV)                                                        \
   do {                                                                                \
-    if (tail) hipLaunchKernelGGL((k_fused<NBV, true>), grid, block, 0, st, p.g, a);   \
-    else hipLaunchKernelGGL((k_fused<NBV, false>), grid, block, 0, st, p.g, a);       \
+    if (tail) DART_LAUNCH((k_fused<NBV, true>), grid, block, 0, st, p.g, a);   \
+    else DART_LAUNCH((k_fused<NBV, false>), grid, block, 0, st, p.g, a);       \
   } while (0)
   switch (NB) {
     case 1: DART_LAUNCH_FUSED(1); break;
@@ -660,10 +683,12 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
   hipStream_t st = static_cast<hipStream_t>(stream);
-  auto mark = [&](int k) -> dart_status {
-    if (events && hipEventRecord(static_cast<hipEvent_t>(events[k]), st) != hipSuccess)
-      return DART_ERR_HIP;
-    return DART_OK;
+  // profiled calls: the kernels launched from here on belong to stage k
+  struct StageGuard {
+    ~StageGuard() { t_stage = StageEvents{}; }
+  } stage_guard;
+  auto stage = [&](int k) {
+    if (events) t_stage = {static_cast<hipEvent_t>(events[2 * k]), static_cast<hipEvent_t>(events[2 * k + 1])};
   };
   int* piv = piv_out ? piv_out : at<int>(ws, p.o_piv);
   float* S = S_out ? S_out : at<float>(ws, p.o_S);
@@ -676,7 +701,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   p.norms_given = p.g.mode != kGiven && p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 &&
                   (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
   DART_TRY(launch_prepare(p, ws, st));
-  DART_TRY(mark(0));
+  stage(0);
   if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
     return launch_fused(p, X, pos, Y, pos_out, keep, cu_keep, piv, S, ws, st);
   if (p.g.mode == kGiven) {
@@ -684,32 +709,30 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     if (random) {
       DART_TRY(launch_random_pivots(p, piv, st));
     } else {
-      hipLaunchKernelGGL(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
+      DART_LAUNCH(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
                          at<int>(ws, p.o_status));
       DART_LAUNCH_CHECK();
     }
-    DART_TRY(mark(1));
+    stage(1);
     DART_TRY(launch_pivot_norms(p, X, piv, 0, piv, ws, st));
-    DART_TRY(mark(2));
   } else {
     // pivots chosen among the tokens (none if all of them come from outside) ...
     if (p.g.Pin > 0)
       DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st,
                              p.norms_given ? at<double>(ws, p.o_l2) : nullptr));
-    DART_TRY(mark(1));
+    stage(1);
     if (p.g.Pin > 0) DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
     // ... then the norms and marks of those from outside
     if (p.g.Pe > 0) DART_TRY(launch_pivot_norms(p, X, piv, p.g.Pin, piv, ws, st));
-    DART_TRY(mark(2));
   }
+  stage(2);
   DART_TRY(launch_scores(p, X, piv, S, ws, st));
-  DART_TRY(mark(3));
+  stage(3);
   DART_TRY(launch_order(p, S, ws, st));
-  DART_TRY(mark(4));
+  stage(4);
   DART_TRY(launch_retain(p, S, piv, X, keep, cu_keep, ws, st, true));
-  DART_TRY(mark(5));
+  stage(5);
   if (Y) DART_TRY(launch_gather(p, X, pos, keep, Y, pos_out, st));  // NULL: the caller compacts
-  DART_TRY(mark(6));
   return DART_OK;
 }
 
@@ -852,11 +875,11 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
   DART_TRY(launch_given_status(p, nullptr, ws, st));
   // every sequence loses its pruned vision tokens; at most this many rows remain
   const long rows_bound = (long)p.g.x_rows - p.g.total_N + p.keep_rows_bound;
-  hipLaunchKernelGGL(k_seq_offsets, dim3(1), dim3(1024), 0, st, p.g, seq_cu, seq_cu_out,
+  DART_LAUNCH(k_seq_offsets, dim3(1), dim3(1024), 0, st, p.g, seq_cu, seq_cu_out,
                      at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
   if (p.g.B == 0 || rows_bound <= 0) return DART_OK;
-  hipLaunchKernelGGL(k_seq_row_map, dim3((unsigned)((rows_bound + 255) / 256)), dim3(256), 0, st,
+  DART_LAUNCH(k_seq_row_map, dim3((unsigned)((rows_bound + 255) / 256)), dim3(256), 0, st,
                      p.g, seq_cu, seq_cu_out, keep, row_map);
   DART_LAUNCH_CHECK();
   const int* n_rows = seq_cu_out + p.g.B;
@@ -871,12 +894,12 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
       ops.src_ld[i] = t.src_ld_bytes;
       ops.dst_ld[i] = t.dst_ld_bytes;
     }
-    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)round_up8((rows_bound + 3) / 4), cnt), dim3(256), 0,
+    DART_LAUNCH(k_gather_rows, dim3((unsigned)round_up8((rows_bound + 3) / 4), cnt), dim3(256), 0,
                        st, ops, n_rows, row_map);
     DART_LAUNCH_CHECK();
   }
   if (pos_planes > 0) {
-    hipLaunchKernelGGL(k_gather_pos, dim3((unsigned)((rows_bound + 255) / 256), pos_planes),
+    DART_LAUNCH(k_gather_pos, dim3((unsigned)((rows_bound + 255) / 256), pos_planes),
                        dim3(256), 0, st, n_rows, row_map,
                        reinterpret_cast<const long long*>(pos), (long)pos_plane_stride,
                        reinterpret_cast<long long*>(pos_out), (long)pos_out_plane_stride);
@@ -899,7 +922,7 @@ dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const voi
                                  int32_t* piv_out, float* S_out, void* ws, size_t ws_bytes,
                                  void* stream, void* const* events) {
   if (!events) return DART_ERR_NULL;
-  for (int k = 0; k < 7; ++k)
+  for (int k = 0; k < 12; ++k)
     if (!events[k]) return DART_ERR_NULL;
   return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
                      S_out, ws, ws_bytes, stream, events);
@@ -952,7 +975,7 @@ dart_status dart_probe_mfma_dot32(const void* A, const void* B, float* out, int3
   if (tiles == 0) return DART_OK;
   if (!A || !B || !out) return DART_ERR_NULL;
   if (misaligned16(A) || misaligned16(B) || misaligned16(out)) return DART_ERR_ALIGN;
-  hipLaunchKernelGGL(k_probe_mfma_dot32, dim3(tiles), dim3(64), 0, static_cast<hipStream_t>(stream),
+  DART_LAUNCH(k_probe_mfma_dot32, dim3(tiles), dim3(64), 0, static_cast<hipStream_t>(stream),
                      static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
                      out);
   DART_LAUNCH_CHECK();

@@ -1,4 +1,6 @@
 """Parity of the four stage entry points of the C ABI with the oracle's steps."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -279,3 +281,36 @@ def test_stage_entry_points_leave_the_pivot_flag_defined():
     assert D.dart_device_status(desc, ws) == D.DART_ERR_DEVICE
     D.dart_gather_compact(desc, Xd, keep, Y, ws)  # reads no pivots: clears the flag
     assert D.dart_device_status(desc, ws) == D.DART_OK
+
+
+def test_profiled_call_matches_the_plain_call_and_times_every_stage():
+    """dart_reduce_profiled: the same outputs as dart_reduce, and for every stage that launches
+    a kernel a positive duration between its two events; a stage without a kernel (the
+    ordering under the single-threshold rule) leaves its events unrecorded."""
+    import sys
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), ".."))
+    from bench import HipEvents
+    w = W.multicrop_batch(B=3, N=700, D=1024, P=16, K=120, n_centroids=64)
+    base = G.run_reduce(w)
+    Xd = G.to_device(w)
+    tot = w.B * w.K
+    for score_mode in (D.DART_SCORE_PER_PIVOT, D.DART_SCORE_MIN):
+        desc = G.desc_of(w, None, score_mode=score_mode)
+        ws = D.alloc_workspace(desc)
+        Y = torch.zeros((tot, w.D), dtype=Xd.dtype, device="cuda")
+        keep = torch.full((tot,), -1, dtype=torch.int32, device="cuda")
+        evs = HipEvents(12)
+        for _ in range(2):  # the second call re-stamps the same events
+            D.dart_reduce_profiled(desc, Xd, Y, keep, ws, evs.handles(0, 12))
+        torch.cuda.synchronize()
+        times = [evs.ms(2 * s, 2 * s + 1, missing=-1.0) for s in range(6)]
+        evs.close()
+        print(f"[case] profiled score_mode={score_mode} stage ms {times}", flush=True)
+        for s, t in enumerate(times):
+            if s == 3 and score_mode != D.DART_SCORE_PER_PIVOT:
+                assert t == -1.0
+            else:
+                assert 0.0 < t < 5.0, (s, t)
+        if score_mode == D.DART_SCORE_PER_PIVOT:
+            np.testing.assert_array_equal(keep.cpu().numpy(), base.keep)
+            assert G.bits(Y).tobytes() == base.Y.tobytes()
