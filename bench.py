@@ -92,6 +92,7 @@ class HipEvents:
         out = C.c_float()
         rc = self.hip.hipEventElapsedTime(C.byref(out), self.ev[a], self.ev[b])
         if rc != 0 and missing is not None:
+            self.hip.hipGetLastError()  # the failed query must not surface in a later HIP call
             return missing
         assert rc == 0, rc
         return out.value
