@@ -116,7 +116,9 @@ typedef enum dart_pivot_mode {
                             draws, in the order they appear, which is also their stage order
                             in step (c).  (After 4096 draws, which 64 pivots among 64 tokens
                             reach with probability below 1e-25, the lowest unused tokens
-                            complete the list.)  No criterion is read: crit is ignored.     */
+                            complete the list; DART_RANDOM_DRAW_LIMIT=n in the environment,
+                            0 <= n <= 4096, lowers that limit so that a test can reach the
+                            completion.)  No criterion is read: crit is ignored.            */
 } dart_pivot_mode;
 
 typedef enum dart_score_mode {

@@ -76,6 +76,8 @@ def lib():
         L.oracle_philox4x32_10.restype = None
         L.oracle_random_pivots.argtypes = [C.c_uint64, i64, i64, i32, vp]
         L.oracle_random_pivots.restype = i32
+        L.oracle_random_pivots_limited.argtypes = [C.c_uint64, i64, i64, i32, i32, vp]
+        L.oracle_random_pivots_limited.restype = i32
         _lib = L
     return _lib
 
@@ -269,11 +271,17 @@ def philox4x32_10(counter, key) -> np.ndarray:
     return out
 
 
-def random_pivots(seed: int, b: int, n: int, P: int, want_draws: bool = False):
+def random_pivots(seed: int, b: int, n: int, P: int, want_draws: bool = False,
+                  max_draws: Optional[int] = None):
     """The P pivots sample b of n tokens draws at random from `seed` (see
-    oracle_random_pivots); with want_draws also the number of draws it took."""
+    oracle_random_pivots); with want_draws also the number of draws it took.  max_draws
+    replaces the rule's limit of 4096 draws (for tests of the fill that follows it)."""
     piv = np.empty(P, dtype=np.int32)
-    t = int(lib().oracle_random_pivots(C.c_uint64(seed & (2**64 - 1)), b, n, P, _p(piv)))
+    if max_draws is None:
+        t = int(lib().oracle_random_pivots(C.c_uint64(seed & (2**64 - 1)), b, n, P, _p(piv)))
+    else:
+        t = int(lib().oracle_random_pivots_limited(C.c_uint64(seed & (2**64 - 1)), b, n, P,
+                                                   max_draws, _p(piv)))
     assert t >= 0
     return (piv, t) if want_draws else piv
 

@@ -314,9 +314,18 @@ void oracle_philox4x32_10(const uint32_t* counter, const uint32_t* key, uint32_t
 // block with counter (t div 4, b, 0, 0) and key (low, high half of seed); its pivots are the
 // first P distinct draws, in the order they appear.  After 4096 draws (never reached in
 // practice) the lowest unused tokens fill the list.  Returns the number of draws used.
+int oracle_random_pivots_limited(uint64_t seed, int64_t b, int64_t N, int P, int max_draws,
+                                 int32_t* piv);
 int oracle_random_pivots(uint64_t seed, int64_t b, int64_t N, int P, int32_t* piv) {
-  const int kMaxDraws = 4096;
-  if (P < 0 || N < P) return -1;
+  return oracle_random_pivots_limited(seed, b, N, P, 4096, piv);
+}
+
+// The same with the draw limit as an argument (the rule's own limit is 4096), so that the
+// fill that follows the last draw can be exercised by a test.
+int oracle_random_pivots_limited(uint64_t seed, int64_t b, int64_t N, int P, int max_draws,
+                                 int32_t* piv) {
+  const int kMaxDraws = max_draws;
+  if (P < 0 || N < P || max_draws < 0) return -1;
   const uint32_t key[2] = {static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32)};
   std::vector<char> used(N, 0);
   int have = 0, t = 0;

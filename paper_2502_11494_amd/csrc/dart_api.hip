@@ -436,9 +436,17 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
 }
 
 // The pivots of DART_PIVOT_RANDOM, drawn on the device (the first Pin entries of every sample).
+// DART_RANDOM_DRAW_LIMIT=n in the environment lowers the rule's limit of 4096 draws per sample
+// (0..4096; for the test of the fill that follows the last draw, which no input reaches).
 dart_status launch_random_pivots(const Plan& p, int* piv, hipStream_t st) {
   if (p.g.Pin == 0) return DART_OK;
-  DART_LAUNCH(k_random_pivots, dim3(p.g.B), dim3(64), 0, st, p.g, p.seed, piv);
+  int limit = kRandomDraws;
+  if (const char* v = std::getenv("DART_RANDOM_DRAW_LIMIT")) {
+    const int n = std::atoi(v);
+    if (n < 0 || n > kRandomDraws) return DART_ERR_SHAPE;
+    limit = n;
+  }
+  DART_LAUNCH(k_random_pivots, dim3(p.g.B), dim3(64), 0, st, p.g, p.seed, limit, piv);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

@@ -139,13 +139,13 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 // Sample b draws tokens d_t = floor(w_t * N_b / 2^32), t = 0, 1, ..., with w_t word t mod 4 of
 // the Philox block of counter (t div 4, b, 0, 0) and key (low, high half of the seed); its
-// Pin pivots are the first Pin distinct draws in the order they appear.  After kRandomDraws
-// draws (a bound for the loop; 64 pivots among 64 tokens need about 300) the lowest unused
-// tokens fill the list.  grid: B blocks of one wave: the lanes compute 256 draws at a time,
-// lane 0 walks them.
+// Pin pivots are the first Pin distinct draws in the order they appear.  After draw_limit
+// draws (kRandomDraws, a bound for the loop: 64 pivots among 64 tokens need about 300; a test
+// may lower it) the lowest unused tokens fill the list.  grid: B blocks of one wave: the lanes
+// compute 256 draws at a time, lane 0 walks them.
 constexpr int kRandomDraws = 4096;
 __global__ __launch_bounds__(64) void k_random_pivots(Geo g, unsigned long long seed,
-                                                      int* __restrict__ piv) {
+                                                      int draw_limit, int* __restrict__ piv) {
   __shared__ uint32_t used[kMaxN / 32];
   __shared__ int draws[256];
   __shared__ int have_sh;
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64) void k_random_pivots(Geo g, unsigned long long 
   int* out = piv + (long)b * g.P;
   for (int t = lane; t < (n + 31) / 32; t += 64) used[t] = 0u;
   int have = 0;
-  for (int base = 0; base < kRandomDraws && have < want; base += 256) {
+  for (int base = 0; base < draw_limit && have < want; base += 256) {
     uint32_t w[4];
     philox4x32_10((uint32_t)(base / 4 + lane), (uint32_t)b, 0u, 0u, (uint32_t)seed,
                   (uint32_t)(seed >> 32), w);
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64) void k_random_pivots(Geo g, unsigned long long 
     for (int u = 0; u < 4; ++u) draws[4 * lane + u] = (int)__umulhi(w[u], (uint32_t)n);
     __syncthreads();
     if (lane == 0) {
-      for (int t = 0; t < 256 && have < want; ++t) {
+      for (int t = 0; t < 256 && base + t < draw_limit && have < want; ++t) {
         const int d = draws[t];
         const uint32_t bit = 1u << (d & 31);
         if ((used[d >> 5] & bit) == 0u) {

@@ -1,6 +1,8 @@
 """DART_PIVOT_RANDOM: pivots drawn on the GPU from a seed (the random rows of the pivot
 ablation, Section 4.3 / Table 8) against the oracle's own Philox4x32-10 draw, and the step
 that follows them against the oracle run with those pivots."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -108,3 +110,29 @@ def test_random_pivots_at_full_size():
     again = G.run_reduce(w, mode=D.DART_PIVOT_RANDOM, seed=2025)
     for f in ("piv", "keep", "S", "Y", "pos_out"):
         np.testing.assert_array_equal(getattr(g, f), getattr(again, f), err_msg=f)
+
+
+@pytest.mark.parametrize("limit", [0, 3, 200, 256, 300])
+def test_the_lowest_unused_tokens_complete_a_list_when_the_draws_run_out(limit):
+    """The rule's limit of 4096 draws is out of reach of any input; with the limit lowered
+    through the environment the completion runs and matches the oracle's (P = N = 64: the three
+    samples need 495, 320 and 234 draws, so the limits cut the draw of all or some of them
+    short, also in the middle and at the end of a block of 256 draws)."""
+    w = W.image_batch(B=3, N=64, D=64, P=64, K=64, n_centroids=8)
+    Xd = G.to_device(w)
+    desc = G.desc_of(w, None, mode=D.DART_PIVOT_RANDOM, seed=99)
+    ws = D.alloc_workspace(desc)
+    piv = torch.full((w.B * w.P,), -1, dtype=torch.int32, device="cuda")
+    os.environ["DART_RANDOM_DRAW_LIMIT"] = str(limit)
+    try:
+        D.dart_select_pivots(desc, Xd, piv, ws)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("DART_RANDOM_DRAW_LIMIT")
+    got = piv.cpu().numpy().reshape(w.B, w.P)
+    cut = 0
+    for b in range(w.B):
+        want, draws = oracle.random_pivots(99, b, 64, 64, want_draws=True, max_draws=limit)
+        cut += draws == limit  # the draw was cut short: the completion ran
+        np.testing.assert_array_equal(got[b], want, err_msg=f"sample {b}")
+    assert cut >= 2

@@ -687,6 +687,23 @@ def test_random_pivots_are_distinct_in_range_and_reproducible():
                                   oracle.random_pivots(9, 2, 500, 5))
 
 
+def test_random_pivots_fill_after_the_last_draw():
+    """When the draws run out the lowest unused tokens complete the list, ascending.  The
+    rule's limit (4096 draws) is out of reach, so the limit is lowered for the test."""
+    full = oracle.random_pivots(0, 0, 1000, 8)
+    assert list(full[:4]) == [399, 880, 735, 605]
+    piv, draws = oracle.random_pivots(0, 0, 1000, 8, want_draws=True, max_draws=4)
+    assert draws == 4 and list(piv) == [399, 880, 735, 605, 0, 1, 2, 3]
+    piv = oracle.random_pivots(0, 0, 3, 3, max_draws=4)  # draws 1, 2, 2, 1, then the fill
+    assert list(piv) == [1, 2, 0]
+    piv = oracle.random_pivots(5, 9, 40, 6, max_draws=0)  # nothing drawn at all
+    assert list(piv) == [0, 1, 2, 3, 4, 5]
+    # a limit that is not reached changes nothing
+    np.testing.assert_array_equal(oracle.random_pivots(0, 0, 1000, 8, max_draws=8), full)
+    # the fill skips tokens that were drawn: N = 7 draws 2, 6, 5, 4
+    assert list(oracle.random_pivots(0, 0, 7, 7, max_draws=4)) == [2, 6, 5, 4, 0, 1, 3]
+
+
 def test_random_pivots_are_uniform():
     """First pivots over 20000 samples of one seed spread evenly over 16 tokens
     (chi-square with 15 degrees of freedom: 99.9 % quantile 37.7)."""
