@@ -328,7 +328,7 @@ dart_status launch_prepare(Plan& p, void* ws, hipStream_t st) {
   int* by_size = p.g.B <= kMaxBySize && (long)p.g.B * p.g.P > compute_units()
                      ? at<int>(ws, p.o_by_size) : nullptr;
   DART_LAUNCH(k_prepare, dim3(1), dim3(1024), 0, st, p.g, cu_keep, tile_start,
-                     at<int>(ws, p.o_status), by_size);
+              at<int>(ws, p.o_status), by_size);
   DART_LAUNCH_CHECK();
   p.g.cu_keep = cu_keep;
   p.g.tile_start = tile_start;
@@ -354,23 +354,23 @@ dart_status launch_row_l1(const Plan& p, const void* C, int Dc, long ldc, float*
 #define DART_LAUNCH_L1(DT)                                                                       \
   do {                                                                                           \
     if (l2sq && p.g.span)                                                                        \
-      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, true, true>), dim3(blocks), dim3(256), 0, \
-                         st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, true, true>), dim3(blocks), dim3(256), 0,        \
+                  st, C, Dc, ldc, rows, l1, p.g, l2sq);                                          \
     else if (l2sq && keep)                                                                       \
-      DART_LAUNCH((k_row_l1<kBF16, ROWS, true, false, true>), dim3(blocks), dim3(256), 0, \
-                         st, C, Dc, ldc, rows, l1, p.g, l2sq);                                   \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, true, false, true>), dim3(blocks), dim3(256), 0,        \
+                  st, C, Dc, ldc, rows, l1, p.g, l2sq);                                          \
     else if (l2sq)                                                                               \
-      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, false, true>), dim3(blocks), dim3(256),   \
-                         0, st, C, Dc, ldc, rows, l1, p.g, l2sq);                                \
-    else if (p.g.span)                                                                                \
-      DART_LAUNCH((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,   \
-                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
+      DART_LAUNCH((k_row_l1<kBF16, ROWS, false, false, true>), dim3(blocks), dim3(256),          \
+                  0, st, C, Dc, ldc, rows, l1, p.g, l2sq);                                       \
+    else if (p.g.span)                                                                           \
+      DART_LAUNCH((k_row_l1<DT, ROWS, false, true>), dim3(blocks), dim3(256), 0, st, C,          \
+                  Dc, ldc, rows, l1, p.g, no_l2sq);                                              \
     else if (keep)                                                                               \
-      DART_LAUNCH((k_row_l1<DT, ROWS, true, false>), dim3(blocks), dim3(256), 0, st, C,   \
-                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
+      DART_LAUNCH((k_row_l1<DT, ROWS, true, false>), dim3(blocks), dim3(256), 0, st, C,          \
+                  Dc, ldc, rows, l1, p.g, no_l2sq);                                              \
     else                                                                                         \
-      DART_LAUNCH((k_row_l1<DT, ROWS, false, false>), dim3(blocks), dim3(256), 0, st, C,  \
-                         Dc, ldc, rows, l1, p.g, no_l2sq);                                       \
+      DART_LAUNCH((k_row_l1<DT, ROWS, false, false>), dim3(blocks), dim3(256), 0, st, C,         \
+                  Dc, ldc, rows, l1, p.g, no_l2sq);                                              \
   } while (0)
   if (p.g.dtype == kBF16) DART_LAUNCH_L1(kBF16); else DART_LAUNCH_L1(kF32);
 #undef DART_LAUNCH_L1
@@ -408,11 +408,11 @@ dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, in
 #define DART_LAUNCH_PIVOTS(PER)                                                                  \
   do {                                                                                           \
     if (p.g.dtype == kBF16)                                                                      \
-      DART_LAUNCH((k_select_pivots<kBF16, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,    \
-                         p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
+      DART_LAUNCH((k_select_pivots<kBF16, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,           \
+                  p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                                   \
     else                                                                                         \
-      DART_LAUNCH((k_select_pivots<kF32, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,     \
-                         p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                            \
+      DART_LAUNCH((k_select_pivots<kF32, 1024, PER>), dim3(p.g.B), dim3(1024), 0, st,            \
+                  p.g, X, C, Dc, ldc, l1, piv, pl2, scr, tau);                                   \
   } while (0)
   DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_PIVOTS);
 #undef DART_LAUNCH_PIVOTS
@@ -426,11 +426,11 @@ dart_status launch_pivot_norms(const Plan& p, const void* X, const int* piv, int
                                int* piv_mark, void* ws, hipStream_t st) {
   double* pl2 = at<double>(ws, p.o_pl2);
   if (p.g.dtype == kBF16)
-    DART_LAUNCH((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
-                       pl2, piv_mark);
+    DART_LAUNCH((k_pivot_norms<kBF16>), dim3(p.g.B), dim3(1024), 0, st, p.g, X, piv, first,
+                pl2, piv_mark);
   else
-    DART_LAUNCH((k_pivot_norms<kF32>), dim3(p.g.B), dim3(256), 0, st, p.g, X, piv, first,
-                       pl2, piv_mark);
+    DART_LAUNCH((k_pivot_norms<kF32>), dim3(p.g.B), dim3(1024), 0, st, p.g, X, piv, first,
+                pl2, piv_mark);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -457,7 +457,7 @@ dart_status launch_given_status(const Plan& p, const int* piv, void* ws, hipStre
   if (p.g.mode != kGiven) return DART_OK;
   if (piv)
     DART_LAUNCH(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
-                       at<int>(ws, p.o_status));
+                at<int>(ws, p.o_status));
   else
     DART_LAUNCH(k_clear_pivot_status, dim3(1), dim3(1), 0, st, at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
@@ -472,8 +472,8 @@ dart_status launch_scores_ksplit_nb(const Plan& p, const void* X, const int* piv
 #define DART_KS_LAUNCH(W, KS)                                                                   \
   if (p.ks_waves == W && p.ks_split == KS) {                                                    \
     if constexpr (ksplit_lds_bytes(NB, KS, W) <= kKsLdsLimit) {                                 \
-      DART_LAUNCH((k_scores_ksplit<NB, KS, W, TAIL, XN>), grid, block, 0, st, p.g, X,    \
-                         piv, pl2, l2sq, S);                                                    \
+      DART_LAUNCH((k_scores_ksplit<NB, KS, W, TAIL, XN>), grid, block, 0, st, p.g, X,           \
+                  piv, pl2, l2sq, S);                                                           \
       DART_LAUNCH_CHECK();                                                                      \
       return DART_OK;                                                                           \
     }                                                                                           \
@@ -506,10 +506,10 @@ dart_status launch_scores(const Plan& p, const void* X, const int* piv, float* S
     // two rows per block while four would not give every compute unit two blocks
     if (p.g.total_N <= 4 * 2 * compute_units())
       DART_LAUNCH(k_scores_f32<2>, dim3(p.tiles_bound * (p.g.tile_rows / 2)), dim3(256), 0,
-                         st, p.g, X, piv, S);
+                  st, p.g, X, piv, S);
     else
       DART_LAUNCH(k_scores_f32<4>, dim3(p.tiles_bound * (p.g.tile_rows / 4)), dim3(256), 0,
-                         st, p.g, X, piv, S);
+                  st, p.g, X, piv, S);
     DART_LAUNCH_CHECK();
     return DART_OK;
   }
@@ -526,13 +526,13 @@ dart_status launch_order(const Plan& p, const float* S, void* ws, hipStream_t st
   unsigned long long* lists = at<unsigned long long>(ws, p.o_lists);
   // 1024 threads: a 256-thread variant measured slower even for short samples
 #define DART_LAUNCH_ORDER(PER)                                                                   \
-  DART_LAUNCH((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S, \
-                     lists)
+  DART_LAUNCH((k_order_scores<1024, PER>), dim3(p.g.B * p.g.P), dim3(1024), 0, st, p.g, S,       \
+              lists)
   // samples of at most 1024 tokens: 512 threads with two values each (measured on 576-token
   // samples: 8.9 against 9.6 us; pivot selection is slower that way, 3072-token samples too)
   if (p.g.max_N <= 1024)
     DART_LAUNCH((k_order_scores<512, 2>), dim3(p.g.B * p.g.P), dim3(512), 0, st, p.g, S,
-                       lists);
+                lists);
   else
     DART_FOR_VALUES_PER_THREAD(values_per_thread(p.g.max_N), DART_LAUNCH_ORDER);
 #undef DART_LAUNCH_ORDER
@@ -551,11 +551,11 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
 #define DART_LAUNCH_SINGLE(PER)                                                                  \
   do {                                                                                           \
     if (p.g.dtype == kBF16)                                                                      \
-      DART_LAUNCH((k_keep_single<kBF16, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,    \
-                         piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
+      DART_LAUNCH((k_keep_single<kBF16, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,           \
+                  piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);                      \
     else                                                                                         \
-      DART_LAUNCH((k_keep_single<kF32, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,     \
-                         piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);               \
+      DART_LAUNCH((k_keep_single<kF32, PER>), dim3(p.g.B), dim3(1024), 0, st, p.g, S,            \
+                  piv, X, keep, cu_keep, scr_f64, two_tau, p.g.score_mode);                      \
   } while (0)
     {
       const int per = values_per_thread(p.g.max_N);
@@ -569,8 +569,8 @@ dart_status launch_retain(const Plan& p, const float* S, const int* piv, const v
     return DART_OK;
   }
 #define DART_LAUNCH_RETAIN(DT, PK)                                                               \
-  DART_LAUNCH((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,   \
-                     piv, X, keep, cu_keep, scr_f64, two_tau, pl2)
+  DART_LAUNCH((k_retain<DT, PK>), dim3(p.g.B), dim3(kRetThreads), 0, st, p.g, S, lists,          \
+              piv, X, keep, cu_keep, scr_f64, two_tau, pl2)
   if (p.g.dtype == kBF16) {
     if (p.retain_packed) DART_LAUNCH_RETAIN(kBF16, true); else DART_LAUNCH_RETAIN(kBF16, false);
   } else {
@@ -586,8 +586,8 @@ dart_status launch_gather(const Plan& p, const void* X, const int64_t* pos, cons
   if (p.keep_rows_bound == 0) return DART_OK;
   const int blocks = (int)round_up8((p.keep_rows_bound + 3) / 4);
   DART_LAUNCH(k_gather, dim3(blocks), dim3(256), 0, st, p.g, p.esz, X,
-                     reinterpret_cast<const long long*>(pos), keep, Y,
-                     reinterpret_cast<long long*>(pos_out));
+              reinterpret_cast<const long long*>(pos), keep, Y,
+              reinterpret_cast<long long*>(pos_out));
   DART_LAUNCH_CHECK();
   return DART_OK;
 }
@@ -603,7 +603,7 @@ dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, in
   int* sstart = at<int>(ws, p.o_sstart);
   int* gstart = at<int>(ws, p.o_gstart);
   DART_LAUNCH(k_fused_init, dim3(1), dim3(1024), 0, st, p.g, score_rows, Y ? 1 : 0, sync,
-                     nstart, sstart, gstart, cu_keep, at<int>(ws, p.o_status));
+              nstart, sstart, gstart, cu_keep, at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
   FusedArgs a;
   a.X = X;
@@ -631,8 +631,8 @@ dart_status launch_fused(Plan& p, const void* X, const int64_t* pos, void* Y, in
   const bool tail = p.g.D % kKsCH != 0;
 #define DART_LAUNCH_FUSED(NBV)                                                        \
   do {                                                                                \
-    if (tail) DART_LAUNCH((k_fused<NBV, true>), grid, block, 0, st, p.g, a);   \
-    else DART_LAUNCH((k_fused<NBV, false>), grid, block, 0, st, p.g, a);       \
+    if (tail) DART_LAUNCH((k_fused<NBV, true>), grid, block, 0, st, p.g, a);          \
+    else DART_LAUNCH((k_fused<NBV, false>), grid, block, 0, st, p.g, a);              \
   } while (0)
   switch (NB) {
     case 1: DART_LAUNCH_FUSED(1); break;
@@ -696,7 +696,9 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     ~StageGuard() { t_stage = StageEvents{}; }
   } stage_guard;
   auto stage = [&](int k) {
-    if (events) t_stage = {static_cast<hipEvent_t>(events[2 * k]), static_cast<hipEvent_t>(events[2 * k + 1])};
+    if (events)
+      t_stage = {static_cast<hipEvent_t>(events[2 * k]),
+                 static_cast<hipEvent_t>(events[2 * k + 1])};
   };
   int* piv = piv_out ? piv_out : at<int>(ws, p.o_piv);
   float* S = S_out ? S_out : at<float>(ws, p.o_S);
@@ -718,7 +720,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
       DART_TRY(launch_random_pivots(p, piv, st));
     } else {
       DART_LAUNCH(k_check_pivots, dim3(1), dim3(1024), 0, st, p.g, piv,
-                         at<int>(ws, p.o_status));
+                  at<int>(ws, p.o_status));
       DART_LAUNCH_CHECK();
     }
     stage(1);
@@ -884,11 +886,11 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
   // every sequence loses its pruned vision tokens; at most this many rows remain
   const long rows_bound = (long)p.g.x_rows - p.g.total_N + p.keep_rows_bound;
   DART_LAUNCH(k_seq_offsets, dim3(1), dim3(1024), 0, st, p.g, seq_cu, seq_cu_out,
-                     at<int>(ws, p.o_status));
+              at<int>(ws, p.o_status));
   DART_LAUNCH_CHECK();
   if (p.g.B == 0 || rows_bound <= 0) return DART_OK;
   DART_LAUNCH(k_seq_row_map, dim3((unsigned)((rows_bound + 255) / 256)), dim3(256), 0, st,
-                     p.g, seq_cu, seq_cu_out, keep, row_map);
+              p.g, seq_cu, seq_cu_out, keep, row_map);
   DART_LAUNCH_CHECK();
   const int* n_rows = seq_cu_out + p.g.B;
   for (int i0 = 0; i0 < n_tensors; i0 += kSeqOps) {
@@ -903,14 +905,14 @@ dart_status dart_compact_sequences(const dart_desc* desc, const int32_t* seq_cu,
       ops.dst_ld[i] = t.dst_ld_bytes;
     }
     DART_LAUNCH(k_gather_rows, dim3((unsigned)round_up8((rows_bound + 3) / 4), cnt), dim3(256), 0,
-                       st, ops, n_rows, row_map);
+                st, ops, n_rows, row_map);
     DART_LAUNCH_CHECK();
   }
   if (pos_planes > 0) {
     DART_LAUNCH(k_gather_pos, dim3((unsigned)((rows_bound + 255) / 256), pos_planes),
-                       dim3(256), 0, st, n_rows, row_map,
-                       reinterpret_cast<const long long*>(pos), (long)pos_plane_stride,
-                       reinterpret_cast<long long*>(pos_out), (long)pos_out_plane_stride);
+                dim3(256), 0, st, n_rows, row_map,
+                reinterpret_cast<const long long*>(pos), (long)pos_plane_stride,
+                reinterpret_cast<long long*>(pos_out), (long)pos_out_plane_stride);
     DART_LAUNCH_CHECK();
   }
   return DART_OK;
@@ -984,8 +986,8 @@ dart_status dart_probe_mfma_dot32(const void* A, const void* B, float* out, int3
   if (!A || !B || !out) return DART_ERR_NULL;
   if (misaligned16(A) || misaligned16(B) || misaligned16(out)) return DART_ERR_ALIGN;
   DART_LAUNCH(k_probe_mfma_dot32, dim3(tiles), dim3(64), 0, static_cast<hipStream_t>(stream),
-                     static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
-                     out);
+              static_cast<const unsigned char*>(A), static_cast<const unsigned char*>(B),
+              out);
   DART_LAUNCH_CHECK();
   return DART_OK;
 }

@@ -206,9 +206,10 @@ __global__ __launch_bounds__(64) void k_probe_mfma_dot32(const unsigned char* __
 
 // Squared Euclidean norms of the rows of pivots first..Ppad-1 in fp64 (0 for padding
 // slots).  piv_mark (optional): entry i of a pivot from outside the sample is set to
-// -1 - (its row in the sample's share of E).  grid: B blocks of 256.
+// -1 - (its row in the sample's share of E).  grid: B blocks of 1024: a wave per pivot, so
+// that up to 16 rows are in flight at once (64 pivots: four rounds).
 template <int DT>
-__global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restrict__ X,
+__global__ __launch_bounds__(1024) void k_pivot_norms(Geo g, const void* __restrict__ X,
                                                      const int* __restrict__ piv, int first,
                                                      double* __restrict__ pl2,
                                                      int* __restrict__ piv_mark) {
@@ -217,7 +218,7 @@ __global__ __launch_bounds__(256) void k_pivot_norms(Geo g, const void* __restri
   const Sample sm = sample_of(g, b);
   const int esz = DT == kBF16 ? 2 : 4;
   if (piv_mark && tid >= g.Pin && tid < g.P) piv_mark[b * g.P + tid] = -1 - (tid - g.Pin);
-  for (int i = first + wave; i < g.Ppad; i += 4) {
+  for (int i = first + wave; i < g.Ppad; i += 16) {
     double l1 = 0.0, l2 = 0.0;
     if (sm.k != 0 && i < g.P) row_l1_l2_f64<DT>(pivot_row(g, X, esz, sm, b, i, piv), g.D, lane, l1, l2);
     if (lane == 0) pl2[b * g.Ppad + i] = l2;
