@@ -235,7 +235,8 @@ def measure(w, args, config_index, steps, warmup, variants=True):
     else:
         desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(lens[0]), K=w.K, **more)
     ws = D.alloc_workspace(desc)
-    tile_w, tile_ks = D.dart_score_tile_shape(desc)
+    tile_w, tile_ks = (D.dart_score_tile_shape_first_read(desc) if args.crit_d > 0 else
+                       D.dart_score_tile_shape(desc))
     score_tile = (None if tile_w == 0 else
                   {"waves": tile_w, "groups": tile_ks, "rows": 16 * tile_w // tile_ks})
     Y = torch.empty((total_K, w.D), dtype=X0.dtype, device="cuda")

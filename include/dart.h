@@ -169,13 +169,23 @@ DART_API size_t dart_workspace_bytes(const dart_desc* desc);
 /* The tile of the score kernel (step (b), Eq. 7) this library would use for the descriptor on
  * the current GPU (256 compute units assumed when there is none): *waves wavefronts per
  * workgroup in *split groups that share 16 * waves / split token rows and split the hidden
- * dimension among them; both 0 for fp32 descriptors, whose score kernel has one shape.  Host
+ * dimension among them; both 0 for fp32 descriptors, whose score kernel has one shape.  This
+ * is the shape of dart_reduce with the hidden states as their own criterion.  Host
  * arithmetic only; waves and split are HOST pointers.  The choice is a cost model over the
  * batch's shape (see the library's source); DART_SCORE_TILE="W,KS" in the environment names
  * one of the built shapes instead, and a value that names none, or one whose tiles do not fit
  * the LDS with this many pivots, makes every entry point return DART_ERR_SHAPE.  The results of
  * the step do not depend on the shape (decisions are certified in fp64). */
 DART_API dart_status dart_score_tile_shape(const dart_desc* desc, int32_t* waves, int32_t* split);
+
+/* The same for calls whose score pass is the first pass over X: dart_reduce with a separate
+ * criterion tensor (its norm pass reads crit, not X) and dart_duplication_scores.  Such calls
+ * find no row of X in the memory-side cache, and small dense batches then do better with
+ * four groups of waves per tile (measured; see the library's source).  For descriptors whose
+ * pivots are given, drawn at random or all from outside, dart_score_tile_shape already
+ * reports this shape (no norm pass over X exists for them). */
+DART_API dart_status dart_score_tile_shape_first_read(const dart_desc* desc, int32_t* waves,
+                                                      int32_t* split);
 
 /* (a) Pivot selection -- Definition 1 with the max-L1-norm criterion of the
  * Table 1 caption.  crit: criterion rows [total_N, crit_D] with row stride

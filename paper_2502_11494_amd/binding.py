@@ -27,6 +27,7 @@ EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_score
            "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
            "dart_reduce_profiled", "dart_reduce_static", "dart_static_scratch_bytes",
            "dart_device_status_static", "dart_probe_mfma_dot32", "dart_score_tile_shape",
+           "dart_score_tile_shape_first_read",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -78,6 +79,7 @@ def lib():
         L.dart_device_status.argtypes = [dp, vp, vp]
         L.dart_reduce_static.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.dart_score_tile_shape.argtypes = [dp, C.POINTER(i32), C.POINTER(i32)]
+        L.dart_score_tile_shape_first_read.argtypes = [dp, C.POINTER(i32), C.POINTER(i32)]
         L.dart_static_scratch_bytes.argtypes = []
         L.dart_static_scratch_bytes.restype = sz
         L.dart_device_status_static.argtypes = [dp, vp]
@@ -86,7 +88,7 @@ def lib():
                      "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
                      "dart_reduce_profiled", "dart_device_status", "dart_reduce_static",
                      "dart_device_status_static", "dart_probe_mfma_dot32",
-                     "dart_score_tile_shape"):
+                     "dart_score_tile_shape", "dart_score_tile_shape_first_read"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -222,6 +224,15 @@ def dart_score_tile_shape(desc) -> tuple:
     w, ks = C.c_int32(0), C.c_int32(0)
     _check(lib().dart_score_tile_shape(C.byref(desc), C.byref(w), C.byref(ks)),
            "dart_score_tile_shape")
+    return int(w.value), int(ks.value)
+
+
+def dart_score_tile_shape_first_read(desc) -> tuple:
+    """The same for calls whose score pass is the first pass over X (a separate criterion
+    tensor, the stage entry point)."""
+    w, ks = C.c_int32(0), C.c_int32(0)
+    _check(lib().dart_score_tile_shape_first_read(C.byref(desc), C.byref(w), C.byref(ks)),
+           "dart_score_tile_shape_first_read")
     return int(w.value), int(ks.value)
 
 

@@ -91,16 +91,21 @@ constexpr KsChoice kKsShapes[] = {
 };
 constexpr size_t kKsLdsLimit = 150 * 1024;  // of the 160 KB of a compute unit
 
-KsChoice choose_score_tiles(const Geo& g, int units) {
+// first_read: the score pass is the first pass of the call over X (pivots given or drawn, a
+// separate criterion tensor, the stage entry point), so no norm pass has left the rows in the
+// memory-side cache.
+KsChoice choose_score_tiles(const Geo& g, int units, bool first_read) {
   const int NB = g.Ppad / 16;
   const double rowbytes = (double)g.D * 2;
   const int chunks = (g.D + kKsCH - 1) / kKsCH;
-  KsChoice best = {4, 1};
-  double best_t = 1e30;
-  for (const KsChoice& c : kKsShapes) {
+  struct Cost {
+    double t, rows_busiest;
+    bool fits;
+  };
+  auto cost = [&](const KsChoice& c) -> Cost {
     const int R = 16 * c.waves / c.split;
     const size_t lds = ksplit_lds_bytes(NB, c.split, c.waves);
-    if (lds > kKsLdsLimit) continue;
+    if (lds > kKsLdsLimit) return {1e30, 0.0, false};
     const double tiles = g.cu == nullptr ? (double)g.B * ((g.N + R - 1) / R)
                                          : (double)g.total_N / R + 0.5 * g.B;
     const double per_unit = std::ceil(tiles / units);
@@ -113,19 +118,62 @@ KsChoice choose_score_tiles(const Geo& g, int units) {
     const double chain = std::ceil(per_unit / resident) * ((chunks + c.split - 1) / c.split) * 0.55e-6 + 4e-6;
     t = std::max(t, chain);
     t += 1e-9 * (256 - R) / 256;  // ties: the taller tile (less pivot traffic)
-    if (t < best_t) {
-      best_t = t;
+    return {t, rows_busiest, true};
+  };
+  KsChoice best = {4, 1};
+  double best_t = 1e30;
+  for (const KsChoice& c : kKsShapes) {
+    const Cost k = cost(c);
+    if (k.fits && k.t < best_t) {
+      best_t = k.t;
       best = c;
+    }
+  }
+  // What the model does not see, measured with every shape forced in turn (score pass by the
+  // launch's own events): where a wave's chain of chunks matters, four groups of waves per
+  // tile beat two or three of the same tile height (32 rows: 8 waves in 4 groups 15.9 us
+  // against 17.4 for 6 in 3 on 32 samples of 256 tokens; 48 rows: 12 in 4 groups 15.2 against
+  // 17.2 for 6 in 2 on sixteen 576-token images, 22.1 against 25.2 at a hidden size of 5120) ...
+  const int R_best = 16 * best.waves / best.split;
+  if (best.split >= 2 && best.split < 4 && (R_best == 32 || R_best == 48)) {
+    const KsChoice four = {R_best / 4, 4};
+    if (cost(four).fits) return four;
+  }
+  // ... and on a first read of X they also beat the single group on small dense batches as
+  // long as no compute unit gets more rows than with the model's pick (eight samples of 2880
+  // tokens: 34.7-35.5 us against 38.6 for 6 waves in one group; with 32 pivots or thousands
+  // of tiles the single group stays ahead: 45.6 against 59.5, 276 against 324 us).
+  if (first_read && best.split == 1 && NB == 1 && g.cu == nullptr) {
+    const Cost picked = cost(best);
+    if (picked.rows_busiest <= 128) {
+      KsChoice alt = best;
+      double alt_t = 1e30;
+      for (const KsChoice& c : {KsChoice{8, 4}, KsChoice{12, 4}}) {
+        const Cost k = cost(c);
+        if (k.fits && k.rows_busiest <= picked.rows_busiest && k.t < alt_t) {
+          alt_t = k.t;
+          alt = c;
+        }
+      }
+      return alt;
     }
   }
   return best;
 }
 
+// Upper bound of the number of score tiles for the tile height in p.g.tile_rows.
+void size_score_tiles(Plan& p) {
+  if (p.g.cu == nullptr)
+    p.tiles_bound = p.g.B * ((p.g.N + p.g.tile_rows - 1) / p.g.tile_rows);
+  else
+    p.tiles_bound = (int)(p.g.total_N / p.g.tile_rows) + p.g.B;
+}
+
 // DART_SCORE_TILE="W,KS" in the environment names the shape instead (for tuning, and for the
 // tests that run every instantiated shape); a value that is not one of the shapes above, or
 // does not fit the LDS with this many pivots, is an error of the call.
-dart_status plan_score_tiles(Plan& p) {
-  KsChoice c = choose_score_tiles(p.g, compute_units());
+dart_status plan_score_tiles(Plan& p, bool first_read) {
+  KsChoice c = choose_score_tiles(p.g, compute_units(), first_read);
   if (const char* v = std::getenv("DART_SCORE_TILE")) {
     int w = 0, ks = 0;
     bool known = false;
@@ -137,7 +185,14 @@ dart_status plan_score_tiles(Plan& p) {
   p.ks_waves = c.waves;
   p.ks_split = c.split;
   p.g.tile_rows = 16 * c.waves / c.split;
+  size_score_tiles(p);
   return DART_OK;
+}
+
+// An entry point whose score pass is the first pass over X plans its tiles again (make_plan
+// assumes a norm pass over X before it).
+dart_status replan_first_read(Plan& p) {
+  return p.g.dtype == kBF16 ? plan_score_tiles(p, true) : DART_OK;
 }
 
 // Entries of all stage lists of a sample of n tokens that keeps k of them with P pivots, Pin
@@ -232,7 +287,9 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   g.tile_rows = 64;
   p.ks_waves = p.ks_split = 0;
   if (d->dtype == DART_BF16) {
-    const dart_status ts = plan_score_tiles(p);
+    // (pivots given, drawn or all from outside: no norm pass reads X before the score pass)
+    const dart_status ts = plan_score_tiles(p, d->pivot_mode == DART_PIVOT_GIVEN ||
+                                                   d->pivot_mode == DART_PIVOT_RANDOM || Pin == 0);
     if (ts != DART_OK) return ts;
   }
   p.esz = esz;
@@ -243,13 +300,12 @@ dart_status make_plan(const dart_desc* d, Plan& p) {
   }
   if (!ragged) {
     p.keep_rows_bound = (long)d->B * K;
-    p.tiles_bound = d->B * ((d->N + g.tile_rows - 1) / g.tile_rows);
   } else {
     p.keep_rows_bound = d->K > 0 ? (long)d->B * d->K
                                  : (long)(((__int128)total * d->keep_num) / g.keep_den);
     if (p.keep_rows_bound > total) p.keep_rows_bound = total;
-    p.tiles_bound = (int)(total / g.tile_rows) + d->B;
   }
+  size_score_tiles(p);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
   p.o_status = take(kAlign);
@@ -690,6 +746,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   if (p.g.mode == kGiven) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
+  if (crit != X) DART_TRY(replan_first_read(p));  // the norm pass reads the criterion, not X
   hipStream_t st = static_cast<hipStream_t>(stream);
   // profiled calls: the kernels launched from here on belong to stage k
   struct StageGuard {
@@ -784,6 +841,17 @@ dart_status dart_score_tile_shape(const dart_desc* desc, int32_t* waves, int32_t
   return DART_OK;
 }
 
+dart_status dart_score_tile_shape_first_read(const dart_desc* desc, int32_t* waves,
+                                             int32_t* split) {
+  if (!waves || !split) return DART_ERR_NULL;
+  Plan p;
+  DART_TRY(make_plan(desc, p));
+  DART_TRY(replan_first_read(p));
+  *waves = p.ks_waves;
+  *split = p.ks_split;
+  return DART_OK;
+}
+
 dart_status dart_select_pivots(const dart_desc* desc, const void* X, const void* crit,
                                int32_t crit_D, int64_t crit_ld, int32_t* piv, float* l1_out,
                                void* ws, size_t ws_bytes, void* stream) {
@@ -817,6 +885,7 @@ dart_status dart_duplication_scores(const dart_desc* desc, const void* X, const 
   if (!X || !piv || !S) return DART_ERR_NULL;
   if (misaligned16(X)) return DART_ERR_ALIGN;
   DART_TRY(check_ws(p, ws, ws_bytes));
+  DART_TRY(replan_first_read(p));
   hipStream_t st = static_cast<hipStream_t>(stream);
   DART_TRY(launch_prepare(p, ws, st));
   DART_TRY(launch_given_status(p, piv, ws, st));

@@ -240,9 +240,25 @@ def test_score_tile_shape_follows_the_batch_and_the_override():
     assert D.dart_score_tile_shape(D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320)) == (6, 1)
     # 4 x 9216 rows: 144-row tiles = 256 tiles, one per unit
     assert D.dart_score_tile_shape(D.make_desc(4, 3584, 32, D.DART_BF16, N=9216, K=1024)) == (9, 1)
-    # 16 x 576 rows: 48-row tiles, the hidden dimension split over two groups of waves
-    w, ks = D.dart_score_tile_shape(D.make_desc(16, 4096, 8, D.DART_BF16, N=576, K=64))
-    assert ks > 1 and 16 * w // ks == 48
+    # 16 x 576 rows: 48-row tiles, the hidden dimension split over four groups of waves
+    assert D.dart_score_tile_shape(D.make_desc(16, 4096, 8, D.DART_BF16, N=576, K=64)) == (12, 4)
+    # a first read of X (no norm pass before the score pass) changes small dense batches only:
+    # the headline shape goes to four groups of waves on tiles that load no unit more ...
+    head = D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320)
+    w, ks = D.dart_score_tile_shape_first_read(head)
+    assert ks == 4 and 16 * w // ks in (32, 48)
+    for mode in (D.DART_PIVOT_GIVEN, D.DART_PIVOT_RANDOM):  # (no norm pass exists for these)
+        assert D.dart_score_tile_shape(D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320,
+                                                   pivot_mode=mode)) == (w, ks)
+    # ... while 32 pivots, or a ragged batch with thousands of tiles, keep their single group
+    video = D.make_desc(4, 3584, 32, D.DART_BF16, N=9216, K=1024)
+    assert D.dart_score_tile_shape_first_read(video) == (9, 1)
+    ragged = D.make_desc(32, 3584, 16, D.DART_BF16, keep_num=111, keep_den=1000,
+                         total_N=234356, max_N=16384)
+    ragged.cu_seqlens = 0x1000  # never dereferenced on the host
+    assert D.dart_score_tile_shape_first_read(ragged) == D.dart_score_tile_shape(ragged)
+    assert D.dart_score_tile_shape_first_read(D.make_desc(1, 4096, 8, D.DART_F32, N=576,
+                                                          K=64)) == (0, 0)
     assert D.dart_score_tile_shape(D.make_desc(1, 4096, 8, D.DART_F32, N=576, K=64)) == (0, 0)
     shapes = _built_tile_shapes(8)
     assert len(shapes) >= 15 and (6, 1) in shapes and (9, 1) in shapes and (1, 1) not in shapes
