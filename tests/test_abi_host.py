@@ -246,7 +246,7 @@ def test_score_tile_shape_follows_the_batch_and_the_override():
     # the headline shape goes to four groups of waves on tiles that load no unit more ...
     head = D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320)
     w, ks = D.dart_score_tile_shape_first_read(head)
-    assert ks == 4 and 16 * w // ks in (32, 48)
+    assert (w, ks) == (8, 4)
     for mode in (D.DART_PIVOT_GIVEN, D.DART_PIVOT_RANDOM):  # (no norm pass exists for these)
         assert D.dart_score_tile_shape(D.make_desc(8, 4096, 16, D.DART_BF16, N=2880, K=320,
                                                    pivot_mode=mode)) == (w, ks)
