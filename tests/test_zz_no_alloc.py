@@ -13,10 +13,10 @@ import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 
-def run_both(w):
+def run_both(w, mode=D.DART_PIVOT_MAX_L1, seed=0):
     Xd = G.to_device(w)
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
-    desc = G.desc_of(w, cu_dev)
+    desc = G.desc_of(w, cu_dev, mode=mode, seed=seed)
     assert D.dart_workspace_bytes(desc) <= D.dart_static_scratch_bytes()
     total_keep = sum(w.budget(b) for b in range(w.B))
     total_N = int(w.cu[-1])
@@ -53,6 +53,9 @@ def test_static_scratch_entry_matches_dart_reduce_twice_in_a_row():
     run_both(W.video_batch(B=2, frames=16, per_frame=144, D=1024, P=32, K=256, n_centroids=16))
     run_both(W.ragged_batch(B=3, n_lo=200, n_hi=600, D=512, P=16))
     run_both(W.single_image(N=300, D=512, P=8, K=64, n_centroids=16))
+    # pivots drawn at random on the device
+    run_both(W.image_batch(B=4, N=333, D=520, P=5, K=64, n_centroids=32),
+             mode=D.DART_PIVOT_RANDOM, seed=77)
 
 
 def test_static_scratch_entry_refuses_oversized_problems():
