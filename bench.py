@@ -181,6 +181,68 @@ def bench_sequences(args):
                                "rotated and fit the memory-side cache"}}))
 
 
+def bench_norms_given(args):
+    """Context run: the criterion norms come from the caller (dart_reduce_with_norms; here they
+    are computed once, outside the timed region, by dart_select_pivots), so the step has no
+    norm pass and reads the hidden states once.  Prints its own JSON line; not the headline
+    measurement."""
+    import torch
+
+    import paper_2502_11494_amd as D
+    from paper_2502_11494_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    w = W.by_index(args.config)
+    total_N = int(w.cu[-1])
+    total_K = sum(w.budget(b) for b in range(w.B))
+    esz = 2 if w.dtype == W.BF16 else 4
+    X0 = (torch.from_numpy(w.X.view("int16")).view(torch.bfloat16) if w.dtype == W.BF16
+          else torch.from_numpy(w.X)).cuda()
+    copies = max(2, -(-(1 << 30) // (total_N * w.D * esz)))  # rotate through more than 1 GB
+    Xs = [X0] + [X0.clone() for _ in range(copies - 1)]
+    cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
+    if w.ragged:
+        desc = D.make_desc(w.B, w.D, w.P, w.dtype, keep_num=w.keep_num, keep_den=w.keep_den,
+                           cu_seqlens=cu_dev, total_N=total_N, max_N=int(w.lengths.max()))
+    else:
+        desc = D.make_desc(w.B, w.D, w.P, w.dtype, N=int(w.lengths[0]), K=w.K)
+    ws = D.alloc_workspace(desc)
+    pos = torch.from_numpy(w.pos).cuda()
+    Y = torch.empty((total_K, w.D), dtype=X0.dtype, device="cuda")
+    keep = torch.empty(total_K, dtype=torch.int32, device="cuda")
+    pos_out = torch.empty(total_K, dtype=torch.int64, device="cuda")
+    piv = torch.empty(w.B * w.P, dtype=torch.int32, device="cuda")
+    l1 = torch.empty(total_N, dtype=torch.float32, device="cuda")
+    D.dart_select_pivots(desc, X0, piv, ws, l1_out=l1)  # the library's own fp32 norms
+    torch.cuda.synchronize()
+    rel_err = 2e-6  # above the norm pass's rounding bound for these row widths
+
+    def step(i):
+        D.dart_reduce_with_norms(desc, Xs[i % copies], Y, keep, ws, l1, rel_err, pos=pos,
+                                 pos_out=pos_out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+    _, compulsory, _ = whole_call_bytes(total_N, total_K, w.D, esz)
+    print(json.dumps({
+        "metric": "vision tokens reduced/sec with the criterion norms supplied by the caller",
+        "value": round(total_N / t_step, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t_step * 1e3, 5),
+        "higher_is_better": True, "data": "synthetic",
+        "dtype": "bf16" if w.dtype == W.BF16 else "f32",
+        "config": {"workload": workload_label(w, args.config, False),
+                   "path": "dart_reduce_with_norms: no norm pass, the hidden states are read once",
+                   "input_copies_rotated": copies},
+        "whole_path_algorithmic_GBps": round(compulsory / t_step / 1e9, 1),
+        "frac_of_hbm_peak": round(compulsory / t_step / 1e9 / HBM_PEAK_GBS, 4)}))
+
+
 def whole_call_bytes(total_N, total_K, D_, esz):
     """Algorithmic HBM bytes of one dart_reduce call: what the method must move (read every
     hidden-state row once, write the retained rows, read and write their position ids), and
@@ -452,6 +514,9 @@ def main():
     ap.add_argument("--sequences", action="store_true",
                     help="context run: spans inside whole sequences and whole-sequence "
                          "compaction (prints its own line)")
+    ap.add_argument("--norms-given", action="store_true",
+                    help="context run: the criterion norms are supplied by the caller "
+                         "(dart_reduce_with_norms: no norm pass; prints its own line)")
     ap.add_argument("--fused", action="store_true",
                     help="context run: the one-launch persistent kernel (DART_FUSED=1) instead of "
                          "the default kernel-per-step path")
@@ -477,6 +542,8 @@ def main():
     ensure_built()  # loads what is built; compiles only a missing or stale library
     if args.sequences:
         return bench_sequences(args)
+    if args.norms_given:
+        return bench_norms_given(args)
     torch.cuda.set_device(0)
     w = W.by_name(args.workload) if args.workload else W.by_index(args.config)
     m = measure(w, args, args.config, args.steps, args.warmup)

@@ -252,6 +252,24 @@ DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const voi
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* dart_reduce for callers that already hold the criterion norms, e.g. from an epilogue of the
+ * projection that produced the criterion rows (the K-norm of the Section 3.3 footnote computed
+ * where the keys are computed): l1[j] (DEVICE float[total_N], packed like S) approximates the
+ * L1 norm of criterion row j with a relative error of at most l1_rel_err (0 <= l1_rel_err <=
+ * 0.25; the caller's promise, not checked).  The norm pass is skipped, so the hidden states
+ * are read once, by the score pass.  The pivots are still those of the exact norms: every
+ * token whose approximate norm could reach the top P within that error is re-evaluated in
+ * fp64 from its criterion row (crit, or X when crit is NULL) and ranked by (exact norm, index),
+ * so a loose bound costs time (more rows to re-read), a wrong one can cost the right pivots.
+ * DART_PIVOT_MAX_L1 / DART_PIVOT_MIN_L1 only (DART_ERR_DTYPE otherwise); everything else as
+ * dart_reduce. */
+DART_API dart_status dart_reduce_with_norms(const dart_desc* desc, const void* X, const void* crit,
+                                            int32_t crit_D, int64_t crit_ld, const float* l1,
+                                            double l1_rel_err, const int64_t* pos, void* Y,
+                                            int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                                            int32_t* piv_out, float* S_out, void* ws,
+                                            size_t ws_bytes, void* stream);
+
 /* dart_reduce for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, results and kernels as dart_reduce, but the scratch memory is a buffer built

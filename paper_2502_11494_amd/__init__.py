@@ -9,7 +9,8 @@ from .binding import (DART_BF16, DART_ERR_ALIGN, DART_ERR_BUDGET, DART_ERR_DEVIC
                       dart_compact_sequences,
                       dart_device_status, dart_duplication_scores, dart_gather_compact,
                       dart_device_status_static, dart_probe_mfma_dot32, dart_reduce,
-                      dart_reduce_profiled, dart_reduce_static, dart_score_tile_shape,
+                      dart_reduce_profiled, dart_reduce_static, dart_reduce_with_norms,
+                      dart_score_tile_shape,
                       dart_score_tile_shape_first_read,
                       dart_select_pivots,
                       dart_static_scratch_bytes, dart_topk_keep,

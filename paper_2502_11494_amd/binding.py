@@ -27,7 +27,7 @@ EXPORTS = ("dart_workspace_bytes", "dart_select_pivots", "dart_duplication_score
            "dart_topk_keep", "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
            "dart_reduce_profiled", "dart_reduce_static", "dart_static_scratch_bytes",
            "dart_device_status_static", "dart_probe_mfma_dot32", "dart_score_tile_shape",
-           "dart_score_tile_shape_first_read",
+           "dart_score_tile_shape_first_read", "dart_reduce_with_norms",
            "dart_device_status", "dart_score_tolerance", "dart_strerror")
 
 
@@ -76,6 +76,8 @@ def lib():
                                              i64, vp, i64, vp, vp, vp, sz, vp]
         L.dart_reduce.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.dart_reduce_profiled.argtypes = L.dart_reduce.argtypes + [C.POINTER(vp)]
+        L.dart_reduce_with_norms.argtypes = [dp, vp, vp, i32, i64, vp, C.c_double, vp, vp, vp, vp,
+                                             vp, vp, vp, vp, sz, vp]
         L.dart_device_status.argtypes = [dp, vp, vp]
         L.dart_reduce_static.argtypes = [dp, vp, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.dart_score_tile_shape.argtypes = [dp, C.POINTER(i32), C.POINTER(i32)]
@@ -88,7 +90,8 @@ def lib():
                      "dart_gather_compact", "dart_compact_sequences", "dart_reduce",
                      "dart_reduce_profiled", "dart_device_status", "dart_reduce_static",
                      "dart_device_status_static", "dart_probe_mfma_dot32",
-                     "dart_score_tile_shape", "dart_score_tile_shape_first_read"):
+                     "dart_score_tile_shape", "dart_score_tile_shape_first_read",
+                     "dart_reduce_with_norms"):
             getattr(L, name).restype = C.c_int
         L.dart_score_tolerance.argtypes = [i32]
         L.dart_score_tolerance.restype = C.c_double
@@ -207,6 +210,17 @@ def dart_reduce(desc, X, Y, keep, ws, *, crit=None, crit_D=0, crit_ld=0, pos=Non
     _check(lib().dart_reduce(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld, _ptr(pos),
                              _ptr(Y), _ptr(pos_out), _ptr(keep), _ptr(cu_keep), _ptr(piv_out),
                              _ptr(S_out), _ptr(ws), ws.numel(), _stream(stream)), "dart_reduce")
+
+
+def dart_reduce_with_norms(desc, X, Y, keep, ws, l1, l1_rel_err, *, crit=None, crit_D=0,
+                           crit_ld=0, pos=None, pos_out=None, cu_keep=None, piv_out=None,
+                           S_out=None, stream=None):
+    """dart_reduce without its norm pass: l1 holds the criterion norms, good to l1_rel_err."""
+    _check(lib().dart_reduce_with_norms(C.byref(desc), _ptr(X), _ptr(crit), crit_D, crit_ld,
+                                        _ptr(l1), float(l1_rel_err), _ptr(pos), _ptr(Y),
+                                        _ptr(pos_out), _ptr(keep), _ptr(cu_keep), _ptr(piv_out),
+                                        _ptr(S_out), _ptr(ws), ws.numel(), _stream(stream)),
+           "dart_reduce_with_norms")
 
 
 def dart_reduce_static(desc, X, Y, keep, *, crit=None, crit_D=0, crit_ld=0, pos=None,

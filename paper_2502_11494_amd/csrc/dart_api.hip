@@ -457,9 +457,12 @@ int values_per_thread(int max_n) {
     default: LAUNCH(16); break;                                                                  \
   }
 
+// l1_rel_err < 0: the norms are the norm pass's own (its rounding bound applies); otherwise the
+// caller's, good to that relative error.
 dart_status launch_select_pivots(const Plan& p, const void* X, const void* C, int Dc, long ldc,
-                                 const float* l1, int* piv, void* ws, hipStream_t st) {
-  const float tau = (float)l1_rel_bound(p.g.dtype, Dc);
+                                 const float* l1, int* piv, void* ws, hipStream_t st,
+                                 double l1_rel_err = -1.0) {
+  const float tau = (float)(l1_rel_err < 0 ? l1_rel_bound(p.g.dtype, Dc) : l1_rel_err);
   double* pl2 = at<double>(ws, p.o_pl2);
   double* scr = at<double>(ws, p.o_scr_f64);
   // 1024 threads: a 256-thread variant measured slower even for short samples
@@ -734,9 +737,12 @@ dart_status check_crit(const Plan& p, const void* X, const void*& crit, int32_t&
 dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, int32_t crit_D,
                         int64_t crit_ld, const int64_t* pos, void* Y, int64_t* pos_out,
                         int32_t* keep, int32_t* cu_keep, int32_t* piv_out, float* S_out, void* ws,
-                        size_t ws_bytes, void* stream, void* const* events) {
+                        size_t ws_bytes, void* stream, void* const* events,
+                        const float* l1_given = nullptr, double l1_rel_err = 0.0) {
   Plan p;
   DART_TRY(make_plan(desc, p));
+  if (l1_given && (p.g.mode == kGiven || p.g.mode == kRandom)) return DART_ERR_DTYPE;
+  if (l1_given && !(l1_rel_err >= 0.0 && l1_rel_err <= 0.25)) return DART_ERR_SHAPE;
   if (p.g.B == 0) return DART_OK;
   if (!X || !keep || (Y && (pos != nullptr) != (pos_out != nullptr))) return DART_ERR_NULL;
   if (p.g.mode == kGiven && !piv_out) return DART_ERR_NULL;
@@ -748,7 +754,8 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   if (p.g.mode == kGiven) crit = nullptr;
   DART_TRY(check_crit(p, X, crit, crit_D, crit_ld));
   DART_TRY(check_ws(p, ws, ws_bytes));
-  if (crit != X) DART_TRY(replan_first_read(p));  // the norm pass reads the criterion, not X
+  // (the norm pass reads the criterion, not X, or there is none: the caller brought the norms)
+  if (crit != X || l1_given) DART_TRY(replan_first_read(p));
   hipStream_t st = static_cast<hipStream_t>(stream);
   // profiled calls: the kernels launched from here on belong to stage k
   struct StageGuard {
@@ -768,7 +775,7 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
   // the gain of the score pass does not pay for it; the tighter error bound also saves the
   // retained-set kernel 10 % on near-duplicate video frames)
   p.norms_given = p.g.mode != kGiven && p.g.Pin > 0 && crit == X && p.g.dtype == kBF16 &&
-                  (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
+                  !l1_given && (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
   DART_TRY(launch_prepare(p, ws, st));
   stage(0);
   if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
@@ -786,11 +793,13 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
     DART_TRY(launch_pivot_norms(p, X, piv, 0, piv, ws, st));
   } else {
     // pivots chosen among the tokens (none if all of them come from outside) ...
-    if (p.g.Pin > 0)
+    if (p.g.Pin > 0 && !l1_given)
       DART_TRY(launch_row_l1(p, crit, crit_D, crit_ld, l1, crit == X, st,
                              p.norms_given ? at<double>(ws, p.o_l2) : nullptr));
     stage(1);
-    if (p.g.Pin > 0) DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1, piv, ws, st));
+    if (p.g.Pin > 0)
+      DART_TRY(launch_select_pivots(p, X, crit, crit_D, crit_ld, l1_given ? l1_given : l1, piv, ws,
+                                    st, l1_given ? l1_rel_err : -1.0));
     // ... then the norms and marks of those from outside
     if (p.g.Pe > 0) DART_TRY(launch_pivot_norms(p, X, piv, p.g.Pin, piv, ws, st));
   }
@@ -1007,6 +1016,17 @@ dart_status dart_reduce_profiled(const dart_desc* desc, const void* X, const voi
     if (!events[k]) return DART_ERR_NULL;
   return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
                      S_out, ws, ws_bytes, stream, events);
+}
+
+dart_status dart_reduce_with_norms(const dart_desc* desc, const void* X, const void* crit,
+                                   int32_t crit_D, int64_t crit_ld, const float* l1,
+                                   double l1_rel_err, const int64_t* pos, void* Y,
+                                   int64_t* pos_out, int32_t* keep, int32_t* cu_keep,
+                                   int32_t* piv_out, float* S_out, void* ws, size_t ws_bytes,
+                                   void* stream) {
+  if (!l1) return DART_ERR_NULL;
+  return reduce_impl(desc, X, crit, crit_D, crit_ld, pos, Y, pos_out, keep, cu_keep, piv_out,
+                     S_out, ws, ws_bytes, stream, nullptr, l1, l1_rel_err);
 }
 
 size_t dart_static_scratch_bytes(void) { return kStaticScratchBytes; }

@@ -137,6 +137,19 @@ def test_null_and_workspace_errors_need_no_device():
     assert D.dart_workspace_bytes(dr) == need
     assert L.dart_select_pivots(C.byref(dr), fake, None, 0, 0, None, None, fake, need,
                                 None) == D.DART_ERR_NULL  # the list it would write is missing
+    # caller-supplied criterion norms: the norms are required, the error bound must be one,
+    # and only the modes that rank norms take them
+    wn = L.dart_reduce_with_norms
+    assert wn(C.byref(d), fake, None, 0, 0, None, 1e-6, None, fake, None, fake, None, None, None,
+              fake, need, None) == D.DART_ERR_NULL
+    for bad_err in (-1e-9, 0.26, float("nan"), float("inf")):
+        assert wn(C.byref(d), fake, None, 0, 0, fake, bad_err, None, fake, None, fake, None, None,
+                  None, fake, need, None) == D.DART_ERR_SHAPE
+    for dm in (dg, dr):
+        assert wn(C.byref(dm), fake, None, 0, 0, fake, 1e-6, None, fake, None, fake, None, fake,
+                  None, fake, need, None) == D.DART_ERR_DTYPE
+    assert wn(C.byref(d), None, None, 0, 0, fake, 1e-6, None, fake, None, fake, None, None, None,
+              fake, need, None) == D.DART_ERR_NULL  # X
     # an empty batch is a valid no-op and needs nothing else
     d0 = D.make_desc(0, 4096, 8, D.DART_BF16, N=576, K=64)
     assert L.dart_reduce(C.byref(d0), None, None, 0, 0, None, None, None, None, None, None,
