@@ -42,7 +42,8 @@ int main(void) {
     d.K = pick(sizes, ns);
     d.keep_num = pick(sizes, ns);
     d.keep_den = pick(sizes, ns);
-    d.pivot_mode = (int32_t)(rnd() % 5) - 1;
+    d.pivot_mode = (int32_t)(rnd() % 6) - 1;
+    d.seed = ((uint64_t)rnd() << 32) ^ rnd();
     d.score_mode = (int32_t)(rnd() % 5) - 1;
     d.P_ext = rnd() % 4 ? 0 : pick(sizes, ns);
     d.ext_ld = strides[rnd() % 9];
@@ -58,7 +59,7 @@ int main(void) {
       d.N = d.P + (int32_t)(rnd() % 16000);
       d.K = d.P + (int32_t)(rnd() % (uint32_t)(d.N - d.P + 1));
       d.dtype = (int32_t)(rnd() % 2);
-      d.pivot_mode = (int32_t)(rnd() % 3);
+      d.pivot_mode = (int32_t)(rnd() % 4);
       d.score_mode = (int32_t)(rnd() % 3);
       d.P_ext = 0;
       d.cu_seqlens = NULL;
@@ -94,6 +95,23 @@ int main(void) {
     if (dart_topk_keep(&d, NULL, NULL, NULL, NULL, NULL, fake, ws, NULL) != DART_ERR_NULL) return 9;
     if (dart_gather_compact(&d, fake, NULL, NULL, fake, NULL, fake, ws, NULL) != DART_ERR_NULL)
       return 10;
+    /* caller-supplied norms: missing norms, then an error bound that is none (or a pivot mode
+       that ranks no norms) */
+    if (dart_reduce_with_norms(&d, fake, NULL, 0, 0, NULL, 1e-6, NULL, fake, NULL, (int32_t*)fake,
+                               NULL, (int32_t*)fake, NULL, fake, ws, NULL) != DART_ERR_NULL)
+      return 13;
+    if (dart_reduce_with_norms(&d, fake, NULL, 0, 0, (const float*)fake, -1.0, NULL, fake, NULL,
+                               (int32_t*)fake, NULL, (int32_t*)fake, NULL, fake, ws, NULL) !=
+        (d.pivot_mode >= DART_PIVOT_GIVEN ? DART_ERR_DTYPE : DART_ERR_SHAPE))
+      return 14;
+    {
+      int32_t w1 = -1, k1 = -1, w2 = -1, k2 = -1;
+      if (dart_score_tile_shape(&d, &w1, &k1) != DART_OK) return 15;
+      if (dart_score_tile_shape_first_read(&d, &w2, &k2) != DART_OK) return 16;
+      if (d.dtype == DART_BF16 ? (w1 < 1 || k1 < 1 || w1 % k1 || w2 < 1 || k2 < 1 || w2 % k2)
+                               : (w1 | k1 | w2 | k2) != 0)
+        return 17;
+    }
   }
   if (valid < 10000 || invalid < 10000) return 11;
   for (int s = 1; s >= -12; --s)
