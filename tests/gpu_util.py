@@ -71,10 +71,12 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
                given_piv: Optional[np.ndarray] = None, expect_status: int = D.DART_OK,
                score_mode: int = D.DART_SCORE_PER_PIVOT,
                ext: Optional[np.ndarray] = None, ext_ld: Optional[int] = None,
-               seed: int = 0) -> GpuResult:
+               seed: int = 0, norms: Optional[tuple] = None) -> GpuResult:
     """given_piv [B, P] int32 (with mode DART_PIVOT_GIVEN): the caller's pivots.
     ext [B, P_ext, D] element bits: pivot rows from outside the samples (the last P_ext
-    of the w.P pivots).  seed: of the draw, with mode DART_PIVOT_RANDOM."""
+    of the w.P pivots).  seed: of the draw, with mode DART_PIVOT_RANDOM.  norms = (l1 float32
+    [total_N], relative error bound): the criterion norms come from the caller
+    (dart_reduce_with_norms)."""
     Xd = to_device(w, ld) if Xd is None else Xd
     cu_dev = torch.from_numpy(w.cu).cuda() if w.ragged else None
     ext_dev, P_ext = None, 0
@@ -103,8 +105,13 @@ def run_reduce(w: W.Workload, ld: Optional[int] = None, mode: int = D.DART_PIVOT
     kw = {}
     if crit is not None:
         kw = dict(crit=crit, crit_D=crit.shape[1], crit_ld=crit.stride(0))
-    D.dart_reduce(desc, Xd, Y, keep, ws, pos=pos, pos_out=pos_out, cu_keep=cu_keep, piv_out=piv,
-                  S_out=S, **kw)
+    if norms is not None:
+        D.dart_reduce_with_norms(desc, Xd, Y, keep, ws, torch.from_numpy(norms[0]).cuda(), norms[1],
+                                 pos=pos, pos_out=pos_out, cu_keep=cu_keep, piv_out=piv, S_out=S,
+                                 **kw)
+    else:
+        D.dart_reduce(desc, Xd, Y, keep, ws, pos=pos, pos_out=pos_out, cu_keep=cu_keep,
+                      piv_out=piv, S_out=S, **kw)
     torch.cuda.synchronize()
     if w.ragged or given_piv is not None:
         assert D.dart_device_status(desc, ws) == expect_status

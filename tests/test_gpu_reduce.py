@@ -251,10 +251,10 @@ def test_random_shapes_sweep():
 
 def test_random_everything_sweep():
     """Seeded random draws over all batch recipes (fp32 and bf16, dense and packed, with and
-    without separate criterion rows, pivots ranked by norm or drawn at random), hidden sizes with
-    and without partial chunks and 1 to 64 pivots, each compared bit for bit.  DART_SWEEP_CASES /
-    DART_SWEEP_SEED in the environment make it as long as wanted (3000 cases take about three
-    minutes)."""
+    without separate criterion rows, pivots ranked by norm -- the library's or the caller's
+    norms -- or drawn at random), hidden sizes with and without partial chunks and 1 to 64
+    pivots, each compared bit for bit.  DART_SWEEP_CASES / DART_SWEEP_SEED in the environment
+    make it as long as wanted (3000 cases take about three minutes)."""
     cases = int(os.environ.get("DART_SWEEP_CASES", "80"))
     rng = np.random.default_rng(int(os.environ.get("DART_SWEEP_SEED", "20261128")))
     done = skipped = 0
@@ -293,6 +293,8 @@ def test_random_everything_sweep():
         use_crit = w.dtype == W.BF16 and rng.random() < 0.35
         drawn = rng.random() < 0.12  # pivots drawn at random on the device instead of ranked
         draw_seed = int(rng.integers(0, 2**63))
+        with_norms = not drawn and rng.random() < 0.12
+        norm_err = float(rng.choice([0.0, 1e-6, 1e-4]))
         crit_bits = (W.key_states(w, int(rng.choice([64, 128, 512])), seed=seed & 0xffff)
                      if use_crit else None)
         if drawn:
@@ -305,11 +307,17 @@ def test_random_everything_sweep():
             skipped += 1
             continue  # a margin below the oracle's own resolution: not a parity case
         print(f"[case {done}] {w.name} B={w.B} D={w.D} P={w.P} K={w.K} "
-              f"lens={w.lengths[:5].tolist()} crit={use_crit} drawn={drawn}", flush=True)
+              f"lens={w.lengths[:5].tolist()} crit={use_crit} drawn={drawn} norms={with_norms}",
+              flush=True)
         crit_dev = (None if crit_bits is None else
                     torch.from_numpy(crit_bits.view(np.int16)).view(torch.bfloat16).cuda())
         if drawn:  # (a criterion tensor, if passed, is ignored)
             g = G.run_reduce(w, crit=crit_dev, mode=D.DART_PIVOT_RANDOM, seed=draw_seed)
+        elif with_norms:  # the caller's norms, off by up to err: no norm pass
+            exact = oracle.l1_norms(w.X if crit_bits is None else crit_bits, w.dtype)
+            noisy = exact * (1.0 + norm_err * np.random.default_rng(draw_seed).uniform(
+                -1.0, 1.0, size=exact.shape))
+            g = G.run_reduce(w, crit=crit_dev, norms=(noisy.astype(np.float32), norm_err + 1e-7))
         else:
             g = G.run_reduce(w, crit=crit_dev)
         G.compare(w, g, refs)
