@@ -778,7 +778,9 @@ dart_status reduce_impl(const dart_desc* desc, const void* X, const void* crit, 
                   !l1_given && (double)p.g.total_N * p.g.ld * p.esz <= 1e9;
   DART_TRY(launch_prepare(p, ws, st));
   stage(0);
-  if (p.fusable && crit == X && events == nullptr && p.g.total_N > 0 && fused_enabled())
+  // (the one-launch path computes its own norms: not for profiled calls or the caller's norms)
+  if (p.fusable && crit == X && events == nullptr && !l1_given && p.g.total_N > 0 &&
+      fused_enabled())
     return launch_fused(p, X, pos, Y, pos_out, keep, cu_keep, piv, S, ws, st);
   if (p.g.mode == kGiven) {
     // the caller's pivots: check them, compute their norms; no pass over the criterion
