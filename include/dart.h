@@ -256,7 +256,8 @@ DART_API dart_status dart_reduce(const dart_desc* desc, const void* X, const voi
  * projection that produced the criterion rows (the K-norm of the Section 3.3 footnote computed
  * where the keys are computed): l1[j] (DEVICE float[total_N], packed like S) approximates the
  * L1 norm of criterion row j with a relative error of at most l1_rel_err (0 <= l1_rel_err <=
- * 0.25; the caller's promise, not checked).  The norm pass is skipped, so the hidden states
+ * 0.1; the caller's promise, not checked; the rounding of an exact norm to fp32 is allowed for
+ * on top of it).  The norm pass is skipped, so the hidden states
  * are read once, by the score pass.  The pivots are still those of the exact norms: every
  * token whose approximate norm could reach the top P within that error is re-evaluated in
  * fp64 from its criterion row (crit, or X when crit is NULL) and ranked by (exact norm, index),

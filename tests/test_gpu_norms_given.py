@@ -41,9 +41,10 @@ def run_with_norms(w, l1, rel_err, crit=None, mode=D.DART_PIVOT_MAX_L1):
 
 
 def noisy_norms(exact, err, seed):
-    """fp32 norms within a relative error of err (plus the rounding to fp32) of the exact ones."""
+    """fp32 norms within a relative error of err of the exact ones (the rounding to fp32 comes
+    on top: the library allows for it)."""
     u = np.random.default_rng(seed).uniform(-1.0, 1.0, size=exact.shape)
-    return (exact * (1.0 + err * u)).astype(np.float32), err + 1e-7
+    return (exact * (1.0 + err * u)).astype(np.float32), err
 
 
 CASES = [
@@ -100,7 +101,7 @@ def test_callers_norms_at_full_size_and_refusals():
     l1d = torch.ones(200, dtype=torch.float32, device="cuda")
     desc = G.desc_of(small, None)
     ws = D.alloc_workspace(desc)
-    for bad_err in (-1e-3, 0.3, float("nan")):
+    for bad_err in (-1e-3, 0.11, float("nan")):
         with pytest.raises(D.DartError) as e:
             D.dart_reduce_with_norms(desc, Xd, None, keep, ws, l1d, bad_err)
         assert e.value.status == D.DART_ERR_SHAPE
